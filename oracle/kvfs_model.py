@@ -1,0 +1,223 @@
+"""State model of the KV-cache file system (test infrastructure, CPU only).
+
+The paper (section 4.2) says only that KV tensors live in fixed-size pages of GPU
+memory, that files can be opened, forked "without duplicating the actual tensors",
+removed and closed, and (section 4.1) that `pred` appends the new tokens' tensors to
+the file.  Everything finer than that is a convention of this build, written out here
+step by step so that the library's integer state can be compared bit for bit:
+
+* allocation takes the free page of lowest rank (rank = position in `free_order`);
+* `kv_fork` copies the page-id list and increments each page's reference count;
+* appending to a file whose last page is partly filled and shared first copies that
+  page's filled slots into a fresh page (copy-on-write); full pages are never copied;
+* `kv_remove` decrements every page once and frees those reaching zero;
+* a batch of appends either fits in the free pages or changes nothing.
+"""
+import heapq
+
+import numpy as np
+
+EINVAL, EBADF, ENOSPC, ENOENT, EEXIST, EBUSY = -1, -2, -3, -4, -5, -6
+
+
+class KVError(Exception):
+    def __init__(self, code, msg=""):
+        super().__init__(f"{code}: {msg}")
+        self.code = code
+
+
+class _File:
+    __slots__ = ("length", "pages", "name", "handles")
+
+    def __init__(self, name):
+        self.length = 0
+        self.pages = []
+        self.name = name
+        self.handles = set()
+
+
+class KVFSModel:
+    def __init__(self, n_pages, page_tokens, free_order=None):
+        self.n_pages = int(n_pages)
+        self.P = int(page_tokens)
+        order = np.arange(self.n_pages) if free_order is None else np.asarray(free_order)
+        assert np.array_equal(np.sort(order), np.arange(self.n_pages)), "free_order must be a permutation"
+        self.order = order.astype(np.int64)                    # rank -> page
+        self.rank = np.empty(self.n_pages, np.int64)           # page -> rank
+        self.rank[self.order] = np.arange(self.n_pages)
+        self.free_ranks = list(range(self.n_pages))            # min-heap of the free pages' ranks
+        self.refcount = np.zeros(self.n_pages, np.int64)
+        self.handles = {}          # handle -> _File
+        self.names = {}            # name -> _File
+        self.cow_copies = 0
+
+    # ---- helpers -------------------------------------------------------------
+    def _file(self, h):
+        f = self.handles.get(h)
+        if f is None:
+            raise KVError(EBADF, f"bad handle {h}")
+        return f
+
+    def _new_handle(self, f):
+        h = 0
+        while h in self.handles:
+            h += 1                                 # lowest free handle slot
+        self.handles[h] = f
+        f.handles.add(h)
+        return h
+
+    def _alloc(self):
+        p = int(self.order[heapq.heappop(self.free_ranks)])   # lowest rank, whatever the release order
+        self.refcount[p] = 1
+        return p
+
+    def _release_pages(self, f):
+        for p in f.pages:
+            self.refcount[p] -= 1
+            if self.refcount[p] == 0:
+                heapq.heappush(self.free_ranks, int(self.rank[p]))
+        f.pages = []
+        f.length = 0
+
+    # ---- file API (names follow the paper's Fig. 1 and section 4.2) ------------
+    def kv_open(self, name=None):
+        if name is not None and name in self.names:
+            return self._new_handle(self.names[name])     # second handle, same file
+        f = _File(name)
+        if name is not None:
+            self.names[name] = f
+        return self._new_handle(f)
+
+    def kv_fork(self, h):
+        parent = self._file(h)
+        f = _File(None)
+        f.pages = list(parent.pages)
+        f.length = parent.length
+        for p in f.pages:
+            self.refcount[p] += 1
+        return self._new_handle(f)
+
+    def kv_remove(self, h):
+        f = self._file(h)
+        self._release_pages(f)
+        for hh in list(f.handles):
+            del self.handles[hh]
+        f.handles.clear()
+        if f.name is not None:
+            del self.names[f.name]
+
+    def kv_close(self, h):
+        f = self._file(h)
+        del self.handles[h]
+        f.handles.discard(h)
+        if f.name is None and not f.handles:
+            self._release_pages(f)                        # anonymous file nobody can reach
+
+    def kv_len(self, h):
+        return self._file(h).length
+
+    def kv_pages(self, h):
+        return list(self._file(h).pages)
+
+    def free_pages(self):
+        return len(self.free_ranks)
+
+    # ---- append planning -------------------------------------------------------
+    def pages_needed(self, items):
+        """Pages a batch of appends [(handle, n_tokens)] would allocate, LIPs taken in
+        batch order (a copy made by an earlier LIP can leave a later one sole owner)."""
+        pending = {}                                      # page -> refcount change so far
+        need = 0
+        for h, n in items:
+            f = self._file(h)
+            L = f.length
+            if L % self.P != 0:
+                last = f.pages[-1]
+                if self.refcount[last] + pending.get(last, 0) > 1:
+                    need += 1
+                    pending[last] = pending.get(last, 0) - 1
+            need += -(-(L + n) // self.P) - (-(-L // self.P))
+        return need
+
+    def append(self, items):
+        """Commit a batch of appends.  Returns (cow, slots): cow = [(src, dst, r)] page
+        copies of slots [0, r); slots = per item, the (page, slot) of each new token."""
+        files = []
+        for h, n in items:
+            if n < 1:
+                raise KVError(EINVAL, "n_tokens must be >= 1")
+            f = self._file(h)
+            if any(f is g for g in files):
+                raise KVError(EBUSY, "same file twice in a batch")
+            files.append(f)
+        if self.pages_needed(items) > len(self.free_ranks):
+            raise KVError(ENOSPC, "page pool exhausted")
+        cow, slots = [], []
+        for (h, n), f in zip(items, files):
+            r = f.length % self.P
+            if r != 0 and self.refcount[f.pages[-1]] > 1:
+                src = f.pages[-1]
+                dst = self._alloc()
+                self.refcount[src] -= 1
+                f.pages[-1] = dst
+                cow.append((src, dst, r))
+                self.cow_copies += 1
+            mine = []
+            for _ in range(n):
+                if f.length % self.P == 0:
+                    f.pages.append(self._alloc())
+                mine.append((f.pages[-1], f.length % self.P))
+                f.length += 1
+            slots.append(mine)
+        return cow, slots
+
+    # ---- audit -----------------------------------------------------------------
+    def audit(self):
+        """State invariants: reference counts equal table references; free = count 0."""
+        seen = {}
+        files = {id(f): f for f in self.handles.values()}
+        files.update({id(f): f for f in self.names.values()})
+        for f in files.values():
+            assert len(f.pages) == -(-f.length // self.P)
+            for p in f.pages:
+                seen[p] = seen.get(p, 0) + 1
+        free = {int(self.order[r]) for r in self.free_ranks}
+        assert len(free) == len(self.free_ranks)
+        for p in range(self.n_pages):
+            assert self.refcount[p] == seen.get(p, 0), (p, self.refcount[p], seen.get(p, 0))
+            assert (p in free) == (self.refcount[p] == 0)
+        return True
+
+
+class PagePool:
+    """Page contents, stored sparsely: page id -> array [2 (K,V), Hkv, P, D]."""
+
+    def __init__(self, n_kv_heads, page_tokens, head_dim, dtype=np.float32):
+        self.shape = (2, n_kv_heads, page_tokens, head_dim)
+        self.dtype = dtype
+        self.data = {}
+
+    def page(self, p):
+        if p not in self.data:
+            self.data[p] = np.zeros(self.shape, self.dtype)
+        return self.data[p]
+
+    def copy_slots(self, src, dst, r):
+        self.page(dst)[:, :, :r, :] = self.page(src)[:, :, :r, :]
+
+    def write_token(self, page, slot, k_row, v_row):
+        pg = self.page(page)
+        pg[0, :, slot, :] = k_row
+        pg[1, :, slot, :] = v_row
+
+    def apply(self, cow, slots, k_new, v_new):
+        """Carry out a plan from KVFSModel.append: copies first, then the token rows
+        k_new/v_new [T, Hkv, D] in batch order."""
+        for src, dst, r in cow:
+            self.copy_slots(src, dst, r)
+        t = 0
+        for mine in slots:
+            for page, slot in mine:
+                self.write_token(page, slot, k_new[t], v_new[t])
+                t += 1
+        assert t == len(k_new)

@@ -1,0 +1,244 @@
+"""Pins for the oracle's attention (CPU only): brute force, closed forms, invariants and a
+library routine, chosen so that a dropped term, a wrong sign/index or a transposed operand
+in the oracle fails at least one of them."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.attention import dense_attention, gather_file, pred_batch
+from oracle.kvfs_model import KVFSModel, PagePool
+from oracle.driver import OracleSession, run_workload, widen
+from paper_2510_25412_amd import synth
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape).astype(np.float32)
+
+
+def brute_force(q, K, V, len_before):
+    """Triple-loop float64 evaluation of the definition, written independently."""
+    n, Hq, D = q.shape
+    N, Hkv, _ = K.shape
+    G = Hq // Hkv
+    out = np.zeros((n, Hq, D))
+    for i in range(n):
+        vis = len_before + i + 1
+        for h in range(Hq):
+            g = h // G
+            s = [sum(float(q[i, h, d]) * float(K[j, g, d]) for d in range(D)) / math.sqrt(D) for j in range(vis)]
+            mx = max(s)
+            w = [math.exp(x - mx) for x in s]
+            z = sum(w)
+            for d in range(D):
+                out[i, h, d] = sum(w[j] * float(V[j, g, d]) for j in range(vis)) / z
+    return out
+
+
+@pytest.mark.parametrize("n,L,Hq,Hkv,D", [(1, 0, 2, 2, 4), (1, 39, 4, 2, 8), (3, 17, 6, 3, 8), (5, 0, 4, 1, 4)])
+def test_brute_force(n, L, Hq, Hkv, D):
+    rng = np.random.default_rng(n * 100 + L)
+    q, K, V = _rand(rng, n, Hq, D), _rand(rng, L + n, Hkv, D), _rand(rng, L + n, Hkv, D)
+    ref = brute_force(q, K, V, L)
+    assert np.abs(dense_attention(q, K, V, L, dtype=np.float64) - ref).max() <= 1e-12
+    assert np.abs(dense_attention(q, K, V, L, dtype=np.float32) - ref).max() <= 1e-6
+
+
+def test_rows_sum_to_one_and_causal_zeroes():
+    rng = np.random.default_rng(3)
+    q, K, V = _rand(rng, 4, 8, 16), _rand(rng, 24, 2, 16), _rand(rng, 24, 2, 16)
+    _, p = dense_attention(q, K, V, 20, return_probs=True)
+    assert np.abs(p.sum(axis=-1) - 1).max() <= 1e-6
+    for i in range(4):
+        assert np.all(p[i, :, 20 + i + 1:] == 0) and np.all(p[i, :, :20 + i + 1] > 0)
+
+
+def test_closed_forms():
+    rng = np.random.default_rng(11)
+    Hq, Hkv, D, N = 8, 2, 16, 50
+    q, K, V = _rand(rng, 1, Hq, D), _rand(rng, N, Hkv, D), _rand(rng, N, Hkv, D)
+    G = Hq // Hkv
+    # (i) zero query -> plain mean of V per kv head
+    o = dense_attention(np.zeros_like(q), K, V, N - 1, dtype=np.float64)
+    for h in range(Hq):
+        assert np.abs(o[0, h] - V[:, h // G].astype(np.float64).mean(axis=0)).max() <= 1e-12
+    # (i') all K rows equal -> mean again
+    o = dense_attention(q, np.repeat(K[:1], N, axis=0), V, N - 1, dtype=np.float64)
+    assert np.abs(o[0, 3] - V[:, 3 // G].astype(np.float64).mean(axis=0)).max() <= 1e-12
+    # (ii) constant V -> that constant
+    c = _rand(rng, 1, Hkv, D)
+    o = dense_attention(q, K, np.repeat(c, N, axis=0), N - 1, dtype=np.float64)
+    for h in range(Hq):
+        assert np.abs(o[0, h] - c[0, h // G]).max() <= 1e-12
+    # (iii) single visible token -> its V row (empty file + one new token)
+    o = dense_attention(q, K[:1], V[:1], 0)
+    for h in range(Hq):
+        assert np.array_equal(o[0, h], V[0, h // G])
+    # (iv) one key aligned with q and scaled huge -> that token's V row
+    K2 = K.copy()
+    for g in range(Hkv):
+        K2[7, g] = 1e4 * q[0, g * G] / np.linalg.norm(q[0, g * G])
+    o = dense_attention(q, K2, V, N - 1, dtype=np.float64)
+    assert np.abs(o[0, 0] - V[7, 0]).max() <= 1e-9 and np.abs(o[0, G] - V[7, 1]).max() <= 1e-9
+    # (v) shifting every key by u changes all scores by q.u, which softmax ignores
+    u = _rand(rng, 1, Hkv, D)
+    a = dense_attention(q, K, V, N - 1, dtype=np.float64)
+    b = dense_attention(q, K.astype(np.float64) + u, V, N - 1, dtype=np.float64)   # shift applied exactly
+    assert np.abs(a - b).max() <= 1e-9
+    # (vi) two tokens, known logits: weights are the logistic function of the score gap
+    q1 = np.zeros((1, 1, 4), np.float32); q1[0, 0, 0] = 2.0
+    K1 = np.zeros((2, 1, 4), np.float32); K1[0, 0, 0] = 1.0; K1[1, 0, 0] = -1.0
+    V1 = np.zeros((2, 1, 4), np.float32); V1[0, 0, 1] = 1.0; V1[1, 0, 2] = 1.0
+    o = dense_attention(q1, K1, V1, 1, dtype=np.float64)      # scores +1, -1 after the 1/sqrt(4) scale
+    w0 = 1 / (1 + math.exp(-2.0))
+    assert abs(o[0, 0, 1] - w0) <= 1e-12 and abs(o[0, 0, 2] - (1 - w0)) <= 1e-12
+
+
+def test_gqa_mapping_is_consecutive_groups():
+    """Query head h reads kv head h // G: making kv head 1 special must move heads G..2G-1 only."""
+    rng = np.random.default_rng(5)
+    Hq, Hkv, D, N = 8, 4, 8, 12
+    q, K, V = _rand(rng, 1, Hq, D), _rand(rng, N, Hkv, D), _rand(rng, N, Hkv, D)
+    a = dense_attention(q, K, V, N - 1)
+    V2 = V.copy(); V2[:, 1] += 1.0
+    b = dense_attention(q, K, V2, N - 1)
+    changed = [h for h in range(Hq) if not np.array_equal(a[0, h], b[0, h])]
+    assert changed == [2, 3]
+    assert np.abs((b - a)[0, 2:4] - 1.0).max() <= 1e-5
+
+
+def test_library_special_case_sdpa():
+    """torch's scaled_dot_product_attention with KV heads repeated and an explicit mask."""
+    rng = np.random.default_rng(9)
+    n, L, Hq, Hkv, D = 6, 45, 8, 2, 32
+    q, K, V = _rand(rng, n, Hq, D), _rand(rng, L + n, Hkv, D), _rand(rng, L + n, Hkv, D)
+    G = Hq // Hkv
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    tv = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    mask = torch.arange(L + n)[None, :] <= (L + torch.arange(n))[:, None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    assert np.abs(dense_attention(q, K, V, L) - ref).max() <= 1e-5
+
+
+def test_contiguous_equals_paged_bit_identical():
+    """Gathering a file's pages gives back exactly the rows that were appended, so attention
+    on the gathered arrays is bit-identical to attention on the original contiguous arrays,
+    for any page placement."""
+    rng = np.random.default_rng(21)
+    Hq, Hkv, D, P = 4, 2, 8, 4
+    for order in (None, rng.permutation(32)):
+        m = KVFSModel(32, P, order)
+        pool = PagePool(Hkv, P, D)
+        h = m.kv_open()
+        K, V = _rand(rng, 23, Hkv, D), _rand(rng, 23, Hkv, D)
+        for lo, hi in ((0, 5), (5, 6), (6, 23)):          # appended in ragged pieces
+            cow, slots = m.append([(h, hi - lo)])
+            pool.apply(cow, slots, K[lo:hi], V[lo:hi])
+        Kg, Vg = gather_file(pool, m.kv_pages(h), 23)
+        assert np.array_equal(Kg, K) and np.array_equal(Vg, V)
+        q = _rand(rng, 1, Hq, D)
+        assert np.array_equal(dense_attention(q, Kg, Vg, 22), dense_attention(q, K, V, 22))
+
+
+def test_fork_cow_append_invariance():
+    """Outputs of forked files equal those of deep-copied unforked files, bit for bit; the
+    parent is unchanged by child activity.  Prefix 22 on pages of 4 forces a page copy."""
+    shape = synth.Shape(4, 2, 8, 4, synth.F32)
+    forked = synth.custom("forked", shape, [("new", 22), ("fork", 0, 0), ("fork", 0, 5), ("fork", 0, 9)],
+                          [(1, 1), (2, 1), (3, 2), (0, 1)], 64, seed=77)
+    out_f, s_f = run_workload(forked)
+    assert s_f.model.cow_copies == 3
+    # unforked twin: every child is its own file holding prefix + private suffix
+    ops = list(forked.setup_ops())
+    prefixKV = ops[1][2], ops[1][3]
+    s_u = OracleSession(shape, 64)
+    app = {op[1]: (op[2], op[3]) for op in ops if op[0] == "append"}
+    for fid in range(4):
+        s_u.setup([("open", fid), ("append", fid, prefixKV[0], prefixKV[1])])
+        if fid != 0 and fid in app:
+            s_u.setup([("append", fid, app[fid][0], app[fid][1])])
+    out_u = s_u.pred(forked.batch())
+    assert np.array_equal(out_f, out_u)
+    assert s_u.model.cow_copies == 0
+    # parent content untouched by the children: its gathered prefix is still the original
+    Kp, _ = gather_file(s_f.pool, s_f.model.kv_pages(s_f.h[0]), 22)
+    assert np.array_equal(Kp, prefixKV[0])
+    s_f.model.audit()
+
+
+def test_chunk_equals_sequential():
+    """One n-token pred equals n one-token preds (pins the in-chunk causal mask and the
+    append order)."""
+    rng = np.random.default_rng(31)
+    Hq, Hkv, D, P, L, n = 4, 2, 8, 4, 10, 7
+    K0, V0 = _rand(rng, L, Hkv, D), _rand(rng, L, Hkv, D)
+    q, kn, vn = _rand(rng, n, Hq, D), _rand(rng, n, Hkv, D), _rand(rng, n, Hkv, D)
+
+    def fresh():
+        m, pool = KVFSModel(16, P), PagePool(Hkv, P, D)
+        h = m.kv_open()
+        cow, slots = m.append([(h, L)])
+        pool.apply(cow, slots, K0, V0)
+        return m, pool, h
+    m, pool, h = fresh()
+    chunk = pred_batch(m, pool, [h], [n], q, kn, vn)
+    m2, pool2, h2 = fresh()
+    seq = np.concatenate([pred_batch(m2, pool2, [h2], [1], q[i:i + 1], kn[i:i + 1], vn[i:i + 1]) for i in range(n)])
+    assert np.abs(chunk - seq).max() <= 1e-6
+    assert m.kv_pages(h) == m2.kv_pages(h2) and m.kv_len(h) == L + n
+
+
+def test_token_permutation_invariance():
+    rng = np.random.default_rng(41)
+    q, K, V = _rand(rng, 1, 4, 8), _rand(rng, 30, 2, 8), _rand(rng, 30, 2, 8)
+    perm = rng.permutation(30)
+    a = dense_attention(q, K, V, 29, dtype=np.float64)
+    b = dense_attention(q, K[perm], V[perm], 29, dtype=np.float64)
+    assert np.abs(a - b).max() <= 1e-12
+
+
+def test_split_merge_identity():
+    """Log-sum-exp merge of partial results over any partition of the keys equals the
+    unsplit result (the identity the GPU's split over pages relies on)."""
+    rng = np.random.default_rng(51)
+    D, N = 8, 57
+    q, K, V = _rand(rng, 1, 1, D), _rand(rng, N, 1, D), _rand(rng, N, 1, D)
+    full = dense_attention(q, K, V, N - 1, dtype=np.float64)[0, 0]
+    cuts = [0, 3, 4, 30, 57]
+    m_i, l_i, acc_i = [], [], []
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        s = (K[lo:hi, 0].astype(np.float64) @ q[0, 0].astype(np.float64)) / math.sqrt(D)
+        m_i.append(s.max()); e = np.exp(s - s.max()); l_i.append(e.sum()); acc_i.append(e @ V[lo:hi, 0].astype(np.float64))
+    M = max(m_i)
+    l = sum(li * math.exp(mi - M) for li, mi in zip(l_i, m_i))
+    o = sum(ai * math.exp(mi - M) for ai, mi in zip(acc_i, m_i)) / l
+    assert np.abs(o - full).max() <= 1e-12
+
+
+def test_fp32_oracle_close_to_fp64():
+    wl = synth.config1()
+    a, _ = run_workload(wl, dtype=np.float32)
+    b, _ = run_workload(wl, dtype=np.float64)
+    assert np.abs(a - b).max() <= 2e-6
+
+
+def test_bf16_rounding_matches_torch():
+    x = np.random.default_rng(1).standard_normal(100000).astype(np.float32)
+    x[:4] = [1.00390625, 1.01171875, -0.0, 3.0e-39]      # exact ties (round to even) and tiny values
+    ours = synth.bf16_round(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, ref)
+    assert np.array_equal(widen(ours), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+    assert np.array_equal(synth.to_f32(ours), widen(ours))
+
+
+def test_workload_shapes():
+    wl = synth.config1()
+    assert [wl.lengths[f] for f in wl.batch_files] == [37, 80, 129, 200]
+    wl2 = synth.config2()
+    L = np.array([wl2.lengths[f] for f in wl2.batch_files])
+    assert len(L) == 64 and L.min() >= 512 and L.max() <= 4096
+    b1, b2 = synth.config1().batch(), synth.config1().batch()
+    assert np.array_equal(b1["q"], b2["q"]) and np.array_equal(b1["k_new"], b2["k_new"])
