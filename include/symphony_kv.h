@@ -1,0 +1,189 @@
+/* symphony_kv.h — C ABI of libsymphony_kv.so
+ *
+ * The data-parallel hot path behind Symphony's `pred` system call (paper section 4.1) on one
+ * MI355X: a KV-cache file system whose files are lists of fixed-size pages of GPU memory
+ * (paper section 4.2, "KVFS"), copy-on-write forks of those files, and ONE batched launch
+ * that appends the new tokens' K/V rows of many LIPs and computes attention for every new
+ * token through the per-file page tables (the batch that the inference scheduler of paper
+ * section 4.4 forms from the pending `pred` calls).
+ *
+ * Conventions
+ *  - Every function returns an int status unless stated: 0 = SYM_OK, negative = error.
+ *    On any error the host state is unchanged (all-or-nothing).  No exception or abort
+ *    crosses this boundary.  sym_strerror() returns the last message of the context.
+ *  - "device" pointers are HIP device memory owned by the CALLER (e.g. a torch tensor's
+ *    data_ptr()).  The library allocates no device memory, never synchronises `stream`
+ *    and enqueues all device work on the `stream` argument (a hipStream_t passed as
+ *    void*; NULL = the default stream).  All calls on one context must be issued on one
+ *    stream, or be ordered by the caller: the descriptor area of the workspace is reused
+ *    from call to call in stream order.
+ *  - "host" pointers are ordinary host memory, read (or written) before the call returns.
+ *  - One mutex per context makes calls thread-safe; a context created with device = -1
+ *    is host-only: file-system state and descriptors work, device calls return SYM_EINVAL.
+ *
+ * Page layout (internal; parity is defined on outputs and page ids, not on pool bytes):
+ *    page = [n_kv_heads][2 (K, V)][row_halves][page_tokens][row_bytes / row_halves],
+ *  row_bytes = head_dim * sizeof(element) = 256, row_halves = 2: each 256-byte K or V row
+ *  of a token is stored as two 128-byte halves, all first halves of the page's tokens
+ *  contiguous, then all second halves, so that 8 consecutive tokens of one half form one
+ *  contiguous 1 KiB run = one 64-lane x 16-byte load.
+ */
+#ifndef SYMPHONY_KV_H
+#define SYMPHONY_KV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SYM_OK      0
+#define SYM_EINVAL (-1)  /* bad argument / unsupported shape                         */
+#define SYM_EBADF  (-2)  /* stale or unknown file handle                             */
+#define SYM_ENOSPC (-3)  /* page pool (or workspace) too small for the request       */
+#define SYM_ENOENT (-4)
+#define SYM_EEXIST (-5)
+#define SYM_EBUSY  (-6)  /* same file twice in one batch (stand-in for the write lock
+                            of paper section 4.2)                                    */
+#define SYM_EHIP   (-7)  /* a HIP runtime call failed                                */
+
+#define SYM_F32  0
+#define SYM_BF16 1
+
+typedef struct sym_ctx sym_ctx;   /* opaque; owns host metadata and pinned staging only */
+typedef int32_t sym_kv;           /* file handle >= 0; the lowest free slot is reused   */
+
+typedef struct sym_config {
+  int32_t n_q_heads;       /* Hq                                                         */
+  int32_t n_kv_heads;      /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv)   */
+  int32_t head_dim;        /* D; D * sizeof(element) must be 256 (bf16: 128, f32: 64)    */
+  int32_t page_tokens;     /* P = 16                                                     */
+  int32_t dtype;           /* SYM_F32 or SYM_BF16: storage type of Q, K, V               */
+  int32_t device;          /* HIP device ordinal, or -1 for a host-only context          */
+  int64_t n_pages;         /* pages in the pool; page ids are int32, n_pages < 2^27      */
+  void*   pool;            /* device, n_pages * sym_page_bytes() bytes, 256-aligned      */
+  void*   workspace;       /* device scratch: descriptors + partial results              */
+  int64_t workspace_bytes;
+  const int32_t* free_order; /* host, optional permutation of [0,n_pages): allocation
+                              ranking (the free page of lowest rank is taken first);
+                              NULL = identity.  Copied by sym_init.                      */
+  float   softmax_scale;   /* 0 = 1/sqrt(D)                                              */
+  int32_t decode_waves;    /* wavefront slots the decode kernel is cut into; 0 = auto    */
+} sym_config;
+
+typedef struct sym_stats {
+  int64_t pages_total, pages_free, pages_shared;  /* shared = reference count > 1        */
+  int64_t cow_copies, pages_allocated, tokens_appended;
+  int64_t pred_batches, kernel_launches;
+  int64_t files, handles;
+} sym_stats;
+
+/* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).
+ * sym_workspace_bytes: a workspace size sufficient for any batch with at most max_lips
+ * files, max_tokens new tokens in total and max_table_entries page-table entries summed
+ * over the batch's files (after the append). */
+int64_t sym_page_bytes(const sym_config* cfg);
+int64_t sym_workspace_bytes(const sym_config* cfg, int64_t max_lips, int64_t max_tokens,
+                            int64_t max_table_entries);
+
+int  sym_init(const sym_config* cfg, sym_ctx** out);
+void sym_destroy(sym_ctx* ctx);
+const char* sym_strerror(sym_ctx* ctx);   /* valid until the next call on ctx */
+
+/* ---- KVFS: the file calls of the paper's Fig. 1 and section 4.2 -------------------- */
+/* kv_open: name NULL = new anonymous empty file; otherwise open the file of that name,
+ * creating it empty if absent; a second open of a name returns a second handle to the SAME
+ * file (files are shared, section 4.2).  Returns a handle >= 0 or a negative status.     */
+sym_kv  sym_kv_open(sym_ctx* ctx, const char* name);
+/* kv_fork: new anonymous file with a copy of the parent's page list; every page's
+ * reference count goes up by one; no tensor is copied, no page allocated, no device work
+ * ("without duplicating the actual tensors", section 4.2).                               */
+sym_kv  sym_kv_fork(sym_ctx* ctx, sym_kv parent);
+/* kv_remove: delete the file: every page's count goes down by one, pages reaching zero
+ * return to the free set; all handles of the file become invalid (Fig. 1).               */
+int     sym_kv_remove(sym_ctx* ctx, sym_kv kv);
+/* kv_close: drop this handle.  A named file persists (section 4.2: files outlive a
+ * process); an anonymous file with no handle left is removed.                            */
+int     sym_kv_close(sym_ctx* ctx, sym_kv kv);
+/* Token count of the file (Fig. 1 `.len()`), or a negative status.                       */
+int64_t sym_kv_len(sym_ctx* ctx, sym_kv kv);
+/* kv_append: the "file is updated with new tensors" half of pred (section 4.1) on its own:
+ * append n >= 1 token rows.  k, v: device, [n][Hkv][D] in the storage dtype.  Allocates
+ * pages as needed; a shared, partly filled last page is first copied (copy-on-write).    */
+int     sym_kv_append(sym_ctx* ctx, sym_kv kv, int32_t n, const void* k, const void* v,
+                      void* stream);
+
+/* ---- pred (section 4.1), batched (section 4.4) ------------------------------------- */
+/* One launch for n_lips pending pred calls.  LIP b appends n_tokens[b] >= 1 rows to file
+ * kv[b] (files distinct, else SYM_EBUSY) and gets one output row per new token: row i of
+ * LIP b attends to file tokens 0 .. len_before_b + i (the whole existing file plus the new
+ * tokens up to itself).  T = sum n_tokens.  q: device [T][Hq][D]; k_new, v_new: device
+ * [T][Hkv][D] (storage dtype, LIPs in batch order); out: device [T][Hq][D] float32.
+ * kv, n_tokens: host.  If the pool cannot hold the batch: SYM_ENOSPC, nothing changes.   */
+int sym_pred_batch(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
+                   const void* q, const void* k_new, const void* v_new, float* out,
+                   void* stream);
+
+/* Kernel-level entry without the allocator: attention only, over page tables the caller
+ * supplies.  K/V of every token (new ones included) must already be in the pool.
+ * page_table_flat: host int32, LIP b's page ids at [pt_offsets[b], pt_offsets[b+1]);
+ * lengths: host int64 [n_lips], tokens of the file INCLUDING this call's n_tokens[b] new
+ * ones; row i of LIP b sees lengths[b] - n_tokens[b] + i + 1 tokens.                      */
+int sym_pred_batch_raw(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
+                       const int32_t* page_table_flat, const int64_t* pt_offsets,
+                       const int64_t* lengths, const void* q, float* out, void* stream);
+
+/* ---- introspection: integer state, compared bit for bit with the oracle's model ----- */
+int64_t sym_kv_pages(sym_ctx* ctx, sym_kv kv, int32_t* out, int64_t cap); /* returns count */
+int32_t sym_page_refcount(sym_ctx* ctx, int32_t page);                    /* < 0 = error   */
+int64_t sym_free_pages(sym_ctx* ctx);
+int     sym_get_stats(sym_ctx* ctx, sym_stats* out);
+
+/* The host half of sym_pred_batch alone (usable in a host-only context): plans AND COMMITS
+ * the append of the batch (page allocation, copy-on-write decisions) and returns the plan:
+ *   cow_out   [3 * cow_cap]  (src page, dst page, slots to copy) per copy, in batch order
+ *   slots_out [T]            destination of each new token as page * P + slot
+ * *n_cow receives the number of copies.  Either output may be NULL.                      */
+int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
+                    int32_t* cow_out, int64_t cow_cap, int32_t* n_cow, int32_t* slots_out);
+
+/* The packed descriptor of the attention launch for a batch given by page tables (same
+ * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.
+ * Layout: words[0..15] = header {n_rows, n_waves, n_partials, n_dec_rows, n_tiles, then
+ * word offsets of the sections: rows, wave_work, merge_off, page_table, pt_off, tiles},
+ * then the sections.  Returns the number of words (or a negative status); writes at most
+ * cap words.                                                                              */
+int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
+                       const int32_t* page_table_flat, const int64_t* pt_offsets,
+                       const int64_t* lengths, int32_t* words_out, int64_t cap);
+
+/* Test/debug aid: gather tokens [start, start+n) of a file from the pool into contiguous
+ * device arrays k_out, v_out [n][Hkv][D] (storage dtype).                                */
+int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out,
+                void* stream);
+
+/* ---- measurement ------------------------------------------------------------------- */
+/* Kernel ids for sym_profile_read. */
+#define SYM_K_COW     0
+#define SYM_K_APPEND  1
+#define SYM_K_DECODE  2
+#define SYM_K_MERGE   3
+#define SYM_K_PREFILL 4
+#define SYM_K_COUNT   5
+/* sym_profile_enable(mask): bit k of mask set = every launch of kernel id k is bracketed by
+ * HIP events on the launch stream (at most 4096 launches are kept per kernel id, later ones
+ * are not timed); mask 0 = off.
+ * sym_profile_read synchronises on the recorded events and returns the summed duration in
+ * milliseconds and the number of timed launches of one kernel id, then forgets them.     */
+int sym_profile_enable(sym_ctx* ctx, int mask);
+int sym_profile_read(sym_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
+
+/* Calibration kernels of known traffic: a streaming read of `bytes` bytes (sum written to
+ * out8, 8 bytes) and a plain copy dst <- src.  bytes must be a multiple of 16.           */
+int sym_calib_read(const void* src, int64_t bytes, void* out8, void* stream);
+int sym_calib_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYMPHONY_KV_H */

@@ -1,0 +1,248 @@
+"""ctypes binding of libsymphony_kv.so: same names as the C ABI (include/symphony_kv.h),
+argument marshalling only.  torch supplies device memory and streams; nothing is computed
+here.  Loading fails loudly if the library has not been built: there is no fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
+
+SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
+SYM_F32, SYM_BF16 = 0, 1
+K_COW, K_APPEND, K_DECODE, K_MERGE, K_PREFILL = 0, 1, 2, 3, 4
+
+
+class SymConfig(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_tokens", C.c_int32), ("dtype", C.c_int32), ("device", C.c_int32),
+                ("n_pages", C.c_int64), ("pool", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_int64), ("free_order", C.POINTER(C.c_int32)),
+                ("softmax_scale", C.c_float), ("decode_waves", C.c_int32)]
+
+
+class SymStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("pages_total", "pages_free", "pages_shared", "cow_copies", "pages_allocated",
+                                         "tokens_appended", "pred_batches", "kernel_launches", "files", "handles")]
+
+
+class SymError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"symphony_kv error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+_I32P, _I64P = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+
+_SIGNATURES = {
+    "sym_page_bytes": (C.c_int64, [C.POINTER(SymConfig)]),
+    "sym_workspace_bytes": (C.c_int64, [C.POINTER(SymConfig), C.c_int64, C.c_int64, C.c_int64]),
+    "sym_init": (C.c_int, [C.POINTER(SymConfig), C.POINTER(C.c_void_p)]),
+    "sym_destroy": (None, [C.c_void_p]),
+    "sym_strerror": (C.c_char_p, [C.c_void_p]),
+    "sym_kv_open": (C.c_int32, [C.c_void_p, C.c_char_p]),
+    "sym_kv_fork": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "sym_kv_remove": (C.c_int, [C.c_void_p, C.c_int32]),
+    "sym_kv_close": (C.c_int, [C.c_void_p, C.c_int32]),
+    "sym_kv_len": (C.c_int64, [C.c_void_p, C.c_int32]),
+    "sym_kv_append": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_pred_batch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_kv_pages": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, C.c_int64]),
+    "sym_page_refcount": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "sym_free_pages": (C.c_int64, [C.c_void_p]),
+    "sym_get_stats": (C.c_int, [C.c_void_p, C.POINTER(SymStats)]),
+    "sym_plan_append": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_int64, _I32P, _I32P]),
+    "sym_build_desc": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, _I32P, C.c_int64]),
+    "sym_kv_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "sym_profile_read": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), _I64P]),
+    "sym_calib_read": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "sym_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
+}
+
+
+def load():
+    """Loads the C-ABI library (once).  Raises if it is missing or lacks a declared symbol."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python __graft_entry__.py` (hipcc, gfx950) first")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)          # AttributeError if the symbol is missing
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, np.int32)
+    return a, a.ctypes.data_as(_I32P)
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, np.int64)
+    return a, a.ctypes.data_as(_I64P)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def make_config(n_q_heads, n_kv_heads, head_dim, page_tokens, dtype, n_pages, device=-1, pool=None, workspace=None,
+                workspace_bytes=0, free_order=None, softmax_scale=0.0, decode_waves=0):
+    cfg = SymConfig()
+    cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_tokens = n_q_heads, n_kv_heads, head_dim, page_tokens
+    cfg.dtype = {"f32": SYM_F32, "bf16": SYM_BF16}.get(dtype, dtype)
+    cfg.device, cfg.n_pages = device, n_pages
+    cfg.pool, cfg.workspace, cfg.workspace_bytes = _ptr(pool), _ptr(workspace), workspace_bytes
+    keep = None
+    if free_order is not None:
+        keep, p = _i32(free_order)
+        cfg.free_order = p
+    cfg.softmax_scale, cfg.decode_waves = softmax_scale, decode_waves
+    cfg._keep = keep
+    return cfg
+
+
+def page_bytes(cfg):
+    return load().sym_page_bytes(C.byref(cfg))
+
+
+def workspace_bytes(cfg, max_lips, max_tokens, max_table_entries):
+    return load().sym_workspace_bytes(C.byref(cfg), max_lips, max_tokens, max_table_entries)
+
+
+class Context:
+    """One sym_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, cfg):
+        self.lib = load()
+        self.cfg = cfg
+        h = C.c_void_p()
+        rc = self.lib.sym_init(C.byref(cfg), C.byref(h))
+        if rc != SYM_OK:
+            raise SymError(rc, "sym_init failed")
+        self.h = h
+
+    def close(self):
+        if self.h:
+            self.lib.sym_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, rc):
+        if rc < 0:
+            raise SymError(rc, self.lib.sym_strerror(self.h).decode())
+        return rc
+
+    # ---- KVFS ----
+    def kv_open(self, name=None):
+        return self._chk(self.lib.sym_kv_open(self.h, None if name is None else name.encode()))
+
+    def kv_fork(self, parent):
+        return self._chk(self.lib.sym_kv_fork(self.h, parent))
+
+    def kv_remove(self, kv):
+        self._chk(self.lib.sym_kv_remove(self.h, kv))
+
+    def kv_close(self, kv):
+        self._chk(self.lib.sym_kv_close(self.h, kv))
+
+    def kv_len(self, kv):
+        return self._chk(self.lib.sym_kv_len(self.h, kv))
+
+    def kv_append(self, kv, n, k, v, stream=None):
+        self._chk(self.lib.sym_kv_append(self.h, kv, n, _ptr(k), _ptr(v), stream))
+
+    # ---- pred ----
+    def pred_batch(self, kv, n_tokens, q, k_new, v_new, out, stream=None):
+        kv_a, kv_p = _i32(kv)
+        nt_a, nt_p = _i32(n_tokens)
+        self._chk(self.lib.sym_pred_batch(self.h, len(kv_a), kv_p, nt_p, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream))
+
+    def pred_batch_raw(self, n_tokens, page_table_flat, pt_offsets, lengths, q, out, stream=None):
+        nt_a, nt_p = _i32(n_tokens)
+        pt_a, pt_p = _i32(page_table_flat)
+        po_a, po_p = _i64(pt_offsets)
+        ln_a, ln_p = _i64(lengths)
+        self._chk(self.lib.sym_pred_batch_raw(self.h, len(nt_a), nt_p, pt_p, po_p, ln_p, _ptr(q), _ptr(out), stream))
+
+    # ---- introspection ----
+    def kv_pages(self, kv):
+        n = self._chk(self.lib.sym_kv_pages(self.h, kv, None, 0))
+        out = np.zeros(max(n, 1), np.int32)
+        self._chk(self.lib.sym_kv_pages(self.h, kv, out.ctypes.data_as(_I32P), n))
+        return out[:n].tolist()
+
+    def page_refcount(self, page):
+        return self._chk(self.lib.sym_page_refcount(self.h, page))
+
+    def free_pages(self):
+        return self._chk(self.lib.sym_free_pages(self.h))
+
+    def get_stats(self):
+        s = SymStats()
+        self._chk(self.lib.sym_get_stats(self.h, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in SymStats._fields_}
+
+    def plan_append(self, kv, n_tokens):
+        kv_a, kv_p = _i32(kv)
+        nt_a, nt_p = _i32(n_tokens)
+        cow = np.zeros(3 * max(len(kv_a), 1), np.int32)
+        slots = np.zeros(max(int(nt_a.sum()) if len(nt_a) else 0, 1), np.int32)
+        n_cow = C.c_int32(0)
+        self._chk(self.lib.sym_plan_append(self.h, len(kv_a), kv_p, nt_p, cow.ctypes.data_as(_I32P), len(kv_a),
+                                           C.byref(n_cow), slots.ctypes.data_as(_I32P)))
+        T = int(nt_a.sum())
+        return [tuple(int(x) for x in cow[3 * i:3 * i + 3]) for i in range(n_cow.value)], slots[:T].copy()
+
+    def build_desc(self, n_tokens, page_table_flat, pt_offsets, lengths):
+        nt_a, nt_p = _i32(n_tokens)
+        pt_a, pt_p = _i32(page_table_flat)
+        po_a, po_p = _i64(pt_offsets)
+        ln_a, ln_p = _i64(lengths)
+        n = self._chk(self.lib.sym_build_desc(self.h, len(nt_a), nt_p, pt_p, po_p, ln_p, None, 0))
+        out = np.zeros(n, np.int32)
+        self._chk(self.lib.sym_build_desc(self.h, len(nt_a), nt_p, pt_p, po_p, ln_p, out.ctypes.data_as(_I32P), n))
+        return out
+
+    def kv_read(self, kv, start, n, k_out, v_out, stream=None):
+        self._chk(self.lib.sym_kv_read(self.h, kv, start, n, _ptr(k_out), _ptr(v_out), stream))
+
+    # ---- measurement ----
+    def profile_enable(self, mask):
+        """mask: bit k = time kernel id k (K_DECODE ...); 0 = off."""
+        self._chk(self.lib.sym_profile_enable(self.h, int(mask)))
+
+    def profile_read(self, kernel_id):
+        ms, n = C.c_double(0), C.c_int64(0)
+        self._chk(self.lib.sym_profile_read(self.h, kernel_id, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+
+def calib_read(src, nbytes, out8, stream=None):
+    rc = load().sym_calib_read(_ptr(src), nbytes, _ptr(out8), stream)
+    if rc:
+        raise SymError(rc, "calib_read")
+
+
+def calib_copy(dst, src, nbytes, stream=None):
+    rc = load().sym_calib_copy(_ptr(dst), _ptr(src), nbytes, stream)
+    if rc:
+        raise SymError(rc, "calib_copy")

@@ -1,0 +1,554 @@
+// C ABI of libsymphony_kv.so (declared in include/symphony_kv.h): glue between the host
+// file-system state, the batch-descriptor builder and the HIP kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/symphony_kv.h"
+#include "desc.hpp"
+#include "kernels.hpp"
+#include "kvfs.hpp"
+
+using namespace symkv;
+
+namespace {
+constexpr int kStages = 4;          // pinned staging buffers in rotation
+constexpr int kMaxTimed = 4096;     // timed launches kept per kernel id
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  return (s && *s) ? std::atoi(s) : dflt;
+}
+}  // namespace
+
+struct sym_ctx {
+  sym_config cfg;
+  int32_t G = 1;
+  int64_t page_bytes = 0;
+  float scale_log2e = 0.f;
+  int32_t max_waves = 0, min_units = 4;
+  std::mutex mu;
+  std::string err;
+  Kvfs* fs = nullptr;
+  AppendPlan plan;
+  BatchDesc desc;
+  std::vector<const int32_t*> tables;
+  std::vector<int64_t> len_after;
+  std::vector<int32_t> scratch_words;
+  // pinned staging ring (device contexts only)
+  int32_t* stage[kStages] = {nullptr, nullptr, nullptr, nullptr};
+  int64_t stage_words[kStages] = {0, 0, 0, 0};
+  hipEvent_t stage_ev[kStages];
+  bool stage_pending[kStages] = {false, false, false, false};
+  int stage_next = 0;
+  // profiling
+  int prof_mask = 0;
+  std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
+  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0, 0};
+  // counters
+  int64_t pred_batches = 0, kernel_launches = 0;
+};
+
+namespace {
+
+int fail(sym_ctx* c, int code, const std::string& msg) {
+  c->err = msg;
+  return code;
+}
+int fail_hip(sym_ctx* c, hipError_t e, const char* what) {
+  c->err = std::string(what) + ": " + hipGetErrorString(e);
+  return SYM_EHIP;
+}
+
+bool shape_ok(const sym_config* cfg) {
+  if (!cfg) return false;
+  const int es = cfg->dtype == SYM_F32 ? 4 : cfg->dtype == SYM_BF16 ? 2 : 0;
+  if (es == 0 || cfg->head_dim * es != 256 || cfg->page_tokens != 16) return false;
+  if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return false;
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  return G == 1 || G == 2 || G == 4 || G == 8;
+}
+
+// 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
+int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
+  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * WAVE_WORDS + T * c->cfg.n_kv_heads + 1 + entries +
+         n_lips + 1 + 3 * n_lips + T + 64;
+}
+int64_t partial_bytes(const sym_ctx* c) {
+  // a wave boundary cuts at most one (row, head) range: <= 2 partial pieces per wave
+  const int64_t np = 2 * (int64_t)c->max_waves + 1;
+  return align_up(np * c->G * 2 * 4, 256) + align_up(np * c->G * c->cfg.head_dim * 4, 256);
+}
+
+// Reserve the next pinned staging buffer with room for `words`; waits for the copy that last used it.
+int stage_acquire(sym_ctx* c, int64_t words, int* idx) {
+  const int i = c->stage_next;
+  c->stage_next = (i + 1) % kStages;
+  if (c->stage_pending[i]) {
+    hipError_t e = hipEventSynchronize(c->stage_ev[i]);
+    if (e != hipSuccess) return fail_hip(c, e, "hipEventSynchronize(stage)");
+    c->stage_pending[i] = false;
+  }
+  if (c->stage_words[i] < words) {
+    if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+    c->stage[i] = nullptr;
+    c->stage_words[i] = 0;
+    const int64_t cap = std::max<int64_t>(words * 3 / 2, 1 << 16);
+    hipError_t e = hipHostMalloc((void**)&c->stage[i], (size_t)cap * 4, hipHostMallocDefault);
+    if (e != hipSuccess) return fail_hip(c, e, "hipHostMalloc(stage)");
+    c->stage_words[i] = cap;
+  }
+  *idx = i;
+  return SYM_OK;
+}
+
+int stage_submit(sym_ctx* c, int i, int64_t words, hipStream_t st) {
+  hipError_t e = hipMemcpyAsync(c->cfg.workspace, c->stage[i], (size_t)words * 4, hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return fail_hip(c, e, "hipMemcpyAsync(descriptor)");
+  e = hipEventRecord(c->stage_ev[i], st);
+  if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
+  c->stage_pending[i] = true;
+  return SYM_OK;
+}
+
+struct Timed {
+  sym_ctx* c;
+  int id;
+  hipStream_t st;
+  bool on;
+  Timed(sym_ctx* ctx, int kid, hipStream_t s) : c(ctx), id(kid), st(s), on(false) {
+    ++c->kernel_launches;
+    if (!((c->prof_mask >> id) & 1) || c->ev_used[id] >= kMaxTimed) return;
+    if ((int)c->ev_start[id].size() <= c->ev_used[id]) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
+        return;
+      }
+      c->ev_start[id].push_back(a);
+      c->ev_stop[id].push_back(b);
+    }
+    on = hipEventRecord(c->ev_start[id][c->ev_used[id]], st) == hipSuccess;
+  }
+  ~Timed() {
+    if (on && hipEventRecord(c->ev_stop[id][c->ev_used[id]], st) == hipSuccess) ++c->ev_used[id];
+  }
+};
+
+// Device pointers of the sections of the blob that sits at the start of the workspace.
+struct BlobView {
+  const int32_t* words;
+  int64_t desc_words, cow_off, slots_off, total_words;
+};
+
+// Launches attention (decode + merge) for the descriptor in c->desc, already copied to the workspace.
+int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, hipStream_t st) {
+  const BatchDesc& d = c->desc;
+  if (d.n_waves == 0) return SYM_OK;
+  const int32_t* dw = (const int32_t*)c->cfg.workspace;
+  uint8_t* base = (uint8_t*)c->cfg.workspace + align_up(blob_words * 4, 256);
+  const int64_t np = 2 * (int64_t)c->max_waves + 1;
+  float* part_ml = (float*)base;
+  float* part_acc = (float*)(base + align_up(np * c->G * 2 * 4, 256));
+  DecodeArgs a;
+  a.pool = (const uint8_t*)c->cfg.pool;
+  a.page_bytes = c->page_bytes;
+  a.q = q;
+  a.out = out;
+  a.part_acc = part_acc;
+  a.part_ml = part_ml;
+  a.rows = dw + d.words[H_OFF_ROWS];
+  a.waves = dw + d.words[H_OFF_WAVES];
+  a.pt = dw + d.words[H_OFF_PT];
+  a.ptoff = dw + d.words[H_OFF_PTOFF];
+  a.n_waves = d.n_waves;
+  a.Hq = c->cfg.n_q_heads;
+  a.Hkv = c->cfg.n_kv_heads;
+  a.scale_log2e = c->scale_log2e;
+  {
+    Timed t(c, SYM_K_DECODE, st);
+    hipError_t e = launch_decode(a, c->cfg.dtype, st);
+    if (e != hipSuccess) return fail_hip(c, e, "decode launch");
+  }
+  if (d.n_partials > 0) {
+    MergeArgs m;
+    m.part_acc = part_acc;
+    m.part_ml = part_ml;
+    m.merge_off = dw + d.words[H_OFF_MERGE];
+    m.rows = a.rows;
+    m.out = out;
+    m.Hq = a.Hq;
+    m.Hkv = a.Hkv;
+    m.D = c->cfg.head_dim;
+    Timed t(c, SYM_K_MERGE, st);
+    hipError_t e = launch_merge(m, d.n_rows, st);
+    if (e != hipSuccess) return fail_hip(c, e, "merge launch");
+  }
+  return SYM_OK;
+}
+
+// cow + append kernels for the plan in c->plan whose words sit at cow_off / slots_off of the blob.
+int launch_append_plan(sym_ctx* c, int64_t cow_off, int64_t slots_off, const void* k, const void* v, hipStream_t st) {
+  const int32_t* dw = (const int32_t*)c->cfg.workspace;
+  const int n_cow = (int)(c->plan.cow.size() / 3);
+  if (n_cow > 0) {
+    CowArgs ca{(uint8_t*)c->cfg.pool, c->page_bytes, dw + cow_off, c->cfg.n_kv_heads};
+    Timed t(c, SYM_K_COW, st);
+    hipError_t e = launch_cow(ca, n_cow, st);
+    if (e != hipSuccess) return fail_hip(c, e, "cow launch");
+  }
+  AppendArgs aa{(uint8_t*)c->cfg.pool, c->page_bytes, k, v, dw + slots_off, (int32_t)c->plan.slots.size(), c->cfg.n_kv_heads};
+  Timed t(c, SYM_K_APPEND, st);
+  hipError_t e = launch_append(aa, st);
+  if (e != hipSuccess) return fail_hip(c, e, "append launch");
+  return SYM_OK;
+}
+
+// Builds c->desc from caller-supplied page tables (lock held).  Returns words or a negative status.
+int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
+                       const int64_t* pt_offsets, const int64_t* lengths) {
+  c->tables.resize(n_lips);
+  for (int32_t b = 0; b < n_lips; ++b) {
+    if (lengths[b] < 1) return fail(c, SYM_EINVAL, "length must be >= 1");
+    const int64_t np = (lengths[b] + c->cfg.page_tokens - 1) / c->cfg.page_tokens;
+    if (pt_offsets[b + 1] - pt_offsets[b] < np) return fail(c, SYM_EINVAL, "page table shorter than the length needs");
+    c->tables[b] = page_table_flat + pt_offsets[b];
+    for (int64_t i = 0; i < np; ++i)
+      if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
+  }
+  DescParams prm{c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units};
+  const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
+  if (rc) return fail(c, rc, "build_desc: bad batch");
+  return (int64_t)c->desc.words.size();
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t sym_page_bytes(const sym_config* cfg) {
+  if (!shape_ok(cfg)) return 0;
+  return (int64_t)cfg->n_kv_heads * 2 * cfg->page_tokens * 256;
+}
+
+int64_t sym_workspace_bytes(const sym_config* cfg, int64_t max_lips, int64_t max_tokens, int64_t max_table_entries) {
+  if (!shape_ok(cfg)) return 0;
+  sym_ctx tmp;
+  tmp.cfg = *cfg;
+  tmp.G = cfg->n_q_heads / cfg->n_kv_heads;
+  tmp.max_waves = cfg->decode_waves > 0 ? cfg->decode_waves : 8192;
+  return align_up(blob_words_bound(&tmp, max_lips, max_tokens, max_table_entries) * 4, 256) + partial_bytes(&tmp) + 256;
+}
+
+int sym_init(const sym_config* cfg, sym_ctx** out) {
+  if (!out) return SYM_EINVAL;
+  *out = nullptr;
+  if (!shape_ok(cfg) || cfg->n_pages < 1 || cfg->n_pages >= (1LL << 27)) return SYM_EINVAL;
+  if (cfg->device >= 0 && (!cfg->pool || !cfg->workspace || cfg->workspace_bytes < 4096)) return SYM_EINVAL;
+  if (cfg->free_order) {   // must be a permutation
+    std::vector<uint8_t> seen((size_t)cfg->n_pages, 0);
+    for (int64_t i = 0; i < cfg->n_pages; ++i) {
+      const int32_t p = cfg->free_order[i];
+      if (p < 0 || p >= cfg->n_pages || seen[p]) return SYM_EINVAL;
+      seen[p] = 1;
+    }
+  }
+  sym_ctx* c = new sym_ctx();
+  c->cfg = *cfg;
+  c->cfg.free_order = nullptr;
+  c->G = cfg->n_q_heads / cfg->n_kv_heads;
+  c->page_bytes = sym_page_bytes(cfg);
+  const float scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  c->scale_log2e = scale * 1.4426950408889634f;
+  c->fs = new Kvfs(cfg->n_pages, cfg->page_tokens, cfg->free_order);
+  c->max_waves = cfg->decode_waves > 0 ? cfg->decode_waves : 2048;
+  if (cfg->device >= 0) {
+    hipError_t e = hipSetDevice(cfg->device);
+    int cus = 0;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device);
+    for (int i = 0; i < kStages && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      delete c->fs;
+      delete c;
+      return SYM_EHIP;
+    }
+    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * 8;   // two waves per SIMD
+  }
+  c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
+  c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
+  if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
+    sym_destroy(c);
+    return SYM_ENOSPC;
+  }
+  *out = c;
+  return SYM_OK;
+}
+
+void sym_destroy(sym_ctx* c) {
+  if (!c) return;
+  if (c->cfg.device >= 0) {
+    for (int i = 0; i < kStages; ++i) {
+      if (c->stage_pending[i]) (void)hipEventSynchronize(c->stage_ev[i]);
+      if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+      (void)hipEventDestroy(c->stage_ev[i]);
+    }
+    for (int k = 0; k < SYM_K_COUNT; ++k)
+      for (size_t i = 0; i < c->ev_start[k].size(); ++i) {
+        (void)hipEventDestroy(c->ev_start[k][i]);
+        (void)hipEventDestroy(c->ev_stop[k][i]);
+      }
+  }
+  delete c->fs;
+  delete c;
+}
+
+const char* sym_strerror(sym_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+sym_kv sym_kv_open(sym_ctx* c, const char* name) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->fs->open(name);
+}
+
+sym_kv sym_kv_fork(sym_ctx* c, sym_kv parent) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int32_t h = c->fs->fork(parent);
+  if (h < 0) c->err = "kv_fork: bad handle";
+  return h;
+}
+
+int sym_kv_remove(sym_ctx* c, sym_kv kv) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int rc = c->fs->remove(kv);
+  if (rc) c->err = "kv_remove: bad handle";
+  return rc;
+}
+
+int sym_kv_close(sym_ctx* c, sym_kv kv) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int rc = c->fs->close(kv);
+  if (rc) c->err = "kv_close: bad handle";
+  return rc;
+}
+
+int64_t sym_kv_len(sym_ctx* c, sym_kv kv) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->fs->len(kv);
+}
+
+int64_t sym_kv_pages(sym_ctx* c, sym_kv kv, int32_t* out, int64_t cap) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const KvFile* f = c->fs->file_of(kv);
+  if (!f) return fail(c, SYM_EBADF, "kv_pages: bad handle");
+  const int64_t n = (int64_t)f->pages.size();
+  if (out) std::memcpy(out, f->pages.data(), (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
+  return n;
+}
+
+int32_t sym_page_refcount(sym_ctx* c, int32_t page) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->fs->refcount(page);
+}
+
+int64_t sym_free_pages(sym_ctx* c) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->fs->free_pages();
+}
+
+int sym_get_stats(sym_ctx* c, sym_stats* s) {
+  if (!c || !s) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  s->pages_total = c->fs->n_pages();
+  s->pages_free = c->fs->free_pages();
+  s->pages_shared = c->fs->count_shared();
+  s->cow_copies = c->fs->cow_copies;
+  s->pages_allocated = c->fs->pages_allocated;
+  s->tokens_appended = c->fs->tokens_appended;
+  s->pred_batches = c->pred_batches;
+  s->kernel_launches = c->kernel_launches;
+  s->files = c->fs->count_files();
+  s->handles = c->fs->count_handles();
+  return SYM_OK;
+}
+
+int sym_plan_append(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, int32_t* cow_out,
+                    int64_t cow_cap, int32_t* n_cow, int32_t* slots_out) {
+  if (!c || n_lips < 0 || (n_lips > 0 && (!kv || !n_tokens))) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (cow_out && cow_cap < n_lips) return fail(c, SYM_EINVAL, "plan_append: cow_cap must be >= n_lips");
+  c->plan.clear();
+  const int rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err);
+  if (rc) return rc;
+  if (n_cow) *n_cow = (int32_t)(c->plan.cow.size() / 3);
+  if (cow_out) std::memcpy(cow_out, c->plan.cow.data(), c->plan.cow.size() * 4);
+  if (slots_out) std::memcpy(slots_out, c->plan.slots.data(), c->plan.slots.size() * 4);
+  return SYM_OK;
+}
+
+int64_t sym_build_desc(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
+                       const int64_t* pt_offsets, const int64_t* lengths, int32_t* words_out, int64_t cap) {
+  if (!c || n_lips < 0 || (n_lips > 0 && (!n_tokens || !page_table_flat || !pt_offsets || !lengths))) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int64_t n = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths);
+  if (n < 0) return n;
+  if (words_out) std::memcpy(words_out, c->desc.words.data(), (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
+  return n;
+}
+
+int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v, void* stream) {
+  if (!c || !k || !v) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  hipStream_t st = (hipStream_t)stream;
+  if ((int64_t)n + 3 + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
+  c->plan.clear();
+  int rc = c->fs->append(1, &kv, &n, &c->plan, &c->err);
+  if (rc) return rc;
+  const int64_t words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size();
+  int si;
+  if ((rc = stage_acquire(c, words, &si))) return rc;
+  std::memcpy(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
+  std::memcpy(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
+  if ((rc = stage_submit(c, si, words, st))) return rc;
+  return launch_append_plan(c, 0, (int64_t)c->plan.cow.size(), k, v, st);
+}
+
+int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q,
+                   const void* k_new, const void* v_new, float* out, void* stream) {
+  if (!c || n_lips < 0) return SYM_EINVAL;
+  if (n_lips == 0) return SYM_OK;
+  if (!kv || !n_tokens || !q || !k_new || !v_new || !out) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  hipStream_t st = (hipStream_t)stream;
+  const int P = c->cfg.page_tokens;
+  // sizes after the append, for the workspace check that must precede any state change
+  int64_t T = 0, entries = 0;
+  for (int32_t b = 0; b < n_lips; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    if (!f) return fail(c, SYM_EBADF, "pred_batch: bad file handle");
+    if (n_tokens[b] < 1) return fail(c, SYM_EINVAL, "pred_batch: n_tokens must be >= 1");
+    T += n_tokens[b];
+    entries += (f->len + n_tokens[b] + P - 1) / P;
+  }
+  if (align_up(blob_words_bound(c, n_lips, T, entries) * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes)
+    return fail(c, SYM_ENOSPC, "workspace too small for this batch");
+  c->plan.clear();
+  int rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err);
+  if (rc) return rc;
+  c->tables.resize(n_lips);
+  c->len_after.resize(n_lips);
+  for (int32_t b = 0; b < n_lips; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    c->tables[b] = f->pages.data();
+    c->len_after[b] = f->len;
+  }
+  DescParams prm{c->cfg.n_kv_heads, P, c->max_waves, c->min_units};
+  rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
+  if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
+  const int64_t dwords = (int64_t)c->desc.words.size();
+  const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
+  const int64_t words = slots_off + (int64_t)c->plan.slots.size();
+  int si;
+  if ((rc = stage_acquire(c, words, &si))) return rc;
+  std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
+  std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
+  std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
+  if ((rc = stage_submit(c, si, words, st))) return rc;
+  if ((rc = launch_append_plan(c, cow_off, slots_off, k_new, v_new, st))) return rc;
+  ++c->pred_batches;
+  return launch_attention(c, words, q, out, st);
+}
+
+int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
+                       const int64_t* pt_offsets, const int64_t* lengths, const void* q, float* out, void* stream) {
+  if (!c || n_lips < 0) return SYM_EINVAL;
+  if (n_lips == 0) return SYM_OK;
+  if (!q || !out || !n_tokens || !page_table_flat || !pt_offsets || !lengths) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  const int64_t dwords = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths);
+  if (dwords < 0) return (int)dwords;
+  if (align_up(dwords * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes)
+    return fail(c, SYM_ENOSPC, "workspace too small for this batch");
+  hipStream_t st = (hipStream_t)stream;
+  int si, rc;
+  if ((rc = stage_acquire(c, dwords, &si))) return rc;
+  std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
+  if ((rc = stage_submit(c, si, dwords, st))) return rc;
+  ++c->pred_batches;
+  return launch_attention(c, dwords, q, out, st);
+}
+
+int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out, void* stream) {
+  if (!c || !k_out || !v_out || n < 0 || start < 0) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  const KvFile* f = c->fs->file_of(kv);
+  if (!f) return fail(c, SYM_EBADF, "kv_read: bad handle");
+  if (start + n > f->len) return fail(c, SYM_EINVAL, "kv_read: range beyond the file");
+  if (n == 0) return SYM_OK;
+  if ((int64_t)n + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
+  const int P = c->cfg.page_tokens;
+  int si, rc;
+  if ((rc = stage_acquire(c, n, &si))) return rc;
+  for (int32_t i = 0; i < n; ++i) {
+    const int64_t t = start + i;
+    c->stage[si][i] = f->pages[t / P] * P + (int32_t)(t % P);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = stage_submit(c, si, n, st))) return rc;
+  AppendArgs aa{(uint8_t*)c->cfg.pool, c->page_bytes, nullptr, nullptr, (const int32_t*)c->cfg.workspace, n, c->cfg.n_kv_heads};
+  hipError_t e = launch_gather(aa, k_out, v_out, st);
+  if (e != hipSuccess) return fail_hip(c, e, "gather launch");
+  return SYM_OK;
+}
+
+int sym_profile_enable(sym_ctx* c, int mask) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  c->prof_mask = mask;
+  return SYM_OK;
+}
+
+int sym_profile_read(sym_ctx* c, int kid, double* total_ms, int64_t* launches) {
+  if (!c || kid < 0 || kid >= SYM_K_COUNT) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  double tot = 0;
+  for (int i = 0; i < c->ev_used[kid]; ++i) {
+    hipError_t e = hipEventSynchronize(c->ev_stop[kid][i]);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev_start[kid][i], c->ev_stop[kid][i]);
+    if (e != hipSuccess) return fail_hip(c, e, "profile_read");
+    tot += ms;
+  }
+  if (total_ms) *total_ms = tot;
+  if (launches) *launches = c->ev_used[kid];
+  c->ev_used[kid] = 0;
+  return SYM_OK;
+}
+
+int sym_calib_read(const void* src, int64_t bytes, void* out8, void* stream) {
+  if (!src || !out8 || bytes <= 0 || bytes % 16) return SYM_EINVAL;
+  return launch_calib_read(src, bytes, out8, (hipStream_t)stream) == hipSuccess ? SYM_OK : SYM_EHIP;
+}
+int sym_calib_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+  if (!dst || !src || bytes <= 0 || bytes % 16) return SYM_EINVAL;
+  return launch_calib_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? SYM_OK : SYM_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,122 @@
+// Batch-descriptor builder (host, integer work only).  See desc.hpp.
+#include "desc.hpp"
+
+#include <algorithm>
+#include <cstring>
+
+#include "../../include/symphony_kv.h"
+
+namespace symkv {
+
+int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, const int64_t* len_after,
+               const int32_t* const* tables, BatchDesc* out) {
+  const int32_t P = prm.page_tokens, H = prm.n_kv_heads;
+  int64_t n_rows = 0, entries = 0;
+  for (int32_t b = 0; b < n_lips; ++b) {
+    if (n_tokens[b] < 1 || len_after[b] < n_tokens[b] || len_after[b] > (int64_t)0x7fffffff) return SYM_EINVAL;
+    n_rows += n_tokens[b];
+    entries += (len_after[b] + P - 1) / P;
+  }
+  if (n_rows > 0x7fffffff / (2 * H) || entries > 0x3fffffff) return SYM_EINVAL;
+
+  // ---- section sizes known up front: rows, page table, offsets
+  int64_t total_units = 0;
+  for (int32_t b = 0; b < n_lips; ++b)
+    for (int32_t i = 0; i < n_tokens[b]; ++i) {
+      int64_t vis = len_after[b] - n_tokens[b] + i + 1;
+      total_units += ((vis + P - 1) / P) * H;
+    }
+  int64_t nw = (total_units + prm.min_units_per_wave - 1) / prm.min_units_per_wave;
+  nw = std::max<int64_t>(1, std::min<int64_t>(nw, prm.max_waves));
+  if (total_units == 0) nw = 0;
+
+  std::vector<int32_t>& w = out->words;
+  const int64_t off_rows = DESC_HEADER_WORDS;
+  const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
+  const int64_t off_merge = off_waves + nw * WAVE_WORDS;
+  const int64_t off_pt = off_merge + n_rows * H + 1;
+  const int64_t off_ptoff = off_pt + entries;
+  const int64_t off_tiles = off_ptoff + n_lips + 1;
+  const int64_t total = off_tiles;
+  if (total > 0x7fffffff) return SYM_EINVAL;
+  w.resize((size_t)total);
+  std::memset(w.data(), 0, DESC_HEADER_WORDS * sizeof(int32_t));
+
+  // ---- rows, page table
+  int32_t* rows = w.data() + off_rows;
+  int32_t* pt = w.data() + off_pt;
+  int32_t* ptoff = w.data() + off_ptoff;
+  int64_t r = 0, e = 0;
+  for (int32_t b = 0; b < n_lips; ++b) {
+    ptoff[b] = (int32_t)e;
+    int64_t np = (len_after[b] + P - 1) / P;
+    std::memcpy(pt + e, tables[b], (size_t)np * sizeof(int32_t));
+    e += np;
+    for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
+      rows[r * ROW_WORDS + 0] = b;
+      rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
+      rows[r * ROW_WORDS + 2] = (int32_t)r;                                       // q / out row
+      rows[r * ROW_WORDS + 3] = 0;
+    }
+  }
+  ptoff[n_lips] = (int32_t)e;
+
+  // ---- cut the unit sequence into nw equal ranges; number the partial results
+  int32_t* waves = w.data() + off_waves;
+  int32_t* merge = w.data() + off_merge;
+  int64_t row = 0;          // current position of the walk: (row, g, p)
+  int32_t g = 0, p = 0;
+  int32_t part = 0;
+  int64_t next_merge = 0;     // merge[] entries filled so far
+  auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
+  for (int64_t k = 0; k < nw; ++k) {
+    int64_t u0 = total_units * k / nw, u1 = total_units * (k + 1) / nw;
+    int64_t remaining = u1 - u0;
+    waves[k * WAVE_WORDS + 0] = (int32_t)row;
+    waves[k * WAVE_WORDS + 1] = g;
+    waves[k * WAVE_WORDS + 2] = p;
+    waves[k * WAVE_WORDS + 3] = (int32_t)remaining;
+    waves[k * WAVE_WORDS + 4] = part;
+    waves[k * WAVE_WORDS + 5] = 0;
+    while (remaining > 0) {
+      int32_t np = row_pages(row);
+      int32_t cnt = (int32_t)std::min<int64_t>(remaining, np - p);
+      int64_t key = row * H + g;
+      while (next_merge <= key) merge[next_merge++] = part;   // first partial of (row, g)
+      if (!(p == 0 && cnt == np)) ++part;                      // a whole (row, g) needs no partial
+      remaining -= cnt;
+      p += cnt;
+      if (p == np) {
+        p = 0;
+        if (++g == H) {
+          g = 0;
+          ++row;
+        }
+      }
+    }
+  }
+  while (next_merge <= n_rows * H) merge[next_merge++] = part;
+
+  w[H_N_ROWS] = (int32_t)n_rows;
+  w[H_N_WAVES] = (int32_t)nw;
+  w[H_N_PARTIALS] = part;
+  w[H_N_LIPS] = n_lips;
+  w[H_N_TILES] = 0;
+  w[H_OFF_ROWS] = (int32_t)off_rows;
+  w[H_OFF_WAVES] = (int32_t)off_waves;
+  w[H_OFF_MERGE] = (int32_t)off_merge;
+  w[H_OFF_PT] = (int32_t)off_pt;
+  w[H_OFF_PTOFF] = (int32_t)off_ptoff;
+  w[H_OFF_TILES] = (int32_t)off_tiles;
+  w[H_TOTAL_WORDS] = (int32_t)total;
+  w[H_TOTAL_UNITS_LO] = (int32_t)(total_units & 0xffffffff);
+  w[H_TOTAL_UNITS_HI] = (int32_t)(total_units >> 32);
+  out->n_rows = (int32_t)n_rows;
+  out->n_waves = (int32_t)nw;
+  out->n_partials = part;
+  out->n_lips = n_lips;
+  out->total_units = total_units;
+  return SYM_OK;
+}
+
+}  // namespace symkv

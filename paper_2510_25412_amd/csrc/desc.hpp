@@ -1,0 +1,47 @@
+// Batch-descriptor builder: turns the pending pred calls of one batch (paper section 4.4:
+// the inference scheduler aggregates pred calls into one GPU batch) into the integer work
+// description of the attention launch.  Pure host code, no HIP.
+//
+// Every new token is a "row" with a visible length (file tokens 0 .. len_before + i).  The
+// work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
+// slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves equal
+// contiguous ranges, one per wavefront, whatever the raggedness of the files.  A range
+// that covers only part of a (row, kv head) produces a partial result (running max, sum,
+// unnormalised accumulator) that the merge kernel combines; a range covering a whole
+// (row, kv head) writes the final output directly and has no partial.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace symkv {
+
+enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 6 };
+// header word indices
+enum {
+  H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
+  H_OFF_ROWS, H_OFF_WAVES, H_OFF_MERGE, H_OFF_PT, H_OFF_PTOFF, H_OFF_TILES, H_TOTAL_WORDS,
+  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI
+};
+
+struct BatchDesc {
+  std::vector<int32_t> words;      // packed descriptor, header first
+  int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0;
+  int64_t total_units = 0;
+
+  const int32_t* rows() const { return words.data() + words[H_OFF_ROWS]; }
+  const int32_t* waves() const { return words.data() + words[H_OFF_WAVES]; }
+  const int32_t* merge_off() const { return words.data() + words[H_OFF_MERGE]; }
+};
+
+struct DescParams {
+  int32_t n_kv_heads, page_tokens;
+  int32_t max_waves;          // wavefront slots of the decode launch
+  int32_t min_units_per_wave; // do not cut finer than this (keeps partial traffic small)
+};
+
+// n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page
+// ids are tables[b][0 .. ceil(len_after/P)).  Returns 0 or a negative status.
+int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, const int64_t* len_after,
+               const int32_t* const* tables, BatchDesc* out);
+
+}  // namespace symkv

@@ -1,0 +1,223 @@
+// KV-cache file system host state (paper section 4.2).  See kvfs.hpp.
+#include "kvfs.hpp"
+
+#include <algorithm>
+#include <numeric>
+
+#include "../../include/symphony_kv.h"
+
+namespace symkv {
+
+Kvfs::Kvfs(int64_t n_pages, int32_t page_tokens, const int32_t* free_order)
+    : n_pages_(n_pages), P_(page_tokens), refcount_(n_pages, 0), order_(n_pages), rank_(n_pages) {
+  if (free_order) {
+    std::copy(free_order, free_order + n_pages, order_.begin());
+  } else {
+    std::iota(order_.begin(), order_.end(), 0);
+  }
+  for (int64_t r = 0; r < n_pages; ++r) rank_[order_[r]] = (int32_t)r;
+  std::vector<int32_t> ranks(n_pages);
+  std::iota(ranks.begin(), ranks.end(), 0);   // ascending = already a valid min-heap
+  free_ranks_ = decltype(free_ranks_)(std::greater<int32_t>(), std::move(ranks));
+}
+
+const KvFile* Kvfs::file_of(int32_t h) const {
+  if (h < 0 || h >= (int32_t)handle_file_.size() || handle_file_[h] < 0) return nullptr;
+  return &files_[handle_file_[h]];
+}
+
+int32_t Kvfs::alloc_page() {
+  int32_t p = order_[free_ranks_.top()];   // lowest rank, whatever the release order
+  free_ranks_.pop();
+  refcount_[p] = 1;
+  ++pages_allocated;
+  return p;
+}
+
+void Kvfs::release_pages(KvFile& f) {
+  for (int32_t p : f.pages)
+    if (--refcount_[p] == 0) free_ranks_.push(rank_[p]);
+  f.pages.clear();
+  f.len = 0;
+}
+
+int32_t Kvfs::new_file() {
+  int32_t id;
+  if (!free_file_ids_.empty()) {
+    id = free_file_ids_.back();
+    free_file_ids_.pop_back();
+  } else {
+    id = (int32_t)files_.size();
+    files_.emplace_back();
+  }
+  KvFile& f = files_[id];
+  f.len = 0;
+  f.pages.clear();
+  f.handles.clear();
+  f.name.clear();
+  f.named = false;
+  f.alive = true;
+  return id;
+}
+
+int32_t Kvfs::new_handle(int32_t file_id) {
+  int32_t h;
+  if (!free_handles_.empty()) {
+    h = free_handles_.top();               // lowest free handle slot
+    free_handles_.pop();
+  } else {
+    h = (int32_t)handle_file_.size();
+    handle_file_.push_back(-1);
+  }
+  handle_file_[h] = file_id;
+  files_[file_id].handles.push_back(h);
+  return h;
+}
+
+void Kvfs::drop_file(int32_t id) {
+  KvFile& f = files_[id];
+  release_pages(f);
+  for (int32_t h : f.handles) {
+    handle_file_[h] = -1;
+    free_handles_.push(h);
+  }
+  f.handles.clear();
+  if (f.named) names_.erase(f.name);
+  f.alive = false;
+  free_file_ids_.push_back(id);
+}
+
+int32_t Kvfs::open(const char* name) {
+  if (name) {
+    auto it = names_.find(name);
+    if (it != names_.end()) return new_handle(it->second);   // second handle, same file
+  }
+  int32_t id = new_file();
+  if (name) {
+    files_[id].name = name;
+    files_[id].named = true;
+    names_[name] = id;
+  }
+  return new_handle(id);
+}
+
+int32_t Kvfs::fork(int32_t parent) {
+  const KvFile* pf = file_of(parent);
+  if (!pf) return SYM_EBADF;
+  int32_t pid = handle_file_[parent];
+  int32_t id = new_file();                  // may grow files_: re-read the parent by index
+  KvFile& child = files_[id];
+  const KvFile& par = files_[pid];
+  child.pages = par.pages;
+  child.len = par.len;
+  for (int32_t p : child.pages) ++refcount_[p];
+  return new_handle(id);
+}
+
+int Kvfs::remove(int32_t h) {
+  if (!file_of(h)) return SYM_EBADF;
+  drop_file(handle_file_[h]);
+  return SYM_OK;
+}
+
+int Kvfs::close(int32_t h) {
+  if (!file_of(h)) return SYM_EBADF;
+  int32_t id = handle_file_[h];
+  KvFile& f = files_[id];
+  f.handles.erase(std::find(f.handles.begin(), f.handles.end(), h));
+  handle_file_[h] = -1;
+  free_handles_.push(h);
+  if (!f.named && f.handles.empty()) drop_file(id);   // nobody can reach it any more
+  return SYM_OK;
+}
+
+int64_t Kvfs::len(int32_t h) const {
+  const KvFile* f = file_of(h);
+  return f ? f->len : (int64_t)SYM_EBADF;
+}
+
+int64_t Kvfs::pages_needed(int32_t n, const int32_t* handles, const int32_t* n_tokens, std::string* err) {
+  pending_.clear();
+  seen_files_.clear();
+  int64_t need = 0;
+  for (int32_t b = 0; b < n; ++b) {
+    const KvFile* f = file_of(handles[b]);
+    if (!f) {
+      if (err) *err = "bad file handle in batch";
+      return SYM_EBADF;
+    }
+    if (n_tokens[b] < 1) {
+      if (err) *err = "n_tokens must be >= 1";
+      return SYM_EINVAL;
+    }
+    int32_t id = handle_file_[handles[b]];
+    if (std::find(seen_files_.begin(), seen_files_.end(), id) != seen_files_.end()) {
+      if (err) *err = "same file twice in one batch";
+      return SYM_EBUSY;
+    }
+    seen_files_.push_back(id);
+    int64_t L = f->len;
+    if (L % P_ != 0) {
+      int32_t last = f->pages.back();
+      int64_t rc = (int64_t)refcount_[last];
+      auto it = pending_.find(last);
+      if (it != pending_.end()) rc += it->second;
+      if (rc > 1) {                        // shared, partly filled: this LIP copies it
+        ++need;
+        pending_[last] -= 1;
+      }
+    }
+    need += (L + n_tokens[b] + P_ - 1) / P_ - (L + P_ - 1) / P_;
+  }
+  return need;
+}
+
+int Kvfs::append(int32_t n, const int32_t* handles, const int32_t* n_tokens, AppendPlan* plan, std::string* err) {
+  int64_t need = pages_needed(n, handles, n_tokens, err);
+  if (need < 0) return (int)need;
+  if (need > free_pages()) {
+    if (err) *err = "page pool exhausted";
+    return SYM_ENOSPC;
+  }
+  for (int32_t b = 0; b < n; ++b) {
+    KvFile& f = files_[handle_file_[handles[b]]];
+    int32_t r = (int32_t)(f.len % P_);
+    if (r != 0 && refcount_[f.pages.back()] > 1) {
+      int32_t src = f.pages.back();
+      int32_t dst = alloc_page();
+      --refcount_[src];
+      f.pages.back() = dst;
+      ++cow_copies;
+      if (plan) {
+        plan->cow.push_back(src);
+        plan->cow.push_back(dst);
+        plan->cow.push_back(r);
+      }
+    }
+    for (int32_t i = 0; i < n_tokens[b]; ++i) {
+      if (f.len % P_ == 0) f.pages.push_back(alloc_page());
+      if (plan) plan->slots.push_back(f.pages.back() * P_ + (int32_t)(f.len % P_));
+      ++f.len;
+    }
+    tokens_appended += n_tokens[b];
+  }
+  return SYM_OK;
+}
+
+int64_t Kvfs::count_shared() const {
+  int64_t c = 0;
+  for (uint32_t r : refcount_) c += r > 1;
+  return c;
+}
+int64_t Kvfs::count_files() const {
+  int64_t c = 0;
+  for (const KvFile& f : files_) c += f.alive;
+  return c;
+}
+int64_t Kvfs::count_handles() const {
+  int64_t c = 0;
+  for (int32_t f : handle_file_) c += f >= 0;
+  return c;
+}
+
+}  // namespace symkv

@@ -1,0 +1,77 @@
+// Host-side state of the KV-cache file system (paper section 4.2): files as page lists,
+// per-page reference counts, copy-on-write forks, a ranked free-page heap.  Pure C++, no
+// HIP: the integer state is what tests compare bit for bit with the CPU model.
+#pragma once
+#include <cstdint>
+#include <functional>
+#include <queue>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+namespace symkv {
+
+struct KvFile {
+  int64_t len = 0;
+  std::vector<int32_t> pages;
+  std::vector<int32_t> handles;
+  std::string name;
+  bool named = false;
+  bool alive = false;
+};
+
+// Result of planning a batch of appends (reused between calls: no per-call allocation once warm).
+struct AppendPlan {
+  std::vector<int32_t> cow;       // (src, dst, r) triples: copy slots [0, r) of src into dst
+  std::vector<int32_t> slots;     // per new token: page * P + slot
+  void clear() { cow.clear(); slots.clear(); }
+};
+
+class Kvfs {
+ public:
+  Kvfs(int64_t n_pages, int32_t page_tokens, const int32_t* free_order);
+
+  int32_t open(const char* name);                 // handle or negative status
+  int32_t fork(int32_t parent);
+  int remove(int32_t h);
+  int close(int32_t h);
+  int64_t len(int32_t h) const;
+  const KvFile* file_of(int32_t h) const;
+
+  // Pages a batch would allocate, LIPs in batch order; negative status on a bad argument.
+  int64_t pages_needed(int32_t n, const int32_t* handles, const int32_t* n_tokens, std::string* err);
+  // Two-phase: validate + count, then commit.  On error nothing changes.
+  int append(int32_t n, const int32_t* handles, const int32_t* n_tokens, AppendPlan* plan, std::string* err);
+
+  int32_t refcount(int32_t page) const { return page < 0 || page >= n_pages_ ? -1 : (int32_t)refcount_[page]; }
+  int64_t free_pages() const { return (int64_t)free_ranks_.size(); }
+  int64_t n_pages() const { return n_pages_; }
+  int32_t page_tokens() const { return P_; }
+
+  int64_t cow_copies = 0, pages_allocated = 0, tokens_appended = 0;
+  int64_t count_shared() const;
+  int64_t count_files() const;
+  int64_t count_handles() const;
+
+ private:
+  int32_t alloc_page();
+  void release_pages(KvFile& f);
+  int32_t new_handle(int32_t file_id);
+  int32_t new_file();
+  void drop_file(int32_t file_id);
+
+  int64_t n_pages_;
+  int32_t P_;
+  std::vector<uint32_t> refcount_;
+  std::vector<int32_t> order_, rank_;       // rank -> page, page -> rank
+  std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_ranks_;
+  std::vector<KvFile> files_;
+  std::vector<int32_t> free_file_ids_;
+  std::vector<int32_t> handle_file_;        // handle -> file id or -1
+  std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_handles_;
+  std::unordered_map<std::string, int32_t> names_;
+  std::unordered_map<int32_t, int32_t> pending_;   // scratch of pages_needed
+  std::vector<int32_t> seen_files_;                 // scratch of append
+};
+
+}  // namespace symkv

@@ -1,0 +1,86 @@
+"""Runs a synthetic workload (synth.Workload) through the HIP library on one GPU.  torch is
+used for device memory and the stream only; every step of the path runs in the library."""
+import numpy as np
+import torch
+
+from . import binding, synth
+
+
+def to_device(a, device):
+    """Stored patterns (uint16 bf16 bits or float32) -> device tensor of the storage dtype."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(device)
+
+
+class HipSession:
+    """Device pool + workspace + library context for one workload shape."""
+
+    def __init__(self, shape, n_pages, free_order=None, device="cuda:0", max_lips=4096, max_tokens=1 << 16,
+                 max_entries=1 << 21, decode_waves=0):
+        self.shape = shape
+        self.device = torch.device(device)
+        cfg = binding.make_config(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.page_tokens, shape.dtype, n_pages,
+                                  device=self.device.index or 0, free_order=free_order, decode_waves=decode_waves)
+        pb = binding.page_bytes(cfg)
+        assert pb > 0, "unsupported shape"
+        self.page_bytes = pb
+        wb = binding.workspace_bytes(cfg, max_lips, max_tokens, max_entries)
+        self.pool = torch.empty(n_pages * pb, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        cfg.pool, cfg.workspace, cfg.workspace_bytes = self.pool.data_ptr(), self.workspace.data_ptr(), wb
+        self.ctx = binding.Context(cfg)
+        self.h = {}
+
+    @property
+    def stream(self):
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def setup(self, ops):
+        for op in ops:
+            if op[0] == "open":
+                self.h[op[1]] = self.ctx.kv_open(None)
+            elif op[0] == "fork":
+                self.h[op[1]] = self.ctx.kv_fork(self.h[op[2]])
+            elif op[0] == "append":
+                _, fid, K, V = op
+                k, v = to_device(K, self.device), to_device(V, self.device)
+                self.ctx.kv_append(self.h[fid], len(K), k, v, self.stream)
+                torch.cuda.current_stream(self.device).synchronize()   # k, v are freed on return
+            elif op[0] == "remove":
+                self.ctx.kv_remove(self.h.pop(op[1]))
+            else:
+                raise ValueError(op[0])
+
+    def upload_batch(self, batch):
+        T = int(sum(batch["n_tokens"]))
+        s = self.shape
+        return dict(kv=[self.h[f] for f in batch["files"]], n_tokens=list(batch["n_tokens"]),
+                    q=to_device(batch["q"], self.device), k_new=to_device(batch["k_new"], self.device),
+                    v_new=to_device(batch["v_new"], self.device),
+                    out=torch.empty((T, s.n_q_heads, s.head_dim), dtype=torch.float32, device=self.device))
+
+    def pred(self, dev_batch):
+        self.ctx.pred_batch(dev_batch["kv"], dev_batch["n_tokens"], dev_batch["q"], dev_batch["k_new"], dev_batch["v_new"],
+                            dev_batch["out"], self.stream)
+        return dev_batch["out"]
+
+    def pages(self, fid):
+        return self.ctx.kv_pages(self.h[fid])
+
+    def close(self):
+        torch.cuda.synchronize(self.device)
+        self.ctx.close()
+
+
+def run_workload(wl, device="cuda:0", **kw):
+    """Builds the files, runs the batch once; returns (outputs as float32 numpy, session)."""
+    entries = sum(wl.pages_after_batch().values()) + 64
+    sess = HipSession(wl.shape, wl.n_pages, wl.free_order, device, max_lips=max(len(wl.batch_files), 1),
+                      max_tokens=max(int(sum(wl.batch_n)), max(wl.lengths.values(), default=1), 1) + 64,
+                      max_entries=entries, **kw)
+    sess.setup(wl.setup_ops())
+    db = sess.upload_batch(wl.batch())
+    out = sess.pred(db)
+    torch.cuda.synchronize(sess.device)
+    return out.cpu().numpy(), sess

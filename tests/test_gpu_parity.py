@@ -1,0 +1,204 @@
+"""GPU parity tests: the HIP path through the C ABI against the CPU oracle, element by element
+on the same seeded inputs.  Bars: page tables / reference counts bit-exact; attention outputs
+within |gpu - ref| <= 2e-3 * max(1, |ref|) (bf16 inputs, fp32 accumulation)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle.driver import run_workload as run_oracle, OracleSession, widen
+from paper_2510_25412_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+def _hip():
+    from paper_2510_25412_amd import driver
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return driver
+
+
+def check_outputs(got, ref, rows=None, tol=TOL):
+    if rows is not None:
+        got, ref = got[rows], ref[rows]
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref) / np.maximum(1.0, np.abs(ref))
+    assert err.max() <= tol, f"max scaled error {err.max():.3e}"
+    return float(err.max())
+
+
+def check_state(wl, sess, osess):
+    for f in wl.lengths:
+        if f in sess.h:
+            assert sess.pages(f) == osess.model.kv_pages(osess.h[f]), f
+            assert sess.ctx.kv_len(sess.h[f]) == osess.model.kv_len(osess.h[f])
+    assert sess.ctx.free_pages() == osess.model.free_pages()
+    used = sorted({p for f in sess.h for p in sess.pages(f)})
+    assert [sess.ctx.page_refcount(p) for p in used] == [int(osess.model.refcount[p]) for p in used]
+
+
+def run_both(wl, only=None, **kw):
+    print(f"[case] {wl.name} lips={len(wl.batch_files)} tokens={sum(wl.batch_n)}", flush=True)
+    got, sess = _hip().run_workload(wl, **kw)
+    ref, osess = run_oracle(wl, dtype=np.float64, only=only)
+    return got, sess, ref, osess
+
+
+def rows_of(wl, lips):
+    starts = np.concatenate([[0], np.cumsum(wl.batch_n)])
+    return np.concatenate([np.arange(starts[b], starts[b + 1]) for b in lips])
+
+
+def test_append_read_roundtrip_and_cow_bytes():
+    """kv_append then kv_read returns the appended rows bit for bit, across page boundaries,
+    for both storage types, and after a copy-on-write of a partly filled shared page."""
+    drv = _hip()
+    for shape in (synth.Shape(8, 8, 64, 16, synth.F32), synth.Shape(32, 8, 128, 16, synth.BF16)):
+        wl = synth.custom("rt", shape, [("new", 45), ("fork", 0, 7), ("fork", 0, 0)], [(0, 1)], 32, seed=5)
+        sess = drv.HipSession(shape, 32)
+        ops = list(wl.setup_ops())
+        sess.setup(ops)
+        K0, V0 = ops[1][2], ops[1][3]
+        K1, V1 = ops[3][2], ops[3][3]
+        tdt = torch.float32 if shape.dtype == synth.F32 else torch.bfloat16
+        for fid, Kx, Vx in ((0, K0, V0), (1, np.concatenate([K0, K1]), np.concatenate([V0, V1])), (2, K0, V0)):
+            n = len(Kx)
+            k = torch.empty((n, shape.n_kv_heads, shape.head_dim), dtype=tdt, device="cuda")
+            v = torch.empty_like(k)
+            sess.ctx.kv_read(sess.h[fid], 0, n, k, v, sess.stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(k.float().cpu().numpy(), widen(Kx)) and np.array_equal(v.float().cpu().numpy(), widen(Vx))
+        assert sess.ctx.get_stats()["cow_copies"] == 1
+        sess.close()
+
+
+def test_config1_tiny_fp32_all_outputs():
+    wl = synth.config1()
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref, tol=1e-5)          # fp32 storage: far inside the bar
+    check_state(wl, sess, osess)
+    sess.close()
+
+
+def test_config2_decode_batch_full_size():
+    wl = synth.config2()
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+
+
+def test_config3_fork_tree_full_size_sampled():
+    wl = synth.config3()
+    lips = list(range(0, 256, 9))
+    got, sess, ref, osess = run_both(wl, only=lips)
+    check_outputs(got, ref, rows_of(wl, lips))
+    check_state(wl, sess, osess)
+    st = sess.ctx.get_stats()
+    assert st["cow_copies"] == 0 and st["pages_shared"] == 16 * 128     # aligned prefix: shared, never copied
+    sess.close()
+
+
+def test_config4_mixed_reduced():
+    """Mixed prefill + decode at reduced size (chunks of 48 tokens on files of 0..600 tokens,
+    plus decode LIPs): every output checked."""
+    wl = synth.config4(n_prefill=4, chunk=48, pre_hi=600, n_decode=12, dec_lo=100, dec_hi=500, slack_pages=64)
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+
+
+def test_config5_long_context_scattered_sampled():
+    """Long contexts with pages scattered by a random allocation ranking over a 200k-page
+    (13 GB) pool; sampled LIPs checked against the oracle, all checked for finiteness."""
+    wl = synth.config5(n_lips=6, n_pages=200_000)
+    lips = [0, 3, 5]
+    got, sess, ref, osess = run_both(wl, only=lips)
+    check_outputs(got, ref, rows_of(wl, lips))
+    assert np.isfinite(got).all()
+    check_state(wl, sess, osess)
+    sess.close()
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_edge_cases(dtype):
+    """Empty file + one token (output = the new V row), page-boundary lengths, a single-token
+    file, small multi-token calls, unaligned forks that force copies, parent appending after
+    its children, 8:1 and 1:1 head groups."""
+    D = 64 if dtype == synth.F32 else 128
+    for Hq, Hkv in ((8, 8), (16, 8), (32, 8), (64, 8), (4, 1)):
+        shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+        files = [("new", 0), ("new", 1), ("new", 15), ("new", 16), ("new", 17), ("new", 31), ("new", 250),
+                 ("fork", 6, 0), ("fork", 6, 9), ("fork", 4, 3), ("fork", 9, 0)]
+        batch = [(0, 1), (1, 1), (2, 1), (3, 1), (4, 2), (5, 5), (7, 1), (8, 3), (10, 1), (9, 1), (6, 1)]
+        wl = synth.custom(f"edge_{dtype}_{Hq}_{Hkv}", shape, files, batch, 128, seed=99 + Hq)
+        got, sess, ref, osess = run_both(wl)
+        check_outputs(got, ref)
+        check_state(wl, sess, osess)
+        assert sess.ctx.get_stats()["cow_copies"] == osess.model.cow_copies > 0
+        # empty file + one new token: exactly the new V row of the matching kv head
+        b = wl.batch()
+        v0 = widen(b["v_new"])[0]
+        G = Hq // Hkv
+        assert np.array_equal(got[0], np.repeat(v0, G, axis=0))
+        sess.close()
+
+
+def test_chunk_equals_sequential_on_gpu():
+    """One 6-token pred equals six 1-token preds (same appended rows), within the bar."""
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    wl = synth.custom("chunk", shape, [("new", 70)], [(0, 6)], 32, seed=123)
+    got, sess = drv.run_workload(wl)
+    sess.close()
+    sess2 = drv.HipSession(shape, 32)
+    sess2.setup(wl.setup_ops())
+    b = wl.batch()
+    outs = []
+    for i in range(6):
+        one = dict(files=[0], n_tokens=[1], q=b["q"][i:i + 1], k_new=b["k_new"][i:i + 1], v_new=b["v_new"][i:i + 1])
+        outs.append(sess2.pred(sess2.upload_batch(one)).cpu().numpy())
+    check_outputs(got, np.concatenate(outs), tol=1e-4)
+    sess2.close()
+
+
+def test_enospc_leaves_device_context_unchanged():
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    wl = synth.custom("full", shape, [("new", 40), ("new", 16)], [(0, 1), (1, 1)], 5, seed=3)   # 3 + 1 pages of 5
+    sess = drv.HipSession(shape, 5)
+    sess.setup(wl.setup_ops())
+    from paper_2510_25412_amd import binding
+    b = wl.batch()
+    big = dict(files=[0, 1], n_tokens=[10, 1], q=np.repeat(b["q"][:1], 11, 0), k_new=np.repeat(b["k_new"][:1], 11, 0),
+               v_new=np.repeat(b["v_new"][:1], 11, 0))
+    snap = (sess.pages(0), sess.pages(1), sess.ctx.free_pages())
+    with pytest.raises(binding.SymError) as e:
+        sess.pred(sess.upload_batch(big))
+    assert e.value.code == binding.SYM_ENOSPC
+    assert snap == (sess.pages(0), sess.pages(1), sess.ctx.free_pages())
+    ref, osess = run_oracle(wl, dtype=np.float64)
+    got = sess.pred(sess.upload_batch(b)).cpu().numpy()
+    check_outputs(got, ref)
+    sess.close()
+
+
+def test_raw_entry_matches_allocator_entry():
+    """pred_batch_raw over the page tables that pred_batch built gives the same outputs."""
+    wl = synth.config2(n_lips=8, lo=100, hi=900, slack_pages=32)
+    got, sess = _hip().run_workload(wl)
+    b = wl.batch()
+    tables = [sess.pages(f) for f in wl.batch_files]
+    flat = np.concatenate(tables).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+    lengths = [sess.ctx.kv_len(sess.h[f]) for f in wl.batch_files]
+    from paper_2510_25412_amd.driver import to_device
+    q = to_device(b["q"], sess.device)
+    out = torch.empty((len(lengths), 32, 128), dtype=torch.float32, device=sess.device)
+    sess.ctx.pred_batch_raw(wl.batch_n, flat, off, lengths, q, out, sess.stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), got)
+    sess.close()

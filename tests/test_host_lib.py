@@ -1,0 +1,218 @@
+"""CPU tests of the C-ABI library's host half: symbols, file-system state against the oracle's
+model (bit-exact), and the batch descriptor's structure.  No GPU, no device calls."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.kvfs_model import KVFSModel, KVError
+from paper_2510_25412_amd import binding
+from trace_util import load_trace, parse_expect
+
+
+def host_ctx(n_pages, free_order=None, Hq=32, Hkv=8, D=128, dtype="bf16", decode_waves=0):
+    cfg = binding.make_config(Hq, Hkv, D, 16, dtype, n_pages, device=-1, free_order=free_order, decode_waves=decode_waves)
+    return binding.Context(cfg)
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    hdr = open(os.path.join(repo_root, "include", "symphony_kv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(sym_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 20
+    lib = binding.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding._SIGNATURES), declared ^ set(binding._SIGNATURES)
+
+
+def test_shapes_supported_and_rejected():
+    ok = binding.make_config(32, 8, 128, 16, "bf16", 8)
+    assert binding.page_bytes(ok) == 8 * 2 * 16 * 256
+    assert binding.page_bytes(binding.make_config(8, 8, 64, 16, "f32", 8)) == 65536
+    assert binding.page_bytes(binding.make_config(8, 8, 128, 16, "f32", 8)) == 0      # row != 256 bytes
+    assert binding.page_bytes(binding.make_config(32, 8, 128, 32, "bf16", 8)) == 0     # page != 16 tokens
+    assert binding.page_bytes(binding.make_config(24, 8, 128, 16, "bf16", 8)) == 0     # group of 3
+    with pytest.raises(binding.SymError):
+        binding.Context(binding.make_config(32, 8, 128, 16, "bf16", 8, device=-1, free_order=[0, 1, 2, 3, 4, 5, 6, 6]))
+
+
+def test_fig1_hand_trace_library():
+    """Same hand-derived trace of the paper's Fig. 1 program that pins the oracle's model.
+    (The library's pages hold 16 tokens, the trace uses 4: token counts are scaled by 4 and
+    slot indices compared after dividing by 4.)"""
+    c = host_ctx(8)
+    for op, args, exp in load_trace("fig1_state_trace.txt"):
+        e = parse_expect(exp)
+        if op == "open":
+            assert c.kv_open(args[0]) == e["h"]
+        elif op == "fork":
+            assert c.kv_fork(int(args[0])) == e["h"]
+        elif op == "append":
+            h, n = int(args[0]), int(args[1]) * 4
+            cow, slots = c.plan_append([h], [n])
+            assert [(s, d, r // 4) for s, d, r in cow] == e["cow"]
+            got = [(int(x) // 16, int(x) % 16 // 4) for x in slots[::4]]
+            assert got == e["slots"]
+            assert c.kv_pages(h) == e["pages"]
+        elif op == "remove":
+            c.kv_remove(int(args[0]))
+        elif op == "close":
+            c.kv_close(int(args[0]))
+        elif op == "len":
+            assert c.kv_len(int(args[0])) == e["len"] * 4
+        if "rc" in e:
+            assert [c.page_refcount(p) for p in range(8)] == e["rc"], (op, args)
+        if "free" in e:
+            assert c.free_pages() == e["free"]
+
+
+def test_random_ops_match_oracle_model_bit_exact():
+    rng = np.random.default_rng(2024)
+    order = rng.permutation(512).astype(np.int32)
+    m = KVFSModel(512, 16, order)
+    c = host_ctx(512, order)
+    live = []
+    for step in range(1500):
+        r = rng.random()
+        if r < 0.12 or not live:
+            a, b = m.kv_open(), c.kv_open()
+            assert a == b
+            live.append(a)
+        elif r < 0.30:
+            p = live[rng.integers(len(live))]
+            a, b = m.kv_fork(p), c.kv_fork(p)
+            assert a == b
+            live.append(a)
+        elif r < 0.85:
+            k = min(len(live), int(rng.integers(1, 6)))
+            hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
+            ns = [int(rng.integers(1, 40)) for _ in hs]
+            try:
+                cow, slots = m.append(list(zip(hs, ns)))
+            except KVError as e:
+                with pytest.raises(binding.SymError) as ce:
+                    c.plan_append(hs, ns)
+                assert ce.value.code == e.code
+            else:
+                ccow, cslots = c.plan_append(hs, ns)
+                assert ccow == cow
+                assert cslots.tolist() == [p * 16 + s for mine in slots for p, s in mine]
+        else:
+            h = live.pop(rng.integers(len(live)))
+            m.kv_remove(h)
+            c.kv_remove(h)
+        if step % 50 == 0 or step == 1499:
+            assert c.free_pages() == m.free_pages()
+            assert [c.page_refcount(p) for p in range(512)] == m.refcount.tolist()
+            for h in live:
+                assert c.kv_pages(h) == m.kv_pages(h) and c.kv_len(h) == m.kv_len(h)
+    st = c.get_stats()
+    assert st["cow_copies"] == m.cow_copies and st["pages_free"] == m.free_pages()
+    assert st["pages_shared"] == int((m.refcount > 1).sum())
+
+
+def test_error_codes_and_all_or_nothing():
+    c = host_ctx(4)
+    a = c.kv_open()
+    c.plan_append([a], [9 * 16 // 4])          # 36 tokens -> 3 pages
+    b = c.kv_fork(a)
+    snap = ([c.page_refcount(p) for p in range(4)], c.kv_pages(a), c.kv_pages(b), c.free_pages(), c.kv_len(a))
+    for kv, n, code in (([a, b], [1, 64], binding.SYM_ENOSPC), ([a, a], [1, 1], binding.SYM_EBUSY),
+                        ([a], [0], binding.SYM_EINVAL), ([99], [1], binding.SYM_EBADF)):
+        with pytest.raises(binding.SymError) as e:
+            c.plan_append(kv, n)
+        assert e.value.code == code
+        assert snap == ([c.page_refcount(p) for p in range(4)], c.kv_pages(a), c.kv_pages(b), c.free_pages(), c.kv_len(a))
+    c.kv_remove(b)
+    with pytest.raises(binding.SymError) as e:
+        c.kv_fork(b)
+    assert e.value.code == binding.SYM_EBADF
+    # named files persist across close; anonymous ones vanish with their last handle
+    n1 = c.kv_open("sys_msg.kv")
+    c.plan_append([n1], [5])
+    c.kv_close(n1)
+    assert c.free_pages() == 0
+    n2 = c.kv_open("sys_msg.kv")
+    assert c.kv_len(n2) == 5
+    c.kv_close(a)
+    assert c.free_pages() == 3
+    # a host-only context refuses device calls instead of touching the GPU
+    with pytest.raises(binding.SymError):
+        c.kv_append(n2, 1, 1, 1)
+
+
+def _walk_desc(words, Hkv, P=16):
+    hdr = words[:16]
+    n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
+    rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
+    waves = words[hdr[6]:hdr[6] + 6 * n_waves].reshape(n_waves, 6)
+    merge = words[hdr[7]:hdr[7] + n_rows * Hkv + 1]
+    pt = words[hdr[8]:hdr[9]]
+    ptoff = words[hdr[9]:hdr[9] + n_lips + 1]
+    return n_rows, n_waves, n_partials, rows, waves, merge, pt, ptoff
+
+
+@pytest.mark.parametrize("lengths,n_tok,waves", [([38, 81, 130, 201], [1, 1, 1, 1], 64), ([700, 16, 17, 1, 4096], [1, 1, 1, 1, 1], 2048),
+                                                 ([40, 300], [8, 1], 32), ([5], [5], 8)])
+def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves):
+    Hkv = 8
+    c = host_ctx(4096, decode_waves=waves)
+    rng = np.random.default_rng(1)
+    np_l = [-(-L // 16) for L in lengths]
+    flat = rng.permutation(4096)[:sum(np_l)].astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
+    words = c.build_desc(n_tok, flat, off, lengths)
+    n_rows, n_waves, n_partials, rows, wv, merge, pt, ptoff = _walk_desc(words, Hkv)
+    assert n_rows == sum(n_tok) and np.array_equal(pt, flat) and np.array_equal(ptoff, off)
+    # rows: lip, visible tokens, q row
+    exp_rows = [(b, L - n + i + 1, None) for b, (L, n) in enumerate(zip(lengths, n_tok)) for i in range(n)]
+    assert [(int(r[0]), int(r[1])) for r in rows] == [(b, v) for b, v, _ in exp_rows]
+    assert rows[:, 2].tolist() == list(range(n_rows))
+    # walk every wave's range exactly as the kernel does; record coverage and partial numbering
+    cover = {}
+    units = []
+    pieces = {}
+    for k in range(n_waves):
+        row, g, p, rem, part = (int(x) for x in wv[k, :5])
+        units.append(rem)
+        while rem > 0:
+            npg = -(-int(rows[row, 1]) // 16)
+            cnt = min(rem, npg - p)
+            for x in range(p, p + cnt):
+                assert (row, g, x) not in cover
+                cover[(row, g, x)] = k
+            whole = p == 0 and cnt == npg
+            pieces.setdefault((row, g), []).append(None if whole else part)
+            if not whole:
+                part += 1
+            rem -= cnt
+            p += cnt
+            if p == npg:
+                p, g = 0, g + 1
+                if g == Hkv:
+                    g, row = 0, row + 1
+    total = sum(-(-int(r[1]) // 16) for r in rows) * Hkv
+    assert len(cover) == total and sum(units) == total
+    assert max(units) - min(units) <= 1                      # equal ranges whatever the raggedness
+    assert n_waves <= waves
+    seen_parts = []
+    for (row, g), ps in sorted(pieces.items()):
+        lo, hi = int(merge[row * Hkv + g]), int(merge[row * Hkv + g + 1])
+        if ps == [None]:
+            assert lo == hi                                   # whole range: final output, no partial
+        else:
+            assert None not in ps and ps == list(range(lo, hi))
+            seen_parts += ps
+    assert seen_parts == list(range(n_partials)) and n_partials <= 2 * n_waves
+
+
+def test_descriptor_rejects_bad_tables():
+    c = host_ctx(64)
+    with pytest.raises(binding.SymError):
+        c.build_desc([1], np.array([1, 2], np.int32), [0, 2], [40])       # needs 3 pages
+    with pytest.raises(binding.SymError):
+        c.build_desc([1], np.array([1, 2, 64], np.int32), [0, 3], [40])   # page id out of range
+    with pytest.raises(binding.SymError):
+        c.build_desc([0], np.array([1], np.int32), [0, 1], [4])
