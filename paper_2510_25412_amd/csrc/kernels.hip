@@ -131,8 +131,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
       for (int x = 0; x < 4; ++x) R.v[x] = *(const uint4*)(base + kBlk + x * 1024);
     };
     // tokens of page index pi (absolute, within the row) that exist: the row's last page may be ragged
-    auto compute = [&](const PageRegs& R, int pi) {
+    auto compute = [&](PageRegs& R, int pi) {
       const int nvalid = vis - pi * kP;          // >= 1; >= 16 for a full page
+      if (nvalid < kP) {
+        // ragged last page: slots past the file's end hold whatever was there before (possibly
+        // NaN patterns); their weight is 0, but 0 * NaN is NaN, so clear their V chunks
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+          if ((hf * 8 + r) >= nvalid) {
+            R.v[hf] = make_uint4(0, 0, 0, 0);
+            R.v[2 + hf] = make_uint4(0, 0, 0, 0);
+          }
+      }
       float s[2][G];
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {

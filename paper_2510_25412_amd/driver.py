@@ -17,7 +17,7 @@ class HipSession:
     """Device pool + workspace + library context for one workload shape."""
 
     def __init__(self, shape, n_pages, free_order=None, device="cuda:0", max_lips=4096, max_tokens=1 << 16,
-                 max_entries=1 << 21, decode_waves=0):
+                 max_entries=1 << 21, decode_waves=0, poison=False):
         self.shape = shape
         self.device = torch.device(device)
         cfg = binding.make_config(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.page_tokens, shape.dtype, n_pages,
@@ -28,6 +28,8 @@ class HipSession:
         wb = binding.workspace_bytes(cfg, max_lips, max_tokens, max_entries)
         self.pool = torch.empty(n_pages * pb, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        if poison:          # every never-written slot reads as NaN (tests: stale slots must not leak)
+            self.pool.fill_(0xFF)
         cfg.pool, cfg.workspace, cfg.workspace_bytes = self.pool.data_ptr(), self.workspace.data_ptr(), wb
         self.ctx = binding.Context(cfg)
         self.h = {}
