@@ -24,6 +24,7 @@ constexpr int kWavesPerBlock = 4;
 constexpr float kTau = 8.0f;        // the running max may lag the true max by up to 2^kTau
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
@@ -34,6 +35,11 @@ __device__ __forceinline__ float octet_sum(float x) {
   x += as_f32(__builtin_amdgcn_update_dpp(0, as_u32(x), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
   x += as_f32(__builtin_amdgcn_update_dpp(0, as_u32(x), 0x141, 0xf, 0xf, false));   // row_half_mirror
   return x;
+}
+
+// Value of the lane 8 away inside the 16-lane row (lane ^ 8): DPP row rotate by 8.
+__device__ __forceinline__ float row_xor8(float x) {
+  return as_f32(__builtin_amdgcn_update_dpp(0, as_u32(x), 0x128, 0xf, 0xf, false));   // row_ror:8
 }
 
 // Element-type traits.  A lane holds, per row half, one 16-byte chunk of a K/V row.
@@ -123,12 +129,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
     }
 
     const uint8_t* slab0 = a.pool + (int64_t)g * kSlab + lane * 16;
+    // K/V pages are read once per launch: stream them (nontemporal), 8 KiB per wave per page
     auto load_page = [&](PageRegs& R, int pid) {
       const uint8_t* base = slab0 + (int64_t)pid * a.page_bytes;
 #pragma unroll
-      for (int x = 0; x < 4; ++x) R.k[x] = *(const uint4*)(base + x * 1024);
+      for (int x = 0; x < 4; ++x) R.k[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + x * 1024)));
 #pragma unroll
-      for (int x = 0; x < 4; ++x) R.v[x] = *(const uint4*)(base + kBlk + x * 1024);
+      for (int x = 0; x < 4; ++x) R.v[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + kBlk + x * 1024)));
     };
     // tokens of page index pi (absolute, within the row) that exist: the row's last page may be ragged
     auto compute = [&](PageRegs& R, int pi) {
@@ -189,19 +196,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
       }
     };
 
-    // page ids: 64 at a time into one VGPR, handed out with readlane
-    int idv = (lane < cnt) ? tbl[lane] : 0;
-    auto pid_at = [&](int k) { return __builtin_amdgcn_readlane(idv, k & 63); };
+    // Page ids come through the scalar cache, two pages ahead of their K/V loads.  Every load in
+    // the loop is unconditional (past the end the last page is fetched again and ignored), so the
+    // loop body has no control-flow join between a prefetch and its use and the compiler can wait
+    // for exactly the older page while the newer one is in flight.
+    const int last = cnt - 1;
+    int id1 = tbl[min(1, last)], id2 = tbl[min(2, last)];
     PageRegs A, B;
-    load_page(A, pid_at(0));
-    for (int k = 0; k < cnt; k += 2) {       // k even: a refill of idv can only fall on k + 2
-      if (k + 1 < cnt) load_page(B, pid_at(k + 1));
+    load_page(A, tbl[0]);
+    for (int k = 0; k < cnt; k += 2) {
+      load_page(B, id1);
+      id1 = tbl[min(k + 3, last)];
       compute(A, p + k);
-      if (k + 1 < cnt) {
-        if (((k + 2) & 63) == 0 && k + 2 < cnt) idv = (k + 2 + lane < cnt) ? tbl[k + 2 + lane] : 0;
-        if (k + 2 < cnt) load_page(A, pid_at(k + 2));
-        compute(B, p + k + 1);
-      }
+      load_page(A, id2);
+      id2 = tbl[min(k + 4, last)];
+      if (k + 1 < cnt) compute(B, p + k + 1);
     }
 
     // combine the 8 token slots (lanes with equal j): max, rescale, sum
@@ -209,18 +218,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float M = m[h];
-      M = fmaxf(M, __shfl_xor(M, 8));
+      M = fmaxf(M, row_xor8(M));
       M = fmaxf(M, __shfl_xor(M, 16));
       M = fmaxf(M, __shfl_xor(M, 32));
       const float f = __builtin_amdgcn_exp2f(m[h] - M);
       float ls = l[h] * f;
-      ls += __shfl_xor(ls, 8);
+      ls += row_xor8(ls);
       ls += __shfl_xor(ls, 16);
       ls += __shfl_xor(ls, 32);
 #pragma unroll
       for (int d = 0; d < DPL; ++d) {
         float x = acc[h][d] * f;
-        x += __shfl_xor(x, 8);
+        x += row_xor8(x);
         x += __shfl_xor(x, 16);
         x += __shfl_xor(x, 32);
         acc[h][d] = x;
@@ -340,16 +349,26 @@ __global__ void cow_kernel(CowArgs a) {
 // ---------------------------------------------------------------------------------------
 // Calibration: streaming read (reduced so that the loads are live) and plain copy.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void calib_read_kernel(const uint4* src, int64_t n16, unsigned long long* out) {
+// Read: every wave streams its own contiguous span with nontemporal 16-byte loads, 16 KiB in
+// flight per wave (the access pattern that reads fastest on this part).
+__global__ __launch_bounds__(256) void calib_read_kernel(const u32x4_t* __restrict__ src, int64_t n16, unsigned long long* out) {
+  constexpr int U = 16;
   uint32_t acc = 0;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    uint4 a0 = src[i], a1 = src[i + stride], a2 = src[i + 2 * stride], a3 = src[i + 3 * stride];
-    acc += (a0.x ^ a0.y ^ a0.z ^ a0.w) + (a1.x ^ a1.y ^ a1.z ^ a1.w) + (a2.x ^ a2.y ^ a2.z ^ a2.w) + (a3.x ^ a3.y ^ a3.z ^ a3.w);
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t per = n16 / nwaves / (64 * U) * (64 * U);
+  const u32x4_t* p = src + wave * per + lane;
+  for (int64_t k = 0; k < per; k += 64 * U) {
+    u32x4_t a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(p + k + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += a[u].x ^ a[u].y ^ a[u].z ^ a[u].w;
   }
-  for (; i < n16; i += stride) {
-    uint4 a0 = src[i];
+  // the tail that does not divide evenly (none when bytes is a multiple of grid * 64 KiB)
+  for (int64_t i = nwaves * per + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x) {
+    u32x4_t a0 = src[i];
     acc += a0.x ^ a0.y ^ a0.z ^ a0.w;
   }
   if (acc == 0x9e3779b9u) atomicAdd(out, 1ull);      // practically never: keeps the loads alive
@@ -407,7 +426,7 @@ hipError_t launch_cow(const CowArgs& a, int n_cow, hipStream_t st) {
 }
 
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st) {
-  hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 8), dim3(256), 0, st, (const uint4*)src, bytes / 16, (unsigned long long*)out8);
+  hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 4), dim3(256), 0, st, (const u32x4_t*)src, bytes / 16, (unsigned long long*)out8);
   return hipGetLastError();
 }
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st) {
