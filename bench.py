@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the pred hot path on one MI355X.
 
-A step = one sym_pred_batch call = the whole hot path (descriptor build, host-to-device
-descriptor copy, copy-on-write copies, KV append, decode attention, split merge) over one batch
+A step = one sym_pred_batch call = the whole hot path (descriptor build, the prologue kernel:
+descriptor copy + copy-on-write copies + KV append; the decode attention kernel; the merge of
+split ranges) over one batch
 of the "decode batch" workload: 64 LIPs, 32 Q / 8 KV heads, head dim 128, bf16, contexts
 uniform 512..4096, one new token each.  Successive steps rotate over several independent
 layer pools (as a real pred walks the model's layers, each with its own KV pages) so that the
@@ -146,12 +147,12 @@ def main():
 
     # ---- per-kernel breakdown (untimed extra pass) and streaming-read ceiling
     for s in sessions:
-        s.ctx.profile_enable(0x1f)
+        s.ctx.profile_enable(0xf)
     for i in range(args.layers * 10):
         step(i)
     torch.cuda.synchronize()
     breakdown = {}
-    for name, kid in (("cow", binding.K_COW), ("append", binding.K_APPEND), ("decode", binding.K_DECODE), ("merge", binding.K_MERGE)):
+    for name, kid in (("prologue", binding.K_PROLOGUE), ("decode", binding.K_DECODE), ("merge", binding.K_MERGE)):
         tot, cnt = 0.0, 0
         for s in sessions:
             ms, n = s.ctx.profile_read(kid)
@@ -203,6 +204,8 @@ def main():
         "stream_read_TBps": round(stream_read, 3) if stream_read else None,
         "frac_of_stream_read": round(achieved / 1e3 / stream_read, 4) if (achieved and stream_read) else None,
         "cpu_baseline": cpu,
+        "host_us_per_step": {"plan_and_descriptor": round(stats["host_ns_plan"] / max(stats["pred_batches"], 1) / 1e3, 2),
+                             "whole_call": round(stats["host_ns_pred"] / max(stats["pred_batches"], 1) / 1e3, 2)},
         "pool_stats": {"pages_total": stats["pages_total"], "pages_free": stats["pages_free"]},
     }
     print(json.dumps(line))

@@ -76,6 +76,9 @@ typedef struct sym_stats {
   int64_t cow_copies, pages_allocated, tokens_appended;
   int64_t pred_batches, kernel_launches;
   int64_t files, handles;
+  int64_t host_ns_plan;   /* host time inside sym_pred_batch spent on append planning +
+                             descriptor build + staging, summed over calls, nanoseconds    */
+  int64_t host_ns_pred;   /* host time of whole sym_pred_batch calls (planning + launches)  */
 } sym_stats;
 
 /* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).
@@ -149,9 +152,13 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
 
 /* The packed descriptor of the attention launch for a batch given by page tables (same
  * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.
- * Layout: words[0..15] = header {n_rows, n_waves, n_partials, n_dec_rows, n_tiles, then
- * word offsets of the sections: rows, wave_work, merge_off, page_table, pt_off, tiles},
- * then the sections.  Returns the number of words (or a negative status); writes at most
+ * Layout: words[0..15] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then
+ * word offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total
+ * words; total units (lo, hi); n_merge}, then the sections: rows [n_rows][4] = {page-table
+ * offset, visible tokens, q/out row, lip}; wave_work [n_waves][8] = {row, kv head, page,
+ * units, first partial, visible tokens, q/out row, page-table offset of the first range};
+ * merge [n_merge][4] = {first partial, pieces, q row * Hq + first query head, 0} for each
+ * (row, kv head) that was cut.  Returns the number of words (or a negative status); writes at most
  * cap words.                                                                              */
 int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
                        const int32_t* page_table_flat, const int64_t* pt_offsets,
@@ -164,12 +171,11 @@ int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, 
 
 /* ---- measurement ------------------------------------------------------------------- */
 /* Kernel ids for sym_profile_read. */
-#define SYM_K_COW     0
-#define SYM_K_APPEND  1
-#define SYM_K_DECODE  2
-#define SYM_K_MERGE   3
-#define SYM_K_PREFILL 4
-#define SYM_K_COUNT   5
+#define SYM_K_PROLOGUE 0   /* descriptor copy + copy-on-write copies + KV append, one launch */
+#define SYM_K_DECODE   1   /* attention over the page tables                                 */
+#define SYM_K_MERGE    2   /* merge of the partial results of ranges that were cut           */
+#define SYM_K_PREFILL  3
+#define SYM_K_COUNT    4
 /* sym_profile_enable(mask): bit k of mask set = every launch of kernel id k is bracketed by
  * HIP events on the launch stream (at most 4096 launches are kept per kernel id, later ones
  * are not timed); mask 0 = off.

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
 
 SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
 SYM_F32, SYM_BF16 = 0, 1
-K_COW, K_APPEND, K_DECODE, K_MERGE, K_PREFILL = 0, 1, 2, 3, 4
+K_PROLOGUE, K_DECODE, K_MERGE, K_PREFILL = 0, 1, 2, 3
 
 
 class SymConfig(C.Structure):
@@ -25,7 +25,8 @@ class SymConfig(C.Structure):
 
 class SymStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("pages_total", "pages_free", "pages_shared", "cow_copies", "pages_allocated",
-                                         "tokens_appended", "pred_batches", "kernel_launches", "files", "handles")]
+                                         "tokens_appended", "pred_batches", "kernel_launches", "files", "handles",
+                                         "host_ns_plan", "host_ns_pred")]
 
 
 class SymError(RuntimeError):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -50,9 +51,10 @@ struct sym_ctx {
   // profiling
   int prof_mask = 0;
   std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
-  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0, 0};
+  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0};
   // counters
   int64_t pred_batches = 0, kernel_launches = 0;
+  int64_t host_ns_plan = 0, host_ns_pred = 0;   // time inside sym_pred_batch: planning + descriptor; whole call
 };
 
 namespace {
@@ -77,7 +79,7 @@ bool shape_ok(const sym_config* cfg) {
 
 // 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
 int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
-  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * WAVE_WORDS + T * c->cfg.n_kv_heads + 1 + entries +
+  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + MERGE_WORDS) + entries +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
 int64_t partial_bytes(const sym_ctx* c) {
@@ -108,15 +110,6 @@ int stage_acquire(sym_ctx* c, int64_t words, int* idx) {
   return SYM_OK;
 }
 
-int stage_submit(sym_ctx* c, int i, int64_t words, hipStream_t st) {
-  hipError_t e = hipMemcpyAsync(c->cfg.workspace, c->stage[i], (size_t)words * 4, hipMemcpyHostToDevice, st);
-  if (e != hipSuccess) return fail_hip(c, e, "hipMemcpyAsync(descriptor)");
-  e = hipEventRecord(c->stage_ev[i], st);
-  if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
-  c->stage_pending[i] = true;
-  return SYM_OK;
-}
-
 struct Timed {
   sym_ctx* c;
   int id;
@@ -142,16 +135,11 @@ struct Timed {
   }
 };
 
-// Device pointers of the sections of the blob that sits at the start of the workspace.
-struct BlobView {
-  const int32_t* words;
-  int64_t desc_words, cow_off, slots_off, total_words;
-};
-
 // Launches attention (decode + merge) for the descriptor in c->desc, already copied to the workspace.
 int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, hipStream_t st) {
   const BatchDesc& d = c->desc;
   if (d.n_waves == 0) return SYM_OK;
+  // workspace: [descriptor words][partial max/sum][partial accumulators]
   const int32_t* dw = (const int32_t*)c->cfg.workspace;
   uint8_t* base = (uint8_t*)c->cfg.workspace + align_up(blob_words * 4, 256);
   const int64_t np = 2 * (int64_t)c->max_waves + 1;
@@ -167,7 +155,6 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   a.rows = dw + d.words[H_OFF_ROWS];
   a.waves = dw + d.words[H_OFF_WAVES];
   a.pt = dw + d.words[H_OFF_PT];
-  a.ptoff = dw + d.words[H_OFF_PTOFF];
   a.n_waves = d.n_waves;
   a.Hq = c->cfg.n_q_heads;
   a.Hkv = c->cfg.n_kv_heads;
@@ -177,37 +164,43 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
     hipError_t e = launch_decode(a, c->cfg.dtype, st);
     if (e != hipSuccess) return fail_hip(c, e, "decode launch");
   }
-  if (d.n_partials > 0) {
-    MergeArgs m;
-    m.part_acc = part_acc;
-    m.part_ml = part_ml;
-    m.merge_off = dw + d.words[H_OFF_MERGE];
-    m.rows = a.rows;
-    m.out = out;
-    m.Hq = a.Hq;
-    m.Hkv = a.Hkv;
-    m.D = c->cfg.head_dim;
+  if (d.n_merge > 0) {
+    MergeArgs m{part_acc, part_ml, dw + d.words[H_OFF_MERGE], out, d.n_merge};
     Timed t(c, SYM_K_MERGE, st);
-    hipError_t e = launch_merge(m, d.n_rows, st);
+    hipError_t e = launch_merge(m, c->G, c->cfg.head_dim, st);
     if (e != hipSuccess) return fail_hip(c, e, "merge launch");
   }
   return SYM_OK;
 }
 
-// cow + append kernels for the plan in c->plan whose words sit at cow_off / slots_off of the blob.
-int launch_append_plan(sym_ctx* c, int64_t cow_off, int64_t slots_off, const void* k, const void* v, hipStream_t st) {
-  const int32_t* dw = (const int32_t*)c->cfg.workspace;
-  const int n_cow = (int)(c->plan.cow.size() / 3);
-  if (n_cow > 0) {
-    CowArgs ca{(uint8_t*)c->cfg.pool, c->page_bytes, dw + cow_off, c->cfg.n_kv_heads};
-    Timed t(c, SYM_K_COW, st);
-    hipError_t e = launch_cow(ca, n_cow, st);
-    if (e != hipSuccess) return fail_hip(c, e, "cow launch");
+// One prologue launch for the staged words in c->stage[si]: the first copy_words words (the
+// descriptor) are copied to the start of the workspace; the copy list at cow_off and the slot
+// map at slots_off are read from the pinned buffer by the kernel itself.  Records the event
+// that lets the staging buffer be reused.
+int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off,
+                           int32_t n_tokens, const void* k, const void* v, hipStream_t st) {
+  PrologueArgs a;
+  a.pool = (uint8_t*)c->cfg.pool;
+  a.page_bytes = c->page_bytes;
+  a.k_new = k;
+  a.v_new = v;
+  a.slots = c->stage[si] + slots_off;
+  a.cow = c->stage[si] + cow_off;
+  a.host_words = c->stage[si];
+  a.dev_words = (int32_t*)c->cfg.workspace;
+  a.copy_words = copy_words;
+  a.n_tokens = n_tokens;
+  a.Hkv = c->cfg.n_kv_heads;
+  a.n_cow = n_cow;
+  a.append_blocks = a.copy_blocks = 0;
+  {
+    Timed t(c, SYM_K_PROLOGUE, st);
+    hipError_t e = launch_prologue(a, st);
+    if (e != hipSuccess) return fail_hip(c, e, "prologue launch");
   }
-  AppendArgs aa{(uint8_t*)c->cfg.pool, c->page_bytes, k, v, dw + slots_off, (int32_t)c->plan.slots.size(), c->cfg.n_kv_heads};
-  Timed t(c, SYM_K_APPEND, st);
-  hipError_t e = launch_append(aa, st);
-  if (e != hipSuccess) return fail_hip(c, e, "append launch");
+  hipError_t e = hipEventRecord(c->stage_ev[si], st);
+  if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
+  c->stage_pending[si] = true;
   return SYM_OK;
 }
 
@@ -223,7 +216,7 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  DescParams prm{c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units};
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "build_desc: bad batch");
   return (int64_t)c->desc.words.size();
@@ -382,6 +375,8 @@ int sym_get_stats(sym_ctx* c, sym_stats* s) {
   s->kernel_launches = c->kernel_launches;
   s->files = c->fs->count_files();
   s->handles = c->fs->count_handles();
+  s->host_ns_plan = c->host_ns_plan;
+  s->host_ns_pred = c->host_ns_pred;
   return SYM_OK;
 }
 
@@ -423,8 +418,7 @@ int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v
   if ((rc = stage_acquire(c, words, &si))) return rc;
   std::memcpy(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
-  if ((rc = stage_submit(c, si, words, st))) return rc;
-  return launch_append_plan(c, 0, (int64_t)c->plan.cow.size(), k, v, st);
+  return launch_prologue_staged(c, si, 0, 0, (int)(c->plan.cow.size() / 3), (int64_t)c->plan.cow.size(), n, k, v, st);
 }
 
 int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q,
@@ -434,6 +428,7 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   if (!kv || !n_tokens || !q || !k_new || !v_new || !out) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  const auto t_begin = std::chrono::steady_clock::now();
   hipStream_t st = (hipStream_t)stream;
   const int P = c->cfg.page_tokens;
   // sizes after the append, for the workspace check that must precede any state change
@@ -457,7 +452,7 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  DescParams prm{c->cfg.n_kv_heads, P, c->max_waves, c->min_units};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units};
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
   const int64_t dwords = (int64_t)c->desc.words.size();
@@ -468,10 +463,16 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
   std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
-  if ((rc = stage_submit(c, si, words, st))) return rc;
-  if ((rc = launch_append_plan(c, cow_off, slots_off, k_new, v_new, st))) return rc;
+  const auto t_planned = std::chrono::steady_clock::now();
+  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, (int)(c->plan.cow.size() / 3), slots_off, (int32_t)c->plan.slots.size(),
+                                   k_new, v_new, st)))
+    return rc;
   ++c->pred_batches;
-  return launch_attention(c, words, q, out, st);
+  rc = launch_attention(c, words, q, out, st);
+  const auto t_end = std::chrono::steady_clock::now();
+  c->host_ns_plan += std::chrono::duration_cast<std::chrono::nanoseconds>(t_planned - t_begin).count();
+  c->host_ns_pred += std::chrono::duration_cast<std::chrono::nanoseconds>(t_end - t_begin).count();
+  return rc;
 }
 
 int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
@@ -489,7 +490,7 @@ int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   int si, rc;
   if ((rc = stage_acquire(c, dwords, &si))) return rc;
   std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
-  if ((rc = stage_submit(c, si, dwords, st))) return rc;
+  if ((rc = launch_prologue_staged(c, si, dwords, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
   ++c->pred_batches;
   return launch_attention(c, dwords, q, out, st);
 }
@@ -511,10 +512,12 @@ int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, vo
     c->stage[si][i] = f->pages[t / P] * P + (int32_t)(t % P);
   }
   hipStream_t st = (hipStream_t)stream;
-  if ((rc = stage_submit(c, si, n, st))) return rc;
-  AppendArgs aa{(uint8_t*)c->cfg.pool, c->page_bytes, nullptr, nullptr, (const int32_t*)c->cfg.workspace, n, c->cfg.n_kv_heads};
-  hipError_t e = launch_gather(aa, k_out, v_out, st);
+  GatherArgs ga{(const uint8_t*)c->cfg.pool, c->page_bytes, c->stage[si], n, c->cfg.n_kv_heads};
+  hipError_t e = launch_gather(ga, k_out, v_out, st);
   if (e != hipSuccess) return fail_hip(c, e, "gather launch");
+  e = hipEventRecord(c->stage_ev[si], st);
+  if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
+  c->stage_pending[si] = true;
   return SYM_OK;
 }
 

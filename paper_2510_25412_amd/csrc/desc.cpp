@@ -34,7 +34,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
-  const int64_t off_pt = off_merge + n_rows * H + 1;
+  const int64_t off_pt = off_merge + nw * MERGE_WORDS;      // at most one cut (row, head) per wave boundary
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
   const int64_t total = off_tiles;
@@ -49,14 +49,15 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int64_t r = 0, e = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     ptoff[b] = (int32_t)e;
+    const int64_t e_lip = e;
     int64_t np = (len_after[b] + P - 1) / P;
     std::memcpy(pt + e, tables[b], (size_t)np * sizeof(int32_t));
     e += np;
     for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
-      rows[r * ROW_WORDS + 0] = b;
+      rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
       rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
       rows[r * ROW_WORDS + 2] = (int32_t)r;                                       // q / out row
-      rows[r * ROW_WORDS + 3] = 0;
+      rows[r * ROW_WORDS + 3] = b;
     }
   }
   ptoff[n_lips] = (int32_t)e;
@@ -67,7 +68,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int64_t row = 0;          // current position of the walk: (row, g, p)
   int32_t g = 0, p = 0;
   int32_t part = 0;
-  int64_t next_merge = 0;     // merge[] entries filled so far
+  int32_t n_merge = 0;        // (row, head) ranges that were cut and need a merge
   auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
   for (int64_t k = 0; k < nw; ++k) {
     int64_t u0 = total_units * k / nw, u1 = total_units * (k + 1) / nw;
@@ -77,13 +78,24 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     waves[k * WAVE_WORDS + 2] = p;
     waves[k * WAVE_WORDS + 3] = (int32_t)remaining;
     waves[k * WAVE_WORDS + 4] = part;
-    waves[k * WAVE_WORDS + 5] = 0;
+    waves[k * WAVE_WORDS + 5] = remaining > 0 ? rows[row * ROW_WORDS + 1] : 0;
+    waves[k * WAVE_WORDS + 6] = remaining > 0 ? rows[row * ROW_WORDS + 2] : 0;
+    waves[k * WAVE_WORDS + 7] = remaining > 0 ? rows[row * ROW_WORDS + 0] : 0;
     while (remaining > 0) {
       int32_t np = row_pages(row);
       int32_t cnt = (int32_t)std::min<int64_t>(remaining, np - p);
-      int64_t key = row * H + g;
-      while (next_merge <= key) merge[next_merge++] = part;   // first partial of (row, g)
-      if (!(p == 0 && cnt == np)) ++part;                      // a whole (row, g) needs no partial
+      if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
+        if (p == 0) {                                          // first piece of a cut (row, g)
+          int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
+          it[0] = part;
+          it[1] = 0;
+          it[2] = rows[row * ROW_WORDS + 2] * prm.n_q_heads + g * (prm.n_q_heads / H);
+          it[3] = 0;
+          ++n_merge;
+        }
+        ++merge[(int64_t)(n_merge - 1) * MERGE_WORDS + 1];
+        ++part;
+      }
       remaining -= cnt;
       p += cnt;
       if (p == np) {
@@ -95,13 +107,13 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       }
     }
   }
-  while (next_merge <= n_rows * H) merge[next_merge++] = part;
 
   w[H_N_ROWS] = (int32_t)n_rows;
   w[H_N_WAVES] = (int32_t)nw;
   w[H_N_PARTIALS] = part;
   w[H_N_LIPS] = n_lips;
   w[H_N_TILES] = 0;
+  w[H_N_MERGE] = n_merge;
   w[H_OFF_ROWS] = (int32_t)off_rows;
   w[H_OFF_WAVES] = (int32_t)off_waves;
   w[H_OFF_MERGE] = (int32_t)off_merge;
@@ -114,6 +126,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   out->n_rows = (int32_t)n_rows;
   out->n_waves = (int32_t)nw;
   out->n_partials = part;
+  out->n_merge = n_merge;
   out->n_lips = n_lips;
   out->total_units = total_units;
   return SYM_OK;

@@ -7,7 +7,7 @@
 // slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves equal
 // contiguous ranges, one per wavefront, whatever the raggedness of the files.  A range
 // that covers only part of a (row, kv head) produces a partial result (running max, sum,
-// unnormalised accumulator) that the merge kernel combines; a range covering a whole
+// unnormalised accumulator) and an entry in the merge list; a range covering a whole
 // (row, kv head) writes the final output directly and has no partial.
 #pragma once
 #include <cstdint>
@@ -15,26 +15,25 @@
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 6 };
+enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 8, MERGE_WORDS = 4 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
   H_OFF_ROWS, H_OFF_WAVES, H_OFF_MERGE, H_OFF_PT, H_OFF_PTOFF, H_OFF_TILES, H_TOTAL_WORDS,
-  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI
+  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI, H_N_MERGE
 };
 
 struct BatchDesc {
   std::vector<int32_t> words;      // packed descriptor, header first
-  int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0;
+  int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0;
   int64_t total_units = 0;
 
   const int32_t* rows() const { return words.data() + words[H_OFF_ROWS]; }
   const int32_t* waves() const { return words.data() + words[H_OFF_WAVES]; }
-  const int32_t* merge_off() const { return words.data() + words[H_OFF_MERGE]; }
 };
 
 struct DescParams {
-  int32_t n_kv_heads, page_tokens;
+  int32_t n_q_heads, n_kv_heads, page_tokens;
   int32_t max_waves;          // wavefront slots of the decode launch
   int32_t min_units_per_wave; // do not cut finer than this (keeps partial traffic small)
 };

@@ -7,6 +7,7 @@
 // [16 tokens][128 bytes], 8 KiB, so 8 tokens of one row half are 1 KiB contiguous.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 #include "kernels.hpp"
@@ -84,7 +85,8 @@ struct PageRegs {
 // half page, j = lane%8: which 16-byte chunk of each row half).  Every lane keeps its own
 // running max / sum / accumulators over the tokens it sees (2 per page), so the page loop
 // has no cross-lane traffic except the 8-lane score reduction; the 8 token slots are
-// combined once, when a (row, kv head) range ends.
+// combined once, when a (row, kv head) range ends; a range that is only part of its (row, kv
+// head) leaves a partial result for the merge kernel.
 // ---------------------------------------------------------------------------------------
 template <typename E, int G>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(DecodeArgs a) {
@@ -96,20 +98,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
-  const int32_t* ww = a.waves + wv * 6;
+  const int32_t* ww = a.waves + wv * 8;
   int row = __builtin_amdgcn_readfirstlane(ww[0]);
   int g = __builtin_amdgcn_readfirstlane(ww[1]);
   int p = __builtin_amdgcn_readfirstlane(ww[2]);
   int remaining = __builtin_amdgcn_readfirstlane(ww[3]);
   int part = __builtin_amdgcn_readfirstlane(ww[4]);
+  // row data of the first range travels with the wave's work item (one dependent load less)
+  int vis = __builtin_amdgcn_readfirstlane(ww[5]);
+  int qrow = __builtin_amdgcn_readfirstlane(ww[6]);
+  int tbl_off = __builtin_amdgcn_readfirstlane(ww[7]);
 
   while (remaining > 0) {
-    const int b = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
-    const int vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
-    const int qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
     const int np = (vis + kP - 1) / kP;
     const int cnt = min(remaining, np - p);
-    const int32_t* tbl = a.pt + __builtin_amdgcn_readfirstlane(a.ptoff[b]) + p;
+    const int32_t* tbl = a.pt + tbl_off + p;
 
     // q chunks of this lane for the G heads of kv head g
     uint4 q[G][2];
@@ -197,24 +200,31 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
     };
 
     // Page ids come through the scalar cache, two pages ahead of their K/V loads.  Every load in
-    // the loop is unconditional (past the end the last page is fetched again and ignored), so the
-    // loop body has no control-flow join between a prefetch and its use and the compiler can wait
-    // for exactly the older page while the newer one is in flight.
+    // the loop is unconditional, so the loop body has no control-flow join between a prefetch and
+    // its use and the compiler can wait for exactly the older page while the newer one is in
+    // flight.  Past the end of the range the prefetch is pointed at page 0 of the pool (valid
+    // memory that every wave touches, so it stays in L2) and its data is never used.
     const int last = cnt - 1;
-    int id1 = tbl[min(1, last)], id2 = tbl[min(2, last)];
+    int id1 = cnt > 1 ? tbl[1] : 0, id2 = cnt > 2 ? tbl[2] : 0;
     PageRegs A, B;
     load_page(A, tbl[0]);
     for (int k = 0; k < cnt; k += 2) {
       load_page(B, id1);
-      id1 = tbl[min(k + 3, last)];
+      id1 = k + 3 <= last ? tbl[k + 3] : 0;
       compute(A, p + k);
       load_page(A, id2);
-      id2 = tbl[min(k + 4, last)];
+      id2 = k + 4 <= last ? tbl[k + 4] : 0;
       if (k + 1 < cnt) compute(B, p + k + 1);
     }
 
-    // combine the 8 token slots (lanes with equal j): max, rescale, sum
+    // ---- end of a (row, kv head) range: combine the 8 token slots (lanes with equal j).
+    // Per head: common max M, rescale, total sum.  The G*DPL accumulators are then reduced with
+    // a halving exchange (lane bit 5, 4, 3 in turn: keep one half of the list, send the other), so
+    // lane (r, j) ends up owning the fully reduced values r*V/8 .. r*V/8 + V/8 - 1 of the list.
     const bool whole = (p == 0 && cnt == np);
+    constexpr int V = G * DPL;
+    float vals[V];
+    float lsum[G], Mh[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float M = m[h];
@@ -226,33 +236,56 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
       ls += row_xor8(ls);
       ls += __shfl_xor(ls, 16);
       ls += __shfl_xor(ls, 32);
+      lsum[h] = ls;
+      Mh[h] = M;
 #pragma unroll
-      for (int d = 0; d < DPL; ++d) {
-        float x = acc[h][d] * f;
-        x += row_xor8(x);
-        x += __shfl_xor(x, 16);
-        x += __shfl_xor(x, 32);
-        acc[h][d] = x;
+      for (int d = 0; d < DPL; ++d) vals[h * DPL + d] = acc[h][d] * f;
+    }
+    {
+      const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+#pragma unroll
+      for (int i = 0; i < V / 2; ++i) {
+        const float keep = b5 ? vals[i + V / 2] : vals[i], send = b5 ? vals[i] : vals[i + V / 2];
+        vals[i] = keep + __shfl_xor(send, 32);
       }
-      if (r == 0) {
-        if (whole) {
-          const float inv = 1.0f / ls;
-          float* o = a.out + ((int64_t)qrow * a.Hq + g * G + h) * D + j * C;
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < V / 4; ++i) {
+        const float keep = b4 ? vals[i + V / 4] : vals[i], send = b4 ? vals[i] : vals[i + V / 4];
+        vals[i] = keep + __shfl_xor(send, 16);
+      }
 #pragma unroll
-            for (int e = 0; e < C; ++e) o[i * (D / 2) + e] = acc[h][i * C + e] * inv;
-        } else {
-          float* o = a.part_acc + ((int64_t)part * G + h) * D + j * C;
+      for (int i = 0; i < V / 8; ++i) {
+        const float keep = b3 ? vals[i + V / 8] : vals[i], send = b3 ? vals[i] : vals[i + V / 8];
+        vals[i] = keep + row_xor8(send);
+      }
+    }
+    // lane (r, j) now holds list entries idx = r * V/8 + t: head idx / DPL, lane-local dim idx % DPL
+    const int64_t out_row = ((int64_t)qrow * a.Hq + g * G) * D;
+    if (whole) {
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+      for (int t = 0; t < V / 8; ++t) {
+        const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+        float ls = lsum[0];
 #pragma unroll
-            for (int e = 0; e < C; ++e) o[i * (D / 2) + e] = acc[h][i * C + e];
-          if (j == 0) {
-            a.part_ml[((int64_t)part * G + h) * 2 + 0] = M;
-            a.part_ml[((int64_t)part * G + h) * 2 + 1] = ls;
-          }
+        for (int hh = 1; hh < G; ++hh) ls = (h == hh) ? lsum[hh] : ls;
+        a.out[out_row + h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t] / ls;
+      }
+    } else {
+      float* pa = a.part_acc + (int64_t)part * G * D;
+#pragma unroll
+      for (int t = 0; t < V / 8; ++t) {
+        const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+        pa[h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t];
+      }
+      if (lane < G) {
+        float mm = Mh[0], ll = lsum[0];
+#pragma unroll
+        for (int hh = 1; hh < G; ++hh) {
+          mm = (lane == hh) ? Mh[hh] : mm;
+          ll = (lane == hh) ? lsum[hh] : ll;
         }
+        a.part_ml[((int64_t)part * G + lane) * 2 + 0] = mm;
+        a.part_ml[((int64_t)part * G + lane) * 2 + 1] = ll;
       }
     }
     if (!whole) ++part;
@@ -263,56 +296,131 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
       if (++g == a.Hkv) {
         g = 0;
         ++row;
+        if (remaining > 0) {
+          tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
+          vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
+          qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
+        }
       }
     }
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// Merge of partial results: out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).
-// One block per (row, query head), one thread per dim.
+// Merge of partial results, one wavefront per (row, kv head) that was cut:
+//   out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M),  M = max_i m_i.
+// The G*D accumulator values of a piece form one flat list; lane owns entries e*64 + lane.  All
+// loads of a group of 4 pieces are issued before any is used (indices past the end re-read the
+// last piece with weight 0), so the kernel costs a few memory round trips.
 // ---------------------------------------------------------------------------------------
-__global__ void merge_kernel(MergeArgs a) {
-  const int row = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
-  const int G = a.Hq / a.Hkv;
-  const int g = hq / G, h = hq % G;
-  const int p0 = a.merge_off[row * a.Hkv + g], p1 = a.merge_off[row * a.Hkv + g + 1];
-  if (p1 == p0) return;                       // written directly by the decode kernel
-  const int d = threadIdx.x;
-  float M = -__builtin_inff();
-  for (int i = p0; i < p1; ++i) M = fmaxf(M, a.part_ml[((int64_t)i * G + h) * 2]);
-  float ls = 0.f, o = 0.f;
-  for (int i = p0; i < p1; ++i) {
-    const float f = __builtin_amdgcn_exp2f(a.part_ml[((int64_t)i * G + h) * 2] - M);
-    ls += a.part_ml[((int64_t)i * G + h) * 2 + 1] * f;
-    o += a.part_acc[((int64_t)i * G + h) * a.D + d] * f;
+template <int G, int D>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+  if (item >= a.n_items) return;
+  const int first = __builtin_amdgcn_readfirstlane(a.items[item * 4 + 0]);
+  const int pieces = __builtin_amdgcn_readfirstlane(a.items[item * 4 + 1]);
+  const int64_t out_row = (int64_t)__builtin_amdgcn_readfirstlane(a.items[item * 4 + 2]) * D;   // (q row * Hq + first head) * D
+  constexpr int VL = G * D / 64;
+  const float* ml0 = a.part_ml + (int64_t)first * G * 2;
+  const float* pa0 = a.part_acc + (int64_t)first * G * D + lane;
+  float Mx[G], ls[G], o[VL];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    Mx[h] = -__builtin_inff();
+    ls[h] = 0.f;
   }
-  const int qrow = a.rows[row * 4 + 2];
-  a.out[((int64_t)qrow * a.Hq + hq) * a.D + d] = o / ls;
+#pragma unroll
+  for (int e = 0; e < VL; ++e) o[e] = 0.f;
+  for (int i0 = 0; i0 < pieces; i0 += 4) {
+    float mv[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int h = 0; h < G; ++h) mv[u][h] = ml0[((int64_t)min(i0 + u, pieces - 1) * G + h) * 2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int h = 0; h < G; ++h) Mx[h] = fmaxf(Mx[h], mv[u][h]);
+  }
+  for (int i0 = 0; i0 < pieces; i0 += 4) {
+    float mv[4][G], lv[4][G], t[4][VL];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t ii = min(i0 + u, pieces - 1);
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        mv[u][h] = ml0[(ii * G + h) * 2];
+        lv[u][h] = ml0[(ii * G + h) * 2 + 1];
+      }
+#pragma unroll
+      for (int e = 0; e < VL; ++e) t[u][e] = pa0[ii * G * D + e * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float w[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        w[h] = (i0 + u < pieces) ? __builtin_amdgcn_exp2f(mv[u][h] - Mx[h]) : 0.f;
+        ls[h] = __builtin_fmaf(lv[u][h], w[h], ls[h]);
+      }
+#pragma unroll
+      for (int e = 0; e < VL; ++e) o[e] = __builtin_fmaf(t[u][e], w[(e * 64) / D], o[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VL; ++e) a.out[out_row + e * 64 + lane] = o[e] / ls[(e * 64) / D];
 }
 
 // ---------------------------------------------------------------------------------------
-// KV append: one thread per 16-byte chunk of a new K or V row.
+// Prologue of a batch, one launch: (1) KV append, one thread per 16-byte chunk of a new K or
+// V row; (2) copy-on-write page copies, one block per copy: slots [0, r) of every (head, K/V,
+// row half) of page src into page dst; (3) the batch descriptor copied from pinned host memory
+// into the device workspace for the attention kernel that follows.  The three parts touch
+// disjoint bytes (a copy covers slots below r, appends write slots from r on), so they need
+// no ordering among themselves.  Slot map and copy list are read straight from the pinned
+// host buffer.
 // ---------------------------------------------------------------------------------------
-__global__ void append_kernel(AppendArgs a) {
-  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
-  if (tid >= total) return;
-  const int c = tid & 15;                 // chunk within the row
-  const int kv = (tid >> 4) & 1;
-  const int64_t th = tid >> 5;            // token * Hkv + head
-  const int g = (int)(th % a.Hkv);
-  const int64_t t = th / a.Hkv;
-  const int slot = a.slots[t];
-  const int page = slot / kP, ts = slot % kP;
-  const uint8_t* src = (const uint8_t*)(kv ? a.v_new : a.k_new) + th * kRowBytes + c * 16;
-  uint8_t* dst = a.pool + (int64_t)page * a.page_bytes + (int64_t)g * kSlab + kv * kBlk +
-                 (c >> 3) * (kP * kHalfBytes) + ts * kHalfBytes + (c & 7) * 16;
-  *(uint4*)dst = *(const uint4*)src;
+__global__ __launch_bounds__(256) void prologue_kernel(PrologueArgs a) {
+  int blk = blockIdx.x;
+  if (blk < a.append_blocks) {
+    const int64_t tid = (int64_t)blk * 256 + threadIdx.x;
+    const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
+    if (tid >= total) return;
+    const int c = tid & 15;                 // chunk within the row
+    const int kv = (tid >> 4) & 1;
+    const int64_t th = tid >> 5;            // token * Hkv + head
+    const int g = (int)(th % a.Hkv);
+    const int64_t t = th / a.Hkv;
+    const int slot = a.slots[t];
+    const int page = slot / kP, ts = slot % kP;
+    const uint8_t* src = (const uint8_t*)(kv ? a.v_new : a.k_new) + th * kRowBytes + c * 16;
+    uint8_t* dst = a.pool + (int64_t)page * a.page_bytes + (int64_t)g * kSlab + kv * kBlk +
+                   (c >> 3) * (kP * kHalfBytes) + ts * kHalfBytes + (c & 7) * 16;
+    *(uint4*)dst = *(const uint4*)src;
+    return;
+  }
+  blk -= a.append_blocks;
+  if (blk < a.n_cow) {
+    const int src = a.cow[blk * 3 + 0], dst = a.cow[blk * 3 + 1], r = a.cow[blk * 3 + 2];
+    const uint8_t* s = a.pool + (int64_t)src * a.page_bytes;
+    uint8_t* d = a.pool + (int64_t)dst * a.page_bytes;
+    const int per_seg = r * (kHalfBytes / 16);           // 16-byte chunks per (head, K/V, half)
+    const int n_seg = a.Hkv * 4;
+    for (int x = threadIdx.x; x < n_seg * per_seg; x += 256) {
+      const int seg = x / per_seg, w = x % per_seg;
+      const int64_t off = (int64_t)seg * (kP * kHalfBytes) + w * 16;
+      *(uint4*)(d + off) = *(const uint4*)(s + off);
+    }
+    return;
+  }
+  blk -= a.n_cow;
+  for (int64_t i = (int64_t)blk * 256 + threadIdx.x; i < a.copy_words; i += (int64_t)a.copy_blocks * 256)
+    a.dev_words[i] = a.host_words[i];
 }
 
 // Inverse of append for a list of token slots: pool -> contiguous [n][Hkv][row].
-__global__ void gather_kernel(AppendArgs a, uint8_t* k_out, uint8_t* v_out) {
+__global__ void gather_kernel(GatherArgs a, uint8_t* k_out, uint8_t* v_out) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
   if (tid >= total) return;
@@ -327,23 +435,6 @@ __global__ void gather_kernel(AppendArgs a, uint8_t* k_out, uint8_t* v_out) {
                        (c >> 3) * (kP * kHalfBytes) + ts * kHalfBytes + (c & 7) * 16;
   uint8_t* dst = (kv ? v_out : k_out) + th * kRowBytes + c * 16;
   *(uint4*)dst = *(const uint4*)src;
-}
-
-// ---------------------------------------------------------------------------------------
-// Copy-on-write: slots [0, r) of every (head, K/V, row half) of page src into page dst.
-// One block per copy.
-// ---------------------------------------------------------------------------------------
-__global__ void cow_kernel(CowArgs a) {
-  const int src = a.cow[blockIdx.x * 3 + 0], dst = a.cow[blockIdx.x * 3 + 1], r = a.cow[blockIdx.x * 3 + 2];
-  const uint8_t* s = a.pool + (int64_t)src * a.page_bytes;
-  uint8_t* d = a.pool + (int64_t)dst * a.page_bytes;
-  const int per_seg = r * (kHalfBytes / 16);           // 16-byte chunks per (head, K/V, half)
-  const int n_seg = a.Hkv * 4;
-  for (int x = threadIdx.x; x < n_seg * per_seg; x += blockDim.x) {
-    const int seg = x / per_seg, w = x % per_seg;
-    const int64_t off = (int64_t)seg * (kP * kHalfBytes) + w * 16;
-    *(uint4*)(d + off) = *(const uint4*)(s + off);
-  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -399,29 +490,31 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st) {
   return dtype == 0 ? launch_decode_g<ElemF32>(a, st) : launch_decode_g<ElemBF16>(a, st);
 }
 
-hipError_t launch_merge(const MergeArgs& a, int n_rows, hipStream_t st) {
-  if (n_rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_kernel, dim3(n_rows * a.Hq), dim3(a.D), 0, st, a);
-  return hipGetLastError();
+hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {
+  if (a.n_items <= 0) return hipSuccess;
+  const dim3 grid((a.n_items + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
+#define SYM_MERGE_CASE(GG, DD) \
+  if (G == GG && D == DD) { hipLaunchKernelGGL((merge_kernel<GG, DD>), grid, block, 0, st, a); return hipGetLastError(); }
+  SYM_MERGE_CASE(1, 64) SYM_MERGE_CASE(2, 64) SYM_MERGE_CASE(4, 64) SYM_MERGE_CASE(8, 64)
+  SYM_MERGE_CASE(1, 128) SYM_MERGE_CASE(2, 128) SYM_MERGE_CASE(4, 128) SYM_MERGE_CASE(8, 128)
+#undef SYM_MERGE_CASE
+  return hipErrorInvalidValue;
 }
 
-hipError_t launch_append(const AppendArgs& a, hipStream_t st) {
-  if (a.n_tokens <= 0) return hipSuccess;
+hipError_t launch_prologue(PrologueArgs a, hipStream_t st) {
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
-  hipLaunchKernelGGL(append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+  a.append_blocks = (int32_t)((total + 255) / 256);
+  a.copy_blocks = a.copy_words > 0 ? (int32_t)std::min<int64_t>((a.copy_words + 255) / 256, 64) : 0;
+  const int64_t blocks = (int64_t)a.append_blocks + a.n_cow + a.copy_blocks;
+  if (blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(prologue_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_gather(const AppendArgs& a, void* k_out, void* v_out, hipStream_t st) {
+hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st) {
   if (a.n_tokens <= 0) return hipSuccess;
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
   hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, (uint8_t*)k_out, (uint8_t*)v_out);
-  return hipGetLastError();
-}
-
-hipError_t launch_cow(const CowArgs& a, int n_cow, hipStream_t st) {
-  if (n_cow <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cow_kernel, dim3(n_cow), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

@@ -13,10 +13,10 @@ struct DecodeArgs {
   float* out;               // [rows][Hq][D]
   float* part_acc;          // [n_partials][G][D]
   float* part_ml;           // [n_partials][G][2] (max in log2 units, sum)
-  const int32_t* rows;      // [n_rows][4]: lip, visible tokens, q/out row, 0
-  const int32_t* waves;     // [n_waves][6]: row, kv head, page, units, first partial, 0
+  const int32_t* rows;      // [n_rows][4]: page-table offset, visible tokens, q/out row, lip
+  const int32_t* waves;     // [n_waves][8]: row, kv head, page, units, first partial, then the
+                            //   first range's visible tokens, q/out row, page-table offset
   const int32_t* pt;        // flattened page tables
-  const int32_t* ptoff;     // [n_lips + 1]
   int32_t n_waves, Hq, Hkv;
   float scale_log2e;        // softmax scale * log2(e)
 };
@@ -24,33 +24,36 @@ struct DecodeArgs {
 struct MergeArgs {
   const float* part_acc;
   const float* part_ml;
-  const int32_t* merge_off; // [n_rows * Hkv + 1]
-  const int32_t* rows;
+  const int32_t* items;     // [n_items][4]: first partial, pieces, q row * Hq + first head, 0
   float* out;
-  int32_t Hq, Hkv, D;
+  int32_t n_items;
 };
 
-struct AppendArgs {
+struct PrologueArgs {
   uint8_t* pool;
   int64_t page_bytes;
-  const void* k_new;        // [n_tokens][Hkv][row]
+  const void* k_new;            // device [n_tokens][Hkv][row]
   const void* v_new;
-  const int32_t* slots;     // [n_tokens]: page * P + slot
+  const int32_t* slots;         // pinned host [n_tokens]: page * P + slot
+  const int32_t* cow;           // pinned host [n_cow][3]: src, dst, slots
+  const int32_t* host_words;    // pinned host: descriptor words to copy
+  int32_t* dev_words;           // device workspace
+  int64_t copy_words;
+  int32_t n_tokens, Hkv, n_cow;
+  int32_t append_blocks, copy_blocks;   // filled by launch_prologue
+};
+
+struct GatherArgs {
+  const uint8_t* pool;
+  int64_t page_bytes;
+  const int32_t* slots;         // pinned host or device [n_tokens]
   int32_t n_tokens, Hkv;
 };
 
-struct CowArgs {
-  uint8_t* pool;
-  int64_t page_bytes;
-  const int32_t* cow;       // [n][3]: src, dst, slots
-  int32_t Hkv;
-};
-
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st);
-hipError_t launch_merge(const MergeArgs& a, int n_rows, hipStream_t st);
-hipError_t launch_append(const AppendArgs& a, hipStream_t st);
-hipError_t launch_gather(const AppendArgs& a, void* k_out, void* v_out, hipStream_t st);
-hipError_t launch_cow(const CowArgs& a, int n_cow, hipStream_t st);
+hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
+hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
+hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st);
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st);
 

@@ -203,3 +203,38 @@ def test_raw_entry_matches_allocator_entry():
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), got)
     sess.close()
+
+
+def test_split_invariance_many_launches():
+    """The same batch cut into 2048 wave ranges (many partial results merged by the last wave to
+    arrive) and into 12 ranges gives the same outputs, launch after launch with fresh queries:
+    a stale or half-written partial from another XCD would show up here."""
+    drv = _hip()
+    wl = synth.config2(n_lips=24, lo=60, hi=2500, slack_pages=32)
+    sa = drv.HipSession(wl.shape, wl.n_pages, decode_waves=2048)
+    sb = drv.HipSession(wl.shape, wl.n_pages, decode_waves=12)
+    ops = list(wl.setup_ops())
+    sa.setup(ops)
+    sb.setup(ops)
+    tables = [sa.pages(f) for f in wl.batch_files]
+    assert tables == [sb.pages(f) for f in wl.batch_files]
+    flat = np.concatenate(tables).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+    lengths = [wl.lengths[f] for f in wl.batch_files]
+    n = len(lengths)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    oa = torch.empty((n, 32, 128), dtype=torch.float32, device="cuda")
+    ob = torch.empty_like(oa)
+    worst = 0.0
+    for it in range(60):
+        q = torch.randn((n, 32, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        oa.fill_(float("nan"))
+        ob.fill_(float("nan"))
+        sa.ctx.pred_batch_raw([1] * n, flat, off, lengths, q, oa, sa.stream)
+        sb.ctx.pred_batch_raw([1] * n, flat, off, lengths, q, ob, sb.stream)
+        torch.cuda.synchronize()
+        d = ((oa - ob).abs() / ob.abs().clamp(min=1.0)).max().item()
+        assert d == d and d <= 2e-5, f"launch {it}: split results differ by {d}"
+        worst = max(worst, d)
+    sa.close()
+    sb.close()

@@ -147,8 +147,8 @@ def _walk_desc(words, Hkv, P=16):
     hdr = words[:16]
     n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
-    waves = words[hdr[6]:hdr[6] + 6 * n_waves].reshape(n_waves, 6)
-    merge = words[hdr[7]:hdr[7] + n_rows * Hkv + 1]
+    waves = words[hdr[6]:hdr[6] + 8 * n_waves].reshape(n_waves, 8)
+    merge = words[hdr[7]:hdr[7] + 4 * int(hdr[14])].reshape(int(hdr[14]), 4)
     pt = words[hdr[8]:hdr[9]]
     ptoff = words[hdr[9]:hdr[9] + n_lips + 1]
     return n_rows, n_waves, n_partials, rows, waves, merge, pt, ptoff
@@ -168,14 +168,16 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert n_rows == sum(n_tok) and np.array_equal(pt, flat) and np.array_equal(ptoff, off)
     # rows: lip, visible tokens, q row
     exp_rows = [(b, L - n + i + 1, None) for b, (L, n) in enumerate(zip(lengths, n_tok)) for i in range(n)]
-    assert [(int(r[0]), int(r[1])) for r in rows] == [(b, v) for b, v, _ in exp_rows]
+    assert [(int(r[3]), int(r[1])) for r in rows] == [(b, v) for b, v, _ in exp_rows]
     assert rows[:, 2].tolist() == list(range(n_rows))
+    assert [int(r[0]) for r in rows] == [int(off[b]) for b, _, _ in exp_rows]
     # walk every wave's range exactly as the kernel does; record coverage and partial numbering
     cover = {}
     units = []
     pieces = {}
     for k in range(n_waves):
         row, g, p, rem, part = (int(x) for x in wv[k, :5])
+        assert wv[k, 5:8].tolist() == [int(rows[row, 1]), int(rows[row, 2]), int(rows[row, 0])]   # first range's row data
         units.append(rem)
         while rem > 0:
             npg = -(-int(rows[row, 1]) // 16)
@@ -197,14 +199,19 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert len(cover) == total and sum(units) == total
     assert max(units) - min(units) <= 1                      # equal ranges whatever the raggedness
     assert n_waves <= waves
+    items = {}
+    for first, cnt, out_idx, _ in merge.tolist():
+        items[out_idx] = (first, cnt)
     seen_parts = []
     for (row, g), ps in sorted(pieces.items()):
-        lo, hi = int(merge[row * Hkv + g]), int(merge[row * Hkv + g + 1])
+        out_idx = int(rows[row, 2]) * 32 + g * 4          # q row * Hq + first query head of the group
         if ps == [None]:
-            assert lo == hi                                   # whole range: final output, no partial
+            assert out_idx not in items                       # whole range: final output, no partial
         else:
-            assert None not in ps and ps == list(range(lo, hi))
+            first, cnt = items.pop(out_idx)
+            assert None not in ps and ps == list(range(first, first + cnt))
             seen_parts += ps
+    assert not items
     assert seen_parts == list(range(n_partials)) and n_partials <= 2 * n_waves
 
 
