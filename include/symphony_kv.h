@@ -78,7 +78,8 @@ typedef struct sym_stats {
   int64_t files, handles;
   int64_t host_ns_plan;   /* host time inside sym_pred_batch spent on append planning +
                              descriptor build + staging, summed over calls, nanoseconds    */
-  int64_t host_ns_pred;   /* host time of whole sym_pred_batch calls (planning + launches)  */
+  int64_t host_ns_pred;   /* host time of whole sym_pred_batch calls (planning + launches),
+                             not counting waits for a staging buffer still in use by the GPU */
 } sym_stats;
 
 /* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).
@@ -155,8 +156,9 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
  * Layout: words[0..15] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then
  * word offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total
  * words; total units (lo, hi); n_merge}, then the sections: rows [n_rows][4] = {page-table
- * offset, visible tokens, q/out row, lip}; wave_work [n_waves][8] = {row, kv head, page,
- * units, first partial, visible tokens, q/out row, page-table offset of the first range};
+ * offset, visible tokens, q/out row, lip}; wave_work [n_waves][12] = {row, kv head, page,
+ * units, first partial, then of the first range: visible tokens, q/out row, page-table
+ * offset, ids of its first three pages, 0};
  * merge [n_merge][4] = {first partial, pieces, q row * Hq + first query head, 0} for each
  * (row, kv head) that was cut.  Returns the number of words (or a negative status); writes at most
  * cap words.                                                                              */

@@ -33,7 +33,7 @@ struct sym_ctx {
   int32_t G = 1;
   int64_t page_bytes = 0;
   float scale_log2e = 0.f;
-  int32_t max_waves = 0, min_units = 4;
+  int32_t max_waves = 0, min_units = 4, range_cost = 3;
   std::mutex mu;
   std::string err;
   Kvfs* fs = nullptr;
@@ -216,7 +216,7 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost};
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "build_desc: bad batch");
   return (int64_t)c->desc.words.size();
@@ -276,6 +276,7 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   }
   c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
   c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
+  c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
     return SYM_ENOSPC;
@@ -452,14 +453,16 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost};
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
   const int64_t dwords = (int64_t)c->desc.words.size();
   const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
   const int64_t words = slots_off + (int64_t)c->plan.slots.size();
+  const auto t_built = std::chrono::steady_clock::now();
   int si;
-  if ((rc = stage_acquire(c, words, &si))) return rc;
+  if ((rc = stage_acquire(c, words, &si))) return rc;      // may wait for the GPU: not host work
+  const auto t_acquired = std::chrono::steady_clock::now();
   std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
   std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
@@ -470,8 +473,9 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   ++c->pred_batches;
   rc = launch_attention(c, words, q, out, st);
   const auto t_end = std::chrono::steady_clock::now();
-  c->host_ns_plan += std::chrono::duration_cast<std::chrono::nanoseconds>(t_planned - t_begin).count();
-  c->host_ns_pred += std::chrono::duration_cast<std::chrono::nanoseconds>(t_end - t_begin).count();
+  const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
+  c->host_ns_plan += ns(t_built - t_begin) + ns(t_planned - t_acquired);
+  c->host_ns_pred += ns(t_end - t_begin) - ns(t_acquired - t_built);
   return rc;
 }
 

@@ -62,28 +62,57 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   }
   ptoff[n_lips] = (int32_t)e;
 
-  // ---- cut the unit sequence into nw equal ranges; number the partial results
+  // ---- cut the unit sequence into nw ranges of equal cost; number the partial results.
+  // Cost of a range = its units + range_cost per (row, head) it starts in (the end-of-range
+  // combine and the restart of the pipeline are not free).  On a virtual axis where every
+  // (row, head) occupies range_cost + pages, wave k ends at total * (k+1) / nw; a cut that
+  // falls into the overhead part of a (row, head) snaps to its first page.
   int32_t* waves = w.data() + off_waves;
   int32_t* merge = w.data() + off_merge;
-  int64_t row = 0;          // current position of the walk: (row, g, p)
-  int32_t g = 0, p = 0;
+  auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
+  const int64_t alpha = prm.range_cost;
+  const int64_t vtotal = total_units + alpha * n_rows * H;
+  {
+    int64_t k = 0, vstart = 0;     // next boundary to place; virtual start of the current (row, head)
+    for (int64_t row = 0; row < n_rows && k < nw; ++row) {
+      const int32_t np = row_pages(row);
+      for (int32_t g = 0; g < H && k < nw; ++g) {
+        const int64_t vend = vstart + alpha + np;
+        while (k < nw && vtotal * k / nw < vend) {
+          const int64_t o = vtotal * k / nw - vstart;
+          int32_t* ww = waves + k * WAVE_WORDS;
+          ww[0] = (int32_t)row;
+          ww[1] = g;
+          ww[2] = (int32_t)std::max<int64_t>(0, o - alpha);
+          ++k;
+        }
+        vstart = vend;
+      }
+    }
+  }
   int32_t part = 0;
   int32_t n_merge = 0;        // (row, head) ranges that were cut and need a merge
-  auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
   for (int64_t k = 0; k < nw; ++k) {
-    int64_t u0 = total_units * k / nw, u1 = total_units * (k + 1) / nw;
-    int64_t remaining = u1 - u0;
-    waves[k * WAVE_WORDS + 0] = (int32_t)row;
-    waves[k * WAVE_WORDS + 1] = g;
-    waves[k * WAVE_WORDS + 2] = p;
-    waves[k * WAVE_WORDS + 3] = (int32_t)remaining;
-    waves[k * WAVE_WORDS + 4] = part;
-    waves[k * WAVE_WORDS + 5] = remaining > 0 ? rows[row * ROW_WORDS + 1] : 0;
-    waves[k * WAVE_WORDS + 6] = remaining > 0 ? rows[row * ROW_WORDS + 2] : 0;
-    waves[k * WAVE_WORDS + 7] = remaining > 0 ? rows[row * ROW_WORDS + 0] : 0;
-    while (remaining > 0) {
-      int32_t np = row_pages(row);
-      int32_t cnt = (int32_t)std::min<int64_t>(remaining, np - p);
+    int32_t* ww = waves + k * WAVE_WORDS;
+    int64_t row = ww[0];
+    int32_t g = ww[1], p = ww[2];
+    // the range ends where the next one starts (or at the end of the batch)
+    const int64_t erow = k + 1 < nw ? ww[WAVE_WORDS + 0] : n_rows;
+    const int32_t eg = k + 1 < nw ? ww[WAVE_WORDS + 1] : 0, ep = k + 1 < nw ? ww[WAVE_WORDS + 2] : 0;
+    ww[4] = part;
+    ww[5] = rows[row * ROW_WORDS + 1];
+    ww[6] = rows[row * ROW_WORDS + 2];
+    ww[7] = rows[row * ROW_WORDS + 0];
+    for (int i = 0; i < 4; ++i) ww[8 + i] = 0;
+    {                                   // ids of the first pages: their loads need no table lookup
+      const int32_t np0 = row_pages(row);
+      const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
+      for (int i = 0; i < 3; ++i) ww[8 + i] = t0[std::min(p + i, np0 - 1)];
+    }
+    int64_t units = 0;
+    while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
+      const int32_t np = row_pages(row);
+      const int32_t cnt = (row == erow && g == eg) ? ep - p : np - p;
       if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
         if (p == 0) {                                          // first piece of a cut (row, g)
           int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
@@ -96,7 +125,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
         ++merge[(int64_t)(n_merge - 1) * MERGE_WORDS + 1];
         ++part;
       }
-      remaining -= cnt;
+      units += cnt;
       p += cnt;
       if (p == np) {
         p = 0;
@@ -106,6 +135,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
         }
       }
     }
+    ww[3] = (int32_t)units;
   }
 
   w[H_N_ROWS] = (int32_t)n_rows;

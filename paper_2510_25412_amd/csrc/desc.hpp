@@ -4,8 +4,8 @@
 //
 // Every new token is a "row" with a visible length (file tokens 0 .. len_before + i).  The
 // work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
-// slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves equal
-// contiguous ranges, one per wavefront, whatever the raggedness of the files.  A range
+// slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves contiguous
+// ranges of equal cost, one per wavefront, whatever the raggedness of the files.  A range
 // that covers only part of a (row, kv head) produces a partial result (running max, sum,
 // unnormalised accumulator) and an entry in the merge list; a range covering a whole
 // (row, kv head) writes the final output directly and has no partial.
@@ -15,7 +15,7 @@
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 8, MERGE_WORDS = 4 };
+enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 4 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
@@ -36,6 +36,7 @@ struct DescParams {
   int32_t n_q_heads, n_kv_heads, page_tokens;
   int32_t max_waves;          // wavefront slots of the decode launch
   int32_t min_units_per_wave; // do not cut finer than this (keeps partial traffic small)
+  int32_t range_cost;         // cost of starting a (row, head) range, in units, when balancing
 };
 
 // n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page

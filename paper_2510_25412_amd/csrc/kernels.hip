@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
-  const int32_t* ww = a.waves + wv * 8;
+  const int32_t* ww = a.waves + wv * 12;
   int row = __builtin_amdgcn_readfirstlane(ww[0]);
   int g = __builtin_amdgcn_readfirstlane(ww[1]);
   int p = __builtin_amdgcn_readfirstlane(ww[2]);
@@ -108,6 +108,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
   int vis = __builtin_amdgcn_readfirstlane(ww[5]);
   int qrow = __builtin_amdgcn_readfirstlane(ww[6]);
   int tbl_off = __builtin_amdgcn_readfirstlane(ww[7]);
+  // ids of the first range's first three pages (no table lookup before the first loads)
+  int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
+  int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
+  int pid2 = __builtin_amdgcn_readfirstlane(ww[10]);
+  bool first_range = true;
 
   while (remaining > 0) {
     const int np = (vis + kP - 1) / kP;
@@ -205,9 +210,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
     // flight.  Past the end of the range the prefetch is pointed at page 0 of the pool (valid
     // memory that every wave touches, so it stays in L2) and its data is never used.
     const int last = cnt - 1;
-    int id1 = cnt > 1 ? tbl[1] : 0, id2 = cnt > 2 ? tbl[2] : 0;
+    if (!first_range) {
+      pid0 = tbl[0];
+      pid1 = tbl[min(1, last)];
+      pid2 = tbl[min(2, last)];
+    }
+    first_range = false;
+    int id1 = cnt > 1 ? pid1 : 0, id2 = cnt > 2 ? pid2 : 0;
     PageRegs A, B;
-    load_page(A, tbl[0]);
+    load_page(A, pid0);
     for (int k = 0; k < cnt; k += 2) {
       load_page(B, id1);
       id1 = k + 3 <= last ? tbl[k + 3] : 0;
@@ -415,8 +426,11 @@ __global__ __launch_bounds__(256) void prologue_kernel(PrologueArgs a) {
     return;
   }
   blk -= a.n_cow;
-  for (int64_t i = (int64_t)blk * 256 + threadIdx.x; i < a.copy_words; i += (int64_t)a.copy_blocks * 256)
-    a.dev_words[i] = a.host_words[i];
+  // 16 bytes per thread, enough blocks that the whole descriptor is one round trip to the host
+  const uint4* src = (const uint4*)a.host_words;
+  uint4* dst = (uint4*)a.dev_words;
+  const int64_t n16 = (a.copy_words + 3) / 4;          // the staging buffer is padded to 16 bytes
+  for (int64_t i = (int64_t)blk * 256 + threadIdx.x; i < n16; i += (int64_t)a.copy_blocks * 256) dst[i] = src[i];
 }
 
 // Inverse of append for a list of token slots: pool -> contiguous [n][Hkv][row].
@@ -504,7 +518,7 @@ hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st) {
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
   a.append_blocks = (int32_t)((total + 255) / 256);
-  a.copy_blocks = a.copy_words > 0 ? (int32_t)std::min<int64_t>((a.copy_words + 255) / 256, 64) : 0;
+  a.copy_blocks = a.copy_words > 0 ? (int32_t)std::min<int64_t>((a.copy_words / 4 + 255) / 256, 256) : 0;
   const int64_t blocks = (int64_t)a.append_blocks + a.n_cow + a.copy_blocks;
   if (blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(prologue_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);

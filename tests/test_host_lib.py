@@ -147,7 +147,7 @@ def _walk_desc(words, Hkv, P=16):
     hdr = words[:16]
     n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
-    waves = words[hdr[6]:hdr[6] + 8 * n_waves].reshape(n_waves, 8)
+    waves = words[hdr[6]:hdr[6] + 12 * n_waves].reshape(n_waves, 12)
     merge = words[hdr[7]:hdr[7] + 4 * int(hdr[14])].reshape(int(hdr[14]), 4)
     pt = words[hdr[8]:hdr[9]]
     ptoff = words[hdr[9]:hdr[9] + n_lips + 1]
@@ -156,8 +156,10 @@ def _walk_desc(words, Hkv, P=16):
 
 @pytest.mark.parametrize("lengths,n_tok,waves", [([38, 81, 130, 201], [1, 1, 1, 1], 64), ([700, 16, 17, 1, 4096], [1, 1, 1, 1, 1], 2048),
                                                  ([40, 300], [8, 1], 32), ([5], [5], 8)])
-def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves):
+@pytest.mark.parametrize("range_cost", [0, 3])
+def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves, range_cost, monkeypatch):
     Hkv = 8
+    monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
     c = host_ctx(4096, decode_waves=waves)
     rng = np.random.default_rng(1)
     np_l = [-(-L // 16) for L in lengths]
@@ -173,13 +175,17 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert [int(r[0]) for r in rows] == [int(off[b]) for b, _, _ in exp_rows]
     # walk every wave's range exactly as the kernel does; record coverage and partial numbering
     cover = {}
-    units = []
+    units, starts = [], []
     pieces = {}
     for k in range(n_waves):
         row, g, p, rem, part = (int(x) for x in wv[k, :5])
         assert wv[k, 5:8].tolist() == [int(rows[row, 1]), int(rows[row, 2]), int(rows[row, 0])]   # first range's row data
+        npg0 = -(-int(rows[row, 1]) // 16)
+        assert wv[k, 8:11].tolist() == [int(pt[int(rows[row, 0]) + min(p + i, npg0 - 1)]) for i in range(3)]
         units.append(rem)
+        starts.append(0)
         while rem > 0:
+            starts[-1] += p == 0
             npg = -(-int(rows[row, 1]) // 16)
             cnt = min(rem, npg - p)
             for x in range(p, p + cnt):
@@ -197,7 +203,11 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
                     g, row = 0, row + 1
     total = sum(-(-int(r[1]) // 16) for r in rows) * Hkv
     assert len(cover) == total and sum(units) == total
-    assert max(units) - min(units) <= 1                      # equal ranges whatever the raggedness
+    # equal cost whatever the raggedness: units + range_cost per (row, head) begun in the range
+    # (a cut that falls into the overhead part of a (row, head) snaps to its first page, which
+    # can move one range_cost from one side of the cut to the other)
+    cost = [u + range_cost * s for u, s in zip(units, starts)]
+    assert max(cost) - min(cost) <= 1 + 2 * range_cost
     assert n_waves <= waves
     items = {}
     for first, cnt, out_idx, _ in merge.tolist():
