@@ -34,6 +34,7 @@ struct sym_ctx {
   int64_t page_bytes = 0;
   float scale_log2e = 0.f;
   int32_t max_waves = 0, min_units = 4, range_cost = 3;
+  int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   std::mutex mu;
   std::string err;
   Kvfs* fs = nullptr;
@@ -80,6 +81,7 @@ bool shape_ok(const sym_config* cfg) {
 // 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
 int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
   return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + MERGE_WORDS) + entries +
+         (T + 8 * n_lips) * c->cfg.n_kv_heads +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
 int64_t partial_bytes(const sym_ctx* c) {
@@ -138,7 +140,7 @@ struct Timed {
 // Launches attention (decode + merge) for the descriptor in c->desc, already copied to the workspace.
 int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, hipStream_t st) {
   const BatchDesc& d = c->desc;
-  if (d.n_waves == 0) return SYM_OK;
+  if (d.n_waves == 0 && d.n_tiles == 0) return SYM_OK;
   // workspace: [descriptor words][partial max/sum][partial accumulators]
   const int32_t* dw = (const int32_t*)c->cfg.workspace;
   uint8_t* base = (uint8_t*)c->cfg.workspace + align_up(blob_words * 4, 256);
@@ -163,6 +165,22 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
     Timed t(c, SYM_K_DECODE, st);
     hipError_t e = launch_decode(a, c->cfg.dtype, st);
     if (e != hipSuccess) return fail_hip(c, e, "decode launch");
+  }
+  if (d.n_tiles > 0) {
+    PrefillArgs pa;
+    pa.pool = (const uint8_t*)c->cfg.pool;
+    pa.page_bytes = c->page_bytes;
+    pa.q = q;
+    pa.out = out;
+    pa.tiles = dw + d.words[H_OFF_TILES];
+    pa.pt = dw + d.words[H_OFF_PT];
+    pa.n_tiles = d.n_tiles;
+    pa.Hq = c->cfg.n_q_heads;
+    pa.Hkv = c->cfg.n_kv_heads;
+    pa.scale_log2e = c->scale_log2e;
+    Timed t(c, SYM_K_PREFILL, st);
+    hipError_t e = launch_prefill(pa, st);
+    if (e != hipSuccess) return fail_hip(c, e, "prefill launch");
   }
   if (d.n_merge > 0) {
     MergeArgs m{part_acc, part_ml, dw + d.words[H_OFF_MERGE], out, d.n_merge};
@@ -216,7 +234,7 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens};
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "build_desc: bad batch");
   return (int64_t)c->desc.words.size();
@@ -276,6 +294,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   }
   c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
   c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
+  c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
+  c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
@@ -453,7 +473,7 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens};
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
   const int64_t dwords = (int64_t)c->desc.words.size();

@@ -11,21 +11,29 @@ namespace symkv {
 int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, const int64_t* len_after,
                const int32_t* const* tables, BatchDesc* out) {
   const int32_t P = prm.page_tokens, H = prm.n_kv_heads;
-  int64_t n_rows = 0, entries = 0;
+  // A LIP with at least prefill_min new tokens goes to the tile kernel (tile_tokens new tokens x
+  // all query heads of one kv head per tile); every other new token is a row of the decode kernel.
+  const int32_t TQ = prm.tile_tokens;
+  auto is_prefill = [&](int32_t b) { return TQ > 0 && n_tokens[b] >= prm.prefill_min; };
+  int64_t n_rows = 0, entries = 0, n_tiles = 0, n_tok_total = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     if (n_tokens[b] < 1 || len_after[b] < n_tokens[b] || len_after[b] > (int64_t)0x7fffffff) return SYM_EINVAL;
-    n_rows += n_tokens[b];
+    if (is_prefill(b)) n_tiles += (int64_t)((n_tokens[b] + TQ - 1) / TQ) * H;
+    else n_rows += n_tokens[b];
+    n_tok_total += n_tokens[b];
     entries += (len_after[b] + P - 1) / P;
   }
-  if (n_rows > 0x7fffffff / (2 * H) || entries > 0x3fffffff) return SYM_EINVAL;
+  if (n_tok_total > 0x7fffffff / (2 * H) || entries > 0x3fffffff || n_tiles > 0x0fffffff) return SYM_EINVAL;
 
   // ---- section sizes known up front: rows, page table, offsets
   int64_t total_units = 0;
-  for (int32_t b = 0; b < n_lips; ++b)
+  for (int32_t b = 0; b < n_lips; ++b) {
+    if (is_prefill(b)) continue;
     for (int32_t i = 0; i < n_tokens[b]; ++i) {
       int64_t vis = len_after[b] - n_tokens[b] + i + 1;
       total_units += ((vis + P - 1) / P) * H;
     }
+  }
   int64_t nw = (total_units + prm.min_units_per_wave - 1) / prm.min_units_per_wave;
   nw = std::max<int64_t>(1, std::min<int64_t>(nw, prm.max_waves));
   if (total_units == 0) nw = 0;
@@ -37,28 +45,45 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_pt = off_merge + nw * MERGE_WORDS;      // at most one cut (row, head) per wave boundary
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
-  const int64_t total = off_tiles;
+  const int64_t total = off_tiles + n_tiles * TILE_WORDS;
   if (total > 0x7fffffff) return SYM_EINVAL;
   w.resize((size_t)total);
   std::memset(w.data(), 0, DESC_HEADER_WORDS * sizeof(int32_t));
 
-  // ---- rows, page table
+  // ---- rows, tiles, page table
   int32_t* rows = w.data() + off_rows;
   int32_t* pt = w.data() + off_pt;
   int32_t* ptoff = w.data() + off_ptoff;
-  int64_t r = 0, e = 0;
+  int32_t* tiles = w.data() + off_tiles;
+  int64_t r = 0, e = 0, tok = 0, ti = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     ptoff[b] = (int32_t)e;
     const int64_t e_lip = e;
     int64_t np = (len_after[b] + P - 1) / P;
     std::memcpy(pt + e, tables[b], (size_t)np * sizeof(int32_t));
     e += np;
-    for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
-      rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
-      rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
-      rows[r * ROW_WORDS + 2] = (int32_t)r;                                       // q / out row
-      rows[r * ROW_WORDS + 3] = b;
+    if (is_prefill(b)) {
+      // order (kv head, token tile): the tiles that read the same K/V are neighbours
+      for (int32_t g = 0; g < H; ++g)
+        for (int32_t t0 = 0; t0 < n_tokens[b]; t0 += TQ, ++ti) {
+          int32_t* t = tiles + ti * TILE_WORDS;
+          t[0] = (int32_t)e_lip;                                   // page-table offset
+          t[1] = (int32_t)(len_after[b] - n_tokens[b]);            // file length before the call
+          t[2] = (int32_t)(tok + t0);                              // q / out row of the tile's first token
+          t[3] = std::min<int32_t>(TQ, n_tokens[b] - t0);          // tokens in the tile
+          t[4] = g;
+          t[5] = t0;                                               // token offset inside the chunk
+          t[6] = t[7] = 0;
+        }
+    } else {
+      for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
+        rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
+        rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
+        rows[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row
+        rows[r * ROW_WORDS + 3] = b;
+      }
     }
+    tok += n_tokens[b];
   }
   ptoff[n_lips] = (int32_t)e;
 
@@ -142,7 +167,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   w[H_N_WAVES] = (int32_t)nw;
   w[H_N_PARTIALS] = part;
   w[H_N_LIPS] = n_lips;
-  w[H_N_TILES] = 0;
+  w[H_N_TILES] = (int32_t)n_tiles;
   w[H_N_MERGE] = n_merge;
   w[H_OFF_ROWS] = (int32_t)off_rows;
   w[H_OFF_WAVES] = (int32_t)off_waves;
@@ -158,6 +183,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   out->n_partials = part;
   out->n_merge = n_merge;
   out->n_lips = n_lips;
+  out->n_tiles = (int32_t)n_tiles;
   out->total_units = total_units;
   return SYM_OK;
 }

@@ -2,7 +2,9 @@
 // the inference scheduler aggregates pred calls into one GPU batch) into the integer work
 // description of the attention launch.  Pure host code, no HIP.
 //
-// Every new token is a "row" with a visible length (file tokens 0 .. len_before + i).  The
+// A LIP that brings many new tokens (a prefill chunk) is cut into tiles of tile_tokens new
+// tokens x one kv head for the MFMA tile kernel.  Every other new token is a "row" with a
+// visible length (file tokens 0 .. len_before + i) for the decode kernel.  The
 // work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
 // slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves contiguous
 // ranges of equal cost, one per wavefront, whatever the raggedness of the files.  A range
@@ -15,7 +17,7 @@
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 4 };
+enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 4, TILE_WORDS = 8 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
@@ -25,7 +27,7 @@ enum {
 
 struct BatchDesc {
   std::vector<int32_t> words;      // packed descriptor, header first
-  int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0;
+  int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
   int64_t total_units = 0;
 
   const int32_t* rows() const { return words.data() + words[H_OFF_ROWS]; }
@@ -37,6 +39,8 @@ struct DescParams {
   int32_t max_waves;          // wavefront slots of the decode launch
   int32_t min_units_per_wave; // do not cut finer than this (keeps partial traffic small)
   int32_t range_cost;         // cost of starting a (row, head) range, in units, when balancing
+  int32_t prefill_min;        // LIPs with at least this many new tokens use the tile kernel
+  int32_t tile_tokens;        // new tokens per tile (0 = no tile kernel for this shape)
 };
 
 // n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page

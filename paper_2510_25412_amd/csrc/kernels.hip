@@ -318,6 +318,191 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
 }
 
 // ---------------------------------------------------------------------------------------
+// Prefill-chunk attention on the matrix cores (bf16 storage, D = 128).  One workgroup of 4
+// wavefronts per tile = (LIP, kv head, TQ = 128/G consecutive new tokens): 128 query rows
+// (token, head of the group), 32 per wavefront.  The file's K/V is walked in blocks of 32 tokens
+// (two pages), staged through LDS and shared by the 4 wavefronts.
+//
+// Everything is computed transposed so that what belongs to one query row lives in one lane:
+//   S^T[token][row] = K · Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
+//   O^T[dim][row]  += V^T · P^T    v_mfma_f32_32x32x16_f16,  A = V^T from LDS, B = P (registers)
+// In both results a lane's column is its query row (lane % 32), so the running max, the sum and
+// the rescale factor are lane-local, and the 16 scores a lane holds are, in register order,
+// exactly the 8+8 token slots it must supply as the B operand of the two PV steps.  The two
+// lanes of a row (lane, lane ^ 32) hold different tokens / dims and share only the max.
+// P is rounded to fp16 (2^-11; bf16's 2^-8 would not fit a 2e-3 bar on rows with few keys) and
+// the softmax sum adds the rounded weights, so the output is an exact weighted mean of V rows
+// for slightly perturbed weights.  V is converted bf16 -> fp16 while it is transposed into LDS:
+// packing the same dim of two neighbouring tokens into one register IS the transposition.
+// ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int kTileRows = 128;            // query rows per workgroup
+constexpr int kKvBlock = 32;              // tokens per K/V block
+constexpr int kKLds = kKvBlock * kRowBytes;      // 8 KiB: K block, 16-byte chunks, xor-swizzled
+constexpr int kVRow = 80;                 // bytes per dim row of V^T in LDS (64 + 16 pad: conflict-free reads)
+constexpr int kVLds = 128 * kVRow;        // 10 KiB
+
+template <int G>
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
+  constexpr int TQ = kTileRows / G;
+  __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
+  // tiles that read the same K/V are neighbours in the list; blocks go round-robin over the 8
+  // XCDs, so give each XCD a contiguous run of the list (only locality depends on this)
+  const int per_xcd = (a.n_tiles + 7) / 8;
+  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= a.n_tiles) return;
+  const int32_t* tw = a.tiles + tile * 8;
+  const int tbl_off = tw[0], L = tw[1], qrow0 = tw[2], nt = tw[3], g = tw[4], t0 = tw[5];
+  const int32_t* tbl = a.pt + tbl_off;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int rho = wv * 32 + col;                 // query row of this lane inside the tile
+  const int tl = rho / G, h = rho % G;
+  const int tlc = min(tl, nt - 1);               // rows past the tile's last token repeat it (never written)
+  const int vis = L + t0 + tlc + 1;              // tokens this row sees
+  const int kv_end = L + t0 + nt;                // tokens the tile's last row sees
+  const int nblk = (kv_end + kKvBlock - 1) / kKvBlock;
+  const int last_page = (kv_end + kP - 1) / kP - 1;
+
+  // Q of this lane's row: 8 k-steps of 16 dims, this lane supplies dims 16*ks + 8*hf .. +8
+  bf16x8_t q[8];
+  {
+    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)(qrow0 + tlc) * a.Hq + g * G + h) * kRowBytes + hf * 16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 32));
+  }
+
+  // ---- staging roles
+  // K: thread copies chunks c = tid and tid + 256 of the block: token c/16, dim chunk c%16
+  // V: thread takes tokens (4*q4 + 2*up, +1) of page pg, dim chunk vc: 8 dims x 2 tokens
+  const int up = tid & 1, q4 = (tid >> 1) & 3, vc = (tid >> 3) & 15, pg = tid >> 7;
+  uint4 kreg0, kreg1, vreg0, vreg1;
+  const uint8_t* slab = a.pool + (int64_t)g * kSlab;
+  auto k_src = [&](int kb, int c) {
+    const int t = c >> 4, dc = c & 15;
+    const int pi = min(2 * kb + (t >> 4), last_page);
+    return slab + (int64_t)tbl[pi] * a.page_bytes + (dc >> 3) * (kP * kHalfBytes) + (t & 15) * kHalfBytes + (dc & 7) * 16;
+  };
+  auto issue_loads = [&](int kb) {
+    kreg0 = *(const uint4*)k_src(kb, tid);
+    kreg1 = *(const uint4*)k_src(kb, tid + 256);
+    const int pi = min(2 * kb + pg, last_page);
+    const uint8_t* p = slab + (int64_t)tbl[pi] * a.page_bytes + kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * q4 + 2 * up) * kHalfBytes + (vc & 7) * 16;
+    vreg0 = *(const uint4*)p;
+    vreg1 = *(const uint4*)(p + kHalfBytes);
+  };
+  auto k_dst = [&](uint8_t* base, int c) {
+    const int t = c >> 4, dc = c & 15;
+    return base + (t * 16 + (dc ^ (t & 15))) * 16;
+  };
+  auto store_lds = [&](int kb, uint8_t* base) {
+    *(uint4*)k_dst(base, tid) = kreg0;
+    *(uint4*)k_dst(base, tid + 256) = kreg1;
+    // tokens past the end of what the tile may see are cleared (their weight is 0, 0 * NaN is not)
+    const int tok = kb * kKvBlock + pg * 16 + 4 * q4 + 2 * up;
+    const bool ok0 = tok < kv_end, ok1 = tok + 1 < kv_end;
+    uint8_t* vb = base + kKLds + (2 * pg + (q4 & 1)) * 16 + (q4 >> 1) * 8 + up * 4 + vc * 8 * kVRow;
+    auto put = [&](int e, uint32_t lo_word0, uint32_t lo_word1, bool high) {
+      const uint32_t x0 = high ? (lo_word0 & 0xffff0000u) : (lo_word0 << 16);
+      const uint32_t x1 = high ? (lo_word1 & 0xffff0000u) : (lo_word1 << 16);
+      const float f0 = ok0 ? as_f32(x0) : 0.f, f1 = ok1 ? as_f32(x1) : 0.f;
+      *(uint32_t*)(vb + e * kVRow) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f0, f1));
+    };
+    put(0, vreg0.x, vreg1.x, false); put(1, vreg0.x, vreg1.x, true);
+    put(2, vreg0.y, vreg1.y, false); put(3, vreg0.y, vreg1.y, true);
+    put(4, vreg0.z, vreg1.z, false); put(5, vreg0.z, vreg1.z, true);
+    put(6, vreg0.w, vreg1.w, false); put(7, vreg0.w, vreg1.w, true);
+  };
+
+  f32x16_t O[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) O[db][v] = 0.f;
+  float m = -1e30f, l = 0.f;
+
+  issue_loads(0);
+  for (int kb = 0; kb < nblk; ++kb) {
+    uint8_t* base = lds[kb & 1];
+    store_lds(kb, base);
+    __syncthreads();           // block kb is in LDS; everyone is done with block kb-1's other buffer
+    if (kb + 1 < nblk) issue_loads(kb + 1);
+
+    // S^T = K Q^T for 32 tokens x 32 rows
+    f32x16_t S;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) S[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8_t kk = *(const bf16x8_t*)(base + (col * 16 + ((2 * ks + hf) ^ (col & 15))) * 16);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, q[ks], S, 0, 0, 0);
+    }
+    // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
+    const int tok0 = kb * kKvBlock + 4 * hf;
+    float mx = -__builtin_inff();
+    if (tok0 + kKvBlock > L + t0 + 1 - 4 * hf) {       // the block reaches the causal edge of some row
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int tok = tok0 + 8 * (v >> 2) + (v & 3);
+        S[v] = tok < vis ? S[v] * a.scale_log2e : -__builtin_inff();
+        mx = fmaxf(mx, S[v]);
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        S[v] *= a.scale_log2e;
+        mx = fmaxf(mx, S[v]);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {     // rare after the first block
+      const float mn = fmaxf(m, mx);
+      const float al = __builtin_amdgcn_exp2f(m - mn);
+      l *= al;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[db][v] *= al;
+      m = mn;
+    }
+    uint32_t pw[8];
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(S[v] - m), __builtin_amdgcn_exp2f(S[v + 1] - m));
+      l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
+      pw[v >> 1] = __builtin_bit_cast(uint32_t, pk);
+    }
+    const f16x8_t P[2] = {__builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3])),
+                          __builtin_bit_cast(f16x8_t, make_uint4(pw[4], pw[5], pw[6], pw[7]))};
+    // O^T += V^T P^T
+    const uint8_t* vbase = base + kKLds + col * kVRow + hf * 16;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const f16x8_t vv = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
+        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv, P[ks], O[db], 0, 0, 0);
+      }
+  }
+
+  l += __shfl_xor(l, 32);
+  if (tl < nt) {
+    const float inv = 1.0f / l;
+    float* o = a.out + ((int64_t)(qrow0 + tl) * a.Hq + g * G + h) * 128 + 4 * hf;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int vb = 0; vb < 4; ++vb)
+        *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb] * inv, O[db][4 * vb + 1] * inv, O[db][4 * vb + 2] * inv, O[db][4 * vb + 3] * inv);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Merge of partial results, one wavefront per (row, kv head) that was cut:
 //   out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M),  M = max_i m_i.
 // The G*D accumulator values of a piece form one flat list; lane owns entries e*64 + lane.  All
@@ -502,6 +687,20 @@ hipError_t launch_decode_g(const DecodeArgs& a, hipStream_t st) {
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st) {
   if (a.n_waves <= 0) return hipSuccess;
   return dtype == 0 ? launch_decode_g<ElemF32>(a, st) : launch_decode_g<ElemBF16>(a, st);
+}
+
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t st) {
+  if (a.n_tiles <= 0) return hipSuccess;
+  const int G = a.Hq / a.Hkv;
+  const dim3 grid(((a.n_tiles + 7) / 8) * 8), block(256);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((prefill_attn_kernel<1>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((prefill_attn_kernel<2>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((prefill_attn_kernel<4>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((prefill_attn_kernel<8>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {

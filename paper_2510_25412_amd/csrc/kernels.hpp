@@ -22,6 +22,18 @@ struct DecodeArgs {
   float scale_log2e;        // softmax scale * log2(e)
 };
 
+struct PrefillArgs {
+  const uint8_t* pool;
+  int64_t page_bytes;
+  const void* q;            // [tokens][Hq][128] bf16
+  float* out;               // [tokens][Hq][128]
+  const int32_t* tiles;     // [n_tiles][8]: page-table offset, length before, first q/out row,
+                            //   tokens in the tile, kv head, token offset in the chunk, 0, 0
+  const int32_t* pt;        // flattened page tables
+  int32_t n_tiles, Hq, Hkv;
+  float scale_log2e;
+};
+
 struct MergeArgs {
   const float* part_acc;
   const float* part_ml;
@@ -52,6 +64,7 @@ struct GatherArgs {
 };
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st);
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);

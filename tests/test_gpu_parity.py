@@ -238,3 +238,39 @@ def test_split_invariance_many_launches():
         worst = max(worst, d)
     sa.close()
     sb.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 8)])
+def test_prefill_chunks_on_matrix_cores(Hq, Hkv):
+    """Multi-token pred calls of 16+ tokens (the MFMA tile kernel): chunk lengths around the
+    tile and block sizes, on empty, tiny, page-aligned and long files, mixed with decode rows
+    and short multi-token calls in one batch; every output checked."""
+    shape = synth.Shape(Hq, Hkv, 128, 16, synth.BF16)
+    files = [("new", 0), ("new", 0), ("new", 5), ("new", 16), ("new", 31), ("new", 100), ("new", 1000), ("new", 333),
+             ("fork", 6, 0), ("new", 64), ("new", 777)]
+    batch = [(0, 16), (1, 129), (2, 17), (3, 33), (4, 100), (5, 64), (6, 200), (7, 1), (8, 48), (9, 5), (10, 31)]
+    wl = synth.custom(f"prefill_{Hq}_{Hkv}", shape, files, batch, 256, seed=4242 + Hq)
+    got, sess, ref, osess = run_both(wl)
+    worst = check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    print(f"prefill {Hq}/{Hkv}: worst scaled error {worst:.2e}")
+    sess.close()
+
+
+def test_prefill_chunk_equals_sequential():
+    """A 40-token chunk through the tile kernel equals 40 single-token preds through the decode
+    kernel (two different kernels, same appended rows)."""
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    wl = synth.custom("chunk40", shape, [("new", 90)], [(0, 40)], 32, seed=321)
+    got, sess = drv.run_workload(wl, poison=True)
+    sess.close()
+    sess2 = drv.HipSession(shape, 32, poison=True)
+    sess2.setup(wl.setup_ops())
+    b = wl.batch()
+    outs = []
+    for i in range(40):
+        one = dict(files=[0], n_tokens=[1], q=b["q"][i:i + 1], k_new=b["k_new"][i:i + 1], v_new=b["v_new"][i:i + 1])
+        outs.append(sess2.pred(sess2.upload_batch(one)).cpu().numpy())
+    check_outputs(got, np.concatenate(outs), tol=1e-3)
+    sess2.close()

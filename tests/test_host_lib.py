@@ -233,3 +233,28 @@ def test_descriptor_rejects_bad_tables():
         c.build_desc([1], np.array([1, 2, 64], np.int32), [0, 3], [40])   # page id out of range
     with pytest.raises(binding.SymError):
         c.build_desc([0], np.array([1], np.int32), [0, 1], [4])
+
+
+def test_descriptor_tiles_for_prefill_chunks():
+    """LIPs with 16+ new tokens become tiles (one per kv head and 32 new tokens at 4 heads per
+    group); the others stay decode rows; q rows keep the batch's token order."""
+    c = host_ctx(4096)
+    lengths, n_tok = [100, 77, 40, 16], [70, 1, 3, 16]
+    np_l = [-(-L // 16) for L in lengths]
+    flat = np.arange(sum(np_l), dtype=np.int32)
+    off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
+    words = c.build_desc(n_tok, flat, off, lengths)
+    hdr = words[:16]
+    n_rows, n_tiles = int(hdr[0]), int(hdr[4])
+    assert n_rows == 4 and n_tiles == (3 + 1) * 8
+    rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
+    assert rows[:, 2].tolist() == [70, 71, 72, 73] and rows[:, 3].tolist() == [1, 2, 2, 2]
+    assert rows[:, 1].tolist() == [77, 38, 39, 40]
+    tiles = words[hdr[10]:hdr[10] + 8 * n_tiles].reshape(n_tiles, 8)
+    exp = [(int(off[0]), 30, t0, min(32, 70 - t0), g, t0) for g in range(8) for t0 in (0, 32, 64)]
+    exp += [(int(off[3]), 0, 74, 16, g, 0) for g in range(8)]
+    assert [tuple(int(x) for x in t[:6]) for t in tiles] == exp
+    # fp32 storage has no tile kernel: everything is a row
+    c32 = host_ctx(4096, Hq=8, Hkv=8, D=64, dtype="f32")
+    w32 = c32.build_desc(n_tok, flat, off, lengths)
+    assert int(w32[0]) == sum(n_tok) and int(w32[4]) == 0
