@@ -1,17 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the pred hot path on one MI355X.
 
-A step = one sym_pred_batch call = the whole hot path (descriptor build, the prologue kernel:
-descriptor copy + copy-on-write copies + KV append; the decode attention kernel; the merge of
-split ranges) over one batch
-of the "decode batch" workload: 64 LIPs, 32 Q / 8 KV heads, head dim 128, bf16, contexts
-uniform 512..4096, one new token each.  Successive steps rotate over several independent
-layer pools (as a real pred walks the model's layers, each with its own KV pages) so that the
-KV bytes of a step come from HBM and not from the 256 MB last-level cache.
+A step = one sym_pred_batch call = the whole hot path (descriptor build; the prologue kernel:
+descriptor copy + copy-on-write copies + KV append; the decode attention kernel; the MFMA tile
+kernel for prefill chunks; the merge of split ranges) over one batch of a synthetic LIP workload.
+
+Default workload (the one the headline metric is quoted on): the "decode batch", 64 LIPs, 32 Q /
+8 KV heads, head dim 128, bf16, contexts uniform 512..4096, one new token each.  Successive steps
+rotate over several independent layer pools (as a real pred walks the model's layers, each with
+its own KV pages) so that the KV bytes of a step come from HBM and not from the 256 MB
+last-level cache.  `--workload fork|mixed|long` times the other configurations the same way.
 
 Prints ONE JSON line: whole-path throughput in algorithmic KV TB/s, plus `roofline` for the
-dominant kernel (decode attention, timed with HIP events on its stream inside the timed
-region) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the same workload).
+dominant kernel (timed with HIP events on its stream inside the timed region) and `cpu_baseline`
+(the CPU oracle timed on the same workload for a bounded time).
 """
 import argparse
 import json
@@ -22,28 +24,27 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_TBPS = 8.0       # MI355X published HBM3E peak
+HBM_PEAK_TBPS = 8.0        # MI355X published HBM3E peak
+MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16/fp16 matrix peak
 
 
-def algorithmic_bytes(shape, lengths_after, n_tokens):
-    """Bytes one launch must move: every valid KV token of every file once, the appended rows
+def kv_token_bytes(shape):
+    return 2 * shape.n_kv_heads * shape.head_dim * (4 if shape.dtype == "f32" else 2)
+
+
+def algorithmic_bytes(shape, kv_tokens, n_tokens, table_entries):
+    """Bytes one launch must move: `kv_tokens` valid KV tokens read once, the appended rows
     written, Q read, O written (fp32), page-table entries read."""
     es = 4 if shape.dtype == "f32" else 2
-    kv_tok = 2 * shape.n_kv_heads * shape.head_dim * es
     T = sum(n_tokens)
-    kv_read = sum(lengths_after) * kv_tok
-    kv_write = T * kv_tok
-    q_read = T * shape.n_q_heads * shape.head_dim * es
-    o_write = T * shape.n_q_heads * shape.head_dim * 4
-    table = sum(-(-L // shape.page_tokens) for L in lengths_after) * 4
-    return kv_read + kv_write + q_read + o_write + table
+    return (kv_tokens * kv_token_bytes(shape) + T * kv_token_bytes(shape) + T * shape.n_q_heads * shape.head_dim * es +
+            T * shape.n_q_heads * shape.head_dim * 4 + table_entries * 4)
 
 
 def read_traffic_note(name):
-    """HBM traffic per decode launch from the committed counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", name)
+    """HBM traffic per launch of the dominant kernel from the committed counter summary."""
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("traffic_bytes_per_launch:"):
                 return float(line.split(":")[1])
     except OSError:
@@ -51,38 +52,45 @@ def read_traffic_note(name):
     return None
 
 
-def cpu_baseline(wl, budget_s, np):
-    """The oracle as it stands on the same workload: all 64 LIPs, one pred step after another
-    (each appends one token per LIP and attends), until about `budget_s` seconds have passed."""
+def cpu_baseline(wl, budget_s, np, reset_lengths):
+    """The oracle as it stands on the same workload: all LIPs, one pred step after another,
+    until about `budget_s` seconds have passed (at least one step)."""
     from oracle.driver import OracleSession
     from threadpoolctl import threadpool_info
     osess = OracleSession(wl.shape, wl.n_pages, wl.free_order)
     osess.setup(wl.setup_ops())
     b = wl.batch()
     n_lips = len(b["files"])
+    P = wl.shape.page_tokens
     steps, nbytes = 0, 0
     t0 = time.perf_counter()
     while True:
-        lengths_after = [osess.model.kv_len(osess.h[f]) + 1 for f in b["files"]]
+        before = [osess.model.kv_len(osess.h[f]) for f in b["files"]]
+        after = [L + n for L, n in zip(before, b["n_tokens"])]
         osess.pred(b, dtype=np.float32)
-        nbytes += algorithmic_bytes(wl.shape, lengths_after, b["n_tokens"])
+        nbytes += algorithmic_bytes(wl.shape, sum(after), b["n_tokens"], sum(-(-L // P) for L in after))
+        if reset_lengths:
+            for f, L in zip(b["files"], before):
+                osess.model.kv_truncate(osess.h[f], L)
         steps += 1
         dt = time.perf_counter() - t0
         if dt >= budget_s:
             break
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": nbytes / dt / 1e12, "unit": "TB/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{steps} pred steps of the same 64-LIP decode batch (append + page gather + fp32 softmax attention "
-                      f"per LIP), {dt:.1f} s wall", "lip_steps_per_s": steps * n_lips / dt}
+            "sample": f"{steps} pred step(s) of the same {n_lips}-LIP batch (append + page gather + fp32 softmax attention per "
+                      f"LIP; logical bytes, every reader counted), {dt:.1f} s wall", "lip_steps_per_s": steps * n_lips / dt}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--layers", type=int, default=4, help="independent layer pools rotated over (cache honesty)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg (0 = skip)")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long"], default="decode")
+    ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
+    ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
+    ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
     ap.add_argument("--no-calib", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,61 +106,121 @@ def main():
     binding.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
-    wl = synth.config2()
+    # workload -> (generator, layer pools, steps, warmup, reset lengths after each step, cpu seconds, label)
+    table = {"decode": (synth.config2, 4, 400, 40, False, 12.0, "decode batch: 64 LIPs, 32Q/8KV heads, head_dim 128, bf16, page 16, "
+                        "contexts U{512..4096}, 1 new token each"),
+             "fork": (lambda: synth.config3(slack_pages=8192), 4, 400, 40, False, 0.0, "fork tree: 16 roots x 2048-token prefix, each forked 16x (256 LIPs), "
+                      "private suffix U{1..256}, 32Q/8KV, bf16, 1 new token each"),
+             "mixed": (synth.config4, 1, 20, 3, True, 0.0, "mixed: 32 LIPs x 512-token prefill chunk on U{0..8192} + 224 decode LIPs "
+                       "U{1024..4096}, 32Q/8KV, bf16 (files truncated back after every step)"),
+             "long": (lambda: synth.config5(n_pages=args.pool_pages), 1, 50, 5, False, 0.0, "long context: 16 LIPs U{32768..131072}, "
+                      "64Q/8KV, bf16, pages scattered over a %d-page pool, 1 new token each" % args.pool_pages)}
+    gen, layers, steps, warmup, reset, cpu_s, label = table[args.workload]
+    layers = args.layers or layers
+    steps = args.steps if args.steps is not None else steps
+    warmup = args.warmup if args.warmup is not None else warmup
+    cpu_s = args.cpu_seconds if args.cpu_seconds is not None else cpu_s
+    wl = gen()
     shape = wl.shape
+    P = shape.page_tokens
     n_lips = len(wl.batch_files)
+    T = int(sum(wl.batch_n))
 
     # ---- build the layer pools (inputs resident in HBM before the timed region)
-    ops = list(wl.setup_ops())
     sessions = []
-    for _ in range(args.layers):
-        s = HipSession(shape, wl.n_pages, wl.free_order, dev, max_lips=n_lips, max_tokens=8192, max_entries=1 << 16)
-        s.setup(ops)
+    entries = sum(wl.pages_after_batch().values()) + 64 * n_lips
+    for li in range(layers):
+        s = HipSession(shape, wl.n_pages, wl.free_order, dev, max_lips=n_lips, max_tokens=max(T, max(wl.lengths.values())) + 64,
+                       max_entries=entries)
+        s.setup(wl.setup_ops())
         sessions.append(s)
-    del ops
+        print(f"[bench] layer pool {li + 1}/{layers} built", file=sys.stderr, flush=True)
     batch = wl.batch()
     dbs = [s.upload_batch(batch) for s in sessions]
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream(dev).cuda_stream
+    len_before = [sessions[0].ctx.kv_len(h) for h in dbs[0]["kv"]]
+    len_before64 = np.asarray(len_before, np.int64)
 
     def step(i):
-        s, db = sessions[i % args.layers], dbs[i % args.layers]
+        s, db = sessions[i % layers], dbs[i % layers]
         s.ctx.pred_batch(db["kv"], db["n_tokens"], db["q"], db["k_new"], db["v_new"], db["out"], stream)
+        if reset:
+            s.ctx.kv_truncate(db["kv"], len_before64)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     len0 = [sessions[0].ctx.kv_len(h) for h in dbs[0]["kv"]]       # lengths before the timed steps (layer 0)
+    timed_mask = (1 << binding.K_DECODE) | (1 << binding.K_PREFILL)
     for s in sessions:
-        s.ctx.profile_enable(1 << binding.K_DECODE)
+        s.ctx.profile_enable(timed_mask)
     t0 = time.perf_counter()
-    for i in range(args.warmup, args.warmup + args.steps):
+    for i in range(warmup, warmup + steps):
         step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    dec_ms, dec_n = 0.0, 0
+    kern = {}
+    for name, kid in (("decode", binding.K_DECODE), ("prefill", binding.K_PREFILL)):
+        ms_sum, n_sum = 0.0, 0
+        for s in sessions:
+            ms, n = s.ctx.profile_read(kid)
+            ms_sum, n_sum = ms_sum + ms, n_sum + n
+        kern[name] = (ms_sum / n_sum if n_sum else None, n_sum)
     for s in sessions:
-        ms, n = s.ctx.profile_read(binding.K_DECODE)
-        dec_ms, dec_n = dec_ms + ms, dec_n + n
         s.ctx.profile_enable(0)
 
-    # mean lengths over the timed steps: each step on a layer adds one token per LIP
-    per_layer = args.steps / args.layers
-    lengths_after = [L + 1 + (per_layer - 1) / 2 for L in len0]
-    step_bytes = algorithmic_bytes(shape, [int(round(x)) for x in lengths_after], [1] * n_lips)
-    ms_per_step = wall / args.steps * 1e3
-    tbps = step_bytes / (wall / args.steps) / 1e12
-    dec_avg_ms = dec_ms / max(dec_n, 1)
-    achieved = step_bytes / (dec_avg_ms * 1e-3) / 1e9 if dec_n else None
+    # ---- bytes and flops of one step, at the mean lengths of the timed steps
+    grow = 0 if reset else (steps / layers - 1) / 2 * np.asarray(wl.batch_n)
+    after = [int(round(L + n + g)) for L, n, g in zip(len0, wl.batch_n, np.broadcast_to(grow, (n_lips,)))]
+    logical_tokens = sum(after)
+    # unique pages: a page shared by forks is counted once, with the most tokens any reader sees in it
+    seen = {}
+    for f, L in zip(wl.batch_files, after):
+        for idx, p in enumerate(sessions[0].pages(f)):
+            seen[p] = max(seen.get(p, 0), min(P, L - idx * P))
+    unique_tokens = sum(v for v in seen.values() if v > 0)
+    table_entries = sum(-(-L // P) for L in after)
+    step_bytes = algorithmic_bytes(shape, unique_tokens, wl.batch_n, table_entries)
+    logical_bytes = algorithmic_bytes(shape, logical_tokens, wl.batch_n, table_entries)
+    min_pre = 16        # LIPs with at least this many new tokens run on the tile kernel
+    dec_n_tok = [n for n in wl.batch_n if n < min_pre]
+    dec_tokens = sum(L for L, n in zip(after, wl.batch_n) if n < min_pre)
+    dec_bytes = algorithmic_bytes(shape, min(dec_tokens, unique_tokens), dec_n_tok,
+                                  sum(-(-L // P) for L, n in zip(after, wl.batch_n) if n < min_pre))
+    pre_pairs = sum(n * (L - n) + n * (n + 1) // 2 for L, n in zip(after, wl.batch_n) if n >= min_pre)   # (query, key) pairs
+    pre_flops = 4 * shape.head_dim * shape.n_q_heads * pre_pairs
+    ms_per_step = wall / steps * 1e3
+    tbps = step_bytes / (wall / steps) / 1e12
+    G = shape.n_q_heads // shape.n_kv_heads
+
+    dec_ms, dec_n = kern["decode"]
+    pre_ms, pre_n = kern["prefill"]
+    roof_dec = None
+    if dec_n:
+        ach = dec_bytes / (dec_ms * 1e-3) / 1e9
+        note = "decode_attn_decode_batch_pmc.txt" if args.workload == "decode" else f"decode_attn_{args.workload}_pmc.txt"
+        roof_dec = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_TBPS * 1e3, "unit": "GB/s",
+                    "frac": round(ach / (HBM_PEAK_TBPS * 1e3), 4), "traffic": read_traffic_note(note),
+                    "kernel": f"decode_attn_kernel<bf16, G={G}>", "avg_launch_us": round(dec_ms * 1e3, 2), "launches": dec_n}
+    roof_pre = None
+    if pre_n:
+        ach = pre_flops / (pre_ms * 1e-3) / 1e12
+        roof_pre = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic_note(f"prefill_attn_{args.workload}_pmc.txt"),
+                    "kernel": f"prefill_attn_kernel<G={G}>", "avg_launch_us": round(pre_ms * 1e3, 2), "launches": pre_n,
+                    "flops_per_launch": pre_flops}
+    dominant = roof_pre if (pre_n and (not dec_n or pre_ms > dec_ms)) else roof_dec
 
     # ---- per-kernel breakdown (untimed extra pass) and streaming-read ceiling
     for s in sessions:
         s.ctx.profile_enable(0xf)
-    for i in range(args.layers * 10):
+    for i in range(max(layers * 5, 5)):
         step(i)
     torch.cuda.synchronize()
     breakdown = {}
-    for name, kid in (("prologue", binding.K_PROLOGUE), ("decode", binding.K_DECODE), ("merge", binding.K_MERGE)):
+    for name, kid in (("prologue", binding.K_PROLOGUE), ("decode", binding.K_DECODE), ("merge", binding.K_MERGE),
+                      ("prefill", binding.K_PREFILL)):
         tot, cnt = 0.0, 0
         for s in sessions:
             ms, n = s.ctx.profile_read(kid)
@@ -184,29 +252,30 @@ def main():
     stats = sessions[0].ctx.get_stats()
     for s in sessions:
         s.close()
+    del sessions, dbs
+    torch.cuda.empty_cache()
 
-    cpu = cpu_baseline(wl, args.cpu_seconds, np) if args.cpu_seconds > 0 else None
+    cpu = cpu_baseline(wl, cpu_s, np, reset) if cpu_s > 0 else None
 
     line = {
         "metric": "pred-batch attention KV TB/s", "value": round(tbps, 4), "unit": "TB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "decode batch: 64 LIPs, 32Q/8KV heads, head_dim 128, bf16, page 16, contexts U{512..4096}, "
-                               "1 new token each; one attention layer per step", "layer_pools_rotated": args.layers,
-                   "kv_tokens_per_step": int(sum(lengths_after)), "algorithmic_bytes_per_step": int(step_bytes)},
+        "config": {"workload": label + "; one attention layer per step", "layer_pools_rotated": layers,
+                   "kv_tokens_per_step": int(unique_tokens), "algorithmic_bytes_per_step": int(step_bytes),
+                   "logical_kv_tokens_per_step": int(logical_tokens), "logical_bytes_per_step": int(logical_bytes)},
         "pct_hbm_peak": round(100 * tbps / HBM_PEAK_TBPS, 2),
-        "lip_steps_per_s": round(n_lips / (wall / args.steps), 1),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_TBPS * 1e3,
-                     "unit": "GB/s", "frac": round(achieved / (HBM_PEAK_TBPS * 1e3), 4) if achieved else None,
-                     "traffic": read_traffic_note("decode_attn_decode_batch_pmc.txt"),
-                     "kernel": "decode_attn_kernel<bf16, G=4>", "avg_launch_us": round(dec_avg_ms * 1e3, 2), "launches": dec_n},
+        "effective_TBps_logical": round(logical_bytes / (wall / steps) / 1e12, 4),
+        "lip_steps_per_s": round(n_lips / (wall / steps), 1),
+        "roofline": dominant,
+        "roofline_decode": roof_dec if dominant is not roof_dec else None,
         "kernel_breakdown": breakdown,
         "stream_read_TBps": round(stream_read, 3) if stream_read else None,
-        "frac_of_stream_read": round(achieved / 1e3 / stream_read, 4) if (achieved and stream_read) else None,
+        "frac_of_stream_read": round(roof_dec["achieved"] / 1e3 / stream_read, 4) if (roof_dec and stream_read) else None,
         "cpu_baseline": cpu,
         "host_us_per_step": {"plan_and_descriptor": round(stats["host_ns_plan"] / max(stats["pred_batches"], 1) / 1e3, 2),
                              "whole_call": round(stats["host_ns_pred"] / max(stats["pred_batches"], 1) / 1e3, 2)},
-        "pool_stats": {"pages_total": stats["pages_total"], "pages_free": stats["pages_free"]},
+        "pool_stats": {"pages_total": stats["pages_total"], "pages_free": stats["pages_free"], "pages_shared": stats["pages_shared"]},
     }
     print(json.dumps(line))
 

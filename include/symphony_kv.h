@@ -111,6 +111,11 @@ int     sym_kv_remove(sym_ctx* ctx, sym_kv kv);
 int     sym_kv_close(sym_ctx* ctx, sym_kv kv);
 /* Token count of the file (Fig. 1 `.len()`), or a negative status.                       */
 int64_t sym_kv_len(sym_ctx* ctx, sym_kv kv);
+/* kv_truncate: for n files at once, drop the tokens from new_len[i] on (POSIX-style truncate
+ * of a KVFS file, section 4.2: a LIP that verifies draft tokens with a multi-token pred,
+ * section 4.1, rolls the rejected ones back).  Host-only: pages no longer needed lose one
+ * reference; K/V bytes are not touched.  kv, new_len: host.  All or nothing.              */
+int     sym_kv_truncate(sym_ctx* ctx, int32_t n, const sym_kv* kv, const int64_t* new_len);
 /* kv_append: the "file is updated with new tensors" half of pred (section 4.1) on its own:
  * append n >= 1 token rows.  k, v: device, [n][Hkv][D] in the storage dtype.  Allocates
  * pages as needed; a shared, partly filled last page is first copied (copy-on-write).    */

@@ -116,6 +116,22 @@ class KVFSModel:
     def kv_len(self, h):
         return self._file(h).length
 
+    def kv_truncate(self, h, new_len):
+        """Drop the file's tokens from new_len on (POSIX-style ftruncate; a LIP that verifies
+        draft tokens with a multi-token pred rolls the rejected ones back this way).  Pages no
+        longer needed lose one reference; a shared last page stays shared until the next append
+        copies it."""
+        f = self._file(h)
+        if new_len < 0 or new_len > f.length:
+            raise KVError(EINVAL, "truncate beyond the file")
+        keep = -(-new_len // self.P)
+        for p in f.pages[keep:]:
+            self.refcount[p] -= 1
+            if self.refcount[p] == 0:
+                heapq.heappush(self.free_ranks, int(self.rank[p]))
+        del f.pages[keep:]
+        f.length = new_len
+
     def kv_pages(self, h):
         return list(self._file(h).pages)
 

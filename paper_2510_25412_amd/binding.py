@@ -49,6 +49,7 @@ _SIGNATURES = {
     "sym_kv_remove": (C.c_int, [C.c_void_p, C.c_int32]),
     "sym_kv_close": (C.c_int, [C.c_void_p, C.c_int32]),
     "sym_kv_len": (C.c_int64, [C.c_void_p, C.c_int32]),
+    "sym_kv_truncate": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I64P]),
     "sym_kv_append": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_pred_batch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -167,6 +168,11 @@ class Context:
 
     def kv_len(self, kv):
         return self._chk(self.lib.sym_kv_len(self.h, kv))
+
+    def kv_truncate(self, kv, new_len):
+        kv_a, kv_p = _i32(kv)
+        ln_a, ln_p = _i64(new_len)
+        self._chk(self.lib.sym_kv_truncate(self.h, len(kv_a), kv_p, ln_p))
 
     def kv_append(self, kv, n, k, v, stream=None):
         self._chk(self.lib.sym_kv_append(self.h, kv, n, _ptr(k), _ptr(v), stream))

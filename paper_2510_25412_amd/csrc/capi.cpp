@@ -361,6 +361,20 @@ int64_t sym_kv_len(sym_ctx* c, sym_kv kv) {
   return c->fs->len(kv);
 }
 
+int sym_kv_truncate(sym_ctx* c, int32_t n, const sym_kv* kv, const int64_t* new_len) {
+  if (!c || n < 0 || (n > 0 && (!kv || !new_len))) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  for (int32_t i = 0; i < n; ++i) {          // validate everything first: all or nothing
+    const KvFile* f = c->fs->file_of(kv[i]);
+    if (!f) return fail(c, SYM_EBADF, "kv_truncate: bad handle");
+    if (new_len[i] < 0 || new_len[i] > f->len) return fail(c, SYM_EINVAL, "kv_truncate: length beyond the file");
+    for (int32_t j = 0; j < i; ++j)
+      if (c->fs->file_of(kv[j]) == f) return fail(c, SYM_EBUSY, "kv_truncate: file listed twice");
+  }
+  for (int32_t i = 0; i < n; ++i) (void)c->fs->truncate(kv[i], new_len[i]);
+  return SYM_OK;
+}
+
 int64_t sym_kv_pages(sym_ctx* c, sym_kv kv, int32_t* out, int64_t cap) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);

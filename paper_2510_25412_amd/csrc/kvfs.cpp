@@ -136,6 +136,18 @@ int64_t Kvfs::len(int32_t h) const {
   return f ? f->len : (int64_t)SYM_EBADF;
 }
 
+int Kvfs::truncate(int32_t h, int64_t new_len) {
+  if (!file_of(h)) return SYM_EBADF;
+  KvFile& f = files_[handle_file_[h]];
+  if (new_len < 0 || new_len > f.len) return SYM_EINVAL;
+  const size_t keep = (size_t)((new_len + P_ - 1) / P_);
+  for (size_t i = keep; i < f.pages.size(); ++i)
+    if (--refcount_[f.pages[i]] == 0) free_ranks_.push(rank_[f.pages[i]]);
+  f.pages.resize(keep);
+  f.len = new_len;
+  return SYM_OK;
+}
+
 int64_t Kvfs::pages_needed(int32_t n, const int32_t* handles, const int32_t* n_tokens, std::string* err) {
   pending_.clear();
   seen_files_.clear();

@@ -36,6 +36,7 @@ class Kvfs {
   int remove(int32_t h);
   int close(int32_t h);
   int64_t len(int32_t h) const;
+  int truncate(int32_t h, int64_t new_len);   // drop tokens from new_len on; frees pages no longer needed
   const KvFile* file_of(int32_t h) const;
 
   // Pages a batch would allocate, LIPs in batch order; negative status on a bad argument.

@@ -85,6 +85,11 @@ def test_random_ops_match_oracle_model_bit_exact():
             a, b = m.kv_fork(p), c.kv_fork(p)
             assert a == b
             live.append(a)
+        elif r < 0.40:
+            h = int(live[rng.integers(len(live))])
+            n = int(rng.integers(0, m.kv_len(h) + 1))
+            m.kv_truncate(h, n)
+            c.kv_truncate([h], [n])
         elif r < 0.85:
             k = min(len(live), int(rng.integers(1, 6)))
             hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
@@ -258,3 +263,15 @@ def test_descriptor_tiles_for_prefill_chunks():
     c32 = host_ctx(4096, Hq=8, Hkv=8, D=64, dtype="f32")
     w32 = c32.build_desc(n_tok, flat, off, lengths)
     assert int(w32[0]) == sum(n_tok) and int(w32[4]) == 0
+
+
+def test_truncate_errors_change_nothing():
+    c = host_ctx(8)
+    a, b = c.kv_open(), c.kv_open()
+    c.plan_append([a, b], [40, 20])
+    for kv, ln, code in (([a, b], [10, 21], binding.SYM_EINVAL), ([a, 77], [1, 1], binding.SYM_EBADF), ([a], [-1], binding.SYM_EINVAL)):
+        with pytest.raises(binding.SymError) as e:
+            c.kv_truncate(kv, ln)
+        assert e.value.code == code and c.kv_len(a) == 40 and c.kv_len(b) == 20
+    c.kv_truncate([a, b], [17, 0])
+    assert c.kv_len(a) == 17 and len(c.kv_pages(a)) == 2 and c.kv_pages(b) == [] and c.free_pages() == 6

@@ -140,3 +140,24 @@ def test_random_ops_keep_invariants():
     for h in live:
         m.kv_remove(h)
     assert m.free_pages() == 256 and int(m.refcount.sum()) == 0
+
+
+def test_truncate_frees_pages_and_keeps_sharing():
+    m = KVFSModel(16, 4)
+    a = m.kv_open()
+    m.append([(a, 10)])                       # pages 0,1,2
+    b = m.kv_fork(a)
+    m.append([(b, 5)])                        # copy of page 2 -> 3, then page 4
+    assert m.kv_pages(b) == [0, 1, 3, 4] and m.kv_len(b) == 15
+    m.kv_truncate(b, 10)                      # drafts rejected: back to the fork point
+    assert m.kv_pages(b) == [0, 1, 3] and m.free_pages() == 12 and m.kv_len(b) == 10
+    m.kv_truncate(b, 8)                       # exactly two pages
+    assert m.kv_pages(b) == [0, 1] and m.refcount.tolist()[:5] == [2, 2, 1, 0, 0]
+    m.kv_truncate(b, 6)                       # into a shared page: stays shared...
+    cow, slots = m.append([(b, 1)])           # ...until the next append copies it
+    assert cow == [(1, 3, 2)] and slots == [[(3, 2)]]
+    with pytest.raises(KVError):
+        m.kv_truncate(b, 99)
+    m.kv_truncate(a, 0)
+    assert m.kv_pages(a) == [] and m.kv_len(a) == 0
+    m.audit()
