@@ -158,15 +158,25 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
 
 /* The packed descriptor of the attention launch for a batch given by page tables (same
  * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.
- * Layout: words[0..15] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then
- * word offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total
- * words; total units (lo, hi); n_merge}, then the sections: rows [n_rows][4] = {page-table
- * offset, visible tokens, q/out row, lip}; wave_work [n_waves][12] = {row, kv head, page,
- * units, first partial, then of the first range: visible tokens, q/out row, page-table
- * offset, ids of its first three pages, 0};
- * merge [n_merge][4] = {first partial, pieces, q row * Hq + first query head, 0} for each
- * (row, kv head) that was cut.  Returns the number of words (or a negative status); writes at most
- * cap words.                                                                              */
+ * Layout: words[0..19] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then word
+ * offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total words;
+ * total units (lo, hi); n_merge; offset of the member list; n_members; n_shared_tiles}, then
+ * the sections:
+ *   rows      [n_rows][4]   page-table offset, visible tokens, q/out row, first page of the
+ *                           row's own range (pages before it belong to a shared prefix)
+ *   wave_work [n_waves][12] row, kv head, page, units, first partial, then of the first range:
+ *                           visible tokens, q/out row, page-table offset, ids of its first
+ *                           three pages, first page of the row's own range
+ *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
+ *                           partials of the row's shared prefix: first, stride, count; 0, 0
+ *   page_table, pt_off [n_lips + 1]
+ *   tiles     [n_tiles][12] page-table offset, file length before the call, first q/out row
+ *                           (shared: offset into the member list), new tokens (shared: members)
+ *                           in the tile, kv head, token offset in the chunk (shared: first
+ *                           partial slot), kind (0 prefill chunk, 1 shared prefix), first page,
+ *                           end page, 0, 0, 0
+ *   members   [n_members]   q rows of the members of shared-prefix tiles
+ * Returns the number of words (or a negative status); writes at most cap words.             */
 int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
                        const int32_t* page_table_flat, const int64_t* pt_offsets,
                        const int64_t* lengths, int32_t* words_out, int64_t cap);

@@ -34,6 +34,7 @@ struct sym_ctx {
   int64_t page_bytes = 0;
   float scale_log2e = 0.f;
   int32_t max_waves = 0, min_units = 4, range_cost = 3;
+  int32_t share_min_lips = 4, share_min_pages = 8;   // decode LIPs / common full pages needed to read a prefix once
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   std::mutex mu;
   std::string err;
@@ -81,12 +82,14 @@ bool shape_ok(const sym_config* cfg) {
 // 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
 int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
   return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + MERGE_WORDS) + entries +
-         (T + 8 * n_lips) * c->cfg.n_kv_heads +
+         (T + 8 * n_lips) * c->cfg.n_kv_heads * 2 + n_lips * (1 + c->cfg.n_kv_heads * (MERGE_WORDS + 8 * TILE_WORDS)) +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
+// Partial-result slots of the workspace: a wave boundary cuts at most one (row, head) range (<= 2
+// partial pieces per wave); the rest is for the partials of shared-prefix tiles.
+int64_t partial_slots(const sym_ctx* c) { return 12 * (int64_t)c->max_waves + 1; }
 int64_t partial_bytes(const sym_ctx* c) {
-  // a wave boundary cuts at most one (row, head) range: <= 2 partial pieces per wave
-  const int64_t np = 2 * (int64_t)c->max_waves + 1;
+  const int64_t np = partial_slots(c);
   return align_up(np * c->G * 2 * 4, 256) + align_up(np * c->G * c->cfg.head_dim * 4, 256);
 }
 
@@ -144,7 +147,7 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   // workspace: [descriptor words][partial max/sum][partial accumulators]
   const int32_t* dw = (const int32_t*)c->cfg.workspace;
   uint8_t* base = (uint8_t*)c->cfg.workspace + align_up(blob_words * 4, 256);
-  const int64_t np = 2 * (int64_t)c->max_waves + 1;
+  const int64_t np = partial_slots(c);
   float* part_ml = (float*)base;
   float* part_acc = (float*)(base + align_up(np * c->G * 2 * 4, 256));
   DecodeArgs a;
@@ -174,6 +177,9 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
     pa.out = out;
     pa.tiles = dw + d.words[H_OFF_TILES];
     pa.pt = dw + d.words[H_OFF_PT];
+    pa.members = dw + d.words[H_OFF_MEMBERS];
+    pa.part_acc = part_acc;
+    pa.part_ml = part_ml;
     pa.n_tiles = d.n_tiles;
     pa.Hq = c->cfg.n_q_heads;
     pa.Hkv = c->cfg.n_kv_heads;
@@ -234,7 +240,8 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
+                 c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "build_desc: bad batch");
   return (int64_t)c->desc.words.size();
@@ -295,6 +302,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
   c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
   c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
+  c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
+  c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));
   c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
@@ -487,7 +496,8 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens};
+  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
+                 c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
   const int64_t dwords = (int64_t)c->desc.words.size();

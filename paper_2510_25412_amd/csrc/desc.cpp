@@ -10,9 +10,7 @@ namespace symkv {
 
 int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, const int64_t* len_after,
                const int32_t* const* tables, BatchDesc* out) {
-  const int32_t P = prm.page_tokens, H = prm.n_kv_heads;
-  // A LIP with at least prefill_min new tokens goes to the tile kernel (tile_tokens new tokens x
-  // all query heads of one kv head per tile); every other new token is a row of the decode kernel.
+  const int32_t P = prm.page_tokens, H = prm.n_kv_heads, G = prm.n_q_heads / H;
   const int32_t TQ = prm.tile_tokens;
   auto is_prefill = [&](int32_t b) { return TQ > 0 && n_tokens[b] >= prm.prefill_min; };
   int64_t n_rows = 0, entries = 0, n_tiles = 0, n_tok_total = 0;
@@ -25,32 +23,151 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   }
   if (n_tok_total > 0x7fffffff / (2 * H) || entries > 0x3fffffff || n_tiles > 0x0fffffff) return SYM_EINVAL;
 
-  // ---- section sizes known up front: rows, page table, offsets
+  // ---- sharing groups: single-token LIPs whose files begin with the same pages.  Same page id
+  // means same bytes, so the group's common FULL pages can be read once for all members.
+  std::vector<int32_t>& share_start = out->share_start;   // per LIP: pages covered by the group (0 = none)
+  std::vector<int32_t>& share_base = out->share_base;     // per LIP: first shared partial of its member tile
+  std::vector<int32_t>& share_k = out->share_k;           // per LIP: members in its tile
+  std::vector<int32_t>& share_ml = out->share_ml;         // per LIP: its index among them
+  std::vector<int32_t>& share_nc = out->share_nc;         // per LIP: key chunks of the common prefix
+  std::vector<int32_t>& member_rows = out->member_rows;   // q rows of the members, tile after tile
+  std::vector<int32_t>& stiles = out->shared_tiles;       // (first lip, member offset, K, C, NC, partial base) per member tile
+  share_start.assign(n_lips, 0);
+  share_base.assign(n_lips, 0);
+  share_k.assign(n_lips, 0);
+  share_ml.assign(n_lips, 0);
+  share_nc.assign(n_lips, 0);
+  member_rows.clear();
+  stiles.clear();
+  int64_t n_shared_partials = 0, n_shared_tiles = 0;
+  const int32_t tile_lips = TQ > 0 ? 128 / G : 0;
+  if (prm.share_min_lips > 0 && tile_lips > 0) {
+    auto& cand = out->by_first_page;
+    cand.clear();
+    std::vector<int32_t>& qrow_of = out->qrow_of;            // token index of each LIP's first row
+    qrow_of.resize(n_lips);
+    int64_t tok = 0;
+    for (int32_t b = 0; b < n_lips; tok += n_tokens[b], ++b) {
+      qrow_of[b] = (int32_t)tok;
+      if (n_tokens[b] == 1 && (len_after[b] - 1) / P >= prm.share_min_pages) cand.emplace_back(tables[b][0], b);
+    }
+    std::sort(cand.begin(), cand.end());
+    // First pass: groups and their common page counts (the second pass sizes the key chunks).
+    // Files that start with the same page are candidates; inside such a run, take the first
+    // unassigned file as representative, measure how many leading pages every other one has in
+    // common with it (limited to full pages), and keep the k closest files that maximise the
+    // pages saved, (k - 1) * common pages.  Files left over get another round among themselves.
+    auto& groups = out->groups;                               // (offset into grp_members, count, C) triples
+    auto& gm = out->grp_members;
+    auto& lcp = out->lcp;                                     // (common pages, index into cand) of the round
+    groups.clear();
+    gm.clear();
+    int64_t base_tiles = 0;
+    for (size_t lo = 0; lo < cand.size();) {
+      size_t hi = lo + 1;
+      while (hi < cand.size() && cand[hi].first == cand[lo].first) ++hi;
+      size_t left = hi - lo;                                  // unassigned files of the run
+      for (size_t rep = lo; rep < hi && (int32_t)left >= prm.share_min_lips; ++rep) {
+        if (cand[rep].first < 0) continue;                    // already assigned
+        const int32_t b0 = cand[rep].second;
+        const int64_t full0 = (len_after[b0] - 1) / P;        // full pages of the file before the call
+        lcp.clear();
+        for (size_t i = rep; i < hi; ++i) {
+          if (cand[i].first < 0) continue;
+          const int32_t b = cand[i].second;
+          const int64_t lim = std::min<int64_t>(full0, (len_after[b] - 1) / P);
+          const int32_t* t = tables[b];
+          const int64_t c = i == rep ? lim : std::mismatch(t, t + lim, tables[b0]).first - t;
+          lcp.emplace_back((int32_t)(c & ~(int64_t)1), (int32_t)i);      // whole 32-token blocks
+        }
+        std::sort(lcp.begin(), lcp.end(), [](const std::pair<int32_t, int32_t>& x, const std::pair<int32_t, int32_t>& y) {
+          return x.first != y.first ? x.first > y.first : x.second < y.second;
+        });
+        int64_t best = 0;
+        size_t best_k = 0;
+        for (size_t k = (size_t)prm.share_min_lips; k <= lcp.size(); ++k) {
+          const int64_t c = lcp[k - 1].first;
+          if (c < prm.share_min_pages) break;
+          if ((int64_t)(k - 1) * c > best) {
+            best = (int64_t)(k - 1) * c;
+            best_k = k;
+          }
+        }
+        if (best_k == 0) {                                    // nothing worth sharing with this file
+          cand[rep].first = -1;
+          --left;
+          continue;
+        }
+        const int32_t C = lcp[best_k - 1].first;
+        std::sort(lcp.begin(), lcp.begin() + best_k, [](const std::pair<int32_t, int32_t>& x, const std::pair<int32_t, int32_t>& y) { return x.second < y.second; });
+        groups.insert(groups.end(), {(int32_t)gm.size(), (int32_t)best_k, C});
+        for (size_t k = 0; k < best_k; ++k) {
+          gm.push_back(cand[lcp[k].second].second);
+          cand[lcp[k].second].first = -1;
+        }
+        left -= best_k;
+        base_tiles += (int64_t)((best_k + tile_lips - 1) / tile_lips) * H;
+      }
+      lo = hi;
+    }
+    if (!groups.empty()) {
+      const int64_t target = 512;                             // about two workgroups per CU
+      const int32_t nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, (target + base_tiles - 1) / base_tiles));
+      for (size_t gi = 0; gi < groups.size(); gi += 3) {
+        const int32_t lo = groups[gi], K = groups[gi + 1], C = groups[gi + 2];
+        int32_t nc = std::max(1, std::min(nc_want, C / 8));
+        while (nc > 1 && n_shared_partials + (int64_t)K * H * nc > prm.max_partials / 2) --nc;   // partial slots must fit
+        if (n_shared_partials + (int64_t)K * H * nc > prm.max_partials / 2) continue;            // no room: plain rows
+        for (int32_t i = 0; i < K; i += tile_lips) {
+          const int32_t k = std::min(tile_lips, K - i);
+          const int32_t moff = (int32_t)member_rows.size();
+          for (int32_t j = 0; j < k; ++j) {
+            const int32_t b = gm[lo + i + j];
+            member_rows.push_back(qrow_of[b]);
+            share_start[b] = C;
+            share_base[b] = (int32_t)n_shared_partials;
+            share_k[b] = k;
+            share_ml[b] = j;
+            share_nc[b] = nc;
+          }
+          stiles.insert(stiles.end(), {gm[lo + i], moff, k, C, nc, (int32_t)n_shared_partials});
+          n_shared_partials += (int64_t)k * H * nc;
+          n_shared_tiles += (int64_t)H * nc;
+        }
+      }
+    }
+  }
+  n_tiles += n_shared_tiles;
+
+  // ---- units of the decode kernel
   int64_t total_units = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     if (is_prefill(b)) continue;
     for (int32_t i = 0; i < n_tokens[b]; ++i) {
       int64_t vis = len_after[b] - n_tokens[b] + i + 1;
-      total_units += ((vis + P - 1) / P) * H;
+      total_units += ((vis + P - 1) / P - share_start[b]) * H;
     }
   }
   int64_t nw = (total_units + prm.min_units_per_wave - 1) / prm.min_units_per_wave;
   nw = std::max<int64_t>(1, std::min<int64_t>(nw, prm.max_waves));
   if (total_units == 0) nw = 0;
+  const int64_t n_members = (int64_t)member_rows.size();
 
   std::vector<int32_t>& w = out->words;
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
-  const int64_t off_pt = off_merge + nw * MERGE_WORDS;      // at most one cut (row, head) per wave boundary
+  // a merge entry per cut (row, head) (at most one per wave boundary) and per (member row, head)
+  const int64_t off_pt = off_merge + (nw + n_members * H) * MERGE_WORDS;
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
-  const int64_t total = off_tiles + n_tiles * TILE_WORDS;
+  const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
+  const int64_t total = off_members + n_members;
   if (total > 0x7fffffff) return SYM_EINVAL;
   w.resize((size_t)total);
   std::memset(w.data(), 0, DESC_HEADER_WORDS * sizeof(int32_t));
 
-  // ---- rows, tiles, page table
+  // ---- rows, prefill tiles, page table
   int32_t* rows = w.data() + off_rows;
   int32_t* pt = w.data() + off_pt;
   int32_t* ptoff = w.data() + off_ptoff;
@@ -67,20 +184,21 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       for (int32_t g = 0; g < H; ++g)
         for (int32_t t0 = 0; t0 < n_tokens[b]; t0 += TQ, ++ti) {
           int32_t* t = tiles + ti * TILE_WORDS;
-          t[0] = (int32_t)e_lip;                                   // page-table offset
-          t[1] = (int32_t)(len_after[b] - n_tokens[b]);            // file length before the call
-          t[2] = (int32_t)(tok + t0);                              // q / out row of the tile's first token
-          t[3] = std::min<int32_t>(TQ, n_tokens[b] - t0);          // tokens in the tile
-          t[4] = g;
-          t[5] = t0;                                               // token offset inside the chunk
-          t[6] = t[7] = 0;
+          std::memset(t, 0, TILE_WORDS * sizeof(int32_t));
+          t[T_TBL] = (int32_t)e_lip;                                // page-table offset
+          t[T_LEN] = (int32_t)(len_after[b] - n_tokens[b]);         // file length before the call
+          t[T_QROW] = (int32_t)(tok + t0);                          // q / out row of the tile's first token
+          t[T_COUNT] = std::min<int32_t>(TQ, n_tokens[b] - t0);     // tokens in the tile
+          t[T_HEAD] = g;
+          t[T_AUX] = t0;                                            // token offset inside the chunk
+          t[T_KIND] = TILE_PREFILL;
         }
     } else {
       for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
         rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
         rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
         rows[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row
-        rows[r * ROW_WORDS + 3] = b;
+        rows[r * ROW_WORDS + 3] = share_start[b];                                   // first page of the row's own range
       }
     }
     tok += n_tokens[b];
@@ -95,20 +213,21 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int32_t* waves = w.data() + off_waves;
   int32_t* merge = w.data() + off_merge;
   auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
+  auto row_first = [&](int64_t rr) { return rows[rr * ROW_WORDS + 3]; };
   const int64_t alpha = prm.range_cost;
   const int64_t vtotal = total_units + alpha * n_rows * H;
   {
     int64_t k = 0, vstart = 0;     // next boundary to place; virtual start of the current (row, head)
     for (int64_t row = 0; row < n_rows && k < nw; ++row) {
-      const int32_t np = row_pages(row);
+      const int32_t np = row_pages(row), p0 = row_first(row);
       for (int32_t g = 0; g < H && k < nw; ++g) {
-        const int64_t vend = vstart + alpha + np;
+        const int64_t vend = vstart + alpha + (np - p0);
         while (k < nw && vtotal * k / nw < vend) {
           const int64_t o = vtotal * k / nw - vstart;
           int32_t* ww = waves + k * WAVE_WORDS;
           ww[0] = (int32_t)row;
           ww[1] = g;
-          ww[2] = (int32_t)std::max<int64_t>(0, o - alpha);
+          ww[2] = p0 + (int32_t)std::max<int64_t>(0, o - alpha);
           ++k;
         }
         vstart = vend;
@@ -116,7 +235,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     }
   }
   int32_t part = 0;
-  int32_t n_merge = 0;        // (row, head) ranges that were cut and need a merge
+  int32_t n_merge = 0;        // (row, head) ranges that need a merge
   for (int64_t k = 0; k < nw; ++k) {
     int32_t* ww = waves + k * WAVE_WORDS;
     int64_t row = ww[0];
@@ -128,23 +247,22 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     ww[5] = rows[row * ROW_WORDS + 1];
     ww[6] = rows[row * ROW_WORDS + 2];
     ww[7] = rows[row * ROW_WORDS + 0];
-    for (int i = 0; i < 4; ++i) ww[8 + i] = 0;
     {                                   // ids of the first pages: their loads need no table lookup
       const int32_t np0 = row_pages(row);
       const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
       for (int i = 0; i < 3; ++i) ww[8 + i] = t0[std::min(p + i, np0 - 1)];
     }
+    ww[11] = row_first(row);
     int64_t units = 0;
     while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
-      const int32_t np = row_pages(row);
+      const int32_t np = row_pages(row), p0 = row_first(row);
       const int32_t cnt = (row == erow && g == eg) ? ep - p : np - p;
       if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
-        if (p == 0) {                                          // first piece of a cut (row, g)
+        if (p == p0) {                                         // first piece of this (row, g)
           int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
+          std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
           it[0] = part;
-          it[1] = 0;
-          it[2] = rows[row * ROW_WORDS + 2] * prm.n_q_heads + g * (prm.n_q_heads / H);
-          it[3] = 0;
+          it[2] = rows[row * ROW_WORDS + 2] * prm.n_q_heads + g * G;
           ++n_merge;
         }
         ++merge[(int64_t)(n_merge - 1) * MERGE_WORDS + 1];
@@ -153,19 +271,62 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       units += cnt;
       p += cnt;
       if (p == np) {
-        p = 0;
         if (++g == H) {
           g = 0;
           ++row;
         }
+        p = row < n_rows ? row_first(row) : 0;
       }
     }
     ww[3] = (int32_t)units;
   }
 
+  // ---- shared-prefix tiles and the extra partials of their members' merge entries
+  const int32_t shared_base = part;
+  if (!stiles.empty()) {
+    int32_t* members = w.data() + off_members;
+    std::memcpy(members, member_rows.data(), member_rows.size() * sizeof(int32_t));
+    for (size_t s = 0; s < stiles.size(); s += 6) {
+      const int32_t b0 = stiles[s], moff = stiles[s + 1], k = stiles[s + 2], C = stiles[s + 3], nc = stiles[s + 4], base = stiles[s + 5];
+      const int32_t cp = ((C + nc - 1) / nc + 1) & ~1;        // pages per key chunk, even
+      for (int32_t g = 0; g < H; ++g)
+        for (int32_t c = 0; c < nc; ++c, ++ti) {
+          int32_t* t = tiles + ti * TILE_WORDS;
+          std::memset(t, 0, TILE_WORDS * sizeof(int32_t));
+          t[T_TBL] = ptoff[b0];
+          t[T_QROW] = moff;                                    // offset into the member list
+          t[T_COUNT] = k;
+          t[T_HEAD] = g;
+          t[T_AUX] = shared_base + base + (g * nc + c) * k;    // first partial of this tile
+          t[T_KIND] = TILE_SHARED;
+          t[T_PAGE0] = std::min(c * cp, C);
+          t[T_PAGE1] = std::min((c + 1) * cp, C);
+        }
+    }
+  }
+  // every (member row, head): extra partials first + i * stride, i < count
+  if (n_members > 0) {
+    // merge entries are sorted by word 2 (q row * Hq + first head), as are the LIPs by q row
+    int64_t tk = 0;
+    int32_t mi = 0;
+    for (int32_t b = 0; b < n_lips; tk += n_tokens[b], ++b) {
+      if (share_start[b] == 0) continue;
+      for (int32_t g = 0; g < H; ++g) {
+        const int32_t key = (int32_t)tk * prm.n_q_heads + g * G;
+        while (mi < n_merge && merge[(int64_t)mi * MERGE_WORDS + 2] < key) ++mi;
+        int32_t* it = merge + (int64_t)mi * MERGE_WORDS;     // exists: a member row never writes final output itself
+        it[3] = shared_base + share_base[b] + g * share_nc[b] * share_k[b] + share_ml[b];
+        it[4] = share_k[b];
+        it[5] = share_nc[b];
+      }
+    }
+  }
+  const int32_t n_partials = shared_base + (int32_t)n_shared_partials;
+  if (n_partials > prm.max_partials) return SYM_ENOSPC;
+
   w[H_N_ROWS] = (int32_t)n_rows;
   w[H_N_WAVES] = (int32_t)nw;
-  w[H_N_PARTIALS] = part;
+  w[H_N_PARTIALS] = n_partials;
   w[H_N_LIPS] = n_lips;
   w[H_N_TILES] = (int32_t)n_tiles;
   w[H_N_MERGE] = n_merge;
@@ -175,12 +336,15 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   w[H_OFF_PT] = (int32_t)off_pt;
   w[H_OFF_PTOFF] = (int32_t)off_ptoff;
   w[H_OFF_TILES] = (int32_t)off_tiles;
+  w[H_OFF_MEMBERS] = (int32_t)off_members;
+  w[H_N_MEMBERS] = (int32_t)n_members;
+  w[H_N_SHARED_TILES] = (int32_t)n_shared_tiles;
   w[H_TOTAL_WORDS] = (int32_t)total;
   w[H_TOTAL_UNITS_LO] = (int32_t)(total_units & 0xffffffff);
   w[H_TOTAL_UNITS_HI] = (int32_t)(total_units >> 32);
   out->n_rows = (int32_t)n_rows;
   out->n_waves = (int32_t)nw;
-  out->n_partials = part;
+  out->n_partials = n_partials;
   out->n_merge = n_merge;
   out->n_lips = n_lips;
   out->n_tiles = (int32_t)n_tiles;

@@ -2,10 +2,15 @@
 // the inference scheduler aggregates pred calls into one GPU batch) into the integer work
 // description of the attention launch.  Pure host code, no HIP.
 //
-// A LIP that brings many new tokens (a prefill chunk) is cut into tiles of tile_tokens new
-// tokens x one kv head for the MFMA tile kernel.  Every other new token is a "row" with a
-// visible length (file tokens 0 .. len_before + i) for the decode kernel.  The
-// work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
+// Three kinds of work come out of a batch:
+//  * prefill tiles: a LIP that brings many new tokens (a prefill chunk) is cut into tiles of
+//    tile_tokens new tokens x one kv head for the MFMA tile kernel;
+//  * shared-prefix tiles: decode LIPs whose files start with the same pages (forks of one prefix,
+//    paper Fig. 1 / section 4.2) are grouped; the common full pages are read ONCE per group by
+//    the tile kernel (rows = members x query heads of the group), leaving partial results;
+//  * decode rows: every other new token is a "row" with a visible length (file tokens
+//    0 .. len_before + i); a member of a sharing group is a row that starts after the common pages.
+// The work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
 // slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves contiguous
 // ranges of equal cost, one per wavefront, whatever the raggedness of the files.  A range
 // that covers only part of a (row, kv head) produces a partial result (running max, sum,
@@ -13,25 +18,29 @@
 // (row, kv head) writes the final output directly and has no partial.
 #pragma once
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 16, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 4, TILE_WORDS = 8 };
+enum { DESC_HEADER_WORDS = 20, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 8, TILE_WORDS = 12 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
   H_OFF_ROWS, H_OFF_WAVES, H_OFF_MERGE, H_OFF_PT, H_OFF_PTOFF, H_OFF_TILES, H_TOTAL_WORDS,
-  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI, H_N_MERGE
+  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI, H_N_MERGE, H_OFF_MEMBERS, H_N_MEMBERS, H_N_SHARED_TILES
 };
+// tile words
+enum { T_TBL = 0, T_LEN, T_QROW, T_COUNT, T_HEAD, T_AUX, T_KIND, T_PAGE0, T_PAGE1 };
+enum { TILE_PREFILL = 0, TILE_SHARED = 1 };
 
 struct BatchDesc {
   std::vector<int32_t> words;      // packed descriptor, header first
   int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
   int64_t total_units = 0;
-
-  const int32_t* rows() const { return words.data() + words[H_OFF_ROWS]; }
-  const int32_t* waves() const { return words.data() + words[H_OFF_WAVES]; }
+  // scratch of the builder, kept between calls
+  std::vector<std::pair<int32_t, int32_t>> by_first_page, lcp;
+  std::vector<int32_t> share_start, share_base, share_k, share_ml, share_nc, member_rows, shared_tiles, qrow_of, groups, grp_members;
 };
 
 struct DescParams {
@@ -41,6 +50,9 @@ struct DescParams {
   int32_t range_cost;         // cost of starting a (row, head) range, in units, when balancing
   int32_t prefill_min;        // LIPs with at least this many new tokens use the tile kernel
   int32_t tile_tokens;        // new tokens per tile (0 = no tile kernel for this shape)
+  int32_t share_min_lips;     // decode LIPs that must share a prefix to form a group (0 = never group)
+  int32_t share_min_pages;    // common full pages a group must have
+  int32_t max_partials;       // partial-result slots the workspace holds
 };
 
 // n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page

@@ -112,6 +112,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
   int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
   int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
   int pid2 = __builtin_amdgcn_readfirstlane(ww[10]);
+  int pstart = __builtin_amdgcn_readfirstlane(ww[11]);   // first page of the row's own range (pages before it are a
+                                                         // shared prefix handled by the tile kernel)
   bool first_range = true;
 
   while (remaining > 0) {
@@ -303,7 +305,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
     remaining -= cnt;
     p += cnt;
     if (p == np) {
-      p = 0;
       if (++g == a.Hkv) {
         g = 0;
         ++row;
@@ -311,8 +312,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
           tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
           vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
           qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
+          pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
         }
       }
+      p = pstart;
     }
   }
 }
@@ -321,7 +324,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(Decode
 // Prefill-chunk attention on the matrix cores (bf16 storage, D = 128).  One workgroup of 4
 // wavefronts per tile = (LIP, kv head, TQ = 128/G consecutive new tokens): 128 query rows
 // (token, head of the group), 32 per wavefront.  The file's K/V is walked in blocks of 32 tokens
-// (two pages), staged through LDS and shared by the 4 wavefronts.
+// (two pages), staged through LDS and shared by the 4 wavefronts.  The same kernel serves
+// shared-prefix tiles: 128 rows = the decode rows (members x heads) of LIPs whose files begin
+// with the same pages; it reads those pages once for all of them and leaves partial results.
 //
 // Everything is computed transposed so that what belongs to one query row lives in one lane:
 //   S^T[token][row] = K · Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
@@ -348,31 +353,38 @@ constexpr int kVLds = 128 * kVRow;        // 10 KiB
 
 template <int G>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
-  constexpr int TQ = kTileRows / G;
   __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
   // tiles that read the same K/V are neighbours in the list; blocks go round-robin over the 8
   // XCDs, so give each XCD a contiguous run of the list (only locality depends on this)
   const int per_xcd = (a.n_tiles + 7) / 8;
   const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (tile >= a.n_tiles) return;
-  const int32_t* tw = a.tiles + tile * 8;
-  const int tbl_off = tw[0], L = tw[1], qrow0 = tw[2], nt = tw[3], g = tw[4], t0 = tw[5];
+  const int32_t* tw = a.tiles + tile * 12;
+  const int tbl_off = tw[0], g = tw[4], count = tw[3];
+  const bool shared = tw[6] != 0;
   const int32_t* tbl = a.pt + tbl_off;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int col = lane & 31, hf = lane >> 5;
   const int rho = wv * 32 + col;                 // query row of this lane inside the tile
-  const int tl = rho / G, h = rho % G;
-  const int tlc = min(tl, nt - 1);               // rows past the tile's last token repeat it (never written)
-  const int vis = L + t0 + tlc + 1;              // tokens this row sees
-  const int kv_end = L + t0 + nt;                // tokens the tile's last row sees
+  const int tl = rho / G, h = rho % G;           // token (prefill) or member (shared prefix) of the row, head
+  const int tlc = min(tl, count - 1);            // rows past the tile's last token/member repeat it (never written)
+  // prefill chunk: `count` new tokens from chunk offset t0 on a file of L tokens; row tl sees
+  // tokens 0 .. L + t0 + tl.  shared prefix: `count` decode rows (q rows in the member list) that
+  // all see the same full pages [page0, page1) of the group's first file.
+  const int L = tw[1], t0 = tw[5];
+  const int qrow = shared ? a.members[tw[2] + tlc] : tw[2] + tlc;
+  const int kv_end = shared ? tw[8] * kP : L + t0 + count;       // tokens the tile's last row sees
+  const int vis = shared ? kv_end : L + t0 + tlc + 1;            // tokens this row sees
+  const int mask_from = shared ? kv_end : L + t0 + 1;            // first token some row may not see
+  const int kb0 = shared ? tw[7] / 2 : 0;                        // first 32-token block (page0 is even)
   const int nblk = (kv_end + kKvBlock - 1) / kKvBlock;
-  const int last_page = (kv_end + kP - 1) / kP - 1;
+  const int last_page = max((kv_end + kP - 1) / kP - 1, 0);
 
   // Q of this lane's row: 8 k-steps of 16 dims, this lane supplies dims 16*ks + 8*hf .. +8
   bf16x8_t q[8];
   {
-    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)(qrow0 + tlc) * a.Hq + g * G + h) * kRowBytes + hf * 16;
+    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * G + h) * kRowBytes + hf * 16;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 32));
   }
@@ -426,8 +438,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
     for (int v = 0; v < 16; ++v) O[db][v] = 0.f;
   float m = -1e30f, l = 0.f;
 
-  issue_loads(0);
-  for (int kb = 0; kb < nblk; ++kb) {
+  if (kb0 < nblk) issue_loads(kb0);
+  for (int kb = kb0; kb < nblk; ++kb) {
     uint8_t* base = lds[kb & 1];
     store_lds(kb, base);
     __syncthreads();           // block kb is in LDS; everyone is done with block kb-1's other buffer
@@ -445,7 +457,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
     // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
     const int tok0 = kb * kKvBlock + 4 * hf;
     float mx = -__builtin_inff();
-    if (tok0 + kKvBlock > L + t0 + 1 - 4 * hf) {       // the block reaches the causal edge of some row
+    if (kb * kKvBlock + kKvBlock > mask_from) {        // the block reaches the causal edge of some row
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int tok = tok0 + 8 * (v >> 2) + (v & 3);
@@ -491,14 +503,29 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
   }
 
   l += __shfl_xor(l, 32);
-  if (tl < nt) {
-    const float inv = 1.0f / l;
-    float* o = a.out + ((int64_t)(qrow0 + tl) * a.Hq + g * G + h) * 128 + 4 * hf;
+  if (tl < count) {
+    if (!shared) {
+      const float inv = 1.0f / l;
+      float* o = a.out + ((int64_t)qrow * a.Hq + g * G + h) * 128 + 4 * hf;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int vb = 0; vb < 4; ++vb)
-        *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb] * inv, O[db][4 * vb + 1] * inv, O[db][4 * vb + 2] * inv, O[db][4 * vb + 3] * inv);
+        for (int vb = 0; vb < 4; ++vb)
+          *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb] * inv, O[db][4 * vb + 1] * inv, O[db][4 * vb + 2] * inv, O[db][4 * vb + 3] * inv);
+    } else {
+      // partial result of member tl for the merge kernel: unnormalised accumulator, max, sum
+      const int64_t part = (int64_t)t0 + tl;             // t0 = first partial slot of this tile
+      float* o = a.part_acc + (part * G + h) * 128 + 4 * hf;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb)
+          *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb], O[db][4 * vb + 1], O[db][4 * vb + 2], O[db][4 * vb + 3]);
+      if (hf == 0) {
+        a.part_ml[(part * G + h) * 2 + 0] = m;
+        a.part_ml[(part * G + h) * 2 + 1] = l;
+      }
+    }
   }
 }
 
@@ -507,19 +534,29 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
 //   out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M),  M = max_i m_i.
 // The G*D accumulator values of a piece form one flat list; lane owns entries e*64 + lane.  All
 // loads of a group of 4 pieces are issued before any is used (indices past the end re-read the
-// last piece with weight 0), so the kernel costs a few memory round trips.
+// last piece with weight 0), so the kernel costs a few memory round trips.  A row that belongs
+// to a shared-prefix group has extra pieces: the partials the tile kernel left for the prefix.
 // ---------------------------------------------------------------------------------------
 template <int G, int D>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a) {
   const int lane = threadIdx.x & 63;
   const int item = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
   if (item >= a.n_items) return;
-  const int first = __builtin_amdgcn_readfirstlane(a.items[item * 4 + 0]);
-  const int pieces = __builtin_amdgcn_readfirstlane(a.items[item * 4 + 1]);
-  const int64_t out_row = (int64_t)__builtin_amdgcn_readfirstlane(a.items[item * 4 + 2]) * D;   // (q row * Hq + first head) * D
+  const int32_t* it = a.items + item * 8;
+  const int first = __builtin_amdgcn_readfirstlane(it[0]);
+  const int own = __builtin_amdgcn_readfirstlane(it[1]);
+  const int64_t out_row = (int64_t)__builtin_amdgcn_readfirstlane(it[2]) * D;   // (q row * Hq + first head) * D
+  // pieces own .. own + xcount - 1 are the partials of the row's shared prefix: xfirst + i * xstride
+  const int xfirst = __builtin_amdgcn_readfirstlane(it[3]);
+  const int xstride = __builtin_amdgcn_readfirstlane(it[4]);
+  const int pieces = own + __builtin_amdgcn_readfirstlane(it[5]);
+  auto slot = [&](int i) -> int64_t {
+    i = min(i, pieces - 1);
+    return i < own ? first + i : xfirst + (int64_t)(i - own) * xstride;
+  };
   constexpr int VL = G * D / 64;
-  const float* ml0 = a.part_ml + (int64_t)first * G * 2;
-  const float* pa0 = a.part_acc + (int64_t)first * G * D + lane;
+  const float* ml0 = a.part_ml;
+  const float* pa0 = a.part_acc + lane;
   float Mx[G], ls[G], o[VL];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
@@ -533,7 +570,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a)
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int h = 0; h < G; ++h) mv[u][h] = ml0[((int64_t)min(i0 + u, pieces - 1) * G + h) * 2];
+      for (int h = 0; h < G; ++h) mv[u][h] = ml0[(slot(i0 + u) * G + h) * 2];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -543,7 +580,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a)
     float mv[4][G], lv[4][G], t[4][VL];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t ii = min(i0 + u, pieces - 1);
+      const int64_t ii = slot(i0 + u);
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         mv[u][h] = ml0[(ii * G + h) * 2];

@@ -27,9 +27,14 @@ struct PrefillArgs {
   int64_t page_bytes;
   const void* q;            // [tokens][Hq][128] bf16
   float* out;               // [tokens][Hq][128]
-  const int32_t* tiles;     // [n_tiles][8]: page-table offset, length before, first q/out row,
-                            //   tokens in the tile, kv head, token offset in the chunk, 0, 0
+  const int32_t* tiles;     // [n_tiles][12]: page-table offset, length before, first q/out row (or offset
+                            //   into members), tokens (or members) in the tile, kv head, token offset in the
+                            //   chunk (or first partial slot), kind (0 prefill, 1 shared prefix), first page,
+                            //   end page, 0, 0, 0
   const int32_t* pt;        // flattened page tables
+  const int32_t* members;   // q rows of the members of shared-prefix tiles
+  float* part_acc;          // partial results (shared-prefix tiles)
+  float* part_ml;
   int32_t n_tiles, Hq, Hkv;
   float scale_log2e;
 };
@@ -37,7 +42,8 @@ struct PrefillArgs {
 struct MergeArgs {
   const float* part_acc;
   const float* part_ml;
-  const int32_t* items;     // [n_items][4]: first partial, pieces, q row * Hq + first head, 0
+  const int32_t* items;     // [n_items][8]: first partial, pieces, q row * Hq + first head, then the extra
+                            //   pieces of a shared prefix: first, stride, count; 0, 0
   float* out;
   int32_t n_items;
 };

@@ -274,3 +274,26 @@ def test_prefill_chunk_equals_sequential():
         outs.append(sess2.pred(sess2.upload_batch(one)).cpu().numpy())
     check_outputs(got, np.concatenate(outs), tol=1e-3)
     sess2.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8)])
+def test_shared_prefix_groups(Hq, Hkv, monkeypatch):
+    """Forks of a prefix decode through the shared-prefix tiles (prefix pages read once per
+    group) + their own rows + the merge: groups larger than a tile, an unaligned prefix, members
+    with no private tokens, a fork of a fork, an unrelated file, in one batch.  Outputs must
+    match the oracle, and match the run with grouping switched off."""
+    shape = synth.Shape(Hq, Hkv, 128, 16, synth.BF16)
+    files = [("new", 600), ("new", 205), ("new", 333)]                       # two prefixes, one loner
+    files += [("fork", 0, int(s)) for s in (0, 1, 15, 16, 17, 40, 100, 3)]    # 8 forks of file 0
+    files += [("fork", 1, 2 * i) for i in range(40)]                         # 40 forks of file 1 (unaligned prefix)
+    files += [("fork", 5, 0), ("fork", 5, 9)]                                # forks of a fork
+    batch = [(f, 1) for f in range(2, len(files))] + [(0, 1)]
+    wl = synth.custom(f"share_{Hq}_{Hkv}", shape, files, batch, 512, seed=77 + Hq)
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+    monkeypatch.setenv("SYM_SHARE_MIN_LIPS", "0")
+    plain, sess2 = _hip().run_workload(wl, poison=True)
+    sess2.close()
+    check_outputs(got, plain, tol=1e-3)     # the tile kernel rounds softmax weights to fp16, the decode kernel does not

@@ -149,11 +149,11 @@ def test_error_codes_and_all_or_nothing():
 
 
 def _walk_desc(words, Hkv, P=16):
-    hdr = words[:16]
+    hdr = words[:20]
     n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
     waves = words[hdr[6]:hdr[6] + 12 * n_waves].reshape(n_waves, 12)
-    merge = words[hdr[7]:hdr[7] + 4 * int(hdr[14])].reshape(int(hdr[14]), 4)
+    merge = words[hdr[7]:hdr[7] + 8 * int(hdr[14])].reshape(int(hdr[14]), 8)
     pt = words[hdr[8]:hdr[9]]
     ptoff = words[hdr[9]:hdr[9] + n_lips + 1]
     return n_rows, n_waves, n_partials, rows, waves, merge, pt, ptoff
@@ -175,7 +175,7 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert n_rows == sum(n_tok) and np.array_equal(pt, flat) and np.array_equal(ptoff, off)
     # rows: lip, visible tokens, q row
     exp_rows = [(b, L - n + i + 1, None) for b, (L, n) in enumerate(zip(lengths, n_tok)) for i in range(n)]
-    assert [(int(r[3]), int(r[1])) for r in rows] == [(b, v) for b, v, _ in exp_rows]
+    assert [int(r[1]) for r in rows] == [v for _, v, _ in exp_rows] and not rows[:, 3].any()
     assert rows[:, 2].tolist() == list(range(n_rows))
     assert [int(r[0]) for r in rows] == [int(off[b]) for b, _, _ in exp_rows]
     # walk every wave's range exactly as the kernel does; record coverage and partial numbering
@@ -215,7 +215,8 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert max(cost) - min(cost) <= 1 + 2 * range_cost
     assert n_waves <= waves
     items = {}
-    for first, cnt, out_idx, _ in merge.tolist():
+    for first, cnt, out_idx, xf, xs, xc, _, _ in merge.tolist():
+        assert xc == 0
         items[out_idx] = (first, cnt)
     seen_parts = []
     for (row, g), ps in sorted(pieces.items()):
@@ -249,16 +250,16 @@ def test_descriptor_tiles_for_prefill_chunks():
     flat = np.arange(sum(np_l), dtype=np.int32)
     off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
     words = c.build_desc(n_tok, flat, off, lengths)
-    hdr = words[:16]
+    hdr = words[:20]
     n_rows, n_tiles = int(hdr[0]), int(hdr[4])
     assert n_rows == 4 and n_tiles == (3 + 1) * 8
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
-    assert rows[:, 2].tolist() == [70, 71, 72, 73] and rows[:, 3].tolist() == [1, 2, 2, 2]
+    assert rows[:, 2].tolist() == [70, 71, 72, 73] and rows[:, 0].tolist() == [int(off[1]), int(off[2]), int(off[2]), int(off[2])]
     assert rows[:, 1].tolist() == [77, 38, 39, 40]
-    tiles = words[hdr[10]:hdr[10] + 8 * n_tiles].reshape(n_tiles, 8)
-    exp = [(int(off[0]), 30, t0, min(32, 70 - t0), g, t0) for g in range(8) for t0 in (0, 32, 64)]
-    exp += [(int(off[3]), 0, 74, 16, g, 0) for g in range(8)]
-    assert [tuple(int(x) for x in t[:6]) for t in tiles] == exp
+    tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
+    exp = [(int(off[0]), 30, t0, min(32, 70 - t0), g, t0, 0) for g in range(8) for t0 in (0, 32, 64)]
+    exp += [(int(off[3]), 0, 74, 16, g, 0, 0) for g in range(8)]
+    assert [tuple(int(x) for x in t[:7]) for t in tiles] == exp
     # fp32 storage has no tile kernel: everything is a row
     c32 = host_ctx(4096, Hq=8, Hkv=8, D=64, dtype="f32")
     w32 = c32.build_desc(n_tok, flat, off, lengths)
@@ -275,3 +276,57 @@ def test_truncate_errors_change_nothing():
         assert e.value.code == code and c.kv_len(a) == 40 and c.kv_len(b) == 20
     c.kv_truncate([a, b], [17, 0])
     assert c.kv_len(a) == 17 and len(c.kv_pages(a)) == 2 and c.kv_pages(b) == [] and c.free_pages() == 6
+
+
+def test_descriptor_shared_prefix_groups():
+    """Single-token LIPs whose page lists start with the same ids form a group: the common full
+    pages become shared tiles (members x kv heads x key chunks), the members' rows start after
+    them, and every (member row, head) gets a merge entry that points at the tiles' partials."""
+    c = host_ctx(4096, decode_waves=64)
+    prefix = list(range(100, 140))                      # 40 shared pages
+    # 6 forks of the prefix with private tails, one unrelated file, one fork that shares only 3 pages
+    tables, lengths = [], []
+    for i in range(6):
+        tail = list(range(1000 + 10 * i, 1000 + 10 * i + 1 + i % 3))
+        tables.append(prefix + tail)
+        lengths.append(16 * 40 + 16 * (len(tail) - 1) + 1 + i)
+    tables.append(list(range(2000, 2020)))
+    lengths.append(16 * 20 - 3)
+    tables.append(prefix[:3] + list(range(3000, 3030)))
+    lengths.append(16 * 33 - 1)
+    flat = np.concatenate(tables).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+    words = c.build_desc([1] * 8, flat, off, lengths)
+    hdr = words[:20]
+    n_rows, n_tiles, n_merge, n_members, n_shared = int(hdr[0]), int(hdr[4]), int(hdr[14]), int(hdr[16]), int(hdr[17])
+    assert n_rows == 8 and n_members == 6 and n_tiles == n_shared and n_shared % 8 == 0
+    nc = n_shared // 8
+    rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
+    assert rows[:, 3].tolist() == [40] * 6 + [0, 0]       # members start after the 40 common pages
+    members = words[hdr[15]:hdr[15] + n_members].tolist()
+    assert members == [0, 1, 2, 3, 4, 5]
+    tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
+    assert all(int(t[6]) == 1 and int(t[3]) == 6 and int(t[0]) == int(off[0]) for t in tiles)
+    covered = {}
+    for t in tiles:
+        covered.setdefault(int(t[4]), []).append((int(t[7]), int(t[8])))
+        assert int(t[7]) % 2 == 0 and int(t[8]) % 2 == 0
+    for g in range(8):                                   # every head: the chunks tile [0, 40) exactly
+        spans = sorted(covered[g])
+        assert spans[0][0] == 0 and spans[-1][1] == 40 and all(a[1] == b[0] for a, b in zip(spans, spans[1:]))
+    merge = words[hdr[7]:hdr[7] + 8 * n_merge].reshape(n_merge, 8)
+    by_out = {int(m[2]): m for m in merge}
+    n_partials = int(hdr[2])
+    used = set()
+    for r in range(6):
+        for g in range(8):
+            m = by_out[r * 32 + g * 4]
+            assert int(m[1]) >= 1 and int(m[5]) == nc and int(m[4]) == 6
+            slots = [int(m[3]) + i * int(m[4]) for i in range(nc)]
+            tile_first = sorted(int(t[5]) for t in tiles if int(t[4]) == g)
+            assert slots == [f + r for f in tile_first]      # member r of each chunk tile of head g
+            used.update(slots)
+            used.update(range(int(m[0]), int(m[0]) + int(m[1])))
+    assert max(used) < n_partials
+    # the unrelated file and the 3-page sharer are ordinary rows
+    assert all(int(by_out[k][5]) == 0 for k in by_out if k // 32 >= 6)
