@@ -189,10 +189,9 @@ int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, 
 /* ---- measurement ------------------------------------------------------------------- */
 /* Kernel ids for sym_profile_read. */
 #define SYM_K_PROLOGUE 0   /* descriptor copy + copy-on-write copies + KV append, one launch */
-#define SYM_K_DECODE   1   /* attention over the page tables                                 */
+#define SYM_K_ATTN     1   /* attention over the page tables: decode ranges + MFMA tiles     */
 #define SYM_K_MERGE    2   /* merge of the partial results of ranges that were cut           */
-#define SYM_K_PREFILL  3
-#define SYM_K_COUNT    4
+#define SYM_K_COUNT    3
 /* sym_profile_enable(mask): bit k of mask set = every launch of kernel id k is bracketed by
  * HIP events on the launch stream (at most 4096 launches are kept per kernel id, later ones
  * are not timed); mask 0 = off.

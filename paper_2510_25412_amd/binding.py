@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
 
 SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
 SYM_F32, SYM_BF16 = 0, 1
-K_PROLOGUE, K_DECODE, K_MERGE, K_PREFILL = 0, 1, 2, 3
+K_PROLOGUE, K_ATTN, K_MERGE = 0, 1, 2
 
 
 class SymConfig(C.Structure):
@@ -183,6 +183,20 @@ class Context:
         nt_a, nt_p = _i32(n_tokens)
         self._chk(self.lib.sym_pred_batch(self.h, len(kv_a), kv_p, nt_p, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream))
 
+    def prepare_batch(self, kv, n_tokens, q, k_new, v_new, out):
+        """Marshals the arguments of pred_batch once, for callers that issue the same batch many
+        times (a decode loop): returns an object for pred_prepared.  The arrays and tensors are
+        kept alive by the object."""
+        kv_a, nt_a = np.ascontiguousarray(kv, np.int32), np.ascontiguousarray(n_tokens, np.int32)
+        keep = (kv_a, nt_a, q, k_new, v_new, out)
+        args = (len(kv_a), C.cast(kv_a.ctypes.data, _I32P), C.cast(nt_a.ctypes.data, _I32P), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out))
+        return keep, args
+
+    def pred_prepared(self, prepared, stream=None):
+        rc = self.lib.sym_pred_batch(self.h, *prepared[1], stream)
+        if rc < 0:
+            self._chk(rc)
+
     def pred_batch_raw(self, n_tokens, page_table_flat, pt_offsets, lengths, q, out, stream=None):
         nt_a, nt_p = _i32(n_tokens)
         pt_a, pt_p = _i32(page_table_flat)
@@ -234,7 +248,7 @@ class Context:
 
     # ---- measurement ----
     def profile_enable(self, mask):
-        """mask: bit k = time kernel id k (K_DECODE ...); 0 = off."""
+        """mask: bit k = time kernel id k (K_ATTN ...); 0 = off."""
         self._chk(self.lib.sym_profile_enable(self.h, int(mask)))
 
     def profile_read(self, kernel_id):

@@ -53,7 +53,7 @@ struct sym_ctx {
   // profiling
   int prof_mask = 0;
   std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
-  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0};
+  int ev_used[SYM_K_COUNT] = {0, 0, 0};
   // counters
   int64_t pred_batches = 0, kernel_launches = 0;
   int64_t host_ns_plan = 0, host_ns_pred = 0;   // time inside sym_pred_batch: planning + descriptor; whole call
@@ -164,29 +164,24 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   a.Hq = c->cfg.n_q_heads;
   a.Hkv = c->cfg.n_kv_heads;
   a.scale_log2e = c->scale_log2e;
+  PrefillArgs pa;
+  pa.pool = (const uint8_t*)c->cfg.pool;
+  pa.page_bytes = c->page_bytes;
+  pa.q = q;
+  pa.out = out;
+  pa.tiles = dw + d.words[H_OFF_TILES];
+  pa.pt = dw + d.words[H_OFF_PT];
+  pa.members = dw + d.words[H_OFF_MEMBERS];
+  pa.part_acc = part_acc;
+  pa.part_ml = part_ml;
+  pa.n_tiles = d.n_tiles;
+  pa.Hq = c->cfg.n_q_heads;
+  pa.Hkv = c->cfg.n_kv_heads;
+  pa.scale_log2e = c->scale_log2e;
   {
-    Timed t(c, SYM_K_DECODE, st);
-    hipError_t e = launch_decode(a, c->cfg.dtype, st);
-    if (e != hipSuccess) return fail_hip(c, e, "decode launch");
-  }
-  if (d.n_tiles > 0) {
-    PrefillArgs pa;
-    pa.pool = (const uint8_t*)c->cfg.pool;
-    pa.page_bytes = c->page_bytes;
-    pa.q = q;
-    pa.out = out;
-    pa.tiles = dw + d.words[H_OFF_TILES];
-    pa.pt = dw + d.words[H_OFF_PT];
-    pa.members = dw + d.words[H_OFF_MEMBERS];
-    pa.part_acc = part_acc;
-    pa.part_ml = part_ml;
-    pa.n_tiles = d.n_tiles;
-    pa.Hq = c->cfg.n_q_heads;
-    pa.Hkv = c->cfg.n_kv_heads;
-    pa.scale_log2e = c->scale_log2e;
-    Timed t(c, SYM_K_PREFILL, st);
-    hipError_t e = launch_prefill(pa, st);
-    if (e != hipSuccess) return fail_hip(c, e, "prefill launch");
+    Timed t(c, SYM_K_ATTN, st);
+    hipError_t e = launch_attn(a, pa, c->cfg.dtype, st);
+    if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {
     MergeArgs m{part_acc, part_ml, dw + d.words[H_OFF_MERGE], out, d.n_merge};
@@ -230,7 +225,7 @@ int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_o
 
 // Builds c->desc from caller-supplied page tables (lock held).  Returns words or a negative status.
 int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
-                       const int64_t* pt_offsets, const int64_t* lengths) {
+                       const int64_t* pt_offsets, const int64_t* lengths, const std::function<int32_t*(int64_t)>& alloc) {
   c->tables.resize(n_lips);
   for (int32_t b = 0; b < n_lips; ++b) {
     if (lengths[b] < 1) return fail(c, SYM_EINVAL, "length must be >= 1");
@@ -242,9 +237,11 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   }
   DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
                  c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
+  c->desc.alloc = alloc;
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
-  if (rc) return fail(c, rc, "build_desc: bad batch");
-  return (int64_t)c->desc.words.size();
+  c->desc.alloc = nullptr;
+  if (rc) return fail(c, rc, "build_desc: bad batch or no room for the descriptor");
+  return c->desc.n_words;
 }
 
 }  // namespace
@@ -442,9 +439,12 @@ int64_t sym_build_desc(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
                        const int64_t* pt_offsets, const int64_t* lengths, int32_t* words_out, int64_t cap) {
   if (!c || n_lips < 0 || (n_lips > 0 && (!n_tokens || !page_table_flat || !pt_offsets || !lengths))) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
-  const int64_t n = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths);
+  const int64_t n = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths, [c](int64_t words) {
+    c->scratch_words.resize((size_t)words);
+    return c->scratch_words.data();
+  });
   if (n < 0) return n;
-  if (words_out) std::memcpy(words_out, c->desc.words.data(), (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
+  if (words_out) std::memcpy(words_out, c->desc.words, (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
   return n;
 }
 
@@ -498,16 +498,22 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   }
   DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
                  c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
+  // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
+  const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
+  int si = -1;
+  int64_t wait_ns = 0;
+  c->desc.alloc = [&](int64_t words) -> int32_t* {
+    const auto w0 = std::chrono::steady_clock::now();
+    if (stage_acquire(c, words + tail_words, &si)) return nullptr;      // may wait for the GPU: not host work
+    wait_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - w0).count();
+    return c->stage[si];
+  };
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
+  c->desc.alloc = nullptr;
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
-  const int64_t dwords = (int64_t)c->desc.words.size();
+  const int64_t dwords = align_up(c->desc.n_words, 4);
   const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
   const int64_t words = slots_off + (int64_t)c->plan.slots.size();
-  const auto t_built = std::chrono::steady_clock::now();
-  int si;
-  if ((rc = stage_acquire(c, words, &si))) return rc;      // may wait for the GPU: not host work
-  const auto t_acquired = std::chrono::steady_clock::now();
-  std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
   std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
   const auto t_planned = std::chrono::steady_clock::now();
@@ -518,8 +524,8 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   rc = launch_attention(c, words, q, out, st);
   const auto t_end = std::chrono::steady_clock::now();
   const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
-  c->host_ns_plan += ns(t_built - t_begin) + ns(t_planned - t_acquired);
-  c->host_ns_pred += ns(t_end - t_begin) - ns(t_acquired - t_built);
+  c->host_ns_plan += ns(t_planned - t_begin) - wait_ns;
+  c->host_ns_pred += ns(t_end - t_begin) - wait_ns;
   return rc;
 }
 
@@ -530,14 +536,14 @@ int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   if (!q || !out || !n_tokens || !page_table_flat || !pt_offsets || !lengths) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
-  const int64_t dwords = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths);
+  int si = -1;
+  const int64_t dwords = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths, [&](int64_t words) -> int32_t* {
+    if (align_up(words * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes) return nullptr;
+    return stage_acquire(c, words + 4, &si) ? nullptr : c->stage[si];
+  });
   if (dwords < 0) return (int)dwords;
-  if (align_up(dwords * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes)
-    return fail(c, SYM_ENOSPC, "workspace too small for this batch");
   hipStream_t st = (hipStream_t)stream;
-  int si, rc;
-  if ((rc = stage_acquire(c, dwords, &si))) return rc;
-  std::memcpy(c->stage[si], c->desc.words.data(), (size_t)dwords * 4);
+  int rc;
   if ((rc = launch_prologue_staged(c, si, dwords, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
   ++c->pred_batches;
   return launch_attention(c, dwords, q, out, st);

@@ -153,7 +153,6 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   if (total_units == 0) nw = 0;
   const int64_t n_members = (int64_t)member_rows.size();
 
-  std::vector<int32_t>& w = out->words;
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
@@ -164,14 +163,17 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
   const int64_t total = off_members + n_members;
   if (total > 0x7fffffff) return SYM_EINVAL;
-  w.resize((size_t)total);
-  std::memset(w.data(), 0, DESC_HEADER_WORDS * sizeof(int32_t));
+  int32_t* const w = out->alloc ? out->alloc(total) : nullptr;   // the caller's buffer (pinned staging memory on the GPU path)
+  if (!w) return SYM_ENOSPC;
+  out->words = w;
+  out->n_words = total;
+  std::memset(w, 0, DESC_HEADER_WORDS * sizeof(int32_t));
 
   // ---- rows, prefill tiles, page table
-  int32_t* rows = w.data() + off_rows;
-  int32_t* pt = w.data() + off_pt;
-  int32_t* ptoff = w.data() + off_ptoff;
-  int32_t* tiles = w.data() + off_tiles;
+  int32_t* rows = w + off_rows;
+  int32_t* pt = w + off_pt;
+  int32_t* ptoff = w + off_ptoff;
+  int32_t* tiles = w + off_tiles;
   int64_t r = 0, e = 0, tok = 0, ti = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     ptoff[b] = (int32_t)e;
@@ -210,8 +212,8 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   // combine and the restart of the pipeline are not free).  On a virtual axis where every
   // (row, head) occupies range_cost + pages, wave k ends at total * (k+1) / nw; a cut that
   // falls into the overhead part of a (row, head) snaps to its first page.
-  int32_t* waves = w.data() + off_waves;
-  int32_t* merge = w.data() + off_merge;
+  int32_t* waves = w + off_waves;
+  int32_t* merge = w + off_merge;
   auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
   auto row_first = [&](int64_t rr) { return rows[rr * ROW_WORDS + 3]; };
   const int64_t alpha = prm.range_cost;
@@ -284,7 +286,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   // ---- shared-prefix tiles and the extra partials of their members' merge entries
   const int32_t shared_base = part;
   if (!stiles.empty()) {
-    int32_t* members = w.data() + off_members;
+    int32_t* members = w + off_members;
     std::memcpy(members, member_rows.data(), member_rows.size() * sizeof(int32_t));
     for (size_t s = 0; s < stiles.size(); s += 6) {
       const int32_t b0 = stiles[s], moff = stiles[s + 1], k = stiles[s + 2], C = stiles[s + 3], nc = stiles[s + 4], base = stiles[s + 5];

@@ -18,6 +18,7 @@
 // (row, kv head) writes the final output directly and has no partial.
 #pragma once
 #include <cstdint>
+#include <functional>
 #include <utility>
 #include <vector>
 
@@ -35,7 +36,11 @@ enum { T_TBL = 0, T_LEN, T_QROW, T_COUNT, T_HEAD, T_AUX, T_KIND, T_PAGE0, T_PAGE
 enum { TILE_PREFILL = 0, TILE_SHARED = 1 };
 
 struct BatchDesc {
-  std::vector<int32_t> words;      // packed descriptor, header first
+  // The packed descriptor (header first) is written straight into memory the caller hands out
+  // once the size is known: alloc(n_words) returns room for n_words words, or nullptr.
+  std::function<int32_t*(int64_t)> alloc;
+  int32_t* words = nullptr;
+  int64_t n_words = 0;
   int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
   int64_t total_units = 0;
   // scratch of the builder, kept between calls

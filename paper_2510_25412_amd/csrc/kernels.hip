@@ -89,12 +89,12 @@ struct PageRegs {
 // head) leaves a partial result for the merge kernel.
 // ---------------------------------------------------------------------------------------
 template <typename E, int G>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void decode_attn_kernel(DecodeArgs a) {
+__device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block) {
   constexpr int C = E::kDimsPerChunk;    // dims per 16-byte chunk
   constexpr int DPL = 2 * C;             // dims per lane
   constexpr int D = 16 * C;              // head dim
   const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+  const int wv = __builtin_amdgcn_readfirstlane(block * kWavesPerBlock + (threadIdx.x >> 6));
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
@@ -352,12 +352,11 @@ constexpr int kVRow = 80;                 // bytes per dim row of V^T in LDS (64
 constexpr int kVLds = 128 * kVRow;        // 10 KiB
 
 template <int G>
-__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
-  __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
+__device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block, uint8_t (*lds)[kKLds + kVLds]) {
   // tiles that read the same K/V are neighbours in the list; blocks go round-robin over the 8
   // XCDs, so give each XCD a contiguous run of the list (only locality depends on this)
   const int per_xcd = (a.n_tiles + 7) / 8;
-  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int tile = (block % 8) * per_xcd + block / 8;
   if (tile >= a.n_tiles) return;
   const int32_t* tw = a.tiles + tile * 12;
   const int tbl_off = tw[0], g = tw[4], count = tw[3];
@@ -527,6 +526,24 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs a) {
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// The attention launch of a batch: the first tile_blocks workgroups run tiles (prefill chunks and
+// shared prefixes, the long-running work, so they start first), the rest run the decode
+// ranges, four wavefronts per workgroup.  One grid, so the two kinds of work fill the GPU
+// together and there is no launch boundary between them.
+// ---------------------------------------------------------------------------------------
+template <typename E, int G>
+__global__ __launch_bounds__(256, (G >= 8 ? 1 : 2)) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
+  if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
+    __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
+    if ((int)blockIdx.x < tile_blocks) {
+      tile_block<G>(pa, blockIdx.x, lds);
+      return;
+    }
+  }
+  decode_ranges<E, G>(da, blockIdx.x - tile_blocks);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -706,14 +723,16 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(uint4* dst, const uint4
 }
 
 template <typename E>
-hipError_t launch_decode_g(const DecodeArgs& a, hipStream_t st) {
-  const int G = a.Hq / a.Hkv;
-  const dim3 grid((a.n_waves + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
+hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, hipStream_t st) {
+  const int G = da.Hq / da.Hkv;
+  const int tile_blocks = ((pa.n_tiles + 7) / 8) * 8;
+  const int decode_blocks = (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  const dim3 grid(tile_blocks + decode_blocks), block(256);
   switch (G) {
-    case 1: hipLaunchKernelGGL((decode_attn_kernel<E, 1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((decode_attn_kernel<E, 2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((decode_attn_kernel<E, 4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((decode_attn_kernel<E, 8>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, pa, tile_blocks); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<E, 2>), grid, block, 0, st, da, pa, tile_blocks); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<E, 4>), grid, block, 0, st, da, pa, tile_blocks); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, pa, tile_blocks); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -721,23 +740,10 @@ hipError_t launch_decode_g(const DecodeArgs& a, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st) {
-  if (a.n_waves <= 0) return hipSuccess;
-  return dtype == 0 ? launch_decode_g<ElemF32>(a, st) : launch_decode_g<ElemBF16>(a, st);
-}
-
-hipError_t launch_prefill(const PrefillArgs& a, hipStream_t st) {
-  if (a.n_tiles <= 0) return hipSuccess;
-  const int G = a.Hq / a.Hkv;
-  const dim3 grid(((a.n_tiles + 7) / 8) * 8), block(256);
-  switch (G) {
-    case 1: hipLaunchKernelGGL((prefill_attn_kernel<1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((prefill_attn_kernel<2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((prefill_attn_kernel<4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((prefill_attn_kernel<8>), grid, block, 0, st, a); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, hipStream_t st) {
+  if (da.n_waves <= 0 && pa.n_tiles <= 0) return hipSuccess;
+  if (dtype == 0) return pa.n_tiles > 0 ? hipErrorInvalidValue : launch_attn_g<ElemF32>(da, pa, st);
+  return launch_attn_g<ElemBF16>(da, pa, st);
 }
 
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {

@@ -69,8 +69,7 @@ struct GatherArgs {
   int32_t n_tokens, Hkv;
 };
 
-hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t st);
-hipError_t launch_prefill(const PrefillArgs& a, hipStream_t st);
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);
