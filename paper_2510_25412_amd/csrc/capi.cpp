@@ -294,7 +294,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
       delete c;
       return SYM_EHIP;
     }
-    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * 8;   // two waves per SIMD
+    // two wavefronts per SIMD; with 8 query heads per kv head a range takes two wavefronts
+    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * (c->G == 8 ? 4 : 8);
   }
   c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
   c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));

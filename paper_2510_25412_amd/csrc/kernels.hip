@@ -88,13 +88,22 @@ struct PageRegs {
 // combined once, when a (row, kv head) range ends; a range that is only part of its (row, kv
 // head) leaves a partial result for the merge kernel.
 // ---------------------------------------------------------------------------------------
-template <typename E, int G>
-__device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block) {
+// GT = query heads per kv head, G = heads this wavefront handles.  G == GT: one wavefront per range,
+// pages double-buffered in registers.  G == GT/2 (used for 8 heads per kv head, whose 8 x 16
+// accumulators do not fit one wavefront's registers twice per SIMD): a workgroup of TWO wavefronts
+// per range, each with half of the heads; wavefront 0 fetches the K half of every page,
+// wavefront 1 the V half, they exchange them through LDS (written and read in the same
+// lane-linear 1 KiB runs, so without bank conflicts), and every page is still read from HBM once.
+template <typename E, int GT, int G>
+__device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block, uint8_t (*plds)[kSlab]) {
+  constexpr bool kPair = G < GT;
+  const int hs = kPair ? (int)(threadIdx.x >> 6) : 0;      // which wavefront of the pair
+  const int h0 = hs * G;                                    // first head (within the group) of this wavefront
   constexpr int C = E::kDimsPerChunk;    // dims per 16-byte chunk
   constexpr int DPL = 2 * C;             // dims per lane
   constexpr int D = 16 * C;              // head dim
   const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(block * kWavesPerBlock + (threadIdx.x >> 6));
+  const int wv = __builtin_amdgcn_readfirstlane(kPair ? block : block * kWavesPerBlock + (int)(threadIdx.x >> 6));
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
@@ -125,7 +134,7 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
     uint4 q[G][2];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * G + h) * kRowBytes + j * 16;
+      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * GT + h0 + h) * kRowBytes + j * 16;
       q[h][0] = *(const uint4*)qp;
       q[h][1] = *(const uint4*)(qp + kHalfBytes);
     }
@@ -218,16 +227,67 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
       pid2 = tbl[min(2, last)];
     }
     first_range = false;
-    int id1 = cnt > 1 ? pid1 : 0, id2 = cnt > 2 ? pid2 : 0;
-    PageRegs A, B;
-    load_page(A, pid0);
-    for (int k = 0; k < cnt; k += 2) {
-      load_page(B, id1);
-      id1 = k + 3 <= last ? tbl[k + 3] : 0;
-      compute(A, p + k);
-      load_page(A, id2);
-      id2 = k + 4 <= last ? tbl[k + 4] : 0;
-      if (k + 1 < cnt) compute(B, p + k + 1);
+    if constexpr (!kPair) {
+      int id1 = cnt > 1 ? pid1 : 0, id2 = cnt > 2 ? pid2 : 0;
+      PageRegs A, B;
+      load_page(A, pid0);
+      for (int k = 0; k < cnt; k += 2) {
+        load_page(B, id1);
+        id1 = k + 3 <= last ? tbl[k + 3] : 0;
+        compute(A, p + k);
+        load_page(A, id2);
+        id2 = k + 4 <= last ? tbl[k + 4] : 0;
+        if (k + 1 < cnt) compute(B, p + k + 1);
+      }
+    } else {
+      // this wavefront's half (K or V) of a page: 4 lane-linear 1 KiB runs -> registers -> LDS
+      const uint8_t* half0 = slab0 + hs * kBlk;
+      auto load_half = [&](uint4 (&st)[4], int pid) {
+        const uint8_t* base = half0 + (int64_t)pid * a.page_bytes;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) st[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + x * 1024)));
+      };
+      int id1 = cnt > 1 ? pid1 : 0, id2 = cnt > 2 ? pid2 : 0;
+      uint4 sa[4], sb[4];                    // pages k and k+1 in flight
+      load_half(sa, pid0);
+      load_half(sb, id1);
+      for (int k = 0; k < cnt; k += 2) {
+        // page k
+        {
+          uint8_t* buf = plds[0] + hs * kBlk + lane * 16;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) *(uint4*)(buf + x * 1024) = sa[x];
+          __syncthreads();                   // both halves of page k are in LDS; the other buffer is free again
+          load_half(sa, id2);
+          id2 = k + 4 <= last ? tbl[k + 4] : 0;
+          PageRegs R;
+          const uint8_t* rb = plds[0] + lane * 16;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) R.k[x] = *(const uint4*)(rb + x * 1024);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) R.v[x] = *(const uint4*)(rb + kBlk + x * 1024);
+          compute(R, p + k);
+        }
+        // page k + 1 (both wavefronts take the same branch: cnt is the same for the pair)
+        {
+          uint8_t* buf = plds[1] + hs * kBlk + lane * 16;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) *(uint4*)(buf + x * 1024) = sb[x];
+          __syncthreads();
+          id1 = k + 3 <= last ? tbl[k + 3] : 0;
+          load_half(sb, id1);
+          if (k + 1 < cnt) {
+            PageRegs R;
+            const uint8_t* rb = plds[1] + lane * 16;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) R.k[x] = *(const uint4*)(rb + x * 1024);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) R.v[x] = *(const uint4*)(rb + kBlk + x * 1024);
+            compute(R, p + k + 1);
+          }
+        }
+      }
+      __syncthreads();                       // the next range of this pair reuses both buffers
     }
 
     // ---- end of a (row, kv head) range: combine the 8 token slots (lanes with equal j).
@@ -273,7 +333,7 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
       }
     }
     // lane (r, j) now holds list entries idx = r * V/8 + t: head idx / DPL, lane-local dim idx % DPL
-    const int64_t out_row = ((int64_t)qrow * a.Hq + g * G) * D;
+    const int64_t out_row = ((int64_t)qrow * a.Hq + g * GT + h0) * D;
     if (whole) {
 #pragma unroll
       for (int t = 0; t < V / 8; ++t) {
@@ -284,7 +344,7 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
         a.out[out_row + h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t] / ls;
       }
     } else {
-      float* pa = a.part_acc + (int64_t)part * G * D;
+      float* pa = a.part_acc + ((int64_t)part * GT + h0) * D;
 #pragma unroll
       for (int t = 0; t < V / 8; ++t) {
         const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
@@ -297,8 +357,8 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
           mm = (lane == hh) ? Mh[hh] : mm;
           ll = (lane == hh) ? lsum[hh] : ll;
         }
-        a.part_ml[((int64_t)part * G + lane) * 2 + 0] = mm;
-        a.part_ml[((int64_t)part * G + lane) * 2 + 1] = ll;
+        a.part_ml[((int64_t)part * GT + h0 + lane) * 2 + 0] = mm;
+        a.part_ml[((int64_t)part * GT + h0 + lane) * 2 + 1] = ll;
       }
     }
     if (!whole) ++part;
@@ -392,28 +452,29 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
   // K: thread copies chunks c = tid and tid + 256 of the block: token c/16, dim chunk c%16
   // V: thread takes tokens (4*q4 + 2*up, +1) of page pg, dim chunk vc: 8 dims x 2 tokens
   const int up = tid & 1, q4 = (tid >> 1) & 3, vc = (tid >> 3) & 15, pg = tid >> 7;
-  uint4 kreg0, kreg1, vreg0, vreg1;
+  // K/V of the blocks in flight (loaded three blocks ahead of their use): three register sets
+  uint4 ka0, ka1, va0, va1, kb0r, kb1r, vb0, vb1, kc0, kc1, vc0, vc1;
   const uint8_t* slab = a.pool + (int64_t)g * kSlab;
   auto k_src = [&](int kb, int c) {
     const int t = c >> 4, dc = c & 15;
     const int pi = min(2 * kb + (t >> 4), last_page);
     return slab + (int64_t)tbl[pi] * a.page_bytes + (dc >> 3) * (kP * kHalfBytes) + (t & 15) * kHalfBytes + (dc & 7) * 16;
   };
-  auto issue_loads = [&](int kb) {
-    kreg0 = *(const uint4*)k_src(kb, tid);
-    kreg1 = *(const uint4*)k_src(kb, tid + 256);
+  auto issue_loads = [&](int kb, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
+    k0 = *(const uint4*)k_src(kb, tid);
+    k1 = *(const uint4*)k_src(kb, tid + 256);
     const int pi = min(2 * kb + pg, last_page);
     const uint8_t* p = slab + (int64_t)tbl[pi] * a.page_bytes + kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * q4 + 2 * up) * kHalfBytes + (vc & 7) * 16;
-    vreg0 = *(const uint4*)p;
-    vreg1 = *(const uint4*)(p + kHalfBytes);
+    v0 = *(const uint4*)p;
+    v1 = *(const uint4*)(p + kHalfBytes);
   };
   auto k_dst = [&](uint8_t* base, int c) {
     const int t = c >> 4, dc = c & 15;
     return base + (t * 16 + (dc ^ (t & 15))) * 16;
   };
-  auto store_lds = [&](int kb, uint8_t* base) {
-    *(uint4*)k_dst(base, tid) = kreg0;
-    *(uint4*)k_dst(base, tid + 256) = kreg1;
+  auto store_lds = [&](int kb, uint8_t* base, const uint4& k0, const uint4& k1, const uint4& v0, const uint4& v1) {
+    *(uint4*)k_dst(base, tid) = k0;
+    *(uint4*)k_dst(base, tid + 256) = k1;
     // tokens past the end of what the tile may see are cleared (their weight is 0, 0 * NaN is not)
     const int tok = kb * kKvBlock + pg * 16 + 4 * q4 + 2 * up;
     const bool ok0 = tok < kv_end, ok1 = tok + 1 < kv_end;
@@ -424,10 +485,10 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
       const float f0 = ok0 ? as_f32(x0) : 0.f, f1 = ok1 ? as_f32(x1) : 0.f;
       *(uint32_t*)(vb + e * kVRow) = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f0, f1));
     };
-    put(0, vreg0.x, vreg1.x, false); put(1, vreg0.x, vreg1.x, true);
-    put(2, vreg0.y, vreg1.y, false); put(3, vreg0.y, vreg1.y, true);
-    put(4, vreg0.z, vreg1.z, false); put(5, vreg0.z, vreg1.z, true);
-    put(6, vreg0.w, vreg1.w, false); put(7, vreg0.w, vreg1.w, true);
+    put(0, v0.x, v1.x, false); put(1, v0.x, v1.x, true);
+    put(2, v0.y, v1.y, false); put(3, v0.y, v1.y, true);
+    put(4, v0.z, v1.z, false); put(5, v0.z, v1.z, true);
+    put(6, v0.w, v1.w, false); put(7, v0.w, v1.w, true);
   };
 
   f32x16_t O[4];
@@ -437,12 +498,15 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     for (int v = 0; v < 16; ++v) O[db][v] = 0.f;
   float m = -1e30f, l = 0.f;
 
-  if (kb0 < nblk) issue_loads(kb0);
-  for (int kb = kb0; kb < nblk; ++kb) {
+  // One block: its K/V (loaded three blocks ago into S) goes to LDS, the loads of the block three
+  // ahead are issued into the same registers, then the block is computed.  All loads and all
+  // blocks are unconditional: past the end the last pages are loaded again and every token is
+  // masked, so the loop (unrolled by three) has no control-flow join between a load and its use.
+  auto do_block = [&](const int kb, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
     uint8_t* base = lds[kb & 1];
-    store_lds(kb, base);
-    __syncthreads();           // block kb is in LDS; everyone is done with block kb-1's other buffer
-    if (kb + 1 < nblk) issue_loads(kb + 1);
+    store_lds(kb, base, k0, k1, v0, v1);
+    __syncthreads();           // block kb is in LDS; everyone is done with the other buffer's previous block
+    issue_loads(kb + 3, k0, k1, v0, v1);
 
     // S^T = K Q^T for 32 tokens x 32 rows
     f32x16_t S;
@@ -454,23 +518,19 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
       S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, q[ks], S, 0, 0, 0);
     }
     // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
+    // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
     const int tok0 = kb * kKvBlock + 4 * hf;
     float mx = -__builtin_inff();
     if (kb * kKvBlock + kKvBlock > mask_from) {        // the block reaches the causal edge of some row
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int tok = tok0 + 8 * (v >> 2) + (v & 3);
-        S[v] = tok < vis ? S[v] * a.scale_log2e : -__builtin_inff();
-        mx = fmaxf(mx, S[v]);
-      }
-    } else {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        S[v] *= a.scale_log2e;
-        mx = fmaxf(mx, S[v]);
+        S[v] = tok < vis ? S[v] : -__builtin_inff();
       }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
     if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {     // rare after the first block
       const float mn = fmaxf(m, mx);
       const float al = __builtin_amdgcn_exp2f(m - mn);
@@ -484,7 +544,8 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     uint32_t pw[8];
 #pragma unroll
     for (int v = 0; v < 16; v += 2) {
-      const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(S[v] - m), __builtin_amdgcn_exp2f(S[v + 1] - m));
+      const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[v], a.scale_log2e, -m)),
+                                                 __builtin_amdgcn_exp2f(__builtin_fmaf(S[v + 1], a.scale_log2e, -m)));
       l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
       pw[v >> 1] = __builtin_bit_cast(uint32_t, pk);
     }
@@ -499,6 +560,15 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
         const f16x8_t vv = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
         O[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv, P[ks], O[db], 0, 0, 0);
       }
+  };
+
+  issue_loads(kb0, ka0, ka1, va0, va1);
+  issue_loads(kb0 + 1, kb0r, kb1r, vb0, vb1);
+  issue_loads(kb0 + 2, kc0, kc1, vc0, vc1);
+  for (int kb = kb0; kb < nblk; kb += 3) {
+    do_block(kb, ka0, ka1, va0, va1);
+    do_block(kb + 1, kb0r, kb1r, vb0, vb1);
+    do_block(kb + 2, kc0, kc1, vc0, vc1);
   }
 
   l += __shfl_xor(l, 32);
@@ -535,7 +605,7 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
 // together and there is no launch boundary between them.
 // ---------------------------------------------------------------------------------------
 template <typename E, int G>
-__global__ __launch_bounds__(256, (G >= 8 ? 1 : 2)) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
+__global__ __launch_bounds__(256, 2) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
   if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
     __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
     if ((int)blockIdx.x < tile_blocks) {
@@ -543,7 +613,14 @@ __global__ __launch_bounds__(256, (G >= 8 ? 1 : 2)) void attn_kernel(DecodeArgs 
       return;
     }
   }
-  decode_ranges<E, G>(da, blockIdx.x - tile_blocks);
+  if constexpr (G < 8) decode_ranges<E, G, G>(da, blockIdx.x - tile_blocks, nullptr);
+}
+
+// Decode ranges for 8 query heads per kv head: one workgroup of two wavefronts per range.
+template <typename E>
+__global__ __launch_bounds__(128, 2) void decode_pair_kernel(DecodeArgs da) {
+  __shared__ __align__(16) uint8_t plds[2][kSlab];
+  decode_ranges<E, 8, 4>(da, blockIdx.x, plds);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -726,15 +803,16 @@ template <typename E>
 hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, hipStream_t st) {
   const int G = da.Hq / da.Hkv;
   const int tile_blocks = ((pa.n_tiles + 7) / 8) * 8;
-  const int decode_blocks = (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int decode_blocks = G == 8 ? 0 : (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
   const dim3 grid(tile_blocks + decode_blocks), block(256);
-  switch (G) {
+  if (grid.x > 0) switch (G) {
     case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, pa, tile_blocks); break;
     case 2: hipLaunchKernelGGL((attn_kernel<E, 2>), grid, block, 0, st, da, pa, tile_blocks); break;
     case 4: hipLaunchKernelGGL((attn_kernel<E, 4>), grid, block, 0, st, da, pa, tile_blocks); break;
     case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, pa, tile_blocks); break;
     default: return hipErrorInvalidValue;
   }
+  if (G == 8 && da.n_waves > 0) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);
   return hipGetLastError();
 }
 
