@@ -34,6 +34,7 @@ struct sym_ctx {
   int64_t page_bytes = 0;
   float scale_log2e = 0.f;
   int32_t max_waves = 0, min_units = 4, range_cost = 3;
+  int32_t decode_mode = 0;                           // 1 = decode ranges on the matrix cores
   int32_t share_min_lips = 4, share_min_pages = 8;   // decode LIPs / common full pages needed to read a prefix once
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   std::mutex mu;
@@ -180,7 +181,7 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.scale_log2e = c->scale_log2e;
   {
     Timed t(c, SYM_K_ATTN, st);
-    hipError_t e = launch_attn(a, pa, c->cfg.dtype, st);
+    hipError_t e = launch_attn(a, pa, c->cfg.dtype, c->decode_mode, st);
     if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {
@@ -295,10 +296,13 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
       return SYM_EHIP;
     }
     // two wavefronts per SIMD; with 8 query heads per kv head a range takes two wavefronts
-    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * (c->G == 8 ? 4 : 8);
+    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * ((c->G == 8 && !env_int("SYM_DECODE_MFMA", 1)) ? 4 : 8);
   }
   c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
   c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
+  // 8 query heads per kv head are bound by vector issue in the VALU decode kernel: matrix cores by default
+  c->decode_mode = env_int("SYM_DECODE_MFMA", (cfg->dtype == SYM_BF16 && c->G == 8) ? 1 : 0) ? 1 : 0;
+  if (cfg->dtype != SYM_BF16) c->decode_mode = 0;
   c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
   c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
   c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));

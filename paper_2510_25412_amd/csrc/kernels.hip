@@ -599,6 +599,219 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
 }
 
 // ---------------------------------------------------------------------------------------
+// Decode ranges on the matrix cores (bf16 storage).  With 8 query heads per kv head the VALU
+// decode kernel above is bound by vector issue, not by HBM (8 flop per KV byte in plain fp32
+// FMAs); the 8 heads of a group are a small query tile, so here one wavefront per range feeds
+// them to 16x16x32 MFMAs (16 columns, GT of them used):
+//   S^T[16 tokens][16 heads] = K · Q^T     A = K rows straight from global memory (64 B per token and
+//                                          k-step, no LDS), B = Q (registers), per page
+//   O^T[128 dims][16 heads] += V^T · P^T    per two pages (k = 32 tokens); V^T through a wavefront-private
+//                                          LDS buffer, written by the wavefront itself while it converts
+//                                          bf16 -> fp16 (pairs of neighbouring tokens packed = the transpose)
+// A lane's column is a head in both results, so max / sum / rescale factor are lane-local; the
+// four lane groups of a head hold different tokens and share only the (lagging) running max.
+// No barrier anywhere: the LDS buffer is private to the wavefront.
+// ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+constexpr int kVtRow = 80;                    // bytes per dim row of V^T (32 tokens fp16 + 16 pad)
+constexpr int kVtLds = 128 * kVtRow;          // 10 KiB per wavefront
+
+template <int GT>
+__device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const int block, uint8_t* vlds) {
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(block * kWavesPerBlock + (int)(threadIdx.x >> 6));
+  if (wv >= a.n_waves) return;
+  const int col = lane & 15, grp = lane >> 4;        // head column, lane group (tokens 4*grp .. 4*grp+3 of a page)
+  const int head = col % GT;                          // columns past GT repeat heads; their results are ignored
+  const int vq4 = lane >> 4, vc = lane & 15;          // V staging role: tokens 4*vq4 .. +3 of a page, dim chunk vc
+
+  const int32_t* ww = a.waves + wv * 12;
+  int row = __builtin_amdgcn_readfirstlane(ww[0]);
+  int g = __builtin_amdgcn_readfirstlane(ww[1]);
+  int p = __builtin_amdgcn_readfirstlane(ww[2]);
+  int remaining = __builtin_amdgcn_readfirstlane(ww[3]);
+  int part = __builtin_amdgcn_readfirstlane(ww[4]);
+  int vis = __builtin_amdgcn_readfirstlane(ww[5]);
+  int qrow = __builtin_amdgcn_readfirstlane(ww[6]);
+  int tbl_off = __builtin_amdgcn_readfirstlane(ww[7]);
+  int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
+  int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
+  int pstart = __builtin_amdgcn_readfirstlane(ww[11]);
+  bool first_range = true;
+
+  while (remaining > 0) {
+    const int np = (vis + kP - 1) / kP;
+    const int cnt = min(remaining, np - p);
+    const int32_t* tbl = a.pt + tbl_off + p;
+    const int last = cnt - 1;
+
+    // Q^T operand: this lane's head, dims 32*ks + 8*grp .. +8 for the four k-steps
+    bf16x8_t q[4];
+    {
+      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * GT + head) * kRowBytes + grp * 16;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 64));
+    }
+    f32x4_t O[8];
+#pragma unroll
+    for (int db = 0; db < 8; ++db) O[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m = -1e30f, l = 0.f;
+
+    const uint8_t* slab = a.pool + (int64_t)g * kSlab;
+    // K of a page as the A operand: token col, chunk 4*ks + grp of its row (row half ks/2, chunk 4*(ks%2) + grp)
+    const int k_off = col * kHalfBytes + grp * 16;
+    // V of a page for the staging: tokens 4*vq4 + u, chunk vc
+    const int v_off = kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * vq4) * kHalfBytes + (vc & 7) * 16;
+    auto load_page = [&](uint4 (&kk)[4], uint4 (&vv)[4], int pid) {
+      const uint8_t* base = slab + (int64_t)pid * a.page_bytes;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        kk[ks] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + k_off + (ks >> 1) * (kP * kHalfBytes) + (ks & 1) * 64)));
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        vv[u] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + v_off + u * kHalfBytes)));
+    };
+    // scores of one page: 4 tokens (4*grp + v) x this lane's head; tokens past nvalid masked
+    auto scores = [&](const uint4 (&kk)[4], int nvalid, float (&sc)[4]) {
+      f32x4_t S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk[ks]), q[ks], S, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sc[v] = (4 * grp + v) < nvalid ? S[v] : -__builtin_inff();
+    };
+    // V of one page -> fp16, transposed, into the wavefront's LDS buffer (half pg of every dim row)
+    auto stage_v = [&](const uint4 (&vv)[4], int nvalid, int pg) {
+      const uint32_t w[4][4] = {{vv[0].x, vv[0].y, vv[0].z, vv[0].w}, {vv[1].x, vv[1].y, vv[1].z, vv[1].w},
+                                {vv[2].x, vv[2].y, vv[2].z, vv[2].w}, {vv[3].x, vv[3].y, vv[3].z, vv[3].w}};
+      bool ok[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) ok[u] = (4 * vq4 + u) < nvalid;      // slots past the file's end may hold anything
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float f[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t x = (e & 1) ? (w[u][e >> 1] & 0xffff0000u) : (w[u][e >> 1] << 16);
+          f[u] = ok[u] ? as_f32(x) : 0.f;
+        }
+        const int d = vc * 8 + e;
+        uint2 pk;
+        pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[0], f[1]));
+        pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[2], f[3]));
+        *(uint2*)(vlds + d * kVtRow + ((vq4 ^ ((d >> 4) & 3)) * 16) + pg * 8) = pk;
+      }
+    };
+    // two pages (32 tokens): scores, softmax weights, O^T += V^T P^T
+    auto compute2 = [&](const uint4 (&kA)[4], const uint4 (&vA)[4], const uint4 (&kB)[4], const uint4 (&vB)[4], int piA, bool haveB) {
+      const int nvA = vis - piA * kP, nvB = haveB ? vis - (piA + 1) * kP : 0;
+      float sA[4], sB[4];
+      scores(kA, nvA, sA);
+      scores(kB, nvB, sB);
+      stage_v(vA, nvA, 0);
+      stage_v(vB, nvB, 1);
+      const float mx = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3]))) * a.scale_log2e;
+      if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {       // rare after the first pages
+        float mn = fmaxf(m, mx);
+        mn = fmaxf(mn, __shfl_xor(mn, 16));
+        mn = fmaxf(mn, __shfl_xor(mn, 32));                        // all four lane groups of the head agree
+        const float al = __builtin_amdgcn_exp2f(m - mn);
+        l *= al;
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) O[db][v] *= al;
+        m = mn;
+      }
+      uint32_t pw[4];
+#pragma unroll
+      for (int v = 0; v < 4; v += 2) {
+        const auto pa = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sA[v], a.scale_log2e, -m)),
+                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(sA[v + 1], a.scale_log2e, -m)));
+        const auto pb = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sB[v], a.scale_log2e, -m)),
+                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(sB[v + 1], a.scale_log2e, -m)));
+        l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pa), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
+        l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pb), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
+        pw[v >> 1] = __builtin_bit_cast(uint32_t, pa);
+        pw[2 + (v >> 1)] = __builtin_bit_cast(uint32_t, pb);
+      }
+      const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+#pragma unroll
+      for (int db = 0; db < 8; ++db) {
+        const f16x8_t vt = *(const f16x8_t*)(vlds + (db * 16 + col) * kVtRow + ((grp ^ (db & 3)) * 16));
+        O[db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vt, P, O[db], 0, 0, 0);
+      }
+    };
+
+    if (!first_range) {
+      pid0 = tbl[0];
+      pid1 = tbl[min(1, last)];
+    }
+    first_range = false;
+    // pages k, k+1 in registers while pages k+2, k+3 are in flight; every load is unconditional
+    // (past the end: page 0 of the pool, never used)
+    uint4 kA[4], vA[4], kB[4], vB[4], kC[4], vC[4], kD[4], vD[4];
+    int id2 = cnt > 2 ? tbl[2] : 0, id3 = cnt > 3 ? tbl[3] : 0;
+    load_page(kA, vA, pid0);
+    load_page(kB, vB, cnt > 1 ? pid1 : 0);
+    for (int k = 0; k < cnt; k += 4) {
+      load_page(kC, vC, id2);
+      load_page(kD, vD, id3);
+      id2 = k + 4 <= last ? tbl[k + 4] : 0;
+      id3 = k + 5 <= last ? tbl[k + 5] : 0;
+      compute2(kA, vA, kB, vB, p + k, k + 1 < cnt);
+      load_page(kA, vA, id2);
+      load_page(kB, vB, id3);
+      id2 = k + 6 <= last ? tbl[k + 6] : 0;
+      id3 = k + 7 <= last ? tbl[k + 7] : 0;
+      if (k + 2 < cnt) compute2(kC, vC, kD, vD, p + k + 2, k + 3 < cnt);
+    }
+
+    // ---- end of the range: the four lane groups of a head add up their sums; O^T is complete
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const bool whole = (p == 0 && cnt == np);
+    if (col < GT) {
+      if (whole) {
+        const float inv = 1.0f / l;
+        float* o = a.out + ((int64_t)qrow * a.Hq + g * GT + head) * 128 + 4 * grp;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0] * inv, O[db][1] * inv, O[db][2] * inv, O[db][3] * inv);
+      } else {
+        float* o = a.part_acc + ((int64_t)part * GT + head) * 128 + 4 * grp;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0], O[db][1], O[db][2], O[db][3]);
+        if (grp == 0) {
+          a.part_ml[((int64_t)part * GT + head) * 2 + 0] = m;
+          a.part_ml[((int64_t)part * GT + head) * 2 + 1] = l;
+        }
+      }
+    }
+    if (!whole) ++part;
+    remaining -= cnt;
+    p += cnt;
+    if (p == np) {
+      if (++g == a.Hkv) {
+        g = 0;
+        ++row;
+        if (remaining > 0) {
+          tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
+          vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
+          qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
+          pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
+        }
+      }
+      p = pstart;
+    }
+  }
+}
+
+template <int GT>
+__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs da) {
+  __shared__ __align__(16) uint8_t vlds[kWavesPerBlock][kVtLds];
+  decode_mfma_ranges<GT>(da, blockIdx.x, vlds[threadIdx.x >> 6]);
+}
+
+// ---------------------------------------------------------------------------------------
 // The attention launch of a batch: the first tile_blocks workgroups run tiles (prefill chunks and
 // shared prefixes, the long-running work, so they start first), the rest run the decode
 // ranges, four wavefronts per workgroup.  One grid, so the two kinds of work fill the GPU
@@ -800,10 +1013,13 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(uint4* dst, const uint4
 }
 
 template <typename E>
-hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, hipStream_t st) {
+hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode_mode, hipStream_t st) {
   const int G = da.Hq / da.Hkv;
+  // decode ranges: matrix cores (mode 1), the two-wavefront VALU kernel for 8 heads (mode 2), or the
+  // VALU kernel fused into the tile launch (mode 0)
+  const int mode = (E::kDimsPerChunk == 8 && decode_mode == 1) ? 1 : (G == 8 ? 2 : 0);
   const int tile_blocks = ((pa.n_tiles + 7) / 8) * 8;
-  const int decode_blocks = G == 8 ? 0 : (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int decode_blocks = mode == 0 ? (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock : 0;
   const dim3 grid(tile_blocks + decode_blocks), block(256);
   if (grid.x > 0) switch (G) {
     case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, pa, tile_blocks); break;
@@ -812,16 +1028,26 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, hipStream_
     case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, pa, tile_blocks); break;
     default: return hipErrorInvalidValue;
   }
-  if (G == 8 && da.n_waves > 0) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);
+  if (da.n_waves > 0 && mode == 2) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);
+  if (da.n_waves > 0 && mode == 1) {
+    const dim3 dgrid((da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
+    switch (G) {
+      case 1: hipLaunchKernelGGL((decode_mfma_kernel<1>), dgrid, block, 0, st, da); break;
+      case 2: hipLaunchKernelGGL((decode_mfma_kernel<2>), dgrid, block, 0, st, da); break;
+      case 4: hipLaunchKernelGGL((decode_mfma_kernel<4>), dgrid, block, 0, st, da); break;
+      case 8: hipLaunchKernelGGL((decode_mfma_kernel<8>), dgrid, block, 0, st, da); break;
+      default: return hipErrorInvalidValue;
+    }
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, hipStream_t st) {
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st) {
   if (da.n_waves <= 0 && pa.n_tiles <= 0) return hipSuccess;
-  if (dtype == 0) return pa.n_tiles > 0 ? hipErrorInvalidValue : launch_attn_g<ElemF32>(da, pa, st);
-  return launch_attn_g<ElemBF16>(da, pa, st);
+  if (dtype == 0) return pa.n_tiles > 0 ? hipErrorInvalidValue : launch_attn_g<ElemF32>(da, pa, 0, st);
+  return launch_attn_g<ElemBF16>(da, pa, decode_mode, st);
 }
 
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {

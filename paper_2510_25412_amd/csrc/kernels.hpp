@@ -69,7 +69,8 @@ struct GatherArgs {
   int32_t n_tokens, Hkv;
 };
 
-hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, hipStream_t st);
+// decode_mode: 0 = VALU decode kernel, 1 = decode ranges on the matrix cores (bf16 storage only)
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);

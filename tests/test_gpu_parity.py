@@ -1,6 +1,8 @@
 """GPU parity tests: the HIP path through the C ABI against the CPU oracle, element by element
 on the same seeded inputs.  Bars: page tables / reference counts bit-exact; attention outputs
 within |gpu - ref| <= 2e-3 * max(1, |ref|) (bf16 inputs, fp32 accumulation)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -226,6 +228,8 @@ def test_split_invariance_many_launches():
     oa = torch.empty((n, 32, 128), dtype=torch.float32, device="cuda")
     ob = torch.empty_like(oa)
     worst = 0.0
+    # on the matrix cores the softmax weights are rounded to fp16, so different cuts round differently
+    split_tol = 1e-3 if os.environ.get("SYM_DECODE_MFMA") == "1" else 2e-5
     for it in range(60):
         q = torch.randn((n, 32, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         oa.fill_(float("nan"))
@@ -234,7 +238,7 @@ def test_split_invariance_many_launches():
         sb.ctx.pred_batch_raw([1] * n, flat, off, lengths, q, ob, sb.stream)
         torch.cuda.synchronize()
         d = ((oa - ob).abs() / ob.abs().clamp(min=1.0)).max().item()
-        assert d == d and d <= 2e-5, f"launch {it}: split results differ by {d}"
+        assert d == d and d <= split_tol, f"launch {it}: split results differ by {d}"
         worst = max(worst, d)
     sa.close()
     sb.close()
