@@ -175,6 +175,7 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.members = dw + d.words[H_OFF_MEMBERS];
   pa.part_acc = part_acc;
   pa.part_ml = part_ml;
+  pa.tile_first = 0;
   pa.n_tiles = d.n_tiles;
   pa.Hq = c->cfg.n_q_heads;
   pa.Hkv = c->cfg.n_kv_heads;
@@ -306,7 +307,7 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
   c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
   c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));
-  c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;
+  c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;   // a tile has 128 query rows
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);

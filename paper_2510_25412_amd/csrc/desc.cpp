@@ -40,7 +40,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   member_rows.clear();
   stiles.clear();
   int64_t n_shared_partials = 0, n_shared_tiles = 0;
-  const int32_t tile_lips = TQ > 0 ? 128 / G : 0;
+  const int32_t tile_lips = TQ > 0 ? 128 / G : 0;           // a shared-prefix tile has 128 query rows
   if (prm.share_min_lips > 0 && tile_lips > 0) {
     auto& cand = out->by_first_page;
     cand.clear();

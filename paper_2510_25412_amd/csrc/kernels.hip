@@ -411,41 +411,47 @@ constexpr int kKLds = kKvBlock * kRowBytes;      // 8 KiB: K block, 16-byte chun
 constexpr int kVRow = 80;                 // bytes per dim row of V^T in LDS (64 + 16 pad: conflict-free reads)
 constexpr int kVLds = 128 * kVRow;        // 10 KiB
 
-template <int G>
+template <int G, int CT>
 __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block, uint8_t (*lds)[kKLds + kVLds]) {
+  // CT = 32-row column tiles per wavefront (a tile has 128*CT query rows); every K / V^T operand read
+  // from LDS feeds CT MFMAs.  CT = 2 was measured: it needs one wavefront per SIMD (~500 registers)
+  // and is 1.7x slower than CT = 1 with two, so CT = 1 is what runs.
   // tiles that read the same K/V are neighbours in the list; blocks go round-robin over the 8
   // XCDs, so give each XCD a contiguous run of the list (only locality depends on this)
   const int per_xcd = (a.n_tiles + 7) / 8;
   const int tile = (block % 8) * per_xcd + block / 8;
   if (tile >= a.n_tiles) return;
-  const int32_t* tw = a.tiles + tile * 12;
+  const int32_t* tw = a.tiles + (int64_t)(a.tile_first + tile) * 12;
   const int tbl_off = tw[0], g = tw[4], count = tw[3];
   const bool shared = tw[6] != 0;
   const int32_t* tbl = a.pt + tbl_off;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int col = lane & 31, hf = lane >> 5;
-  const int rho = wv * 32 + col;                 // query row of this lane inside the tile
-  const int tl = rho / G, h = rho % G;           // token (prefill) or member (shared prefix) of the row, head
-  const int tlc = min(tl, count - 1);            // rows past the tile's last token/member repeat it (never written)
   // prefill chunk: `count` new tokens from chunk offset t0 on a file of L tokens; row tl sees
   // tokens 0 .. L + t0 + tl.  shared prefix: `count` decode rows (q rows in the member list) that
   // all see the same full pages [page0, page1) of the group's first file.
   const int L = tw[1], t0 = tw[5];
-  const int qrow = shared ? a.members[tw[2] + tlc] : tw[2] + tlc;
   const int kv_end = shared ? tw[8] * kP : L + t0 + count;       // tokens the tile's last row sees
-  const int vis = shared ? kv_end : L + t0 + tlc + 1;            // tokens this row sees
   const int mask_from = shared ? kv_end : L + t0 + 1;            // first token some row may not see
   const int kb0 = shared ? tw[7] / 2 : 0;                        // first 32-token block (page0 is even)
   const int nblk = (kv_end + kKvBlock - 1) / kKvBlock;
   const int last_page = max((kv_end + kP - 1) / kP - 1, 0);
+  const bool wave_live = wv * 32 * CT < count * G;               // a wavefront whose rows are all padding only stages
 
-  // Q of this lane's row: 8 k-steps of 16 dims, this lane supplies dims 16*ks + 8*hf .. +8
-  bf16x8_t q[8];
-  {
-    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * G + h) * kRowBytes + hf * 16;
+  int tl[CT], h[CT], qrow[CT], vis[CT];
+  bf16x8_t q[CT][8];             // Q of this lane's rows: 8 k-steps of 16 dims, this lane supplies dims 16*ks + 8*hf .. +8
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 32));
+  for (int ct = 0; ct < CT; ++ct) {
+    const int rho = (wv * CT + ct) * 32 + col;     // query row of this lane inside the tile
+    tl[ct] = rho / G;                              // token (prefill) or member (shared prefix) of the row
+    h[ct] = rho % G;
+    const int tlc = min(tl[ct], count - 1);        // rows past the tile's last token/member repeat it (never written)
+    qrow[ct] = shared ? a.members[tw[2] + tlc] : tw[2] + tlc;
+    vis[ct] = shared ? kv_end : L + t0 + tlc + 1;  // tokens this row sees
+    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow[ct] * a.Hq + g * G + h[ct]) * kRowBytes + hf * 16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q[ct][ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 32));
   }
 
   // ---- staging roles
@@ -491,14 +497,19 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     put(6, v0.w, v1.w, false); put(7, v0.w, v1.w, true);
   };
 
-  f32x16_t O[4];
+  f32x16_t O[CT][4];
+  float m[CT], l[CT];
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+  for (int ct = 0; ct < CT; ++ct) {
+    m[ct] = -1e30f;
+    l[ct] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) O[db][v] = 0.f;
-  float m = -1e30f, l = 0.f;
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) O[ct][db][v] = 0.f;
+  }
 
-  // One block: its K/V (loaded three blocks ago into S) goes to LDS, the loads of the block three
+  // One block: its K/V (loaded three blocks ago) goes to LDS, the loads of the block three
   // ahead are issued into the same registers, then the block is computed.  All loads and all
   // blocks are unconditional: past the end the last pages are loaded again and every token is
   // masked, so the loop (unrolled by three) has no control-flow join between a load and its use.
@@ -507,58 +518,68 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     store_lds(kb, base, k0, k1, v0, v1);
     __syncthreads();           // block kb is in LDS; everyone is done with the other buffer's previous block
     issue_loads(kb + 3, k0, k1, v0, v1);
+    if (!wave_live) return;
 
-    // S^T = K Q^T for 32 tokens x 32 rows
-    f32x16_t S;
+    // S^T = K Q^T for 32 tokens x 32 rows per column tile; each K operand read feeds CT MFMAs
+    f32x16_t S[CT];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) S[v] = 0.f;
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) S[ct][v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const bf16x8_t kk = *(const bf16x8_t*)(base + (col * 16 + ((2 * ks + hf) ^ (col & 15))) * 16);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, q[ks], S, 0, 0, 0);
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) S[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, q[ct][ks], S[ct], 0, 0, 0);
     }
     // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
     // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
     const int tok0 = kb * kKvBlock + 4 * hf;
-    float mx = -__builtin_inff();
-    if (kb * kKvBlock + kKvBlock > mask_from) {        // the block reaches the causal edge of some row
+    const bool edge = kb * kKvBlock + kKvBlock > mask_from;      // the block reaches the causal edge of some row
+    f16x8_t P[CT][2];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int tok = tok0 + 8 * (v >> 2) + (v & 3);
-        S[v] = tok < vis ? S[v] : -__builtin_inff();
+    for (int ct = 0; ct < CT; ++ct) {
+      float mx = -__builtin_inff();
+      if (edge) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int tok = tok0 + 8 * (v >> 2) + (v & 3);
+          S[ct][v] = tok < vis[ct] ? S[ct][v] : -__builtin_inff();
+        }
       }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[ct][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
+      if (__builtin_amdgcn_ballot_w64(mx > m[ct] + kTau) != 0) {     // rare after the first block
+        const float mn = fmaxf(m[ct], mx);
+        const float al = __builtin_amdgcn_exp2f(m[ct] - mn);
+        l[ct] *= al;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) O[ct][db][v] *= al;
+        m[ct] = mn;
+      }
+      uint32_t pw[8];
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+        const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v], a.scale_log2e, -m[ct])),
+                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v + 1], a.scale_log2e, -m[ct])));
+        l[ct] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[ct], false);
+        pw[v >> 1] = __builtin_bit_cast(uint32_t, pk);
+      }
+      P[ct][0] = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+      P[ct][1] = __builtin_bit_cast(f16x8_t, make_uint4(pw[4], pw[5], pw[6], pw[7]));
     }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
-    if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {     // rare after the first block
-      const float mn = fmaxf(m, mx);
-      const float al = __builtin_amdgcn_exp2f(m - mn);
-      l *= al;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) O[db][v] *= al;
-      m = mn;
-    }
-    uint32_t pw[8];
-#pragma unroll
-    for (int v = 0; v < 16; v += 2) {
-      const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[v], a.scale_log2e, -m)),
-                                                 __builtin_amdgcn_exp2f(__builtin_fmaf(S[v + 1], a.scale_log2e, -m)));
-      l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
-      pw[v >> 1] = __builtin_bit_cast(uint32_t, pk);
-    }
-    const f16x8_t P[2] = {__builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3])),
-                          __builtin_bit_cast(f16x8_t, make_uint4(pw[4], pw[5], pw[6], pw[7]))};
-    // O^T += V^T P^T
+    // O^T += V^T P^T; each V^T operand read feeds CT MFMAs
     const uint8_t* vbase = base + kKLds + col * kVRow + hf * 16;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         const f16x8_t vv = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
-        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv, P[ks], O[db], 0, 0, 0);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) O[ct][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv, P[ct][ks], O[ct][db], 0, 0, 0);
       }
   };
 
@@ -571,28 +592,31 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     do_block(kb + 2, kc0, kc1, vc0, vc1);
   }
 
-  l += __shfl_xor(l, 32);
-  if (tl < count) {
-    if (!shared) {
-      const float inv = 1.0f / l;
-      float* o = a.out + ((int64_t)qrow * a.Hq + g * G + h) * 128 + 4 * hf;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+  for (int ct = 0; ct < CT; ++ct) {
+    const float lt = l[ct] + __shfl_xor(l[ct], 32);
+    if (tl[ct] < count) {
+      if (!shared) {
+        const float inv = 1.0f / lt;
+        float* o = a.out + ((int64_t)qrow[ct] * a.Hq + g * G + h[ct]) * 128 + 4 * hf;
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb)
-          *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb] * inv, O[db][4 * vb + 1] * inv, O[db][4 * vb + 2] * inv, O[db][4 * vb + 3] * inv);
-    } else {
-      // partial result of member tl for the merge kernel: unnormalised accumulator, max, sum
-      const int64_t part = (int64_t)t0 + tl;             // t0 = first partial slot of this tile
-      float* o = a.part_acc + (part * G + h) * 128 + 4 * hf;
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+          for (int vb = 0; vb < 4; ++vb)
+            *(float4*)(o + db * 32 + vb * 8) = make_float4(O[ct][db][4 * vb] * inv, O[ct][db][4 * vb + 1] * inv, O[ct][db][4 * vb + 2] * inv, O[ct][db][4 * vb + 3] * inv);
+      } else {
+        // partial result of member tl for the merge kernel: unnormalised accumulator, max, sum
+        const int64_t part = (int64_t)t0 + tl[ct];           // t0 = first partial slot of this tile
+        float* o = a.part_acc + (part * G + h[ct]) * 128 + 4 * hf;
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb)
-          *(float4*)(o + db * 32 + vb * 8) = make_float4(O[db][4 * vb], O[db][4 * vb + 1], O[db][4 * vb + 2], O[db][4 * vb + 3]);
-      if (hf == 0) {
-        a.part_ml[(part * G + h) * 2 + 0] = m;
-        a.part_ml[(part * G + h) * 2 + 1] = l;
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int vb = 0; vb < 4; ++vb)
+            *(float4*)(o + db * 32 + vb * 8) = make_float4(O[ct][db][4 * vb], O[ct][db][4 * vb + 1], O[ct][db][4 * vb + 2], O[ct][db][4 * vb + 3]);
+        if (hf == 0) {
+          a.part_ml[(part * G + h[ct]) * 2 + 0] = m[ct];
+          a.part_ml[(part * G + h[ct]) * 2 + 1] = lt;
+        }
       }
     }
   }
@@ -822,7 +846,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(DecodeArgs da, PrefillArgs
   if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
     __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
     if ((int)blockIdx.x < tile_blocks) {
-      tile_block<G>(pa, blockIdx.x, lds);
+      tile_block<G, 1>(pa, blockIdx.x, lds);
       return;
     }
   }
@@ -1018,14 +1042,16 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   // decode ranges: matrix cores (mode 1), the two-wavefront VALU kernel for 8 heads (mode 2), or the
   // VALU kernel fused into the tile launch (mode 0)
   const int mode = (E::kDimsPerChunk == 8 && decode_mode == 1) ? 1 : (G == 8 ? 2 : 0);
-  const int tile_blocks = ((pa.n_tiles + 7) / 8) * 8;
+  PrefillArgs ps = pa;
+  ps.tile_first = 0;
+  const int tile_blocks = ((ps.n_tiles + 7) / 8) * 8;
   const int decode_blocks = mode == 0 ? (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock : 0;
   const dim3 grid(tile_blocks + decode_blocks), block(256);
   if (grid.x > 0) switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, pa, tile_blocks); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<E, 2>), grid, block, 0, st, da, pa, tile_blocks); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<E, 4>), grid, block, 0, st, da, pa, tile_blocks); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, pa, tile_blocks); break;
+    case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, ps, tile_blocks); break;
+    case 2: hipLaunchKernelGGL((attn_kernel<E, 2>), grid, block, 0, st, da, ps, tile_blocks); break;
+    case 4: hipLaunchKernelGGL((attn_kernel<E, 4>), grid, block, 0, st, da, ps, tile_blocks); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, ps, tile_blocks); break;
     default: return hipErrorInvalidValue;
   }
   if (da.n_waves > 0 && mode == 2) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);

@@ -35,7 +35,8 @@ struct PrefillArgs {
   const int32_t* members;   // q rows of the members of shared-prefix tiles
   float* part_acc;          // partial results (shared-prefix tiles)
   float* part_ml;
-  int32_t n_tiles, Hq, Hkv;
+  int32_t tile_first, n_tiles;   // the launch covers tiles [tile_first, tile_first + n_tiles)
+  int32_t Hq, Hkv;
   float scale_log2e;
 };
 

@@ -243,7 +243,7 @@ def test_descriptor_rejects_bad_tables():
 
 def test_descriptor_tiles_for_prefill_chunks():
     """LIPs with 16+ new tokens become tiles (one per kv head and 32 new tokens at 4 heads per
-    group); the others stay decode rows; q rows keep the batch's token order."""
+    group: 128 query rows); the others stay decode rows; q rows keep the batch's token order."""
     c = host_ctx(4096)
     lengths, n_tok = [100, 77, 40, 16], [70, 1, 3, 16]
     np_l = [-(-L // 16) for L in lengths]
