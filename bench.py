@@ -113,7 +113,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft"], default="decode")
     ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
@@ -139,6 +139,8 @@ def main():
                       "private suffix U{1..256}, 32Q/8KV, bf16, 1 new token each"),
              "mixed": (synth.config4, 1, 20, 3, True, 0.0, "mixed: 32 LIPs x 512-token prefill chunk on U{0..8192} + 224 decode LIPs "
                        "U{1024..4096}, 32Q/8KV, bf16 (files truncated back after every step)"),
+             "draft": (lambda: synth.config2(n_new=4, slack_pages=4096), 4, 200, 20, False, 0.0, "draft verify: the decode batch (64 LIPs, 32Q/8KV, "
+                       "bf16, contexts U{512..4096}) with 4 new tokens per LIP and call"),
              "long": (lambda: synth.config5(n_pages=args.pool_pages), 1, 50, 5, False, 0.0, "long context: 16 LIPs U{32768..131072}, "
                       "64Q/8KV, bf16, pages scattered over a %d-page pool, 1 new token each" % args.pool_pages)}
     gen, layers, steps, warmup, reset, cpu_s, label = table[args.workload]
@@ -220,12 +222,14 @@ def main():
     hbm_ach = step_bytes / (attn_ms * 1e-3) / 1e9
     mfma_ach = mfma_flops / (attn_ms * 1e-3) / 1e12
     note = {"decode": "attn_decode_batch_pmc.txt"}.get(args.workload, f"attn_{args.workload}_pmc.txt")
+    # decode ranges run on the matrix cores for 8 query heads per kv head and for multi-token rows
+    kname = f"decode_mfma_kernel<G={G}>" if args.workload in ("long", "draft") else f"attn_kernel<bf16, G={G}>"
     roof_hbm = {"bound": "hbm", "achieved": round(hbm_ach, 1), "peak": HBM_PEAK_TBPS * 1e3, "unit": "GB/s",
                 "frac": round(hbm_ach / (HBM_PEAK_TBPS * 1e3), 4), "traffic": read_traffic_note(note),
-                "kernel": f"attn_kernel<bf16, G={G}>", "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_n}
+                "kernel": kname, "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_n}
     roof_mfma = {"bound": "mfma", "achieved": round(mfma_ach, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                  "frac": round(mfma_ach / MFMA_PEAK_TFLOPS, 4), "traffic": read_traffic_note(note),
-                 "kernel": f"attn_kernel<bf16, G={G}>", "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_n,
+                 "kernel": kname, "avg_launch_us": round(attn_ms * 1e3, 2), "launches": attn_n,
                  "flops_per_launch": int(mfma_flops)}
     dominant, other = (roof_mfma, roof_hbm) if roof_mfma["frac"] > roof_hbm["frac"] else (roof_hbm, roof_mfma)
 

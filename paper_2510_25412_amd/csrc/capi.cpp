@@ -37,6 +37,7 @@ struct sym_ctx {
   int32_t decode_mode = 0;                           // 1 = decode ranges on the matrix cores
   int32_t share_min_lips = 4, share_min_pages = 8;   // decode LIPs / common full pages needed to read a prefix once
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
+  int32_t row_tokens = 1;                      // new tokens of one LIP per decode row (bf16: up to 16 / G, at most 4)
   std::mutex mu;
   std::string err;
   Kvfs* fs = nullptr;
@@ -82,13 +83,18 @@ bool shape_ok(const sym_config* cfg) {
 
 // 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
 int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
-  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + MERGE_WORDS) + entries +
+  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + ROW_TOKENS_MAX * MERGE_WORDS) + entries +
          (T + 8 * n_lips) * c->cfg.n_kv_heads * 2 + n_lips * (1 + c->cfg.n_kv_heads * (MERGE_WORDS + 8 * TILE_WORDS)) +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
 // Partial-result slots of the workspace: a wave boundary cuts at most one (row, head) range (<= 2
-// partial pieces per wave); the rest is for the partials of shared-prefix tiles.
-int64_t partial_slots(const sym_ctx* c) { return 12 * (int64_t)c->max_waves + 1; }
+// pieces per wave, each a partial per token of the row); the rest is for the partials of
+// shared-prefix tiles and of their members' own ranges.
+int64_t partial_slots(const sym_ctx* c) { return (2 * ROW_TOKENS_MAX + 10) * (int64_t)c->max_waves + 1; }
+DescParams desc_params(const sym_ctx* c) {
+  return DescParams{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min,
+                    c->tile_tokens, c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c), c->row_tokens};
+}
 int64_t partial_bytes(const sym_ctx* c) {
   const int64_t np = partial_slots(c);
   return align_up(np * c->G * 2 * 4, 256) + align_up(np * c->G * c->cfg.head_dim * 4, 256);
@@ -182,7 +188,8 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.scale_log2e = c->scale_log2e;
   {
     Timed t(c, SYM_K_ATTN, st);
-    hipError_t e = launch_attn(a, pa, c->cfg.dtype, c->decode_mode, st);
+    // rows that hold several new tokens exist for the matrix-core decode kernel only
+    hipError_t e = launch_attn(a, pa, c->cfg.dtype, (c->decode_mode || d.max_row_tokens > 1) ? 1 : 0, st);
     if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {
@@ -237,8 +244,7 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
-                 c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
+  const DescParams prm = desc_params(c);
   c->desc.alloc = alloc;
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   c->desc.alloc = nullptr;
@@ -308,6 +314,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
   c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));
   c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;   // a tile has 128 query rows
+  // a short draft (2 .. prefill_min - 1 new tokens) shares one pass over its file: 16 MFMA columns = tokens x heads
+  c->row_tokens = cfg->dtype == SYM_BF16 ? std::max(1, std::min(env_int("SYM_ROW_TOKENS", ROW_TOKENS_MAX), std::min<int>(ROW_TOKENS_MAX, 16 / c->G))) : 1;
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
@@ -502,8 +510,7 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  DescParams prm{c->cfg.n_q_heads, c->cfg.n_kv_heads, P, c->max_waves, c->min_units, c->range_cost, c->prefill_min, c->tile_tokens,
-                 c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c)};
+  const DescParams prm = desc_params(c);
   // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
   const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
   int si = -1;

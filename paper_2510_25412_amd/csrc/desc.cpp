@@ -13,11 +13,18 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int32_t P = prm.page_tokens, H = prm.n_kv_heads, G = prm.n_q_heads / H;
   const int32_t TQ = prm.tile_tokens;
   auto is_prefill = [&](int32_t b) { return TQ > 0 && n_tokens[b] >= prm.prefill_min; };
+  // A decode row holds up to RT consecutive new tokens of one LIP (a short draft to verify):
+  // they share one pass over the file's pages.
+  const int32_t RT = std::max(1, std::min(prm.row_tokens, (int32_t)ROW_TOKENS_MAX));
+  int32_t max_nt = 1;
   int64_t n_rows = 0, entries = 0, n_tiles = 0, n_tok_total = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     if (n_tokens[b] < 1 || len_after[b] < n_tokens[b] || len_after[b] > (int64_t)0x7fffffff) return SYM_EINVAL;
     if (is_prefill(b)) n_tiles += (int64_t)((n_tokens[b] + TQ - 1) / TQ) * H;
-    else n_rows += n_tokens[b];
+    else {
+      n_rows += (n_tokens[b] + RT - 1) / RT;
+      max_nt = std::max(max_nt, std::min(RT, n_tokens[b]));
+    }
     n_tok_total += n_tokens[b];
     entries += (len_after[b] + P - 1) / P;
   }
@@ -40,6 +47,10 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   member_rows.clear();
   stiles.clear();
   int64_t n_shared_partials = 0, n_shared_tiles = 0;
+  // Partial slots: a wave boundary cuts one (row, head), whose two pieces leave a partial per token
+  // of the row; the rest is split between the prefix partials of sharing groups and the
+  // members' own ranges (one partial per (member, head), never more than the former).
+  const int64_t shared_budget = std::max<int64_t>(0, ((int64_t)prm.max_partials - 2 * (int64_t)RT * prm.max_waves) / 2);
   const int32_t tile_lips = TQ > 0 ? 128 / G : 0;           // a shared-prefix tile has 128 query rows
   if (prm.share_min_lips > 0 && tile_lips > 0) {
     auto& cand = out->by_first_page;
@@ -116,8 +127,8 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       for (size_t gi = 0; gi < groups.size(); gi += 3) {
         const int32_t lo = groups[gi], K = groups[gi + 1], C = groups[gi + 2];
         int32_t nc = std::max(1, std::min(nc_want, C / 8));
-        while (nc > 1 && n_shared_partials + (int64_t)K * H * nc > prm.max_partials / 2) --nc;   // partial slots must fit
-        if (n_shared_partials + (int64_t)K * H * nc > prm.max_partials / 2) continue;            // no room: plain rows
+        while (nc > 1 && n_shared_partials + (int64_t)K * H * nc > shared_budget) --nc;   // partial slots must fit
+        if (n_shared_partials + (int64_t)K * H * nc > shared_budget) continue;            // no room: plain rows
         for (int32_t i = 0; i < K; i += tile_lips) {
           const int32_t k = std::min(tile_lips, K - i);
           const int32_t moff = (int32_t)member_rows.size();
@@ -143,9 +154,9 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int64_t total_units = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     if (is_prefill(b)) continue;
-    for (int32_t i = 0; i < n_tokens[b]; ++i) {
-      int64_t vis = len_after[b] - n_tokens[b] + i + 1;
-      total_units += ((vis + P - 1) / P - share_start[b]) * H;
+    for (int32_t i = 0; i < n_tokens[b]; i += RT) {
+      const int64_t vis_last = len_after[b] - n_tokens[b] + std::min(i + RT, n_tokens[b]);   // what the row's last token sees
+      total_units += ((vis_last + P - 1) / P - share_start[b]) * H;
     }
   }
   int64_t nw = (total_units + prm.min_units_per_wave - 1) / prm.min_units_per_wave;
@@ -156,8 +167,8 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
-  // a merge entry per cut (row, head) (at most one per wave boundary) and per (member row, head)
-  const int64_t off_pt = off_merge + (nw + n_members * H) * MERGE_WORDS;
+  // a merge entry per token of a cut (row, head) (at most one cut per wave boundary) and per (member row, head)
+  const int64_t off_pt = off_merge + (nw * max_nt + n_members * H) * MERGE_WORDS;
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
   const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
@@ -196,11 +207,12 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
           t[T_KIND] = TILE_PREFILL;
         }
     } else {
-      for (int32_t i = 0; i < n_tokens[b]; ++i, ++r) {
+      for (int32_t i = 0; i < n_tokens[b]; i += RT, ++r) {
+        const int32_t nt = std::min(RT, n_tokens[b] - i);
         rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
-        rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // visible tokens
-        rows[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row
-        rows[r * ROW_WORDS + 3] = share_start[b];                                   // first page of the row's own range
+        rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // tokens the row's first token sees
+        rows[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row of its first token
+        rows[r * ROW_WORDS + 3] = share_start[b] | ((nt - 1) << ROW_NT_SHIFT);      // first page of the row's own range; tokens - 1
       }
     }
     tok += n_tokens[b];
@@ -214,8 +226,9 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   // falls into the overhead part of a (row, head) snaps to its first page.
   int32_t* waves = w + off_waves;
   int32_t* merge = w + off_merge;
-  auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + P - 1) / P; };
-  auto row_first = [&](int64_t rr) { return rows[rr * ROW_WORDS + 3]; };
+  auto row_nt = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 3] >> ROW_NT_SHIFT) + 1; };
+  auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + row_nt(rr) - 1 + P - 1) / P; };   // pages its last token sees
+  auto row_first = [&](int64_t rr) { return rows[rr * ROW_WORDS + 3] & ROW_PAGE_MASK; };
   const int64_t alpha = prm.range_cost;
   const int64_t vtotal = total_units + alpha * n_rows * H;
   {
@@ -254,21 +267,24 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
       for (int i = 0; i < 3; ++i) ww[8 + i] = t0[std::min(p + i, np0 - 1)];
     }
-    ww[11] = row_first(row);
+    ww[11] = rows[row * ROW_WORDS + 3];
     int64_t units = 0;
     while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
       const int32_t np = row_pages(row), p0 = row_first(row);
       const int32_t cnt = (row == erow && g == eg) ? ep - p : np - p;
       if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
+        const int32_t nt = row_nt(row);                        // a piece leaves one partial per token of the row
         if (p == p0) {                                         // first piece of this (row, g)
-          int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
-          std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
-          it[0] = part;
-          it[2] = rows[row * ROW_WORDS + 2] * prm.n_q_heads + g * G;
-          ++n_merge;
+          for (int32_t t = 0; t < nt; ++t, ++n_merge) {
+            int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
+            std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
+            it[0] = part + t;
+            it[2] = (rows[row * ROW_WORDS + 2] + t) * prm.n_q_heads + g * G;
+            it[6] = nt;                                        // distance between the token's pieces
+          }
         }
-        ++merge[(int64_t)(n_merge - 1) * MERGE_WORDS + 1];
-        ++part;
+        for (int32_t t = 0; t < nt; ++t) ++merge[(int64_t)(n_merge - 1 - t) * MERGE_WORDS + 1];
+        part += nt;
       }
       units += cnt;
       p += cnt;
@@ -351,6 +367,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   out->n_lips = n_lips;
   out->n_tiles = (int32_t)n_tiles;
   out->total_units = total_units;
+  out->max_row_tokens = max_nt;
   return SYM_OK;
 }
 

@@ -10,6 +10,9 @@
 //    the tile kernel (rows = members x query heads of the group), leaving partial results;
 //  * decode rows: every other new token is a "row" with a visible length (file tokens
 //    0 .. len_before + i); a member of a sharing group is a row that starts after the common pages.
+//    A LIP that brings a few new tokens (a short draft to verify, paper section 4.1) packs up to
+//    row_tokens consecutive ones into one row: they share a single pass over the file, each
+//    with its own visible length.
 // The work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
 // slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves contiguous
 // ranges of equal cost, one per wavefront, whatever the raggedness of the files.  A range
@@ -34,6 +37,9 @@ enum {
 // tile words
 enum { T_TBL = 0, T_LEN, T_QROW, T_COUNT, T_HEAD, T_AUX, T_KIND, T_PAGE0, T_PAGE1 };
 enum { TILE_PREFILL = 0, TILE_SHARED = 1 };
+// word 3 of a row (and word 11 of a wave record): first page of the row's own range in the low
+// bits, (new tokens in the row) - 1 above them
+enum { ROW_NT_SHIFT = 28, ROW_PAGE_MASK = (1 << ROW_NT_SHIFT) - 1, ROW_TOKENS_MAX = 4 };
 
 struct BatchDesc {
   // The packed descriptor (header first) is written straight into memory the caller hands out
@@ -42,6 +48,7 @@ struct BatchDesc {
   int32_t* words = nullptr;
   int64_t n_words = 0;
   int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
+  int32_t max_row_tokens = 1;   // > 1: some row holds several new tokens (needs the matrix-core decode kernel)
   int64_t total_units = 0;
   // scratch of the builder, kept between calls
   std::vector<std::pair<int32_t, int32_t>> by_first_page, lcp;
@@ -58,6 +65,7 @@ struct DescParams {
   int32_t share_min_lips;     // decode LIPs that must share a prefix to form a group (0 = never group)
   int32_t share_min_pages;    // common full pages a group must have
   int32_t max_partials;       // partial-result slots the workspace holds
+  int32_t row_tokens;         // new tokens of one LIP a decode row may hold (1 = a row per token)
 };
 
 // n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page

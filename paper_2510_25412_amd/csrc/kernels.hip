@@ -635,6 +635,9 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
 // A lane's column is a head in both results, so max / sum / rescale factor are lane-local; the
 // four lane groups of a head hold different tokens and share only the (lagging) running max.
 // No barrier anywhere: the LDS buffer is private to the wavefront.
+// A row may hold nt <= 16 / GT consecutive new tokens of one LIP (a short draft being verified,
+// paper section 4.1): column c is then (token c / GT, head c % GT), token t sees vis + t file
+// tokens, and the page loop runs to the last token's limit: one pass over K/V for all of them.
 // ---------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int kVtRow = 80;                    // bytes per dim row of V^T (32 tokens fp16 + 16 pad)
@@ -645,8 +648,8 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(block * kWavesPerBlock + (int)(threadIdx.x >> 6));
   if (wv >= a.n_waves) return;
-  const int col = lane & 15, grp = lane >> 4;        // head column, lane group (tokens 4*grp .. 4*grp+3 of a page)
-  const int head = col % GT;                          // columns past GT repeat heads; their results are ignored
+  const int col = lane & 15, grp = lane >> 4;        // query column, lane group (tokens 4*grp .. 4*grp+3 of a page)
+  const int head = col % GT;                          // columns past nt * GT repeat earlier ones; their results are ignored
   const int vq4 = lane >> 4, vc = lane & 15;          // V staging role: tokens 4*vq4 .. +3 of a page, dim chunk vc
 
   const int32_t* ww = a.waves + wv * 12;
@@ -661,18 +664,21 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
   int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
   int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
   int pstart = __builtin_amdgcn_readfirstlane(ww[11]);
+  int nt = (pstart >> 28) + 1;                        // new tokens in the row
+  pstart &= 0x0fffffff;
   bool first_range = true;
 
   while (remaining > 0) {
-    const int np = (vis + kP - 1) / kP;
+    const int np = (vis + nt - 1 + kP - 1) / kP;      // pages the row's last token sees
     const int cnt = min(remaining, np - p);
     const int32_t* tbl = a.pt + tbl_off + p;
     const int last = cnt - 1;
+    const int tok = min(col / GT, nt - 1);            // this column's token within the row
 
-    // Q^T operand: this lane's head, dims 32*ks + 8*grp .. +8 for the four k-steps
+    // Q^T operand: this lane's (token, head), dims 32*ks + 8*grp .. +8 for the four k-steps
     bf16x8_t q[4];
     {
-      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qrow * a.Hq + g * GT + head) * kRowBytes + grp * 16;
+      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)(qrow + tok) * a.Hq + g * GT + head) * kRowBytes + grp * 16;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 64));
     }
@@ -727,12 +733,14 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
     };
     // two pages (32 tokens): scores, softmax weights, O^T += V^T P^T
     auto compute2 = [&](const uint4 (&kA)[4], const uint4 (&vA)[4], const uint4 (&kB)[4], const uint4 (&vB)[4], int piA, bool haveB) {
-      const int nvA = vis - piA * kP, nvB = haveB ? vis - (piA + 1) * kP : 0;
+      // tokens of the page visible to this column's token; slots that hold file tokens at all
+      const int nvA = vis + tok - piA * kP, nvB = haveB ? nvA - kP : 0;
+      const int nsA = vis + nt - 1 - piA * kP, nsB = haveB ? nsA - kP : 0;
       float sA[4], sB[4];
       scores(kA, nvA, sA);
       scores(kB, nvB, sB);
-      stage_v(vA, nvA, 0);
-      stage_v(vB, nvB, 1);
+      stage_v(vA, nsA, 0);
+      stage_v(vB, nsB, 1);
       const float mx = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3]))) * a.scale_log2e;
       if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {       // rare after the first pages
         float mn = fmaxf(m, mx);
@@ -794,23 +802,24 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const bool whole = (p == 0 && cnt == np);
-    if (col < GT) {
+    if (col < nt * GT) {
       if (whole) {
         const float inv = 1.0f / l;
-        float* o = a.out + ((int64_t)qrow * a.Hq + g * GT + head) * 128 + 4 * grp;
+        float* o = a.out + ((int64_t)(qrow + tok) * a.Hq + g * GT + head) * 128 + 4 * grp;
 #pragma unroll
         for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0] * inv, O[db][1] * inv, O[db][2] * inv, O[db][3] * inv);
       } else {
-        float* o = a.part_acc + ((int64_t)part * GT + head) * 128 + 4 * grp;
+        const int64_t slot = (int64_t)(part + tok) * GT + head;   // a piece leaves one partial per token of the row
+        float* o = a.part_acc + slot * 128 + 4 * grp;
 #pragma unroll
         for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0], O[db][1], O[db][2], O[db][3]);
         if (grp == 0) {
-          a.part_ml[((int64_t)part * GT + head) * 2 + 0] = m;
-          a.part_ml[((int64_t)part * GT + head) * 2 + 1] = l;
+          a.part_ml[slot * 2 + 0] = m;
+          a.part_ml[slot * 2 + 1] = l;
         }
       }
     }
-    if (!whole) ++part;
+    if (!whole) part += nt;
     remaining -= cnt;
     p += cnt;
     if (p == np) {
@@ -822,6 +831,8 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
           vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
           qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
           pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
+          nt = (pstart >> 28) + 1;
+          pstart &= 0x0fffffff;
         }
       }
       p = pstart;
@@ -881,9 +892,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a)
   const int xfirst = __builtin_amdgcn_readfirstlane(it[3]);
   const int xstride = __builtin_amdgcn_readfirstlane(it[4]);
   const int pieces = own + __builtin_amdgcn_readfirstlane(it[5]);
+  const int ostride = __builtin_amdgcn_readfirstlane(it[6]);      // distance between own pieces (tokens in the row)
   auto slot = [&](int i) -> int64_t {
     i = min(i, pieces - 1);
-    return i < own ? first + i : xfirst + (int64_t)(i - own) * xstride;
+    return i < own ? first + (int64_t)i * ostride : xfirst + (int64_t)(i - own) * xstride;
   };
   constexpr int VL = G * D / 64;
   const float* ml0 = a.part_ml;

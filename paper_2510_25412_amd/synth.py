@@ -131,16 +131,17 @@ def config1():
     return _finish(wl, st)
 
 
-def config2(n_lips=64, lo=512, hi=4096, slack_pages=2048):
-    """Decode batch: 64 LIPs, 32 Q / 8 KV heads, D 128, bf16, lengths U{512..4096}."""
+def config2(n_lips=64, lo=512, hi=4096, slack_pages=2048, n_new=1):
+    """Decode batch: 64 LIPs, 32 Q / 8 KV heads, D 128, bf16, lengths U{512..4096}; n_new tokens
+    per LIP and call (1 = plain decode; 2..8 = a draft being verified, paper section 4.1)."""
     st = _Streams(1002)
     lengths = st.root.integers(lo, hi + 1, size=n_lips)
     P = 16
-    n_pages = int(sum(-(-(int(L) + 1) // P) for L in lengths)) + slack_pages
-    wl = Workload("decode_batch", Shape(32, 8, 128, P, BF16), n_pages, None)
+    n_pages = int(sum(-(-(int(L) + n_new) // P) for L in lengths)) + slack_pages
+    wl = Workload("decode_batch" if n_new == 1 else f"draft{n_new}_batch", Shape(32, 8, 128, P, BF16), n_pages, None)
     _plain_files(wl, st, lengths)
     wl.batch_files = list(range(n_lips))
-    wl.batch_n = [1] * n_lips
+    wl.batch_n = [int(n_new)] * n_lips
     return _finish(wl, st)
 
 

@@ -160,11 +160,16 @@ def _walk_desc(words, Hkv, P=16):
 
 
 @pytest.mark.parametrize("lengths,n_tok,waves", [([38, 81, 130, 201], [1, 1, 1, 1], 64), ([700, 16, 17, 1, 4096], [1, 1, 1, 1, 1], 2048),
-                                                 ([40, 300], [8, 1], 32), ([5], [5], 8)])
+                                                 ([40, 300], [8, 1], 32), ([5], [5], 8), ([1030, 64, 333, 2000], [3, 2, 1, 7], 96)])
 @pytest.mark.parametrize("range_cost", [0, 3])
-def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves, range_cost, monkeypatch):
+@pytest.mark.parametrize("row_tokens", [1, 4])
+def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves, range_cost, row_tokens, monkeypatch):
+    """Rows (up to row_tokens new tokens of one LIP each, a short draft sharing one pass over the
+    file), wave ranges, partial numbering and merge entries of the descriptor, walked the way the
+    decode kernel walks them."""
     Hkv = 8
     monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
+    monkeypatch.setenv("SYM_ROW_TOKENS", str(row_tokens))
     c = host_ctx(4096, decode_waves=waves)
     rng = np.random.default_rng(1)
     np_l = [-(-L // 16) for L in lengths]
@@ -172,12 +177,18 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
     words = c.build_desc(n_tok, flat, off, lengths)
     n_rows, n_waves, n_partials, rows, wv, merge, pt, ptoff = _walk_desc(words, Hkv)
-    assert n_rows == sum(n_tok) and np.array_equal(pt, flat) and np.array_equal(ptoff, off)
-    # rows: lip, visible tokens, q row
-    exp_rows = [(b, L - n + i + 1, None) for b, (L, n) in enumerate(zip(lengths, n_tok)) for i in range(n)]
-    assert [int(r[1]) for r in rows] == [v for _, v, _ in exp_rows] and not rows[:, 3].any()
-    assert rows[:, 2].tolist() == list(range(n_rows))
-    assert [int(r[0]) for r in rows] == [int(off[b]) for b, _, _ in exp_rows]
+    assert np.array_equal(pt, flat) and np.array_equal(ptoff, off)
+    # rows: page-table offset, tokens the first token sees, its q row, (tokens - 1) << 28 | first own page
+    exp_rows, q0 = [], 0
+    for b, (L, n) in enumerate(zip(lengths, n_tok)):
+        for i in range(0, n, row_tokens):
+            exp_rows.append((int(off[b]), L - n + i + 1, q0 + i, min(row_tokens, n - i)))
+        q0 += n
+    assert n_rows == len(exp_rows)
+    assert [(int(r[0]), int(r[1]), int(r[2]), (int(r[3]) >> 28) + 1) for r in rows] == exp_rows
+    assert not (rows[:, 3] & 0x0fffffff).any()
+    nts = [e[3] for e in exp_rows]
+    npgs = [-(-(e[1] + e[3] - 1) // 16) for e in exp_rows]        # pages the row's last token sees
     # walk every wave's range exactly as the kernel does; record coverage and partial numbering
     cover = {}
     units, starts = [], []
@@ -185,13 +196,13 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     for k in range(n_waves):
         row, g, p, rem, part = (int(x) for x in wv[k, :5])
         assert wv[k, 5:8].tolist() == [int(rows[row, 1]), int(rows[row, 2]), int(rows[row, 0])]   # first range's row data
-        npg0 = -(-int(rows[row, 1]) // 16)
-        assert wv[k, 8:11].tolist() == [int(pt[int(rows[row, 0]) + min(p + i, npg0 - 1)]) for i in range(3)]
+        assert int(wv[k, 11]) == int(rows[row, 3])
+        assert wv[k, 8:11].tolist() == [int(pt[int(rows[row, 0]) + min(p + i, npgs[row] - 1)]) for i in range(3)]
         units.append(rem)
         starts.append(0)
         while rem > 0:
             starts[-1] += p == 0
-            npg = -(-int(rows[row, 1]) // 16)
+            npg = npgs[row]
             cnt = min(rem, npg - p)
             for x in range(p, p + cnt):
                 assert (row, g, x) not in cover
@@ -199,14 +210,14 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
             whole = p == 0 and cnt == npg
             pieces.setdefault((row, g), []).append(None if whole else part)
             if not whole:
-                part += 1
+                part += nts[row]
             rem -= cnt
             p += cnt
             if p == npg:
                 p, g = 0, g + 1
                 if g == Hkv:
                     g, row = 0, row + 1
-    total = sum(-(-int(r[1]) // 16) for r in rows) * Hkv
+    total = sum(npgs) * Hkv
     assert len(cover) == total and sum(units) == total
     # equal cost whatever the raggedness: units + range_cost per (row, head) begun in the range
     # (a cut that falls into the overhead part of a (row, head) snaps to its first page, which
@@ -215,20 +226,22 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     assert max(cost) - min(cost) <= 1 + 2 * range_cost
     assert n_waves <= waves
     items = {}
-    for first, cnt, out_idx, xf, xs, xc, _, _ in merge.tolist():
-        assert xc == 0
-        items[out_idx] = (first, cnt)
+    for first, cnt, out_idx, xf, xs, xc, stride, _ in merge.tolist():
+        assert xc == 0 and out_idx not in items
+        items[out_idx] = (first, cnt, stride)
     seen_parts = []
     for (row, g), ps in sorted(pieces.items()):
-        out_idx = int(rows[row, 2]) * 32 + g * 4          # q row * Hq + first query head of the group
-        if ps == [None]:
-            assert out_idx not in items                       # whole range: final output, no partial
-        else:
-            first, cnt = items.pop(out_idx)
-            assert None not in ps and ps == list(range(first, first + cnt))
-            seen_parts += ps
+        for t in range(nts[row]):
+            out_idx = (int(rows[row, 2]) + t) * 32 + g * 4          # q row * Hq + first query head of the group
+            if ps == [None]:
+                assert out_idx not in items                       # whole range: final output, no partial
+            else:
+                first, cnt, stride = items.pop(out_idx)
+                assert None not in ps and stride == nts[row] and cnt == len(ps)
+                assert [x + t for x in ps] == [first + i * stride for i in range(cnt)]
+                seen_parts += [x + t for x in ps]
     assert not items
-    assert seen_parts == list(range(n_partials)) and n_partials <= 2 * n_waves
+    assert sorted(seen_parts) == list(range(n_partials)) and n_partials <= 2 * n_waves * row_tokens
 
 
 def test_descriptor_rejects_bad_tables():
@@ -252,10 +265,10 @@ def test_descriptor_tiles_for_prefill_chunks():
     words = c.build_desc(n_tok, flat, off, lengths)
     hdr = words[:20]
     n_rows, n_tiles = int(hdr[0]), int(hdr[4])
-    assert n_rows == 4 and n_tiles == (3 + 1) * 8
+    assert n_rows == 2 and n_tiles == (3 + 1) * 8            # the 3-token LIP is one row of three tokens
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
-    assert rows[:, 2].tolist() == [70, 71, 72, 73] and rows[:, 0].tolist() == [int(off[1]), int(off[2]), int(off[2]), int(off[2])]
-    assert rows[:, 1].tolist() == [77, 38, 39, 40]
+    assert rows[:, 2].tolist() == [70, 71] and rows[:, 0].tolist() == [int(off[1]), int(off[2])]
+    assert rows[:, 1].tolist() == [77, 38] and rows[:, 3].tolist() == [0, 2 << 28]
     tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
     exp = [(int(off[0]), 30, t0, min(32, 70 - t0), g, t0, 0) for g in range(8) for t0 in (0, 32, 64)]
     exp += [(int(off[3]), 0, 74, 16, g, 0, 0) for g in range(8)]
