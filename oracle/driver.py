@@ -34,6 +34,12 @@ class OracleSession:
                 self.pool.apply(cow, slots, widen(K), widen(V))
             elif op[0] == "remove":
                 self.model.kv_remove(self.h.pop(op[1]))
+            elif op[0] == "extract":                      # ("extract", new fid, source fid, token indices)
+                self.h[op[1]], moves = self.model.kv_extract(self.h[op[2]], op[3])
+                self.pool.move_tokens(moves)
+            elif op[0] == "merge":                        # ("merge", new fid, [source fids])
+                self.h[op[1]], moves = self.model.kv_merge([self.h[f] for f in op[2]])
+                self.pool.move_tokens(moves)
             else:
                 raise ValueError(op[0])
 

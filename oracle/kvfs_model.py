@@ -11,7 +11,13 @@ step by step so that the library's integer state can be compared bit for bit:
 * appending to a file whose last page is partly filled and shared first copies that
   page's filled slots into a fresh page (copy-on-write); full pages are never copied;
 * `kv_remove` decrements every page once and frees those reaching zero;
-* a batch of appends either fits in the free pages or changes nothing.
+* a batch of appends either fits in the free pages or changes nothing;
+* `kv_extract` / `kv_merge` (section 4.2: a new file from chosen token indices of a file / from
+  the concatenation of files) build a new anonymous file token by token.  The stored K/V rows
+  move unchanged.  A destination page whose tokens are slots 0, 1, 2, ... of ONE existing page,
+  in that order, is not copied: the new file references that page (count + 1), like a fork;
+  every other destination page is a fresh page (lowest rank first, in destination order) that
+  receives copies of its tokens' rows.  Either the whole new file fits or nothing changes.
 """
 import heapq
 
@@ -187,6 +193,48 @@ class KVFSModel:
             slots.append(mine)
         return cow, slots
 
+    # ---- extract / merge (section 4.2) -------------------------------------------
+    def kv_gather(self, refs):
+        """New anonymous file whose token j is token i of the file behind handle h, for
+        (h, i) = refs[j].  Returns (handle, moves), moves = [(src_page, src_slot, dst_page,
+        dst_slot)] for every token that has to be copied (tokens of shared pages have none)."""
+        P = self.P
+        src = []                                          # (page, slot) of every destination token
+        for h, i in refs:
+            f = self._file(h)
+            if i < 0 or i >= f.length:
+                raise KVError(EINVAL, f"token index {i} outside the file")
+            src.append((f.pages[i // P], i % P))
+        n = len(src)
+        shared = []                                       # per destination page: the page it references, or None
+        for d in range(-(-n // P)):
+            toks = src[d * P:(d + 1) * P]
+            same = all(pg == toks[0][0] and sl == k for k, (pg, sl) in enumerate(toks))
+            shared.append(toks[0][0] if same else None)
+        if sum(s is None for s in shared) > len(self.free_ranks):
+            raise KVError(ENOSPC, "page pool exhausted")
+        f = _File(None)
+        moves = []
+        for d, s in enumerate(shared):
+            if s is not None:
+                self.refcount[s] += 1
+                f.pages.append(s)
+            else:
+                dst = self._alloc()
+                f.pages.append(dst)
+                for k, (pg, sl) in enumerate(src[d * P:(d + 1) * P]):
+                    moves.append((pg, sl, dst, k))
+        f.length = n
+        return self._new_handle(f), moves
+
+    def kv_extract(self, h, idx):
+        """New file from the chosen token indices of file h, in the order given."""
+        return self.kv_gather([(h, int(i)) for i in idx])
+
+    def kv_merge(self, handles):
+        """New file = the files' tokens one file after the other."""
+        return self.kv_gather([(h, i) for h in handles for i in range(self._file(h).length)])
+
     # ---- audit -----------------------------------------------------------------
     def audit(self):
         """State invariants: reference counts equal table references; free = count 0."""
@@ -225,6 +273,11 @@ class PagePool:
         pg = self.page(page)
         pg[0, :, slot, :] = k_row
         pg[1, :, slot, :] = v_row
+
+    def move_tokens(self, moves):
+        """Carry out the copies of KVFSModel.kv_gather: rows of (src page, slot) into (dst page, slot)."""
+        for sp, ss, dp, ds in moves:
+            self.page(dp)[:, :, ds, :] = self.page(sp)[:, :, ss, :]
 
     def apply(self, cow, slots, k_new, v_new):
         """Carry out a plan from KVFSModel.append: copies first, then the token rows

@@ -242,3 +242,34 @@ def test_workload_shapes():
     assert len(L) == 64 and L.min() >= 512 and L.max() <= 4096
     b1, b2 = synth.config1().batch(), synth.config1().batch()
     assert np.array_equal(b1["q"], b2["q"]) and np.array_equal(b1["k_new"], b2["k_new"])
+
+
+def test_pred_on_extracted_and_merged_files_equals_dense_on_indexed_arrays():
+    """extract / merge (section 4.2) defined on plain arrays: the new file's K/V are the source
+    rows indexed (or concatenated) with numpy, and a pred on the new file is dense attention on
+    those arrays plus the new row, bit for bit; the sources still read as before."""
+    rng = np.random.default_rng(5)
+    Hq, Hkv, D, P = 4, 2, 8, 4
+    sess = OracleSession(synth.Shape(Hq, Hkv, D, P, synth.F32), 64, rng.permutation(64))
+    Ka, Va = _rand(rng, 23, Hkv, D), _rand(rng, 23, Hkv, D)
+    Kb, Vb = _rand(rng, 10, Hkv, D), _rand(rng, 10, Hkv, D)
+    idx = [0, 1, 2, 3, 9, 8, 20, 21, 22, 5, 5]
+    sess.setup([("open", 0), ("append", 0, Ka, Va), ("open", 1), ("append", 1, Kb, Vb),
+                ("extract", 2, 0, idx), ("merge", 3, [1, 0, 1]), ("extract", 4, 0, list(range(23)))])
+    expect = {2: (Ka[idx], Va[idx]), 3: (np.concatenate([Kb, Ka, Kb]), np.concatenate([Vb, Va, Vb])), 4: (Ka, Va),
+              0: (Ka, Va), 1: (Kb, Vb)}
+    for fid, (K, V) in expect.items():
+        Kg, Vg = gather_file(sess.pool, sess.model.kv_pages(sess.h[fid]), len(K))
+        assert np.array_equal(Kg, K) and np.array_equal(Vg, V), fid
+    files = [2, 3, 4, 0]
+    q, kn, vn = _rand(rng, 4, Hq, D), _rand(rng, 4, Hkv, D), _rand(rng, 4, Hkv, D)
+    out = sess.pred(dict(files=files, n_tokens=[1] * 4, q=q, k_new=kn, v_new=vn))
+    for i, fid in enumerate(files):
+        K, V = expect[fid]
+        ref = dense_attention(q[i:i + 1], np.concatenate([K, kn[i:i + 1]]), np.concatenate([V, vn[i:i + 1]]), len(K))
+        assert np.array_equal(out[i:i + 1], ref), fid
+    # file 4 shared every page with file 0: both appended into the partly filled last page, one of them a copy
+    assert sess.model.cow_copies == 1
+    Kg, _ = gather_file(sess.pool, sess.model.kv_pages(sess.h[0]), 24)
+    assert np.array_equal(Kg[:23], Ka) and np.array_equal(Kg[23], kn[3])
+    sess.model.audit()

@@ -161,3 +161,151 @@ def test_truncate_frees_pages_and_keeps_sharing():
     m.kv_truncate(a, 0)
     assert m.kv_pages(a) == [] and m.kv_len(a) == 0
     m.audit()
+
+
+# ---- extract / merge (section 4.2) ---------------------------------------------------------
+
+def test_extract_merge_hand_trace():
+    """Worked by hand, page size 4.  A destination page that is slots 0, 1, 2, ... of one existing
+    page is referenced; anything else is a fresh page filled token by token."""
+    m = KVFSModel(16, 4)
+    a = m.kv_open()
+    m.append([(a, 10)])                                   # pages 0,1,2 (slots: 4,4,2)
+    # tokens 0..3 = page 0 in order -> shared; (8, 9, 4) = page 2 slot 0, page 2 slot 1, page 1 slot 0 -> copied
+    b, moves = m.kv_extract(a, [0, 1, 2, 3, 8, 9, 4])
+    assert m.kv_pages(b) == [0, 3] and m.kv_len(b) == 7
+    assert moves == [(2, 0, 3, 0), (2, 1, 3, 1), (1, 0, 3, 2)]
+    assert m.refcount.tolist()[:5] == [2, 1, 1, 1, 0]
+    # a partly filled destination page can be shared too: tokens 8, 9 = slots 0, 1 of page 2
+    c, moves = m.kv_extract(a, [8, 9])
+    assert m.kv_pages(c) == [2] and moves == [] and m.refcount.tolist()[:5] == [2, 1, 2, 1, 0]
+    # ...and the next append to it copies the shared page first, as after an unaligned fork
+    cow, slots = m.append([(c, 1)])
+    assert cow == [(2, 4, 2)] and slots == [[(4, 2)]] and m.kv_pages(c) == [4]
+    # slots in the wrong order, or starting past slot 0, are copies
+    d, moves = m.kv_extract(a, [1, 0, 5, 6])
+    assert m.kv_pages(d) == [5] and moves == [(0, 1, 5, 0), (0, 0, 5, 1), (1, 1, 5, 2), (1, 2, 5, 3)]
+    # merge: a's aligned pages are referenced; the page where a ends and b starts is assembled
+    e, moves = m.kv_merge([a, b])                         # 10 + 7 tokens
+    assert m.kv_len(e) == 17 and m.kv_pages(e) == [0, 1, 6, 7, 8]
+    assert moves[:4] == [(2, 0, 6, 0), (2, 1, 6, 1), (0, 0, 6, 2), (0, 1, 6, 3)]       # a8 a9 b0 b1
+    assert moves[4:8] == [(0, 2, 7, 0), (0, 3, 7, 1), (3, 0, 7, 2), (3, 1, 7, 3)]      # b2 b3 b4 b5
+    assert moves[8:] == [(3, 2, 8, 0)]                                                 # b6
+    # empty results
+    z, moves = m.kv_extract(a, [])
+    assert m.kv_len(z) == 0 and m.kv_pages(z) == [] and moves == []
+    m.audit()
+
+
+def test_identity_extract_and_single_merge_equal_fork():
+    m = KVFSModel(64, 16)
+    a = m.kv_open()
+    m.append([(a, 100)])
+    f = m.kv_fork(a)
+    x, mv1 = m.kv_extract(a, range(100))
+    y, mv2 = m.kv_merge([a])
+    assert m.kv_pages(x) == m.kv_pages(y) == m.kv_pages(f) == m.kv_pages(a) and mv1 == mv2 == []
+    assert m.kv_len(x) == m.kv_len(y) == 100 and set(m.refcount[m.kv_pages(a)]) == {4}
+    # a prefix that ends inside a page: still no copy
+    z, mv = m.kv_extract(a, range(37))
+    assert m.kv_pages(z) == m.kv_pages(a)[:3] and mv == []
+    m.audit()
+
+
+def test_extract_errors_change_nothing():
+    m = KVFSModel(8, 4)
+    a = m.kv_open()
+    m.append([(a, 22)])                                   # 6 pages, 2 free
+    snap = (m.refcount.copy(), m.free_pages(), dict(m.handles))
+    with pytest.raises(KVError) as e:
+        m.kv_extract(a, [3, 2, 1, 0, 7, 6, 5, 4, 11, 10, 9, 8])    # three fresh pages, two free
+    assert e.value.code == ENOSPC
+    with pytest.raises(KVError) as e:
+        m.kv_extract(a, [0, 22])
+    assert e.value.code == EINVAL
+    with pytest.raises(KVError) as e:
+        m.kv_extract(a, [-1])
+    assert e.value.code == EINVAL
+    with pytest.raises(KVError) as e:
+        m.kv_merge([a, 99])
+    assert e.value.code == EBADF
+    assert np.array_equal(snap[0], m.refcount) and snap[1] == m.free_pages() and snap[2] == m.handles
+    b, _ = m.kv_extract(a, [3, 2, 1, 0, 7, 6, 5, 4])      # exactly the two free pages
+    assert m.free_pages() == 0 and m.kv_pages(b) == [6, 7]
+    m.audit()
+
+
+def test_random_ops_with_extract_merge_against_token_lists():
+    """Every file is shadowed by a plain Python list of unique token ids; each token's K row holds its
+    id.  After any mix of append / fork / extract / merge / truncate / remove, reading a file
+    through its pages must give exactly the shadow list: a wrong page decision, a missing copy or
+    a copy into a page someone else still reads shows up as a wrong id."""
+    from oracle.kvfs_model import PagePool
+    from oracle.attention import gather_file
+    rng = np.random.default_rng(11)
+    P = 4
+    m = KVFSModel(512, P, rng.permutation(512))
+    pool = PagePool(1, P, 1, np.float64)
+    shadow = {}
+    next_id = [1]
+
+    def append(h, n):
+        ids = np.arange(next_id[0], next_id[0] + n, dtype=np.float64).reshape(n, 1, 1)
+        cow, slots = m.append([(h, n)])
+        pool.apply(cow, slots, ids, -ids)
+        shadow[h] += [int(i) for i in ids.ravel()]
+        next_id[0] += n
+
+    for step in range(700):
+        r = rng.random()
+        live = list(shadow)
+        try:
+            if r < 0.1 or not live:
+                shadow[m.kv_open()] = []
+            elif r < 0.4:
+                append(live[rng.integers(len(live))], int(rng.integers(1, 12)))
+            elif r < 0.5:
+                src = live[rng.integers(len(live))]
+                shadow[m.kv_fork(src)] = list(shadow[src])
+            elif r < 0.7:
+                src = live[rng.integers(len(live))]
+                L = len(shadow[src])
+                kind = rng.integers(4)
+                if kind == 0:
+                    idx = rng.integers(0, max(L, 1), size=int(rng.integers(0, 20))) if L else []
+                elif kind == 1:
+                    idx = np.flatnonzero(rng.random(L) < 0.7)                     # pruning: keep a subset, in order
+                elif kind == 2:
+                    idx = np.r_[np.arange(min(L, 5)), np.arange(max(L - 9, min(L, 5)), L)]   # first tokens + recent window
+                else:
+                    idx = np.arange(L)[:int(rng.integers(0, L + 1))]
+                h, moves = m.kv_extract(src, [int(i) for i in idx])
+                pool.move_tokens(moves)
+                shadow[h] = [shadow[src][int(i)] for i in idx]
+            elif r < 0.8:
+                srcs = [live[i] for i in rng.integers(len(live), size=int(rng.integers(1, 4)))]
+                h, moves = m.kv_merge(srcs)
+                pool.move_tokens(moves)
+                shadow[h] = [t for s in srcs for t in shadow[s]]
+            elif r < 0.9:
+                h = live[rng.integers(len(live))]
+                n = int(rng.integers(0, len(shadow[h]) + 1))
+                m.kv_truncate(h, n)
+                del shadow[h][n:]
+            else:
+                h = live[rng.integers(len(live))]
+                m.kv_remove(h)
+                del shadow[h]
+        except KVError as e:
+            assert e.code == ENOSPC
+            h = max(shadow, key=lambda x: len(shadow[x]))
+            m.kv_remove(h)
+            del shadow[h]
+        if step % 20 == 0:
+            m.audit()
+            for h, toks in shadow.items():
+                K, V = gather_file(pool, m.kv_pages(h), len(toks))
+                assert K.ravel().tolist() == toks and V.ravel().tolist() == [-t for t in toks], (step, h)
+    for h in list(shadow):
+        m.kv_remove(h)
+    assert m.free_pages() == 512
