@@ -9,7 +9,8 @@ Default workload (the one the headline metric is quoted on): the "decode batch",
 8 KV heads, head dim 128, bf16, contexts uniform 512..4096, one new token each.  Successive steps
 rotate over several independent layer pools (as a real pred walks the model's layers, each with
 its own KV pages) so that the KV bytes of a step come from HBM and not from the 256 MB
-last-level cache.  `--workload fork|mixed|long` times the other configurations the same way.
+last-level cache.  `--workload fork|mixed|long|draft` times the other configurations the same way;
+`--workload prune` times kv_extract (context pruning, paper section 4.2) on the decode batch's files.
 
 Prints ONE JSON line: whole-path throughput in algorithmic KV TB/s, plus `roofline` for the
 dominant kernel (the attention launch, timed with HIP events on its stream inside the timed region) and `cpu_baseline`
@@ -108,12 +109,102 @@ def cpu_baseline(wl, budget_s, np, reset_lengths):
                       f"LIP; logical bytes, every reader counted), {dt:.1f} s wall", "lip_steps_per_s": steps * n_lips / dt}
 
 
+def bench_prune(args, np, torch, binding, synth, HipSession, dev):
+    """kv_extract over the 64 files of the decode batch in one call: every file keeps its first page
+    and each later token with probability 1/2, in order (a pruned context).  A step = the whole call
+    (planning on the host, move list through pinned staging, the copy kernel) + removing the new
+    files again.  Roofline: the copy kernel against HBM, bytes = kept tokens x K/V bytes, read + written."""
+    wl = synth.config2(slack_pages=8192)
+    shape, P = wl.shape, wl.shape.page_tokens
+    layers = args.layers or 4
+    steps = args.steps if args.steps is not None else 200
+    warmup = args.warmup if args.warmup is not None else 20
+    n_files = len(wl.batch_files)
+    sessions = []
+    for li in range(layers):
+        s = HipSession(shape, wl.n_pages, wl.free_order, dev, max_lips=n_files, max_tokens=max(wl.lengths.values()) + 64,
+                       max_entries=sum(wl.pages_after_batch().values()) + 64 * n_files)
+        s.setup(wl.setup_ops())
+        sessions.append(s)
+        print(f"[bench] layer pool {li + 1}/{layers} built", file=sys.stderr, flush=True)
+    rng = np.random.default_rng(1002)
+    lengths = [wl.lengths[f] for f in wl.batch_files]
+    idx_lists = [np.r_[np.arange(P), P + np.flatnonzero(rng.random(L - P) < 0.5)].astype(np.int64) for L in lengths]
+    off = np.zeros(n_files + 1, np.int64)
+    off[1:] = np.cumsum([len(i) for i in idx_lists])
+    flat = np.concatenate(idx_lists)
+    srcs = [[s.h[f] for f in wl.batch_files] for s in sessions]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    torch.cuda.synchronize()
+
+    def step(i):
+        s = sessions[i % layers]
+        for h in s.ctx.kv_extract_batch(srcs[i % layers], None, stream, flat=flat, off=off):
+            s.ctx.kv_remove(h)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    st0 = sessions[0].ctx.get_stats()
+    for s in sessions:
+        s.ctx.profile_enable(1 << binding.K_MOVE)
+    t0 = time.perf_counter()
+    for i in range(warmup, warmup + steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms, n = 0.0, 0
+    for s in sessions:
+        a, b = s.ctx.profile_read(binding.K_MOVE)
+        ms, n = ms + a, n + b
+        s.ctx.profile_enable(0)
+    st1 = sessions[0].ctx.get_stats()
+    moved = (st1["tokens_moved"] - st0["tokens_moved"]) / max(1, len([i for i in range(warmup, warmup + steps) if i % layers == 0]))
+    step_bytes = moved * (2 * kv_token_bytes(shape) + 16)          # rows read + written, move list read by staging and kernel
+    move_ms = ms / max(n, 1)
+    ach = step_bytes / (move_ms * 1e-3) / 1e9
+    for s in sessions:
+        s.close()
+    del sessions
+    torch.cuda.empty_cache()
+    cpu = None
+    cpu_s = args.cpu_seconds if args.cpu_seconds is not None else 8.0
+    if cpu_s > 0:
+        from oracle.driver import OracleSession
+        from threadpoolctl import threadpool_info
+        small = synth.config2(n_lips=4, slack_pages=512)
+        osess = OracleSession(small.shape, small.n_pages)
+        osess.setup(small.setup_ops())
+        t1 = time.perf_counter()
+        done, toks = 0, 0
+        while time.perf_counter() - t1 < cpu_s:
+            f = done % 4
+            h, moves = osess.model.kv_extract(osess.h[f], [int(i) for i in idx_lists[f]])
+            osess.pool.move_tokens(moves)
+            osess.model.kv_remove(h)
+            toks += len(moves)
+            done += 1
+        dt = time.perf_counter() - t1
+        cpu = {"value": toks * 2 * kv_token_bytes(shape) / dt / 1e12, "unit": "TB/s", "cores": int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1])),
+               "kind": "oracle", "sample": f"{done} kv_extract calls on the first 4 files of the same workload (page decisions + row copies), {dt:.1f} s wall"}
+    line = {"metric": "kv_extract moved KV TB/s (read + written)", "value": round(step_bytes / (wall / steps) / 1e12, 4), "unit": "TB/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(wall / steps * 1e3, 5), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "prune: kv_extract of the 64 decode-batch files (contexts U{512..4096}, 32Q/8KV, bf16) in one call, first page "
+                                   "kept (shared), later tokens kept with probability 1/2; new files removed after every step",
+                       "layer_pools_rotated": layers, "tokens_copied_per_step": int(moved), "algorithmic_bytes_per_step": int(step_bytes)},
+            "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_TBPS * 1e3, "unit": "GB/s", "frac": round(ach / (HBM_PEAK_TBPS * 1e3), 4),
+                         "traffic": read_traffic_note("move_prune_pmc.txt"), "kernel": "move_kernel", "avg_launch_us": round(move_ms * 1e3, 2), "launches": n},
+            "cpu_baseline": cpu}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune"], default="decode")
     ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
@@ -132,6 +223,8 @@ def main():
     binding.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
+    if args.workload == "prune":
+        return bench_prune(args, np, torch, binding, synth, HipSession, dev)
     # workload -> (generator, layer pools, steps, warmup, reset lengths after each step, cpu seconds, label)
     table = {"decode": (synth.config2, 4, 400, 40, False, 12.0, "decode batch: 64 LIPs, 32Q/8KV heads, head_dim 128, bf16, page 16, "
                         "contexts U{512..4096}, 1 new token each"),

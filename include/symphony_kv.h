@@ -80,6 +80,8 @@ typedef struct sym_stats {
                              descriptor build + staging, summed over calls, nanoseconds    */
   int64_t host_ns_pred;   /* host time of whole sym_pred_batch calls (planning + launches),
                              not counting waits for a staging buffer still in use by the GPU */
+  int64_t tokens_moved;      /* tokens copied by sym_kv_extract / sym_kv_merge              */
+  int64_t pages_referenced;  /* pages those calls shared with the source instead of copying */
 } sym_stats;
 
 /* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).
@@ -121,6 +123,29 @@ int     sym_kv_truncate(sym_ctx* ctx, int32_t n, const sym_kv* kv, const int64_t
  * pages as needed; a shared, partly filled last page is first copied (copy-on-write).    */
 int     sym_kv_append(sym_ctx* ctx, sym_kv kv, int32_t n, const void* k, const void* v,
                       void* stream);
+
+/* kv_extract, kv_merge (section 4.2: "create new files from existing ones by extracting
+ * specific token indices" / "merging existing files into one", e.g. to prune a context).
+ * Both make NEW anonymous files; the source files are not modified.
+ *   sym_kv_extract: for n_files files at once (one launch): token j of new file i is token
+ *     idx[idx_off[i] + j] of src[i], j < idx_off[i+1] - idx_off[i].  src, idx_off [n_files + 1],
+ *     idx: host; indices in any order, repeats allowed, each inside its source file (else
+ *     SYM_EINVAL); an empty range gives an empty file.  out [n_files]: host, receives the new
+ *     handles.  All files or none (SYM_ENOSPC, SYM_EBADF, SYM_EINVAL: nothing changed).
+ *   sym_kv_merge: returns the handle (or a negative status) of a new file holding the tokens of
+ *     files[0], then files[1], ... (m >= 0 files, host handles; a file may appear more than once).
+ * The stored K/V rows move bit for bit (no re-encoding of positions).  A destination page
+ * whose tokens are slots 0, 1, 2, ... of one existing page references that page (its count
+ * goes up, nothing is copied: an identity extract or a merge of one file is a fork); every
+ * other destination page is a fresh page (lowest rank first, in destination order) filled by
+ * the copy kernel on `stream`.  In a host-only context only the integer state is built.   */
+int     sym_kv_extract(sym_ctx* ctx, int32_t n_files, const sym_kv* src, const int64_t* idx_off,
+                       const int64_t* idx, sym_kv* out, void* stream);
+sym_kv  sym_kv_merge(sym_ctx* ctx, int32_t m, const sym_kv* files, void* stream);
+/* The copy list of the last sym_kv_extract / sym_kv_merge on this context, for inspection:
+ * (source, destination) pairs of token slots, each page * P + slot, in destination order.
+ * Returns the number of pairs; writes at most cap of them (out may be NULL).             */
+int64_t sym_last_moves(sym_ctx* ctx, int32_t* out, int64_t cap);
 
 /* ---- pred (section 4.1), batched (section 4.4) ------------------------------------- */
 /* One launch for n_lips pending pred calls.  LIP b appends n_tokens[b] >= 1 rows to file
@@ -191,7 +216,8 @@ int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, 
 #define SYM_K_PROLOGUE 0   /* descriptor copy + copy-on-write copies + KV append, one launch */
 #define SYM_K_ATTN     1   /* attention over the page tables: decode ranges + MFMA tiles     */
 #define SYM_K_MERGE    2   /* merge of the partial results of ranges that were cut           */
-#define SYM_K_COUNT    3
+#define SYM_K_MOVE     3   /* token copies of sym_kv_extract / sym_kv_merge                  */
+#define SYM_K_COUNT    4
 /* sym_profile_enable(mask): bit k of mask set = every launch of kernel id k is bracketed by
  * HIP events on the launch stream (at most 4096 launches are kept per kernel id, later ones
  * are not timed); mask 0 = off.

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
 
 SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
 SYM_F32, SYM_BF16 = 0, 1
-K_PROLOGUE, K_ATTN, K_MERGE = 0, 1, 2
+K_PROLOGUE, K_ATTN, K_MERGE, K_MOVE = 0, 1, 2, 3
 
 
 class SymConfig(C.Structure):
@@ -26,7 +26,7 @@ class SymConfig(C.Structure):
 class SymStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("pages_total", "pages_free", "pages_shared", "cow_copies", "pages_allocated",
                                          "tokens_appended", "pred_batches", "kernel_launches", "files", "handles",
-                                         "host_ns_plan", "host_ns_pred")]
+                                         "host_ns_plan", "host_ns_pred", "tokens_moved", "pages_referenced")]
 
 
 class SymError(RuntimeError):
@@ -51,6 +51,9 @@ _SIGNATURES = {
     "sym_kv_len": (C.c_int64, [C.c_void_p, C.c_int32]),
     "sym_kv_truncate": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I64P]),
     "sym_kv_append": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_kv_extract": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I64P, _I64P, _I32P, C.c_void_p]),
+    "sym_kv_merge": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, C.c_void_p]),
+    "sym_last_moves": (C.c_int64, [C.c_void_p, _I32P, C.c_int64]),
     "sym_pred_batch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_kv_pages": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, C.c_int64]),
@@ -176,6 +179,34 @@ class Context:
 
     def kv_append(self, kv, n, k, v, stream=None):
         self._chk(self.lib.sym_kv_append(self.h, kv, n, _ptr(k), _ptr(v), stream))
+
+    def kv_extract(self, src, idx, stream=None):
+        """One file: handle of the new file holding tokens idx of file src."""
+        return self.kv_extract_batch([src], [idx], stream)[0]
+
+    def kv_extract_batch(self, srcs, idx_lists, stream=None, flat=None, off=None):
+        """Several files in one call (one copy launch): list of new handles.  idx_lists: one index
+        list per file, or None with the flattened indices `flat` and their offsets `off` given."""
+        s_a, s_p = _i32(srcs)
+        if idx_lists is not None:
+            off = np.zeros(len(s_a) + 1, np.int64)
+            off[1:] = np.cumsum([len(i) for i in idx_lists])
+            flat = np.concatenate([np.asarray(i, np.int64).ravel() for i in idx_lists]) if len(idx_lists) else np.zeros(0, np.int64)
+        ix_a, ix_p = _i64(flat)
+        of_a, of_p = _i64(off)
+        out = np.empty(len(s_a), np.int32)
+        self._chk(self.lib.sym_kv_extract(self.h, len(s_a), s_p, of_p, ix_p, out.ctypes.data_as(_I32P), stream))
+        return [int(h) for h in out]
+
+    def kv_merge(self, files, stream=None):
+        f_a, f_p = _i32(files)
+        return self._chk(self.lib.sym_kv_merge(self.h, len(f_a), f_p, stream))
+
+    def last_moves(self):
+        n = self._chk(self.lib.sym_last_moves(self.h, None, 0))
+        out = np.empty((n, 2), np.int32)
+        self._chk(self.lib.sym_last_moves(self.h, out.ctypes.data_as(_I32P), n))
+        return out
 
     # ---- pred ----
     def pred_batch(self, kv, n_tokens, q, k_new, v_new, out, stream=None):

@@ -42,6 +42,7 @@ struct sym_ctx {
   std::string err;
   Kvfs* fs = nullptr;
   AppendPlan plan;
+  GatherPlan gplan;
   BatchDesc desc;
   std::vector<const int32_t*> tables;
   std::vector<int64_t> len_after;
@@ -55,7 +56,7 @@ struct sym_ctx {
   // profiling
   int prof_mask = 0;
   std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
-  int ev_used[SYM_K_COUNT] = {0, 0, 0};
+  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0};
   // counters
   int64_t pred_batches = 0, kernel_launches = 0;
   int64_t host_ns_plan = 0, host_ns_pred = 0;   // time inside sym_pred_batch: planning + descriptor; whole call
@@ -229,6 +230,26 @@ int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_o
   hipError_t e = hipEventRecord(c->stage_ev[si], st);
   if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
   c->stage_pending[si] = true;
+  return SYM_OK;
+}
+
+// Carries out the copies of c->gplan on the device: the move list goes through pinned staging
+// into the workspace (bulk copy by the prologue kernel), chunk by chunk, then the move kernel.
+int run_moves(sym_ctx* c, hipStream_t st) {
+  const std::vector<int32_t>& mv = c->gplan.moves;
+  const int64_t n = (int64_t)mv.size() / 2;
+  const int64_t cap = std::min<int64_t>((c->cfg.workspace_bytes / 4 - 64) / 2, 1 << 20);   // tokens per chunk
+  for (int64_t off = 0; off < n; off += cap) {
+    const int64_t cnt = std::min(cap, n - off);
+    int si, rc;
+    if ((rc = stage_acquire(c, 2 * cnt + 4, &si))) return rc;
+    std::memcpy(c->stage[si], mv.data() + 2 * off, (size_t)cnt * 8);
+    if ((rc = launch_prologue_staged(c, si, 2 * cnt, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
+    MoveArgs ma{(uint8_t*)c->cfg.pool, c->page_bytes, (const int32_t*)c->cfg.workspace, cnt, c->cfg.n_kv_heads};
+    Timed t(c, SYM_K_MOVE, st);
+    hipError_t e = launch_move(ma, st);
+    if (e != hipSuccess) return fail_hip(c, e, "move launch");
+  }
   return SYM_OK;
 }
 
@@ -432,6 +453,8 @@ int sym_get_stats(sym_ctx* c, sym_stats* s) {
   s->handles = c->fs->count_handles();
   s->host_ns_plan = c->host_ns_plan;
   s->host_ns_pred = c->host_ns_pred;
+  s->tokens_moved = c->fs->tokens_moved;
+  s->pages_referenced = c->fs->pages_referenced;
   return SYM_OK;
 }
 
@@ -477,6 +500,43 @@ int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v
   std::memcpy(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
   return launch_prologue_staged(c, si, 0, 0, (int)(c->plan.cow.size() / 3), (int64_t)c->plan.cow.size(), n, k, v, st);
+}
+
+int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t* idx_off, const int64_t* idx, sym_kv* out,
+                   void* stream) {
+  if (!c || n_files < 0) return SYM_EINVAL;
+  if (n_files == 0) return SYM_OK;
+  if (!src || !idx_off || !out || (idx_off[n_files] > 0 && !idx)) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int64_t none = 0;
+  if (!idx) idx = &none;
+  int64_t need = 0;                                       // all files or none: plan them all, count the fresh pages
+  c->gplan.reset();
+  for (int32_t i = 0; i < n_files; ++i) {
+    const int64_t k = c->fs->gather_need(1, src + i, idx_off + i, idx, &c->gplan, &c->err);
+    if (k < 0) return (int)k;
+    need += k;
+  }
+  if (need > c->fs->free_pages()) return fail(c, SYM_ENOSPC, "page pool exhausted");
+  for (int32_t i = 0; i < n_files; ++i) out[i] = c->fs->gather_commit(&c->gplan, i);
+  return c->cfg.device < 0 ? SYM_OK : run_moves(c, (hipStream_t)stream);
+}
+
+sym_kv sym_kv_merge(sym_ctx* c, int32_t m, const sym_kv* files, void* stream) {
+  if (!c || m < 0 || (m > 0 && !files)) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const sym_kv h = c->fs->gather(m, files, nullptr, nullptr, &c->gplan, &c->err);
+  if (h < 0 || c->cfg.device < 0) return h;
+  const int rc = run_moves(c, (hipStream_t)stream);
+  return rc ? rc : h;
+}
+
+int64_t sym_last_moves(sym_ctx* c, int32_t* out, int64_t cap) {
+  if (!c || cap < 0) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int64_t n = (int64_t)c->gplan.moves.size() / 2;
+  if (out) std::memcpy(out, c->gplan.moves.data(), (size_t)std::min(n, cap) * 8);
+  return n;
 }
 
 int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q,

@@ -1016,6 +1016,22 @@ __global__ void gather_kernel(GatherArgs a, uint8_t* k_out, uint8_t* v_out) {
   *(uint4*)dst = *(const uint4*)src;
 }
 
+// extract / merge (paper section 4.2): K and V rows of whole tokens copied from one slot of the
+// pool to another, bit for bit.  A token is Hkv * 4 pieces of 128 bytes (kv head, K/V, row half);
+// a thread moves 16 bytes, eight neighbouring threads one piece, so every access is a full
+// 128-byte line.  Sources are pages of existing files, destinations fresh pages: disjoint.
+__global__ __launch_bounds__(256) void move_kernel(MoveArgs a) {
+  const int per_tok = a.Hkv * 32;                                   // 16-byte chunks per token
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (tid >= a.n_tokens * per_tok) return;
+  const int64_t t = tid / per_tok;
+  const int x = (int)(tid % per_tok);
+  const int s = a.moves[2 * t], d = a.moves[2 * t + 1];
+  const int64_t in_page = (int64_t)(x >> 3) * (kP * kHalfBytes) + (x & 7) * 16;
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)(a.pool + (int64_t)(s / kP) * a.page_bytes + in_page + (s % kP) * kHalfBytes));
+  *(u32x4_t*)(a.pool + (int64_t)(d / kP) * a.page_bytes + in_page + (d % kP) * kHalfBytes) = v;
+}
+
 // ---------------------------------------------------------------------------------------
 // Calibration: streaming read (reduced so that the loads are live) and plain copy.
 // ---------------------------------------------------------------------------------------
@@ -1113,6 +1129,14 @@ hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStrea
   if (a.n_tokens <= 0) return hipSuccess;
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
   hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, (uint8_t*)k_out, (uint8_t*)v_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_move(const MoveArgs& a, hipStream_t st) {
+  if (a.n_tokens <= 0) return hipSuccess;
+  const int64_t blocks = (a.n_tokens * a.Hkv * 32 + 255) / 256;
+  if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(move_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

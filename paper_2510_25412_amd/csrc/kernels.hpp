@@ -70,11 +70,20 @@ struct GatherArgs {
   int32_t n_tokens, Hkv;
 };
 
+struct MoveArgs {
+  uint8_t* pool;
+  int64_t page_bytes;
+  const int32_t* moves;         // device [n_tokens][2]: source, destination token slot (page * P + slot)
+  int64_t n_tokens;
+  int32_t Hkv;
+};
+
 // decode_mode: 0 = VALU decode kernel, 1 = decode ranges on the matrix cores (bf16 storage only)
 hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);
+hipError_t launch_move(const MoveArgs& a, hipStream_t st);
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st);
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st);
 

@@ -216,6 +216,89 @@ int Kvfs::append(int32_t n, const int32_t* handles, const int32_t* n_tokens, App
   return SYM_OK;
 }
 
+int64_t Kvfs::gather_need(int32_t n_seg, const int32_t* seg_handle, const int64_t* seg_off, const int64_t* idx, GatherPlan* plan,
+                          std::string* err) {
+  std::vector<int32_t>& src = plan->src;
+  std::vector<int32_t>& shared = plan->shared;
+  const size_t s0 = src.size(), h0 = shared.size();
+  plan->bounds.push_back((int64_t)s0);
+  plan->bounds.push_back((int64_t)h0);
+  for (int32_t s = 0; s < n_seg; ++s) {
+    const KvFile* f = file_of(seg_handle[s]);
+    if (!f) {
+      if (err) *err = "extract/merge: bad file handle";
+      return SYM_EBADF;
+    }
+    const int64_t lo = idx ? seg_off[s] : 0, hi = idx ? seg_off[s + 1] : f->len;
+    if (hi < lo || (int64_t)(src.size() - s0) + (hi - lo) > (int64_t)0x7fffffff) {
+      if (err) *err = "extract/merge: bad segment bounds or result too long";
+      return SYM_EINVAL;
+    }
+    for (int64_t j = lo; j < hi; ++j) {
+      const int64_t i = idx ? idx[j] : j;
+      if (i < 0 || i >= f->len) {
+        if (err) *err = "extract: token index outside the file";
+        return SYM_EINVAL;
+      }
+      src.push_back(f->pages[i / P_] * P_ + (int32_t)(i % P_));
+    }
+  }
+  const int64_t n = (int64_t)(src.size() - s0), np = (n + P_ - 1) / P_;
+  shared.resize(h0 + (size_t)np, -1);
+  int64_t need = 0;
+  for (int64_t d = 0; d < np; ++d) {
+    const int64_t base = (int64_t)s0 + d * P_, c = std::min<int64_t>(P_, n - d * P_);
+    const int32_t first = src[base];
+    bool same = first % P_ == 0;
+    for (int64_t k = 1; k < c && same; ++k) same = src[base + k] == first + (int32_t)k;
+    if (same) shared[h0 + d] = first / P_;
+    else ++need;
+  }
+  return need;
+}
+
+int32_t Kvfs::gather_commit(GatherPlan* plan, int32_t k) {
+  const bool last = (size_t)(2 * k + 2) >= plan->bounds.size();
+  const int64_t s0 = plan->bounds[2 * k], h0 = plan->bounds[2 * k + 1];
+  const int64_t n = (last ? (int64_t)plan->src.size() : plan->bounds[2 * k + 2]) - s0;
+  const int64_t np = (last ? (int64_t)plan->shared.size() : plan->bounds[2 * k + 3]) - h0;
+  const int32_t* src = plan->src.data() + s0;
+  const int32_t* shared = plan->shared.data() + h0;
+  const int32_t id = new_file();
+  files_[id].pages.reserve((size_t)np);
+  for (int64_t d = 0; d < np; ++d) {
+    if (shared[d] >= 0) {
+      ++refcount_[shared[d]];
+      files_[id].pages.push_back(shared[d]);
+      ++plan->pages_shared;
+      ++pages_referenced;
+    } else {
+      const int32_t dst = alloc_page();
+      files_[id].pages.push_back(dst);
+      const int64_t base = d * P_, c = std::min<int64_t>(P_, n - base);
+      for (int64_t t = 0; t < c; ++t) {
+        plan->moves.push_back(src[base + t]);
+        plan->moves.push_back(dst * P_ + (int32_t)t);
+      }
+      tokens_moved += c;
+    }
+  }
+  files_[id].len = n;
+  return new_handle(id);
+}
+
+int32_t Kvfs::gather(int32_t n_seg, const int32_t* seg_handle, const int64_t* seg_off, const int64_t* idx, GatherPlan* plan,
+                     std::string* err) {
+  plan->reset();
+  const int64_t need = gather_need(n_seg, seg_handle, seg_off, idx, plan, err);
+  if (need < 0) return (int32_t)need;
+  if (need > free_pages()) {
+    if (err) *err = "page pool exhausted";
+    return SYM_ENOSPC;
+  }
+  return gather_commit(plan, 0);
+}
+
 int64_t Kvfs::count_shared() const {
   int64_t c = 0;
   for (uint32_t r : refcount_) c += r > 1;

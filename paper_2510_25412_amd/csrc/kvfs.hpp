@@ -27,6 +27,17 @@ struct AppendPlan {
   void clear() { cow.clear(); slots.clear(); }
 };
 
+// Result of building a file out of tokens of existing files (extract / merge).
+struct GatherPlan {
+  std::vector<int32_t> moves;     // (source, destination) pairs of token slots (page * P + slot) to copy
+  int64_t pages_shared = 0;       // destination pages that reference an existing page instead
+  // scratch of the planning pass, one stretch per planned file
+  std::vector<int32_t> src;       // source slot of every destination token
+  std::vector<int32_t> shared;    // per destination page, the page it references or -1
+  std::vector<int64_t> bounds;    // per planned file: where its stretch of src / of shared begins
+  void reset() { moves.clear(); src.clear(); shared.clear(); bounds.clear(); pages_shared = 0; }
+};
+
 class Kvfs {
  public:
   Kvfs(int64_t n_pages, int32_t page_tokens, const int32_t* free_order);
@@ -44,12 +55,27 @@ class Kvfs {
   // Two-phase: validate + count, then commit.  On error nothing changes.
   int append(int32_t n, const int32_t* handles, const int32_t* n_tokens, AppendPlan* plan, std::string* err);
 
+  // extract / merge (paper section 4.2): a new anonymous file of the tokens of n_seg segments, one
+  // after the other.  Segment s takes from file seg_handle[s]: with idx, the tokens
+  // idx[seg_off[s]] .. idx[seg_off[s+1] - 1] (any order, repeats allowed); without, the whole
+  // file in order.  A destination page that is slots 0, 1, 2, ... of one existing page
+  // references that page; every other one is a fresh page and its tokens go into plan->moves.
+  // gather_need validates one file and adds it to the plan's scratch; returns the fresh pages it
+  // needs or a negative status.  gather_commit builds planned file k from that scratch (the
+  // caller has checked that the pages are free), appends its copies to plan->moves and returns
+  // the handle.  gather = one file, both steps, with the free-page check (on error nothing changed).
+  int64_t gather_need(int32_t n_seg, const int32_t* seg_handle, const int64_t* seg_off, const int64_t* idx, GatherPlan* plan,
+                      std::string* err);
+  int32_t gather_commit(GatherPlan* plan, int32_t k);
+  int32_t gather(int32_t n_seg, const int32_t* seg_handle, const int64_t* seg_off, const int64_t* idx, GatherPlan* plan,
+                 std::string* err);
+
   int32_t refcount(int32_t page) const { return page < 0 || page >= n_pages_ ? -1 : (int32_t)refcount_[page]; }
   int64_t free_pages() const { return (int64_t)free_ranks_.size(); }
   int64_t n_pages() const { return n_pages_; }
   int32_t page_tokens() const { return P_; }
 
-  int64_t cow_copies = 0, pages_allocated = 0, tokens_appended = 0;
+  int64_t cow_copies = 0, pages_allocated = 0, tokens_appended = 0, tokens_moved = 0, pages_referenced = 0;
   int64_t count_shared() const;
   int64_t count_files() const;
   int64_t count_handles() const;

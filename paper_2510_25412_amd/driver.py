@@ -51,6 +51,10 @@ class HipSession:
                 torch.cuda.current_stream(self.device).synchronize()   # k, v are freed on return
             elif op[0] == "remove":
                 self.ctx.kv_remove(self.h.pop(op[1]))
+            elif op[0] == "extract":                      # ("extract", new fid, source fid, token indices)
+                self.h[op[1]] = self.ctx.kv_extract(self.h[op[2]], op[3], self.stream)
+            elif op[0] == "merge":                        # ("merge", new fid, [source fids])
+                self.h[op[1]] = self.ctx.kv_merge([self.h[f] for f in op[2]], self.stream)
             else:
                 raise ValueError(op[0])
 

@@ -205,8 +205,9 @@ def config5(n_lips=16, lo=32768, hi=131072, n_pages=3_000_000):
 
 
 def custom(name, shape, files, batch, n_pages, seed, free_order=None):
-    """Free-form workload for edge cases.  files: list of ("new", length) or
-    ("fork", parent_index, extra_tokens); batch: list of (file_index, n_tokens)."""
+    """Free-form workload for edge cases.  files: list of ("new", length),
+    ("fork", parent_index, extra_tokens), ("extract", source_index, token indices) or
+    ("merge", [source indices]); batch: list of (file_index, n_tokens)."""
     st = _Streams(seed)
     wl = Workload(name, shape, n_pages, free_order)
     for fid, spec in enumerate(files):
@@ -215,6 +216,13 @@ def custom(name, shape, files, batch, n_pages, seed, free_order=None):
             if spec[1] > 0:
                 wl.program.append(("append", fid, int(spec[1]), st.child(), st.child()))
             wl.lengths[fid] = int(spec[1])
+        elif spec[0] == "extract":
+            idx = [int(i) for i in spec[2]]
+            wl.program.append(("extract", fid, spec[1], idx))
+            wl.lengths[fid] = len(idx)
+        elif spec[0] == "merge":
+            wl.program.append(("merge", fid, list(spec[1])))
+            wl.lengths[fid] = sum(wl.lengths[p] for p in spec[1])
         else:
             _, parent, extra = spec
             wl.program.append(("fork", fid, parent))

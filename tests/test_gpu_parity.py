@@ -327,3 +327,55 @@ def test_draft_verify_rows(Hq, Hkv, waves, monkeypatch):
     sess2.close()
     check_outputs(got, plain, tol=1e-3)
     print(f"draft rows {Hq}/{Hkv} waves={waves}: worst scaled error {worst:.2e}")
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,dtype", [(32, 8, 128, synth.BF16), (8, 8, 64, synth.F32), (4, 1, 128, synth.BF16)])
+def test_extract_merge_bytes_state_and_pred(Hq, Hkv, D, dtype):
+    """kv_extract / kv_merge (section 4.2) on the GPU: page tables and reference counts equal the
+    oracle model's bit for bit, every file reads back (kv_read) exactly the oracle's rows, and a
+    pred over the new files (and their sources) matches the oracle.  Extracts: pruned subset, first
+    page + recent window (unaligned shift), reversed order with repeats, identity, empty; merges:
+    unaligned concatenation, a file with itself, of extracts."""
+    from oracle.attention import gather_file
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    rng = np.random.default_rng(31)
+    keep = np.flatnonzero(rng.random(1000) < 0.6)
+    files = [("new", 1000), ("new", 77), ("new", 160),
+             ("extract", 0, keep),                                            # 3 pruned context
+             ("extract", 0, np.r_[np.arange(16), np.arange(700, 1000)]),      # 4 first page + recent window
+             ("extract", 1, np.r_[np.arange(76, -1, -1), [5, 5, 5]]),         # 5 reversed, repeats
+             ("extract", 2, np.arange(160)),                                  # 6 identity: all pages shared
+             ("extract", 2, []),                                              # 7 empty
+             ("merge", [1, 2]),                                               # 8 unaligned: 77 + 160
+             ("merge", [2, 2, 1]),                                            # 9 aligned start, itself twice
+             ("merge", [4, 7, 5]),                                            # 10 of extracts, with an empty one
+             ("fork", 6, 3)]                                                  # 11 fork of an extract + private tokens
+    batch = [(3, 1), (4, 2), (5, 1), (6, 1), (7, 3), (8, 1), (9, 1), (10, 5), (11, 1), (0, 1), (2, 1)]
+    wl = synth.custom(f"xm_{Hq}_{Hkv}_{dtype}", shape, files, batch, 512, seed=1234 + Hq)
+    print(f"[case] {wl.name}", flush=True)
+    drv = _hip()
+    sess = drv.HipSession(shape, wl.n_pages, poison=True)
+    sess.setup(wl.setup_ops())
+    osess = OracleSession(shape, wl.n_pages)
+    osess.setup(wl.setup_ops())
+    check_state(wl, sess, osess)
+    tdt = torch.float32 if dtype == synth.F32 else torch.bfloat16
+    for fid in range(len(files)):
+        n = osess.model.kv_len(osess.h[fid])
+        assert sess.ctx.kv_len(sess.h[fid]) == n
+        if n == 0:
+            continue
+        k = torch.empty((n, Hkv, D), dtype=tdt, device="cuda")
+        v = torch.empty_like(k)
+        sess.ctx.kv_read(sess.h[fid], 0, n, k, v, sess.stream)
+        torch.cuda.synchronize()
+        Ko, Vo = gather_file(osess.pool, osess.model.kv_pages(osess.h[fid]), n)
+        assert np.array_equal(k.float().cpu().numpy(), Ko) and np.array_equal(v.float().cpu().numpy(), Vo), fid
+    st = sess.ctx.get_stats()
+    assert st["tokens_moved"] > 0 and st["pages_referenced"] >= 10 + 1 + 10      # identity extract, first page, merge 9's first file
+    b = wl.batch()
+    got = sess.pred(sess.upload_batch(b)).cpu().numpy()
+    ref = osess.pred(b, dtype=np.float64)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()

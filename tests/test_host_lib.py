@@ -90,6 +90,32 @@ def test_random_ops_match_oracle_model_bit_exact():
             n = int(rng.integers(0, m.kv_len(h) + 1))
             m.kv_truncate(h, n)
             c.kv_truncate([h], [n])
+        elif r < 0.52:                       # extract / merge: a new file out of existing tokens
+            src = int(live[rng.integers(len(live))])
+            L = m.kv_len(src)
+            kind = int(rng.integers(5))
+            try:
+                if kind == 0:
+                    srcs = [int(live[i]) for i in rng.integers(len(live), size=int(rng.integers(0, 4)))]
+                    a, moves = m.kv_merge(srcs)
+                    b = None
+                else:
+                    idx = {1: np.arange(L)[:int(rng.integers(0, L + 1))],                               # a prefix: all shared
+                           2: np.flatnonzero(rng.random(L) < 0.8),                                      # pruned, in order
+                           3: np.r_[np.arange(min(L, 16)), np.arange(max(L - 40, min(L, 16)), L)],      # first page + recent window
+                           4: rng.integers(0, max(L, 1), size=int(rng.integers(0, 50))) if L else np.zeros(0, np.int64)}[kind]
+                    a, moves = m.kv_extract(src, [int(i) for i in idx])
+                    b = c.kv_extract(src, idx)
+            except KVError as e:
+                with pytest.raises(binding.SymError) as ce:
+                    c.kv_merge(srcs) if kind == 0 else c.kv_extract(src, idx)
+                assert ce.value.code == e.code == binding.SYM_ENOSPC
+            else:
+                if b is None:
+                    b = c.kv_merge(srcs)
+                assert a == b
+                assert c.last_moves().tolist() == [[sp * 16 + ss, dp * 16 + ds] for sp, ss, dp, ds in moves]
+                live.append(a)
         elif r < 0.85:
             k = min(len(live), int(rng.integers(1, 6)))
             hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
@@ -116,6 +142,47 @@ def test_random_ops_match_oracle_model_bit_exact():
     st = c.get_stats()
     assert st["cow_copies"] == m.cow_copies and st["pages_free"] == m.free_pages()
     assert st["pages_shared"] == int((m.refcount > 1).sum())
+    assert st["tokens_moved"] > 0 and st["pages_referenced"] > 0
+
+
+def test_extract_merge_hand_trace_library():
+    """The hand-worked page-size-16 twin of the model's extract / merge trace, on the library."""
+    c = host_ctx(16)
+    a = c.kv_open()
+    c.plan_append([a], [40])                              # pages 0,1,2 (16, 16, 8 tokens)
+    b = c.kv_extract(a, list(range(16)) + [32, 33, 16])   # page 0 referenced; (32, 33, 16) assembled in page 3
+    assert c.kv_pages(b) == [0, 3] and c.kv_len(b) == 19
+    assert c.last_moves().tolist() == [[32, 48], [33, 49], [16, 50]]
+    assert [c.page_refcount(p) for p in range(5)] == [2, 1, 1, 1, 0]
+    d = c.kv_extract(a, [32, 33])                         # slots 0, 1 of page 2: a shared, partly used page
+    assert c.kv_pages(d) == [2] and len(c.last_moves()) == 0 and c.page_refcount(2) == 2
+    cow, slots = c.plan_append([d], [1])                  # the next append copies it first
+    assert cow == [(2, 4, 2)] and slots.tolist() == [4 * 16 + 2]
+    e = c.kv_merge([a, b])                                # 40 + 19 tokens: pages 0, 1 referenced, the rest assembled
+    assert c.kv_len(e) == 59 and c.kv_pages(e) == [0, 1, 5, 6]
+    mv = c.last_moves().tolist()
+    assert mv[:8] == [[32 + k, 80 + k] for k in range(8)] and mv[8:16] == [[k, 88 + k] for k in range(8)]
+    assert mv[16:24] == [[8 + k, 96 + k] for k in range(8)] and mv[24:] == [[48, 104], [49, 105], [50, 106]]
+    z = c.kv_extract(a, [])
+    assert c.kv_len(z) == 0 and c.kv_pages(z) == []
+    assert c.kv_merge([]) >= 0
+    # several files in one call: all or none, same result as one call each
+    snap = ([c.page_refcount(p) for p in range(16)], c.free_pages())
+    with pytest.raises(binding.SymError) as err:
+        c.kv_extract_batch([a, b, a], [[1, 2], [18, 0], [0, 40]])
+    assert err.value.code == binding.SYM_EINVAL and snap == ([c.page_refcount(p) for p in range(16)], c.free_pages())
+    x, y = c.kv_extract_batch([a, b], [[1, 2], list(range(19))])
+    assert c.kv_pages(x) == [7] and c.kv_pages(y) == [0, 3] and c.last_moves().tolist() == [[1, 112], [2, 113]]
+    c.kv_remove(x)
+    c.kv_remove(y)
+    snap = ([c.page_refcount(p) for p in range(16)], c.free_pages())
+    for call, code in ((lambda: c.kv_extract(a, [40]), binding.SYM_EINVAL), (lambda: c.kv_extract(a, [-1]), binding.SYM_EINVAL),
+                       (lambda: c.kv_extract(77, [0]), binding.SYM_EBADF), (lambda: c.kv_merge([a, 77]), binding.SYM_EBADF),
+                       (lambda: c.kv_extract(a, np.tile(np.arange(39, -1, -1), 4)), binding.SYM_ENOSPC)):   # 10 fresh pages, 9 free
+        with pytest.raises(binding.SymError) as err:
+            call()
+        assert err.value.code == code
+        assert snap == ([c.page_refcount(p) for p in range(16)], c.free_pages())
 
 
 def test_error_codes_and_all_or_nothing():
