@@ -159,6 +159,14 @@ def bench_prune(args, np, torch, binding, synth, HipSession, dev):
         ms, n = ms + a, n + b
         s.ctx.profile_enable(0)
     st1 = sessions[0].ctx.get_stats()
+    if not args.no_calib:
+        # one plain copy of known size (1 GiB read + 1 GiB written): the reference dispatch that
+        # scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command
+        buf = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        buf.random_(0, 255)
+        binding.calib_copy(buf[1 << 30:], buf, 1 << 30, stream)
+        torch.cuda.synchronize()
+        del buf
     moved = (st1["tokens_moved"] - st0["tokens_moved"]) / max(1, len([i for i in range(warmup, warmup + steps) if i % layers == 0]))
     step_bytes = moved * (2 * kv_token_bytes(shape) + 16)          # rows read + written, move list read by staging and kernel
     move_ms = ms / max(n, 1)
