@@ -17,7 +17,16 @@ step by step so that the library's integer state can be compared bit for bit:
   move unchanged.  A destination page whose tokens are slots 0, 1, 2, ... of ONE existing page,
   in that order, is not copied: the new file references that page (count + 1), like a fork;
   every other destination page is a fresh page (lowest rank first, in destination order) that
-  receives copies of its tokens' rows.  Either the whole new file fits or nothing changes.
+  receives copies of its tokens' rows.  Either the whole new file fits or nothing changes;
+* `kv_offload` / `kv_restore` (section 4.3: the KV cache of a thread that waits for I/O moves to
+  CPU memory and comes back when the wait ends).  A waiting file cannot be read or written
+  (EBUSY) but can be removed.  A page leaves the GPU when EVERY reference to it belongs to a
+  waiting file: it is copied to the lowest free host slot, every referencing table entry becomes
+  -(slot + 1), and the page returns to the free set.  A page with a reference from a file that
+  does not wait stays where it is.  Restoring a file brings each of its host slots back into a
+  fresh page (lowest rank first, in table order) and rewrites EVERY entry that referenced the
+  slot, also those of files that still wait: a page is on the host only while all its readers
+  wait.  Either all files of a restore call fit or nothing changes.
 """
 import heapq
 
@@ -33,13 +42,14 @@ class KVError(Exception):
 
 
 class _File:
-    __slots__ = ("length", "pages", "name", "handles")
+    __slots__ = ("length", "pages", "name", "handles", "waiting")
 
     def __init__(self, name):
         self.length = 0
-        self.pages = []
+        self.pages = []                # page ids; -(slot + 1) for a page that is on the host
         self.name = name
         self.handles = set()
+        self.waiting = False
 
 
 class KVFSModel:
@@ -56,12 +66,18 @@ class KVFSModel:
         self.handles = {}          # handle -> _File
         self.names = {}            # name -> _File
         self.cow_copies = 0
+        self.waiters = {}          # resident page -> [(file, index)] entries of waiting files that reference it
+        self.host_refs = {}        # host slot -> [(file, index)] entries that reference it
+        self.free_slots = []       # min-heap of host slots freed so far
+        self.n_slots = 0           # host slots ever created
 
     # ---- helpers -------------------------------------------------------------
-    def _file(self, h):
+    def _file(self, h, usable=False):
         f = self.handles.get(h)
         if f is None:
             raise KVError(EBADF, f"bad handle {h}")
+        if usable and f.waiting:
+            raise KVError(EBUSY, f"file of handle {h} is offloaded")
         return f
 
     def _new_handle(self, f):
@@ -77,13 +93,28 @@ class KVFSModel:
         self.refcount[p] = 1
         return p
 
-    def _release_pages(self, f):
-        for p in f.pages:
-            self.refcount[p] -= 1
-            if self.refcount[p] == 0:
-                heapq.heappush(self.free_ranks, int(self.rank[p]))
-        f.pages = []
-        f.length = 0
+    def _drop_ref(self, p):
+        self.refcount[p] -= 1
+        if self.refcount[p] == 0:
+            heapq.heappush(self.free_ranks, int(self.rank[p]))
+
+    def _release_pages(self, f, keep=0):
+        """Drop the file's table entries from index `keep` on."""
+        for i in range(keep, len(f.pages)):
+            e = f.pages[i]
+            if e >= 0:
+                if f.waiting:
+                    self.waiters[e].remove((f, i))
+                    if not self.waiters[e]:
+                        del self.waiters[e]
+                self._drop_ref(e)
+            else:                                          # on the host: the slot is free once nobody refers to it
+                refs = self.host_refs[-e - 1]
+                refs.remove((f, i))
+                if not refs:
+                    del self.host_refs[-e - 1]
+                    heapq.heappush(self.free_slots, -e - 1)
+        del f.pages[keep:]
 
     # ---- file API (names follow the paper's Fig. 1 and section 4.2) ------------
     def kv_open(self, name=None):
@@ -95,7 +126,7 @@ class KVFSModel:
         return self._new_handle(f)
 
     def kv_fork(self, h):
-        parent = self._file(h)
+        parent = self._file(h, usable=True)
         f = _File(None)
         f.pages = list(parent.pages)
         f.length = parent.length
@@ -106,6 +137,8 @@ class KVFSModel:
     def kv_remove(self, h):
         f = self._file(h)
         self._release_pages(f)
+        f.length = 0
+        f.waiting = False
         for hh in list(f.handles):
             del self.handles[hh]
         f.handles.clear()
@@ -118,6 +151,8 @@ class KVFSModel:
         f.handles.discard(h)
         if f.name is None and not f.handles:
             self._release_pages(f)                        # anonymous file nobody can reach
+            f.length = 0
+            f.waiting = False
 
     def kv_len(self, h):
         return self._file(h).length
@@ -127,15 +162,10 @@ class KVFSModel:
         draft tokens with a multi-token pred rolls the rejected ones back this way).  Pages no
         longer needed lose one reference; a shared last page stays shared until the next append
         copies it."""
-        f = self._file(h)
+        f = self._file(h, usable=True)
         if new_len < 0 or new_len > f.length:
             raise KVError(EINVAL, "truncate beyond the file")
-        keep = -(-new_len // self.P)
-        for p in f.pages[keep:]:
-            self.refcount[p] -= 1
-            if self.refcount[p] == 0:
-                heapq.heappush(self.free_ranks, int(self.rank[p]))
-        del f.pages[keep:]
+        self._release_pages(f, keep=-(-new_len // self.P))
         f.length = new_len
 
     def kv_pages(self, h):
@@ -151,7 +181,7 @@ class KVFSModel:
         pending = {}                                      # page -> refcount change so far
         need = 0
         for h, n in items:
-            f = self._file(h)
+            f = self._file(h, usable=True)
             L = f.length
             if L % self.P != 0:
                 last = f.pages[-1]
@@ -168,7 +198,7 @@ class KVFSModel:
         for h, n in items:
             if n < 1:
                 raise KVError(EINVAL, "n_tokens must be >= 1")
-            f = self._file(h)
+            f = self._file(h, usable=True)
             if any(f is g for g in files):
                 raise KVError(EBUSY, "same file twice in a batch")
             files.append(f)
@@ -201,7 +231,7 @@ class KVFSModel:
         P = self.P
         src = []                                          # (page, slot) of every destination token
         for h, i in refs:
-            f = self._file(h)
+            f = self._file(h, usable=True)
             if i < 0 or i >= f.length:
                 raise KVError(EINVAL, f"token index {i} outside the file")
             src.append((f.pages[i // P], i % P))
@@ -233,18 +263,93 @@ class KVFSModel:
 
     def kv_merge(self, handles):
         """New file = the files' tokens one file after the other."""
-        return self.kv_gather([(h, i) for h in handles for i in range(self._file(h).length)])
+        return self.kv_gather([(h, i) for h in handles for i in range(self._file(h, usable=True).length)])
+
+    # ---- offload / restore (section 4.3) -------------------------------------------
+    def _files_of(self, handles, waiting):
+        files = []
+        for h in handles:
+            f = self._file(h)
+            if f.waiting != waiting or any(f is g for g in files):
+                raise KVError(EBUSY, "file already offloaded" if f.waiting else "file is not offloaded (or named twice)")
+            files.append(f)
+        return files
+
+    def kv_offload(self, handles):
+        """The files start to wait.  Returns the evictions [(page, host slot)] in the order they
+        happen: the page's bytes must be copied to the slot before the page is reused."""
+        out = []
+        for f in self._files_of(handles, waiting=False):
+            f.waiting = True
+            for i, p in enumerate(f.pages):
+                self.waiters.setdefault(p, []).append((f, i))
+                if len(self.waiters[p]) == self.refcount[p]:       # every reader waits: the page leaves
+                    if self.free_slots:
+                        s = heapq.heappop(self.free_slots)
+                    else:
+                        s, self.n_slots = self.n_slots, self.n_slots + 1
+                    refs = self.waiters.pop(p)
+                    for g, j in refs:
+                        g.pages[j] = -(s + 1)
+                    self.host_refs[s] = refs
+                    self.refcount[p] = 0
+                    heapq.heappush(self.free_ranks, int(self.rank[p]))
+                    out.append((p, s))
+        return out
+
+    def kv_restore(self, handles):
+        """The files' waits end.  Returns the loads [(host slot, page)]: the slot's bytes go into
+        the page.  Needs one free page per distinct host slot the files reference, else ENOSPC."""
+        files = self._files_of(handles, waiting=True)
+        need = {-e - 1 for f in files for e in f.pages if e < 0}
+        if len(need) > len(self.free_ranks):
+            raise KVError(ENOSPC, "page pool exhausted")
+        out = []
+        for f in files:
+            f.waiting = False
+            for i in range(len(f.pages)):
+                e = f.pages[i]
+                if e >= 0:                                     # never left, or already back through another entry
+                    if (f, i) in self.waiters.get(e, ()):
+                        self.waiters[e].remove((f, i))
+                        if not self.waiters[e]:
+                            del self.waiters[e]
+                    continue
+                s = -e - 1
+                q = self._alloc()
+                refs = self.host_refs.pop(s)
+                for g, j in refs:
+                    g.pages[j] = q
+                self.refcount[q] = len(refs)
+                still = [(g, j) for g, j in refs if g.waiting]
+                if still:
+                    self.waiters[q] = still
+                heapq.heappush(self.free_slots, s)
+                out.append((s, q))
+        return out
+
+    def is_waiting(self, h):
+        return self._file(h).waiting
 
     # ---- audit -----------------------------------------------------------------
     def audit(self):
         """State invariants: reference counts equal table references; free = count 0."""
-        seen = {}
+        seen, on_host, wait = {}, {}, {}
         files = {id(f): f for f in self.handles.values()}
         files.update({id(f): f for f in self.names.values()})
         for f in files.values():
             assert len(f.pages) == -(-f.length // self.P)
-            for p in f.pages:
+            for i, p in enumerate(f.pages):
+                if p < 0:
+                    assert f.waiting                       # a page is on the host only while all its readers wait
+                    on_host.setdefault(-p - 1, []).append((id(f), i))
+                    continue
                 seen[p] = seen.get(p, 0) + 1
+                if f.waiting:
+                    wait.setdefault(p, []).append((id(f), i))
+        assert {s: sorted(v) for s, v in on_host.items()} == {s: sorted((id(g), j) for g, j in v) for s, v in self.host_refs.items()}
+        assert {p: sorted(v) for p, v in wait.items()} == {p: sorted((id(g), j) for g, j in v) for p, v in self.waiters.items()}
+        assert sorted(self.free_slots) == sorted(set(range(self.n_slots)) - set(self.host_refs))
         free = {int(self.order[r]) for r in self.free_ranks}
         assert len(free) == len(self.free_ranks)
         for p in range(self.n_pages):
@@ -273,6 +378,18 @@ class PagePool:
         pg = self.page(page)
         pg[0, :, slot, :] = k_row
         pg[1, :, slot, :] = v_row
+
+    def swap_out(self, evictions):
+        """Carry out KVFSModel.kv_offload: page contents to host slots."""
+        if not hasattr(self, "host"):
+            self.host = {}
+        for p, s in evictions:
+            self.host[s] = self.page(p).copy()
+
+    def swap_in(self, loads):
+        """Carry out KVFSModel.kv_restore: host slots back into pages."""
+        for s, q in loads:
+            self.data[q] = self.host.pop(s)
 
     def move_tokens(self, moves):
         """Carry out the copies of KVFSModel.kv_gather: rows of (src page, slot) into (dst page, slot)."""

@@ -309,3 +309,140 @@ def test_random_ops_with_extract_merge_against_token_lists():
     for h in list(shadow):
         m.kv_remove(h)
     assert m.free_pages() == 512
+
+
+# ---- offload / restore (section 4.3) ---------------------------------------------------------
+
+def test_offload_restore_hand_trace():
+    """Worked by hand, page size 4: a page leaves when all its readers wait, comes back for all of
+    them when one of them is restored."""
+    m = KVFSModel(16, 4)
+    a = m.kv_open()
+    m.append([(a, 10)])                                   # a: pages 0,1,2
+    b = m.kv_fork(a)
+    m.append([(b, 3)])                                    # b: 0,1,3,4 (page 2 copied into 3)
+    assert m.kv_pages(b) == [0, 1, 3, 4]
+    assert m.kv_offload([a]) == [(2, 0)]                  # pages 0, 1 are still read by b; page 2 leaves
+    assert m.kv_pages(a) == [0, 1, -1] and m.refcount.tolist()[:5] == [2, 2, 0, 1, 1] and m.free_pages() == 12
+    with pytest.raises(KVError) as e:
+        m.append([(b, 1), (a, 1)])                        # a waits: the whole batch is refused
+    assert e.value.code == EBUSY and m.kv_len(b) == 13
+    with pytest.raises(KVError) as e:
+        m.kv_fork(a)
+    assert e.value.code == EBUSY
+    assert m.kv_offload([b]) == [(0, 1), (1, 2), (3, 3), (4, 4)]
+    assert m.kv_pages(a) == [-2, -3, -1] and m.kv_pages(b) == [-2, -3, -4, -5] and m.free_pages() == 16
+    m.audit()
+    # b comes back: fresh pages lowest first; a's entries for the shared pages follow
+    assert m.kv_restore([b]) == [(1, 0), (2, 1), (3, 2), (4, 3)]
+    assert m.kv_pages(b) == [0, 1, 2, 3] and m.kv_pages(a) == [0, 1, -1]
+    assert m.refcount.tolist()[:5] == [2, 2, 1, 1, 0]
+    m.audit()
+    cow, slots = m.append([(b, 1)])                       # b works again; page 3 (one token) is its own
+    assert cow == [] and slots == [[(3, 1)]]
+    assert m.kv_restore([a]) == [(0, 4)]
+    assert m.kv_pages(a) == [0, 1, 4] and not m.is_waiting(a)
+    with pytest.raises(KVError) as e:
+        m.kv_restore([a])
+    assert e.value.code == EBUSY
+    # a waiting file can be removed: its host slots are released
+    m.kv_offload([a])
+    assert m.kv_pages(a) == [0, 1, -1]                    # slot 0 again (lowest free)
+    m.kv_remove(a)
+    assert m.host_refs == {} and m.refcount.tolist()[:5] == [1, 1, 1, 1, 0]
+    m.audit()
+
+
+def test_restore_needs_room_or_changes_nothing():
+    m = KVFSModel(6, 4)
+    a, b = m.kv_open(), m.kv_open()
+    m.append([(a, 12)])
+    m.kv_offload([a])
+    m.append([(b, 16)])                                   # takes 4 of the 6 pages
+    snap = (m.refcount.copy(), m.free_pages(), m.kv_pages(a), dict(m.host_refs))
+    with pytest.raises(KVError) as e:
+        m.kv_restore([a])                                 # three pages needed, two free
+    assert e.value.code == ENOSPC and m.is_waiting(a)
+    assert np.array_equal(snap[0], m.refcount) and snap[1:] == (m.free_pages(), m.kv_pages(a), m.host_refs)
+    m.kv_truncate(b, 9)
+    assert m.kv_restore([a]) == [(0, 3), (1, 4), (2, 5)]
+    m.audit()
+
+
+def test_random_ops_with_offload_against_token_lists():
+    """The token-list shadow model again, now with files that wait on the host in between: whatever
+    the interleaving of offload / restore with appends, forks, extracts and removals of the other
+    files, every file that does not wait reads back exactly its tokens, and so does every waiting
+    file once it is restored."""
+    from oracle.kvfs_model import PagePool
+    from oracle.attention import gather_file
+    rng = np.random.default_rng(13)
+    P = 4
+    m = KVFSModel(256, P, rng.permutation(256))
+    pool = PagePool(1, P, 1, np.float64)
+    shadow, next_id = {}, [1]
+
+    def check(h):
+        toks = shadow[h]
+        K, V = gather_file(pool, m.kv_pages(h), len(toks))
+        assert K.ravel().tolist() == toks and V.ravel().tolist() == [-t for t in toks], h
+
+    for step in range(900):
+        r = rng.random()
+        live = [h for h in shadow if not m.is_waiting(h)]
+        waiting = [h for h in shadow if m.is_waiting(h)]
+        try:
+            if r < 0.1 or not shadow:
+                shadow[m.kv_open()] = []
+            elif r < 0.4 and live:
+                h = live[rng.integers(len(live))]
+                n = int(rng.integers(1, 12))
+                ids = np.arange(next_id[0], next_id[0] + n, dtype=np.float64).reshape(n, 1, 1)
+                cow, slots = m.append([(h, n)])
+                pool.apply(cow, slots, ids, -ids)
+                shadow[h] += [int(i) for i in ids.ravel()]
+                next_id[0] += n
+            elif r < 0.5 and live:
+                src = live[rng.integers(len(live))]
+                shadow[m.kv_fork(src)] = list(shadow[src])
+            elif r < 0.58 and live:
+                src = live[rng.integers(len(live))]
+                idx = np.flatnonzero(rng.random(len(shadow[src])) < 0.7)
+                h, moves = m.kv_extract(src, [int(i) for i in idx])
+                pool.move_tokens(moves)
+                shadow[h] = [shadow[src][int(i)] for i in idx]
+            elif r < 0.72 and live:
+                k = int(rng.integers(1, min(4, len(live)) + 1))
+                hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
+                pool.swap_out(m.kv_offload(hs))
+            elif r < 0.86 and waiting:
+                k = int(rng.integers(1, min(3, len(waiting)) + 1))
+                hs = [int(x) for x in rng.choice(waiting, size=k, replace=False)]
+                pool.swap_in(m.kv_restore(hs))
+                for h in hs:
+                    check(h)
+            elif r < 0.92 and live:
+                h = live[rng.integers(len(live))]
+                n = int(rng.integers(0, len(shadow[h]) + 1))
+                m.kv_truncate(h, n)
+                del shadow[h][n:]
+            elif shadow:
+                h = list(shadow)[rng.integers(len(shadow))]        # waiting files can be removed too
+                m.kv_remove(h)
+                del shadow[h]
+        except KVError as e:
+            assert e.code == ENOSPC
+            h = max(shadow, key=lambda x: len(shadow[x]))
+            m.kv_remove(h)
+            del shadow[h]
+        if step % 15 == 0:
+            m.audit()
+            for h in shadow:
+                if not m.is_waiting(h):
+                    check(h)
+    for h in sorted(shadow, key=m.is_waiting):             # the files that do not wait first: they make room
+        if m.is_waiting(h):
+            pool.swap_in(m.kv_restore([h]))
+        check(h)
+        m.kv_remove(h)
+    assert m.free_pages() == 256 and m.host_refs == {} and m.waiters == {} and not getattr(pool, "host", {})
