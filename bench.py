@@ -10,7 +10,8 @@ Default workload (the one the headline metric is quoted on): the "decode batch",
 rotate over several independent layer pools (as a real pred walks the model's layers, each with
 its own KV pages) so that the KV bytes of a step come from HBM and not from the 256 MB
 last-level cache.  `--workload fork|mixed|long|draft` times the other configurations the same way;
-`--workload prune` times kv_extract (context pruning, paper section 4.2) on the decode batch's files.
+`--workload prune` times kv_extract (context pruning, paper section 4.2) on the decode batch's files;
+`--workload offload` times kv_offload + kv_restore (paper section 4.3) of those files over the host link.
 
 Prints ONE JSON line: whole-path throughput in algorithmic KV TB/s, plus `roofline` for the
 dominant kernel (the attention launch, timed with HIP events on its stream inside the timed region) and `cpu_baseline`
@@ -207,12 +208,65 @@ def bench_prune(args, np, torch, binding, synth, HipSession, dev):
     print(json.dumps(line))
 
 
+PCIE_PEAK_GBPS = 64.0      # PCIe 5.0 x16, one direction, before protocol overhead
+
+
+def bench_offload(args, np, torch, binding, synth, HipSession, dev):
+    """kv_offload then kv_restore of the 64 files of the decode batch (every page leaves for pinned
+    host memory and comes back).  A step = both calls.  The copy kernel is bound by the host link,
+    not by HBM: its rate is reported against the link's one-direction peak."""
+    wl = synth.config2()
+    shape = wl.shape
+    steps = args.steps if args.steps is not None else 10
+    warmup = args.warmup if args.warmup is not None else 2
+    s = HipSession(shape, wl.n_pages, wl.free_order, dev, max_lips=64, max_tokens=max(wl.lengths.values()) + 64,
+                   max_entries=sum(wl.pages_after_batch().values()) + 64 * 64)
+    s.setup(wl.setup_ops())
+    hs = [s.h[f] for f in wl.batch_files]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    n_pages = sum(len(s.pages(f)) for f in wl.batch_files)
+    nbytes = n_pages * s.page_bytes
+    torch.cuda.synchronize()
+    out_ms, in_ms = [], []
+    t_wall = 0.0
+    for i in range(warmup + steps):
+        s.ctx.profile_enable(1 << binding.K_SWAP)
+        t0 = time.perf_counter()
+        s.ctx.kv_offload(hs, stream)
+        torch.cuda.synchronize()
+        a, _ = s.ctx.profile_read(binding.K_SWAP)
+        s.ctx.kv_restore(hs, stream)
+        torch.cuda.synchronize()
+        b, _ = s.ctx.profile_read(binding.K_SWAP)
+        dt = time.perf_counter() - t0
+        if i >= warmup:
+            out_ms.append(a)
+            in_ms.append(b)
+            t_wall += dt
+    st = s.ctx.get_stats()
+    s.close()
+    o, r = float(np.mean(out_ms)), float(np.mean(in_ms))
+    slow = max(o, r)
+    line = {"metric": "kv_offload + kv_restore GB/s over the host link", "value": round(2 * nbytes / (t_wall / steps) / 1e9, 2), "unit": "GB/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(t_wall / steps * 1e3, 3), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "offload: all 64 files of the decode batch (contexts U{512..4096}, 32Q/8KV, bf16) leave for pinned host "
+                                   "memory in one call and come back in one call", "pages": n_pages, "bytes_each_way": int(nbytes)},
+            "offload_GBps": round(nbytes / (o * 1e-3) / 1e9, 2), "restore_GBps": round(nbytes / (r * 1e-3) / 1e9, 2),
+            "offload_ms": round(o, 3), "restore_ms": round(r, 3),
+            "roofline": {"bound": "pcie", "achieved": round(nbytes / (slow * 1e-3) / 1e9, 2), "peak": PCIE_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(nbytes / (slow * 1e-3) / 1e9 / PCIE_PEAK_GBPS, 4), "traffic": None, "kernel": "swap_kernel (slower direction)",
+                         "avg_launch_us": round(slow * 1e3, 1), "launches": 2 * steps},
+            "cpu_baseline": None, "pool_stats": {"host_slots": st["host_slots"], "pages_offloaded": st["pages_offloaded"]}}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune", "offload"], default="decode")
     ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
@@ -233,6 +287,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "prune":
         return bench_prune(args, np, torch, binding, synth, HipSession, dev)
+    if args.workload == "offload":
+        return bench_offload(args, np, torch, binding, synth, HipSession, dev)
     # workload -> (generator, layer pools, steps, warmup, reset lengths after each step, cpu seconds, label)
     table = {"decode": (synth.config2, 4, 400, 40, False, 12.0, "decode batch: 64 LIPs, 32Q/8KV heads, head_dim 128, bf16, page 16, "
                         "contexts U{512..4096}, 1 new token each"),

@@ -82,6 +82,8 @@ typedef struct sym_stats {
                              not counting waits for a staging buffer still in use by the GPU */
   int64_t tokens_moved;      /* tokens copied by sym_kv_extract / sym_kv_merge              */
   int64_t pages_referenced;  /* pages those calls shared with the source instead of copying */
+  int64_t pages_offloaded, pages_restored;   /* page copies of sym_kv_offload / sym_kv_restore */
+  int64_t host_slots;        /* pinned host slots (pages) the context has created so far      */
 } sym_stats;
 
 /* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).
@@ -146,6 +148,30 @@ sym_kv  sym_kv_merge(sym_ctx* ctx, int32_t m, const sym_kv* files, void* stream)
  * (source, destination) pairs of token slots, each page * P + slot, in destination order.
  * Returns the number of pairs; writes at most cap of them (out may be NULL).             */
 int64_t sym_last_moves(sym_ctx* ctx, int32_t* out, int64_t cap);
+
+/* kv_offload, kv_restore (section 4.3: while a thread waits for I/O its KV cache moves from
+ * the GPU to CPU memory and is restored when the I/O completes).  kv: host, n distinct handles.
+ *   sym_kv_offload: the files start to wait.  A waiting file cannot be read or written (pred,
+ *     append, fork, truncate, extract, merge, read: SYM_EBUSY) but can be removed or closed.  A
+ *     page leaves the GPU when EVERY reference to it belongs to a waiting file ("a shared page
+ *     leaves only when all sharers wait"): it is copied into pinned host memory owned by the
+ *     context (host slots, lowest free first, allocated with hipHostMalloc as needed, kept until
+ *     sym_destroy), every table entry that referenced it becomes -(slot + 1) (as sym_kv_pages
+ *     shows), and the page returns to the free set.  Other pages stay where they are.
+ *   sym_kv_restore: the files' waits end.  Every host slot they reference comes back into a
+ *     fresh page (lowest rank first, in table order) and EVERY entry that referenced the slot is
+ *     rewritten, also those of files that still wait.  SYM_ENOSPC (nothing changed) if the pages
+ *     do not fit.
+ * Files already (not) waiting, or named twice: SYM_EBUSY.  The copies are one kernel launch per
+ * call on `stream`, before the call returns control of the freed pages / slots to the allocator
+ * (stream order keeps later writers behind them).  sym_kv_waiting: 1, 0 or a negative status.
+ * In a host-only context only the integer state is built.                                 */
+int     sym_kv_offload(sym_ctx* ctx, int32_t n, const sym_kv* kv, void* stream);
+int     sym_kv_restore(sym_ctx* ctx, int32_t n, const sym_kv* kv, void* stream);
+int     sym_kv_waiting(sym_ctx* ctx, sym_kv kv);
+/* The page copies of the last sym_kv_offload ((page, host slot) pairs) or sym_kv_restore
+ * ((host slot, page) pairs) on this context, for inspection.  Returns the number of pairs. */
+int64_t sym_last_swaps(sym_ctx* ctx, int32_t* out, int64_t cap);
 
 /* ---- pred (section 4.1), batched (section 4.4) ------------------------------------- */
 /* One launch for n_lips pending pred calls.  LIP b appends n_tokens[b] >= 1 rows to file
@@ -217,7 +243,8 @@ int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, 
 #define SYM_K_ATTN     1   /* attention over the page tables: decode ranges + MFMA tiles     */
 #define SYM_K_MERGE    2   /* merge of the partial results of ranges that were cut           */
 #define SYM_K_MOVE     3   /* token copies of sym_kv_extract / sym_kv_merge                  */
-#define SYM_K_COUNT    4
+#define SYM_K_SWAP     4   /* page copies of sym_kv_offload / sym_kv_restore                 */
+#define SYM_K_COUNT    5
 /* sym_profile_enable(mask): bit k of mask set = every launch of kernel id k is bracketed by
  * HIP events on the launch stream (at most 4096 launches are kept per kernel id, later ones
  * are not timed); mask 0 = off.

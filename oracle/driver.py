@@ -40,6 +40,10 @@ class OracleSession:
             elif op[0] == "merge":                        # ("merge", new fid, [source fids])
                 self.h[op[1]], moves = self.model.kv_merge([self.h[f] for f in op[2]])
                 self.pool.move_tokens(moves)
+            elif op[0] == "offload":                      # ("offload", [fids]) / ("restore", [fids])
+                self.pool.swap_out(self.model.kv_offload([self.h[f] for f in op[1]]))
+            elif op[0] == "restore":
+                self.pool.swap_in(self.model.kv_restore([self.h[f] for f in op[1]]))
             else:
                 raise ValueError(op[0])
 

@@ -259,6 +259,7 @@ class KVFSModel:
 
     def kv_extract(self, h, idx):
         """New file from the chosen token indices of file h, in the order given."""
+        self._file(h, usable=True)                        # the source must exist and not wait, even for no tokens
         return self.kv_gather([(h, int(i)) for i in idx])
 
     def kv_merge(self, handles):

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
 
 SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
 SYM_F32, SYM_BF16 = 0, 1
-K_PROLOGUE, K_ATTN, K_MERGE, K_MOVE = 0, 1, 2, 3
+K_PROLOGUE, K_ATTN, K_MERGE, K_MOVE, K_SWAP = 0, 1, 2, 3, 4
 
 
 class SymConfig(C.Structure):
@@ -26,7 +26,8 @@ class SymConfig(C.Structure):
 class SymStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("pages_total", "pages_free", "pages_shared", "cow_copies", "pages_allocated",
                                          "tokens_appended", "pred_batches", "kernel_launches", "files", "handles",
-                                         "host_ns_plan", "host_ns_pred", "tokens_moved", "pages_referenced")]
+                                         "host_ns_plan", "host_ns_pred", "tokens_moved", "pages_referenced",
+                                         "pages_offloaded", "pages_restored", "host_slots")]
 
 
 class SymError(RuntimeError):
@@ -54,6 +55,10 @@ _SIGNATURES = {
     "sym_kv_extract": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I64P, _I64P, _I32P, C.c_void_p]),
     "sym_kv_merge": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, C.c_void_p]),
     "sym_last_moves": (C.c_int64, [C.c_void_p, _I32P, C.c_int64]),
+    "sym_kv_offload": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_void_p]),
+    "sym_kv_restore": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_void_p]),
+    "sym_kv_waiting": (C.c_int, [C.c_void_p, C.c_int32]),
+    "sym_last_swaps": (C.c_int64, [C.c_void_p, _I32P, C.c_int64]),
     "sym_pred_batch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_kv_pages": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, C.c_int64]),
@@ -201,6 +206,23 @@ class Context:
     def kv_merge(self, files, stream=None):
         f_a, f_p = _i32(files)
         return self._chk(self.lib.sym_kv_merge(self.h, len(f_a), f_p, stream))
+
+    def kv_offload(self, kv, stream=None):
+        kv_a, kv_p = _i32(kv)
+        self._chk(self.lib.sym_kv_offload(self.h, len(kv_a), kv_p, stream))
+
+    def kv_restore(self, kv, stream=None):
+        kv_a, kv_p = _i32(kv)
+        self._chk(self.lib.sym_kv_restore(self.h, len(kv_a), kv_p, stream))
+
+    def kv_waiting(self, kv):
+        return bool(self._chk(self.lib.sym_kv_waiting(self.h, kv)))
+
+    def last_swaps(self):
+        n = self._chk(self.lib.sym_last_swaps(self.h, None, 0))
+        out = np.empty((n, 2), np.int32)
+        self._chk(self.lib.sym_last_swaps(self.h, out.ctypes.data_as(_I32P), n))
+        return out
 
     def last_moves(self):
         n = self._chk(self.lib.sym_last_moves(self.h, None, 0))

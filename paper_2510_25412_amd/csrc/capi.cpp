@@ -43,6 +43,9 @@ struct sym_ctx {
   Kvfs* fs = nullptr;
   AppendPlan plan;
   GatherPlan gplan;
+  SwapPlan splan;
+  std::vector<uint8_t*> host_chunks;   // pinned memory of the host slots, kHostChunk pages each
+  int64_t pages_offloaded = 0, pages_restored = 0;
   BatchDesc desc;
   std::vector<const int32_t*> tables;
   std::vector<int64_t> len_after;
@@ -56,7 +59,7 @@ struct sym_ctx {
   // profiling
   int prof_mask = 0;
   std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
-  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0};
+  int ev_used[SYM_K_COUNT] = {0, 0, 0, 0, 0};
   // counters
   int64_t pred_batches = 0, kernel_launches = 0;
   int64_t host_ns_plan = 0, host_ns_pred = 0;   // time inside sym_pred_batch: planning + descriptor; whole call
@@ -233,6 +236,48 @@ int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_o
   return SYM_OK;
 }
 
+// Host slots live in pinned chunks of kHostChunk pages each, allocated when first needed.
+constexpr int64_t kHostChunk = 1024;
+int ensure_host_slots(sym_ctx* c, int64_t n_slots) {
+  while ((int64_t)c->host_chunks.size() * kHostChunk < n_slots) {
+    uint8_t* p = nullptr;
+    hipError_t e = hipHostMalloc((void**)&p, (size_t)(kHostChunk * c->page_bytes), hipHostMallocDefault);
+    if (e != hipSuccess) return fail_hip(c, e, "hipHostMalloc(host slots)");
+    c->host_chunks.push_back(p);
+  }
+  return SYM_OK;
+}
+uint8_t* host_slot(const sym_ctx* c, int32_t s) { return c->host_chunks[s / kHostChunk] + (int64_t)(s % kHostChunk) * c->page_bytes; }
+
+// Carries out the page copies of c->splan ((page, slot) pairs when to_host, (slot, page) otherwise).
+int run_swaps(sym_ctx* c, bool to_host, hipStream_t st) {
+  const std::vector<int32_t>& pr = c->splan.pairs;
+  const int64_t n = (int64_t)pr.size() / 2;
+  const int64_t cap = 1 << 18;                                        // pages per launch
+  for (int64_t off = 0; off < n; off += cap) {
+    const int64_t cnt = std::min(cap, n - off);
+    int si, rc;
+    if ((rc = stage_acquire(c, 4 * cnt, &si))) return rc;
+    uint64_t* list = (uint64_t*)c->stage[si];
+    for (int64_t i = 0; i < cnt; ++i) {
+      const int32_t a = pr[2 * (off + i)], b = pr[2 * (off + i) + 1];
+      list[2 * i] = (uint64_t)(to_host ? a : b);
+      list[2 * i + 1] = (uint64_t)(uintptr_t)host_slot(c, to_host ? b : a);
+    }
+    SwapArgs sa{(uint8_t*)c->cfg.pool, c->page_bytes, list, (int32_t)cnt, to_host ? 1 : 0};
+    {
+      Timed t(c, SYM_K_SWAP, st);
+      hipError_t e = launch_swap(sa, st);
+      if (e != hipSuccess) return fail_hip(c, e, "swap launch");
+    }
+    hipError_t e = hipEventRecord(c->stage_ev[si], st);
+    if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
+    c->stage_pending[si] = true;
+  }
+  (to_host ? c->pages_offloaded : c->pages_restored) += n;
+  return SYM_OK;
+}
+
 // Carries out the copies of c->gplan on the device: the move list goes through pinned staging
 // into the workspace (bulk copy by the prologue kernel), chunk by chunk, then the move kernel.
 int run_moves(sym_ctx* c, hipStream_t st) {
@@ -354,6 +399,7 @@ void sym_destroy(sym_ctx* c) {
       if (c->stage[i]) (void)hipHostFree(c->stage[i]);
       (void)hipEventDestroy(c->stage_ev[i]);
     }
+    for (uint8_t* p : c->host_chunks) (void)hipHostFree(p);
     for (int k = 0; k < SYM_K_COUNT; ++k)
       for (size_t i = 0; i < c->ev_start[k].size(); ++i) {
         (void)hipEventDestroy(c->ev_start[k][i]);
@@ -376,7 +422,7 @@ sym_kv sym_kv_fork(sym_ctx* c, sym_kv parent) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   const int32_t h = c->fs->fork(parent);
-  if (h < 0) c->err = "kv_fork: bad handle";
+  if (h < 0) c->err = h == SYM_EBUSY ? "kv_fork: file is offloaded" : "kv_fork: bad handle";
   return h;
 }
 
@@ -408,6 +454,7 @@ int sym_kv_truncate(sym_ctx* c, int32_t n, const sym_kv* kv, const int64_t* new_
   for (int32_t i = 0; i < n; ++i) {          // validate everything first: all or nothing
     const KvFile* f = c->fs->file_of(kv[i]);
     if (!f) return fail(c, SYM_EBADF, "kv_truncate: bad handle");
+    if (f->waiting) return fail(c, SYM_EBUSY, "kv_truncate: file is offloaded");
     if (new_len[i] < 0 || new_len[i] > f->len) return fail(c, SYM_EINVAL, "kv_truncate: length beyond the file");
     for (int32_t j = 0; j < i; ++j)
       if (c->fs->file_of(kv[j]) == f) return fail(c, SYM_EBUSY, "kv_truncate: file listed twice");
@@ -455,6 +502,9 @@ int sym_get_stats(sym_ctx* c, sym_stats* s) {
   s->host_ns_pred = c->host_ns_pred;
   s->tokens_moved = c->fs->tokens_moved;
   s->pages_referenced = c->fs->pages_referenced;
+  s->pages_offloaded = c->pages_offloaded;
+  s->pages_restored = c->pages_restored;
+  s->host_slots = c->fs->host_slots();
   return SYM_OK;
 }
 
@@ -529,6 +579,53 @@ sym_kv sym_kv_merge(sym_ctx* c, int32_t m, const sym_kv* files, void* stream) {
   if (h < 0 || c->cfg.device < 0) return h;
   const int rc = run_moves(c, (hipStream_t)stream);
   return rc ? rc : h;
+}
+
+int sym_kv_offload(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
+  if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  int rc;
+  if (c->cfg.device >= 0) {
+    // Host memory first, so that running out of it changes nothing: at most every page of the
+    // files leaves, into the lowest free slots.
+    int64_t pages = 0;
+    for (int32_t b = 0; b < n; ++b) {
+      const KvFile* f = c->fs->file_of(kv[b]);
+      if (f) pages += (int64_t)f->pages.size();
+    }
+    if ((rc = ensure_host_slots(c, std::max(c->fs->host_slots(), c->fs->host_slots_in_use() + pages)))) return rc;
+  }
+  if ((rc = c->fs->offload(n, kv, &c->splan, &c->err))) return rc;
+  if (c->cfg.device < 0) {
+    c->pages_offloaded += (int64_t)c->splan.pairs.size() / 2;
+    return SYM_OK;
+  }
+  return run_swaps(c, true, (hipStream_t)stream);
+}
+
+int sym_kv_restore(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
+  if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int rc = c->fs->restore(n, kv, &c->splan, &c->err);
+  if (rc || c->cfg.device < 0) {
+    if (!rc) c->pages_restored += (int64_t)c->splan.pairs.size() / 2;
+    return rc;
+  }
+  return run_swaps(c, false, (hipStream_t)stream);
+}
+
+int sym_kv_waiting(sym_ctx* c, sym_kv kv) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->fs->waiting(kv);
+}
+
+int64_t sym_last_swaps(sym_ctx* c, int32_t* out, int64_t cap) {
+  if (!c || cap < 0) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  const int64_t n = (int64_t)c->splan.pairs.size() / 2;
+  if (out) std::memcpy(out, c->splan.pairs.data(), (size_t)std::min(n, cap) * 8);
+  return n;
 }
 
 int64_t sym_last_moves(sym_ctx* c, int32_t* out, int64_t cap) {
@@ -628,6 +725,7 @@ int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, vo
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
   const KvFile* f = c->fs->file_of(kv);
   if (!f) return fail(c, SYM_EBADF, "kv_read: bad handle");
+  if (f->waiting) return fail(c, SYM_EBUSY, "kv_read: file is offloaded");
   if (start + n > f->len) return fail(c, SYM_EINVAL, "kv_read: range beyond the file");
   if (n == 0) return SYM_OK;
   if ((int64_t)n + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");

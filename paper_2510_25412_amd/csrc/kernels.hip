@@ -1032,6 +1032,30 @@ __global__ __launch_bounds__(256) void move_kernel(MoveArgs a) {
   *(u32x4_t*)(a.pool + (int64_t)(d / kP) * a.page_bytes + in_page + (d % kP) * kHalfBytes) = v;
 }
 
+// offload / restore (paper section 4.3): whole pages between the pool and pinned host memory, over
+// the host link.  Four workgroups per page, 16 bytes per thread and pass; the list (page id, host
+// address) is read from pinned memory by every workgroup for itself.
+constexpr int kSwapSplit = 4;
+__global__ __launch_bounds__(256) void swap_kernel(SwapArgs a) {
+  const int e = blockIdx.x / kSwapSplit, part = blockIdx.x % kSwapSplit;
+  const int64_t page = (int64_t)a.list[2 * e];
+  uint8_t* host = (uint8_t*)a.list[2 * e + 1];
+  uint8_t* dev = a.pool + page * a.page_bytes;
+  const int64_t n16 = a.page_bytes / 16, per = (n16 + kSwapSplit - 1) / kSwapSplit;
+  const int64_t lo = part * per, hi = min(n16, lo + per);
+  const u32x4_t* src = (const u32x4_t*)(a.to_host ? dev : host);
+  u32x4_t* dst = (u32x4_t*)(a.to_host ? host : dev);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 4 * 256) {      // four loads in flight per thread
+    u32x4_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * 256 < hi) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * 256 < hi) dst[i + u * 256] = v[u];
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Calibration: streaming read (reduced so that the loads are live) and plain copy.
 // ---------------------------------------------------------------------------------------
@@ -1137,6 +1161,12 @@ hipError_t launch_move(const MoveArgs& a, hipStream_t st) {
   const int64_t blocks = (a.n_tokens * a.Hkv * 32 + 255) / 256;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(move_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_swap(const SwapArgs& a, hipStream_t st) {
+  if (a.n_pages <= 0) return hipSuccess;
+  hipLaunchKernelGGL(swap_kernel, dim3((unsigned)a.n_pages * kSwapSplit), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

@@ -78,12 +78,21 @@ struct MoveArgs {
   int32_t Hkv;
 };
 
+struct SwapArgs {
+  uint8_t* pool;
+  int64_t page_bytes;
+  const uint64_t* list;         // pinned host [n_pages][2]: page id, address of the page's host slot
+  int32_t n_pages;
+  int32_t to_host;              // 1 = pool -> host slots, 0 = host slots -> pool
+};
+
 // decode_mode: 0 = VALU decode kernel, 1 = decode ranges on the matrix cores (bf16 storage only)
 hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);
 hipError_t launch_move(const MoveArgs& a, hipStream_t st);
+hipError_t launch_swap(const SwapArgs& a, hipStream_t st);
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st);
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st);
 

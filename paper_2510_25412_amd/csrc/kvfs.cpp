@@ -34,11 +34,42 @@ int32_t Kvfs::alloc_page() {
   return p;
 }
 
-void Kvfs::release_pages(KvFile& f) {
-  for (int32_t p : f.pages)
-    if (--refcount_[p] == 0) free_ranks_.push(rank_[p]);
-  f.pages.clear();
-  f.len = 0;
+void Kvfs::drop_ref(int32_t p) {
+  if (--refcount_[p] == 0) free_ranks_.push(rank_[p]);
+}
+
+namespace {
+void erase_ref(std::vector<std::pair<int32_t, int32_t>>& v, int32_t file_id, int32_t idx) {
+  auto it = std::find(v.begin(), v.end(), std::make_pair(file_id, idx));
+  if (it != v.end()) {
+    *it = v.back();
+    v.pop_back();
+  }
+}
+}  // namespace
+
+// Drops the file's table entries from index keep on.
+void Kvfs::release_entries(int32_t id, size_t keep) {
+  KvFile& f = files_[id];
+  for (size_t i = keep; i < f.pages.size(); ++i) {
+    const int32_t e = f.pages[i];
+    if (e >= 0) {
+      if (f.waiting) {
+        auto w = waiters_.find(e);
+        erase_ref(w->second, id, (int32_t)i);
+        if (w->second.empty()) waiters_.erase(w);
+      }
+      drop_ref(e);
+    } else {                                  // on the host: the slot is free once nobody refers to it
+      auto r = host_refs_.find(-e - 1);
+      erase_ref(r->second, id, (int32_t)i);
+      if (r->second.empty()) {
+        host_refs_.erase(r);
+        free_slots_.push(-e - 1);
+      }
+    }
+  }
+  f.pages.resize(keep);
 }
 
 int32_t Kvfs::new_file() {
@@ -57,6 +88,7 @@ int32_t Kvfs::new_file() {
   f.name.clear();
   f.named = false;
   f.alive = true;
+  f.waiting = false;
   return id;
 }
 
@@ -76,7 +108,9 @@ int32_t Kvfs::new_handle(int32_t file_id) {
 
 void Kvfs::drop_file(int32_t id) {
   KvFile& f = files_[id];
-  release_pages(f);
+  release_entries(id, 0);
+  f.len = 0;
+  f.waiting = false;
   for (int32_t h : f.handles) {
     handle_file_[h] = -1;
     free_handles_.push(h);
@@ -104,6 +138,7 @@ int32_t Kvfs::open(const char* name) {
 int32_t Kvfs::fork(int32_t parent) {
   const KvFile* pf = file_of(parent);
   if (!pf) return SYM_EBADF;
+  if (pf->waiting) return SYM_EBUSY;
   int32_t pid = handle_file_[parent];
   int32_t id = new_file();                  // may grow files_: re-read the parent by index
   KvFile& child = files_[id];
@@ -139,11 +174,9 @@ int64_t Kvfs::len(int32_t h) const {
 int Kvfs::truncate(int32_t h, int64_t new_len) {
   if (!file_of(h)) return SYM_EBADF;
   KvFile& f = files_[handle_file_[h]];
+  if (f.waiting) return SYM_EBUSY;
   if (new_len < 0 || new_len > f.len) return SYM_EINVAL;
-  const size_t keep = (size_t)((new_len + P_ - 1) / P_);
-  for (size_t i = keep; i < f.pages.size(); ++i)
-    if (--refcount_[f.pages[i]] == 0) free_ranks_.push(rank_[f.pages[i]]);
-  f.pages.resize(keep);
+  release_entries(handle_file_[h], (size_t)((new_len + P_ - 1) / P_));
   f.len = new_len;
   return SYM_OK;
 }
@@ -161,6 +194,10 @@ int64_t Kvfs::pages_needed(int32_t n, const int32_t* handles, const int32_t* n_t
     if (n_tokens[b] < 1) {
       if (err) *err = "n_tokens must be >= 1";
       return SYM_EINVAL;
+    }
+    if (f->waiting) {
+      if (err) *err = "file is offloaded";
+      return SYM_EBUSY;
     }
     int32_t id = handle_file_[handles[b]];
     if (std::find(seen_files_.begin(), seen_files_.end(), id) != seen_files_.end()) {
@@ -228,6 +265,10 @@ int64_t Kvfs::gather_need(int32_t n_seg, const int32_t* seg_handle, const int64_
     if (!f) {
       if (err) *err = "extract/merge: bad file handle";
       return SYM_EBADF;
+    }
+    if (f->waiting) {
+      if (err) *err = "extract/merge: file is offloaded";
+      return SYM_EBUSY;
     }
     const int64_t lo = idx ? seg_off[s] : 0, hi = idx ? seg_off[s + 1] : f->len;
     if (hi < lo || (int64_t)(src.size() - s0) + (hi - lo) > (int64_t)0x7fffffff) {
@@ -297,6 +338,105 @@ int32_t Kvfs::gather(int32_t n_seg, const int32_t* seg_handle, const int64_t* se
     return SYM_ENOSPC;
   }
   return gather_commit(plan, 0);
+}
+
+int Kvfs::waiting(int32_t h) const {
+  const KvFile* f = file_of(h);
+  return f ? (f->waiting ? 1 : 0) : SYM_EBADF;
+}
+
+int Kvfs::check_swap_args(int32_t n, const int32_t* handles, bool want_waiting, std::string* err) {
+  seen_files_.clear();
+  for (int32_t b = 0; b < n; ++b) {
+    const KvFile* f = file_of(handles[b]);
+    if (!f) {
+      if (err) *err = "offload/restore: bad file handle";
+      return SYM_EBADF;
+    }
+    const int32_t id = handle_file_[handles[b]];
+    if (f->waiting != want_waiting || std::find(seen_files_.begin(), seen_files_.end(), id) != seen_files_.end()) {
+      if (err) *err = want_waiting ? "restore: file is not offloaded, or named twice" : "offload: file already offloaded, or named twice";
+      return SYM_EBUSY;
+    }
+    seen_files_.push_back(id);
+  }
+  return SYM_OK;
+}
+
+int Kvfs::offload(int32_t n, const int32_t* handles, SwapPlan* plan, std::string* err) {
+  plan->pairs.clear();
+  const int rc = check_swap_args(n, handles, false, err);
+  if (rc) return rc;
+  for (int32_t b = 0; b < n; ++b) {
+    const int32_t id = handle_file_[handles[b]];
+    KvFile& f = files_[id];
+    f.waiting = true;
+    for (size_t i = 0; i < f.pages.size(); ++i) {
+      const int32_t p = f.pages[i];
+      RefList& w = waiters_[p];
+      w.emplace_back(id, (int32_t)i);
+      if (w.size() != refcount_[p]) continue;
+      int32_t s;                                  // every reader waits: the page leaves for the lowest free slot
+      if (!free_slots_.empty()) {
+        s = free_slots_.top();
+        free_slots_.pop();
+      } else {
+        s = n_slots_++;
+      }
+      for (const auto& r : w) files_[r.first].pages[r.second] = -(s + 1);
+      host_refs_[s] = std::move(w);
+      waiters_.erase(p);
+      refcount_[p] = 0;
+      free_ranks_.push(rank_[p]);
+      plan->pairs.push_back(p);
+      plan->pairs.push_back(s);
+    }
+  }
+  return SYM_OK;
+}
+
+int Kvfs::restore(int32_t n, const int32_t* handles, SwapPlan* plan, std::string* err) {
+  plan->pairs.clear();
+  const int rc = check_swap_args(n, handles, true, err);
+  if (rc) return rc;
+  pending_.clear();                               // distinct host slots of the files
+  for (int32_t id : seen_files_)
+    for (int32_t e : files_[id].pages)
+      if (e < 0) pending_[-e - 1] = 1;
+  if ((int64_t)pending_.size() > free_pages()) {
+    if (err) *err = "page pool exhausted";
+    return SYM_ENOSPC;
+  }
+  for (int32_t b = 0; b < n; ++b) {
+    const int32_t id = handle_file_[handles[b]];
+    files_[id].waiting = false;
+    for (size_t i = 0; i < files_[id].pages.size(); ++i) {
+      const int32_t e = files_[id].pages[i];
+      if (e >= 0) {                               // never left, or already back through another entry
+        auto w = waiters_.find(e);
+        if (w != waiters_.end()) {
+          erase_ref(w->second, id, (int32_t)i);
+          if (w->second.empty()) waiters_.erase(w);
+        }
+        continue;
+      }
+      const int32_t s = -e - 1;
+      const int32_t q = alloc_page();
+      RefList refs = std::move(host_refs_[s]);
+      host_refs_.erase(s);
+      RefList still;
+      for (const auto& r : refs) {
+        files_[r.first].pages[r.second] = q;
+        if (files_[r.first].waiting) still.push_back(r);
+      }
+      refcount_[q] = (uint32_t)refs.size();
+      if (!still.empty()) waiters_[q] = std::move(still);
+      free_slots_.push(s);
+      plan->pairs.push_back(s);
+      plan->pairs.push_back(q);
+    }
+  }
+  return SYM_OK;
 }
 
 int64_t Kvfs::count_shared() const {

@@ -13,7 +13,8 @@ namespace symkv {
 
 struct KvFile {
   int64_t len = 0;
-  std::vector<int32_t> pages;
+  std::vector<int32_t> pages;      // page ids; -(slot + 1) for a page that is on the host
+  bool waiting = false;            // offloaded: its thread waits for I/O (paper section 4.3)
   std::vector<int32_t> handles;
   std::string name;
   bool named = false;
@@ -36,6 +37,12 @@ struct GatherPlan {
   std::vector<int32_t> shared;    // per destination page, the page it references or -1
   std::vector<int64_t> bounds;    // per planned file: where its stretch of src / of shared begins
   void reset() { moves.clear(); src.clear(); shared.clear(); bounds.clear(); pages_shared = 0; }
+};
+
+// Page copies of an offload ((page, host slot) pairs, device to host) or of a restore ((host
+// slot, page) pairs, host to device), in the order they must happen.
+struct SwapPlan {
+  std::vector<int32_t> pairs;
 };
 
 class Kvfs {
@@ -70,6 +77,18 @@ class Kvfs {
   int32_t gather(int32_t n_seg, const int32_t* seg_handle, const int64_t* seg_off, const int64_t* idx, GatherPlan* plan,
                  std::string* err);
 
+  // offload / restore (paper section 4.3: the KV cache of a thread that waits for I/O moves to CPU
+  // memory and comes back when the wait ends).  A waiting file cannot be read or written
+  // (SYM_EBUSY) but can be removed.  A page leaves when EVERY reference to it belongs to a waiting
+  // file: lowest free host slot, all referencing entries become -(slot + 1), the page is freed.
+  // restore brings each host slot of the files back into a fresh page and rewrites every entry
+  // that referenced the slot, also those of files still waiting.  All or nothing.
+  int offload(int32_t n, const int32_t* handles, SwapPlan* plan, std::string* err);
+  int restore(int32_t n, const int32_t* handles, SwapPlan* plan, std::string* err);
+  int waiting(int32_t h) const;                 // 1, 0 or a negative status
+  int64_t host_slots() const { return n_slots_; }   // host slots ever created (ids 0 .. n - 1)
+  int64_t host_slots_in_use() const { return (int64_t)host_refs_.size(); }
+
   int32_t refcount(int32_t page) const { return page < 0 || page >= n_pages_ ? -1 : (int32_t)refcount_[page]; }
   int64_t free_pages() const { return (int64_t)free_ranks_.size(); }
   int64_t n_pages() const { return n_pages_; }
@@ -82,7 +101,9 @@ class Kvfs {
 
  private:
   int32_t alloc_page();
-  void release_pages(KvFile& f);
+  void release_entries(int32_t file_id, size_t keep);
+  void drop_ref(int32_t page);
+  int check_swap_args(int32_t n, const int32_t* handles, bool want_waiting, std::string* err);
   int32_t new_handle(int32_t file_id);
   int32_t new_file();
   void drop_file(int32_t file_id);
@@ -97,6 +118,11 @@ class Kvfs {
   std::vector<int32_t> handle_file_;        // handle -> file id or -1
   std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_handles_;
   std::unordered_map<std::string, int32_t> names_;
+  typedef std::vector<std::pair<int32_t, int32_t>> RefList;          // (file id, table index) entries
+  std::unordered_map<int32_t, RefList> waiters_;    // resident page -> entries of waiting files that reference it
+  std::unordered_map<int32_t, RefList> host_refs_;  // host slot -> entries that reference it
+  std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_slots_;
+  int32_t n_slots_ = 0;
   std::unordered_map<int32_t, int32_t> pending_;   // scratch of pages_needed
   std::vector<int32_t> seen_files_;                 // scratch of append
 };

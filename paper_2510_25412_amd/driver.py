@@ -55,6 +55,10 @@ class HipSession:
                 self.h[op[1]] = self.ctx.kv_extract(self.h[op[2]], op[3], self.stream)
             elif op[0] == "merge":                        # ("merge", new fid, [source fids])
                 self.h[op[1]] = self.ctx.kv_merge([self.h[f] for f in op[2]], self.stream)
+            elif op[0] == "offload":                      # ("offload", [fids]) / ("restore", [fids])
+                self.ctx.kv_offload([self.h[f] for f in op[1]], self.stream)
+            elif op[0] == "restore":
+                self.ctx.kv_restore([self.h[f] for f in op[1]], self.stream)
             else:
                 raise ValueError(op[0])
 

@@ -204,10 +204,12 @@ def config5(n_lips=16, lo=32768, hi=131072, n_pages=3_000_000):
     return _finish(wl, st)
 
 
-def custom(name, shape, files, batch, n_pages, seed, free_order=None):
+def custom(name, shape, files, batch, n_pages, seed, free_order=None, then=()):
     """Free-form workload for edge cases.  files: list of ("new", length),
     ("fork", parent_index, extra_tokens), ("extract", source_index, token indices) or
-    ("merge", [source indices]); batch: list of (file_index, n_tokens)."""
+    ("merge", [source indices]); batch: list of (file_index, n_tokens); then: operations that
+    follow the files, ("offload", [file indices]), ("restore", [file indices]), ("append",
+    file_index, n_tokens) or ("remove", file_index)."""
     st = _Streams(seed)
     wl = Workload(name, shape, n_pages, free_order)
     for fid, spec in enumerate(files):
@@ -229,6 +231,12 @@ def custom(name, shape, files, batch, n_pages, seed, free_order=None):
             if extra > 0:
                 wl.program.append(("append", fid, int(extra), st.child(), st.child()))
             wl.lengths[fid] = wl.lengths[parent] + int(extra)
+    for op in then:
+        if op[0] == "append":
+            wl.program.append(("append", op[1], int(op[2]), st.child(), st.child()))
+            wl.lengths[op[1]] += int(op[2])
+        else:
+            wl.program.append((op[0], list(op[1]) if op[0] in ("offload", "restore") else op[1]))
     # a parent that is appended to after a fork changes length: lengths[] holds the value at
     # the time the file was created; callers that append to parents later track it themselves
     wl.batch_files = [f for f, _ in batch]

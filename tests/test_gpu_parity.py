@@ -379,3 +379,57 @@ def test_extract_merge_bytes_state_and_pred(Hq, Hkv, D, dtype):
     check_outputs(got, ref)
     check_state(wl, sess, osess)
     sess.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,dtype", [(32, 8, 128, synth.BF16), (8, 8, 64, synth.F32)])
+def test_offload_restore_bytes_state_and_pred(Hq, Hkv, D, dtype):
+    """kv_offload / kv_restore (section 4.3) on the GPU: files leave for pinned host memory and come
+    back while other files keep appending into the pages they freed (so a copy that ran late, or
+    into the wrong slot, would read overwritten bytes).  Page tables, reference counts and host
+    slots equal the oracle model's bit for bit; every file reads back exactly the oracle's rows;
+    a pred over all files matches the oracle."""
+    from oracle.attention import gather_file
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    files = [("new", 300), ("fork", 0, 20), ("new", 77), ("new", 1000), ("fork", 3, 0), ("extract", 3, np.arange(0, 1000, 3))]
+    then = [("offload", [0]), ("append", 2, 100),            # file 1 still reads file 0's first pages: only the last one leaves
+            ("offload", [1, 3]), ("append", 2, 700),         # 0 and 1 all out; 3's pages stay (4 reads them); 2 grows into freed pages
+            ("offload", [4]), ("append", 5, 40),             # now 3 and 4 both wait: their pages leave
+            ("restore", [1]), ("append", 1, 5),              # back for 0 and 1 at once; 1 copies the shared last page
+            ("restore", [4, 0]), ("append", 2, 30), ("restore", [3])]
+    batch = [(0, 1), (1, 2), (2, 1), (3, 1), (4, 3), (5, 1)]
+    wl = synth.custom(f"swap_{Hq}_{Hkv}_{dtype}", shape, files, batch, 256, seed=555 + Hq, then=then)
+    print(f"[case] {wl.name}", flush=True)
+    drv = _hip()
+    sess = drv.HipSession(shape, wl.n_pages, poison=True)
+    osess = OracleSession(shape, wl.n_pages)
+    for op in wl.setup_ops():                              # step by step: the state is compared after every operation
+        sess.setup([op])
+        osess.setup([op])
+        for fid in sess.h:
+            assert sess.pages(fid) == osess.model.kv_pages(osess.h[fid]), (op[0], fid)
+        assert sess.ctx.free_pages() == osess.model.free_pages()
+    torch.cuda.synchronize()
+    check_state(wl, sess, osess)
+    st = sess.ctx.get_stats()
+    assert st["pages_offloaded"] == st["pages_restored"] > 80 and st["host_slots"] == osess.model.n_slots
+    tdt = torch.float32 if dtype == synth.F32 else torch.bfloat16
+    for fid in range(len(files)):
+        n = osess.model.kv_len(osess.h[fid])
+        k = torch.empty((n, Hkv, D), dtype=tdt, device="cuda")
+        v = torch.empty_like(k)
+        sess.ctx.kv_read(sess.h[fid], 0, n, k, v, sess.stream)
+        torch.cuda.synchronize()
+        Ko, Vo = gather_file(osess.pool, osess.model.kv_pages(osess.h[fid]), n)
+        assert np.array_equal(k.float().cpu().numpy(), Ko) and np.array_equal(v.float().cpu().numpy(), Vo), fid
+    b = wl.batch()
+    got = sess.pred(sess.upload_batch(b)).cpu().numpy()
+    ref = osess.pred(b, dtype=np.float64)
+    check_outputs(got, ref)
+    # a waiting file refuses work and leaves the batch untouched
+    from paper_2510_25412_amd import binding
+    sess.ctx.kv_offload([sess.h[2]], sess.stream)
+    before = sess.ctx.kv_len(sess.h[0])
+    with pytest.raises(binding.SymError) as e:
+        sess.pred(sess.upload_batch(b))
+    assert e.value.code == binding.SYM_EBUSY and sess.ctx.kv_len(sess.h[0]) == before
+    sess.close()

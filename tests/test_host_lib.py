@@ -410,3 +410,112 @@ def test_descriptor_shared_prefix_groups():
     assert max(used) < n_partials
     # the unrelated file and the 3-page sharer are ordinary rows
     assert all(int(by_out[k][5]) == 0 for k in by_out if k // 32 >= 6)
+
+
+def test_offload_restore_hand_trace_library():
+    """The model's hand-worked offload / restore trace at page size 16, on the library."""
+    c = host_ctx(16)
+    a = c.kv_open()
+    c.plan_append([a], [40])                              # a: pages 0,1,2
+    b = c.kv_fork(a)
+    c.plan_append([b], [12])                              # b: 0,1,3,4 (page 2 copied into 3)
+    assert c.kv_pages(b) == [0, 1, 3, 4]
+    c.kv_offload([a])
+    assert c.last_swaps().tolist() == [[2, 0]] and c.kv_pages(a) == [0, 1, -1] and c.free_pages() == 12 and c.kv_waiting(a)
+    for call in (lambda: c.plan_append([b, a], [1, 1]), lambda: c.kv_fork(a), lambda: c.kv_truncate([a], [3]),
+                 lambda: c.kv_extract(a, [0]), lambda: c.kv_merge([b, a]), lambda: c.kv_offload([a]), lambda: c.kv_restore([b]),
+                 lambda: c.kv_offload([b, b])):
+        with pytest.raises(binding.SymError) as e:
+            call()
+        assert e.value.code == binding.SYM_EBUSY
+    assert c.kv_len(b) == 52 and c.kv_len(a) == 40 and not c.kv_waiting(b)
+    c.kv_offload([b])
+    assert c.last_swaps().tolist() == [[0, 1], [1, 2], [3, 3], [4, 4]]
+    assert c.kv_pages(a) == [-2, -3, -1] and c.kv_pages(b) == [-2, -3, -4, -5] and c.free_pages() == 16
+    c.kv_restore([b])
+    assert c.last_swaps().tolist() == [[1, 0], [2, 1], [3, 2], [4, 3]]
+    assert c.kv_pages(b) == [0, 1, 2, 3] and c.kv_pages(a) == [0, 1, -1]
+    assert [c.page_refcount(p) for p in range(5)] == [2, 2, 1, 1, 0]
+    c.kv_restore([a])
+    assert c.last_swaps().tolist() == [[0, 4]] and c.kv_pages(a) == [0, 1, 4]
+    c.kv_offload([a])
+    assert c.kv_pages(a) == [0, 1, -1]
+    c.kv_remove(a)                                        # a waiting file can be removed: its slot is released
+    st = c.get_stats()
+    assert [c.page_refcount(p) for p in range(5)] == [1, 1, 1, 1, 0] and st["host_slots"] == 5
+    assert st["pages_offloaded"] == 6 and st["pages_restored"] == 5
+    c.kv_offload([b])
+    assert c.last_swaps().tolist() == [[0, 0], [1, 1], [2, 2], [3, 3]]       # lowest free slots again
+
+
+def test_random_ops_with_offload_match_oracle_model_bit_exact():
+    rng = np.random.default_rng(77)
+    order = rng.permutation(384).astype(np.int32)
+    m = KVFSModel(384, 16, order)
+    c = host_ctx(384, order)
+    live = []
+
+    def both(fm, fc):
+        """Same call on model and library: same result or the same error code."""
+        try:
+            a = fm()
+        except KVError as e:
+            with pytest.raises(binding.SymError) as ce:
+                fc()
+            assert ce.value.code == e.code
+            return None, None
+        return a, fc()
+
+    for step in range(1500):
+        r = rng.random()
+        h = int(live[rng.integers(len(live))]) if live else None
+        if r < 0.1 or not live:
+            a, b = m.kv_open(), c.kv_open()
+            assert a == b
+            live.append(a)
+        elif r < 0.2:
+            a, b = both(lambda: m.kv_fork(h), lambda: c.kv_fork(h))
+            assert a == b
+            if a is not None:
+                live.append(a)
+        elif r < 0.28:
+            n = int(rng.integers(0, m.kv_len(h) + 1))
+            both(lambda: m.kv_truncate(h, n), lambda: c.kv_truncate([h], [n]))
+        elif r < 0.36:
+            L = m.kv_len(h)
+            idx = np.flatnonzero(rng.random(L) < 0.8)
+            a, b = both(lambda: m.kv_extract(h, [int(i) for i in idx]), lambda: c.kv_extract(h, idx))
+            if a is not None:
+                assert a[0] == b
+                live.append(b)
+        elif r < 0.62:
+            k = min(len(live), int(rng.integers(1, 5)))
+            hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
+            ns = [int(rng.integers(1, 40)) for _ in hs]
+            a, b = both(lambda: m.append(list(zip(hs, ns))), lambda: c.plan_append(hs, ns))
+            if a is not None:
+                assert b[0] == a[0] and b[1].tolist() == [p * 16 + s for mine in a[1] for p, s in mine]
+        elif r < 0.78:
+            k = min(len(live), int(rng.integers(1, 4)))
+            hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
+            a, _ = both(lambda: m.kv_offload(hs), lambda: c.kv_offload(hs))
+            if a is not None:
+                assert c.last_swaps().tolist() == [list(x) for x in a]
+        elif r < 0.92:
+            k = min(len(live), int(rng.integers(1, 4)))
+            hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
+            a, _ = both(lambda: m.kv_restore(hs), lambda: c.kv_restore(hs))
+            if a is not None:
+                assert c.last_swaps().tolist() == [list(x) for x in a]
+        else:
+            live.remove(h)
+            m.kv_remove(h)
+            c.kv_remove(h)
+        if step % 40 == 0 or step == 1499:
+            m.audit()
+            assert c.free_pages() == m.free_pages()
+            assert [c.page_refcount(p) for p in range(384)] == m.refcount.tolist()
+            for x in live:
+                assert c.kv_pages(x) == m.kv_pages(x) and c.kv_len(x) == m.kv_len(x) and c.kv_waiting(x) == m.is_waiting(x)
+    st = c.get_stats()
+    assert st["pages_offloaded"] > 100 and st["pages_restored"] > 50 and st["host_slots"] == m.n_slots
