@@ -237,6 +237,34 @@ int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
 int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out,
                 void* stream);
 
+/* ---- inference scheduler: when to fire a batch (section 4.4) ------------------------- */
+/* The controller that decides WHEN the pending pred calls go to the GPU as one batch.  The
+ * paper states the trade-off (too early wastes the GPU, too late makes threads wait) and that
+ * the batch size follows the average call frequency via "models like Poisson process"; the
+ * formulas are this library's: arrival rate lambda = 1 / (exponentially weighted mean gap);
+ * service time S(b) = a + c*b fitted to the batches reported with sym_sched_done; target batch
+ * b* = lambda*a / (1 - lambda*c) (the fixed point b = lambda*S(b): expected arrivals during one
+ * service period), max_batch when lambda*c >= 1.  sym_sched_decide, asked while the GPU is
+ * idle, returns how many of the OLDEST pending calls to fire now: all of them (at most
+ * max_batch) if there are b* of them, if the oldest has waited max_wait_us, or if the missing
+ * ones are not expected before that deadline; otherwise 0 (wait; ask again at the next arrival
+ * or at sym_sched_next_deadline).  Times are microseconds on any clock of the caller's.  Host
+ * only, no device work; not thread-safe (one scheduler thread owns it).
+ *   weight: weight of a new sample in the running means (0 < weight <= 1, e.g. 0.125);
+ *   a_us, c_us: service model until measurements arrive.                                   */
+typedef struct sym_sched sym_sched;
+sym_sched* sym_sched_create(int32_t max_batch, double max_wait_us, double weight, double a_us,
+                            double c_us);               /* NULL on a bad argument */
+void    sym_sched_destroy(sym_sched* s);
+void    sym_sched_arrive(sym_sched* s, double now_us);  /* one pred call became pending   */
+int32_t sym_sched_decide(sym_sched* s, double now_us, int gpu_idle);
+void    sym_sched_fired(sym_sched* s, int32_t n);       /* the n oldest calls were fired  */
+void    sym_sched_done(sym_sched* s, int32_t n, double service_us);   /* that batch took this long */
+double  sym_sched_next_deadline(sym_sched* s);          /* +inf when nothing is pending   */
+/* Current estimates; any output pointer may be NULL. */
+int     sym_sched_state(sym_sched* s, double* rate_per_us, double* target_batch, double* a_us,
+                        double* c_us, int64_t* pending);
+
 /* ---- measurement ------------------------------------------------------------------- */
 /* Kernel ids for sym_profile_read. */
 #define SYM_K_PROLOGUE 0   /* descriptor copy + copy-on-write copies + KV append, one launch */

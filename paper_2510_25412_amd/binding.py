@@ -68,6 +68,15 @@ _SIGNATURES = {
     "sym_plan_append": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_int64, _I32P, _I32P]),
     "sym_build_desc": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, _I32P, C.c_int64]),
     "sym_kv_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_sched_create": (C.c_void_p, [C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "sym_sched_destroy": (None, [C.c_void_p]),
+    "sym_sched_arrive": (None, [C.c_void_p, C.c_double]),
+    "sym_sched_decide": (C.c_int32, [C.c_void_p, C.c_double, C.c_int]),
+    "sym_sched_fired": (None, [C.c_void_p, C.c_int32]),
+    "sym_sched_done": (None, [C.c_void_p, C.c_int32, C.c_double]),
+    "sym_sched_next_deadline": (C.c_double, [C.c_void_p]),
+    "sym_sched_state": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double), _I64P]),
     "sym_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "sym_profile_read": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), _I64P]),
     "sym_calib_read": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
@@ -131,6 +140,48 @@ def page_bytes(cfg):
 
 def workspace_bytes(cfg, max_lips, max_tokens, max_table_entries):
     return load().sym_workspace_bytes(C.byref(cfg), max_lips, max_tokens, max_table_entries)
+
+
+class BatchTimer:
+    """The batch-firing controller of the inference scheduler (paper section 4.4): marshalling only."""
+
+    def __init__(self, max_batch, max_wait_us, weight=0.125, a_us=50.0, c_us=1.0):
+        self.lib = load()
+        self.s = self.lib.sym_sched_create(max_batch, max_wait_us, weight, a_us, c_us)
+        if not self.s:
+            raise SymError(SYM_EINVAL, "sym_sched_create: bad argument")
+
+    def arrive(self, now_us):
+        self.lib.sym_sched_arrive(self.s, now_us)
+
+    def decide(self, now_us, gpu_idle=True):
+        return self.lib.sym_sched_decide(self.s, now_us, 1 if gpu_idle else 0)
+
+    def fired(self, n):
+        self.lib.sym_sched_fired(self.s, n)
+
+    def done(self, n, service_us):
+        self.lib.sym_sched_done(self.s, n, service_us)
+
+    def next_deadline(self):
+        return self.lib.sym_sched_next_deadline(self.s)
+
+    def state(self):
+        r, t, a, c = C.c_double(), C.c_double(), C.c_double(), C.c_double()
+        p = C.c_int64()
+        self.lib.sym_sched_state(self.s, C.byref(r), C.byref(t), C.byref(a), C.byref(c), C.byref(p))
+        return dict(rate=r.value, target=t.value, a=a.value, c=c.value, pending=p.value)
+
+    def close(self):
+        if self.s:
+            self.lib.sym_sched_destroy(self.s)
+            self.s = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Context:

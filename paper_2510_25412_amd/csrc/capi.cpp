@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <limits>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -15,6 +16,7 @@
 #include "desc.hpp"
 #include "kernels.hpp"
 #include "kvfs.hpp"
+#include "sched.hpp"
 
 using namespace symkv;
 
@@ -743,6 +745,37 @@ int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, vo
   e = hipEventRecord(c->stage_ev[si], st);
   if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
   c->stage_pending[si] = true;
+  return SYM_OK;
+}
+
+sym_sched* sym_sched_create(int32_t max_batch, double max_wait_us, double weight, double a_us, double c_us) {
+  if (max_batch < 1 || !(max_wait_us >= 0.0) || !(weight > 0.0 && weight <= 1.0) || !(a_us >= 0.0) || !(c_us >= 0.0)) return nullptr;
+  return reinterpret_cast<sym_sched*>(new BatchTimer(max_batch, max_wait_us, weight, a_us, c_us));
+}
+void sym_sched_destroy(sym_sched* s) { delete reinterpret_cast<BatchTimer*>(s); }
+void sym_sched_arrive(sym_sched* s, double now_us) {
+  if (s) reinterpret_cast<BatchTimer*>(s)->arrive(now_us);
+}
+int32_t sym_sched_decide(sym_sched* s, double now_us, int gpu_idle) {
+  return s ? reinterpret_cast<BatchTimer*>(s)->decide(now_us, gpu_idle != 0) : 0;
+}
+void sym_sched_fired(sym_sched* s, int32_t n) {
+  if (s) reinterpret_cast<BatchTimer*>(s)->fired(n);
+}
+void sym_sched_done(sym_sched* s, int32_t n, double service_us) {
+  if (s && n > 0) reinterpret_cast<BatchTimer*>(s)->done(n, service_us);
+}
+double sym_sched_next_deadline(sym_sched* s) {
+  return s ? reinterpret_cast<BatchTimer*>(s)->next_deadline() : std::numeric_limits<double>::infinity();
+}
+int sym_sched_state(sym_sched* s, double* rate, double* target, double* a_us, double* c_us, int64_t* pending) {
+  if (!s) return SYM_EINVAL;
+  const BatchTimer* t = reinterpret_cast<const BatchTimer*>(s);
+  if (rate) *rate = t->rate();
+  if (target) *target = t->target();
+  if (a_us) *a_us = t->a();
+  if (c_us) *c_us = t->c();
+  if (pending) *pending = t->pending();
   return SYM_OK;
 }
 

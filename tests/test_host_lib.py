@@ -519,3 +519,35 @@ def test_random_ops_with_offload_match_oracle_model_bit_exact():
                 assert c.kv_pages(x) == m.kv_pages(x) and c.kv_len(x) == m.kv_len(x) and c.kv_waiting(x) == m.is_waiting(x)
     st = c.get_stats()
     assert st["pages_offloaded"] > 100 and st["pages_restored"] > 50 and st["host_slots"] == m.n_slots
+
+
+@pytest.mark.parametrize("lam,a,c,max_wait", [(1e-4, 100.0, 2.0, 200.0), (0.05, 100.0, 2.0, 200.0), (0.2, 60.0, 1.5, 50.0),
+                                               (1.0, 100.0, 2.0, 200.0), (0.02, 400.0, 9.0, 1000.0)])
+def test_batch_timer_matches_oracle_decision_by_decision(lam, a, c, max_wait):
+    """The library's firing controller against the oracle's on the same Poisson trace: every decision
+    at every event time, the waits, and the estimates (identical doubles: same operations in the
+    same order)."""
+    from oracle.scheduler import BatchTimer as OracleTimer
+    from sched_sim import simulate, poisson_arrivals
+    arr = poisson_arrivals(lam, 6000, seed=int(lam * 1e5) + 1)
+    o, l = OracleTimer(64, max_wait, 0.125, 50.0, 1.0), binding.BatchTimer(64, max_wait, 0.125, 50.0, 1.0)
+    lo, ll = [], []
+    ro = simulate(o, arr, a, c, log=lo)
+    rl = simulate(l, arr, a, c, log=ll)
+    assert lo == ll and len(lo) > 90
+    assert np.array_equal(ro["waits"], rl["waits"]) and np.array_equal(ro["batches"], rl["batches"])
+    st = l.state()
+    assert (st["rate"], st["target"], st["a"], st["c"], st["pending"]) == (o.rate(), o.target(), o.a, o.c, len(o.pending))
+    l.close()
+
+
+def test_batch_timer_rejects_bad_arguments():
+    for args in ((0, 100.0, 0.1, 1.0, 1.0), (8, -1.0, 0.1, 1.0, 1.0), (8, 100.0, 0.0, 1.0, 1.0), (8, 100.0, 1.5, 1.0, 1.0),
+                 (8, 100.0, 0.1, -1.0, 1.0), (8, float("nan"), 0.1, 1.0, 1.0)):
+        with pytest.raises(binding.SymError):
+            binding.BatchTimer(*args)
+    t = binding.BatchTimer(8, 100.0)
+    assert t.decide(0.0) == 0 and t.next_deadline() == float("inf")
+    t.arrive(5.0)
+    assert t.decide(5.0) == 1 and t.decide(5.0, gpu_idle=False) == 0 and t.next_deadline() == 105.0
+    t.close()
