@@ -11,7 +11,10 @@ rotate over several independent layer pools (as a real pred walks the model's la
 its own KV pages) so that the KV bytes of a step come from HBM and not from the 256 MB
 last-level cache.  `--workload fork|mixed|long|draft` times the other configurations the same way;
 `--workload prune` times kv_extract (context pruning, paper section 4.2) on the decode batch's files;
-`--workload offload` times kv_offload + kv_restore (paper section 4.3) of those files over the host link.
+`--workload offload` times kv_offload + kv_restore (paper section 4.3) of those files over the host link;
+`--workload rag` drives the library with the paper's section 5 workload (100 documents x 3000 tokens,
+prompt caching of the 20 most requested topics, Poisson requests, batches fired by the library's
+controller) for several Pareto indices, end to end in virtual time.
 
 Prints ONE JSON line: whole-path throughput in algorithmic KV TB/s, plus `roofline` for the
 dominant kernel (the attention launch, timed with HIP events on its stream inside the timed region) and `cpu_baseline`
@@ -261,16 +264,50 @@ def bench_offload(args, np, torch, binding, synth, HipSession, dev):
     print(json.dumps(line))
 
 
+def bench_rag(args, np, torch, binding, synth, HipSession, dev):
+    """Section 5's RAG scenario on the attention path alone: throughput and latency against the
+    Pareto index of the topic popularity, with and without the LIP's prompt cache."""
+    from paper_2510_25412_amd import rag
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    n_req = args.steps if args.steps is not None else 1500
+    rows = []
+    for pareto, retain in ((0.5, 20), (1.0, 20), (2.0, 20), (1.0, 0)):
+        cfg = rag.RagConfig(pareto_index=pareto, retain=retain, n_requests=n_req, rate_per_s=args.rag_rate)
+        # room for every request's file at once (no admission control here) + the retained documents
+        n_pages = (n_req + retain + 8) * ((cfg.doc_tokens + cfg.answer_tokens) // 16 + 2)
+        s = HipSession(shape, n_pages, None, dev, max_lips=cfg.max_batch, max_tokens=cfg.max_batch * cfg.prefill_chunk + 64,
+                       max_entries=cfg.max_batch * ((cfg.doc_tokens + cfg.answer_tokens) // 16 + 2) + 64)
+        d = rag.RagDriver(s, cfg)
+        r = d.run()
+        r.update(pareto_index=pareto, retain=retain)
+        rows.append(r)
+        print(f"[bench] rag pareto {pareto} retain {retain}: {r['requests_per_s']:.0f} req/s, hit {r['hit_rate']:.2f}", file=sys.stderr, flush=True)
+        d.close()
+        s.close()
+        torch.cuda.empty_cache()
+    head = rows[1]
+    line = {"metric": "RAG LIP-steps/s (pred calls per second, attention path only)", "value": round(head["lip_steps_per_s"], 1), "unit": "LIP-steps/s",
+            "n_gpus": 1, "steps": n_req, "warmup": 0, "ms_per_step": round(1e3 / head["lip_steps_per_s"], 5), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"rag: 100 documents x 3000 tokens, 32 answer tokens, top-20 topics retained (prompt caching by fork), Poisson "
+                                   f"requests at {args.rag_rate:.0f}/s, Pareto topic popularity, 32Q/8KV bf16, batches fired by sym_sched; virtual time "
+                                   "advanced by measured batch wall time; value quoted at Pareto index 1.0"},
+            "by_pareto_index": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items() if k != "scheduler"} for r in rows],
+            "roofline": None, "cpu_baseline": None}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune", "offload"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune", "offload", "rag"], default="decode")
     ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
     ap.add_argument("--no-calib", action="store_true")
+    ap.add_argument("--rag-rate", type=float, default=6000.0, help="request arrivals per second of the rag workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path is single-GPU; see DESIGN.md for how it would shard); "
@@ -289,6 +326,8 @@ def main():
         return bench_prune(args, np, torch, binding, synth, HipSession, dev)
     if args.workload == "offload":
         return bench_offload(args, np, torch, binding, synth, HipSession, dev)
+    if args.workload == "rag":
+        return bench_rag(args, np, torch, binding, synth, HipSession, dev)
     # workload -> (generator, layer pools, steps, warmup, reset lengths after each step, cpu seconds, label)
     table = {"decode": (synth.config2, 4, 400, 40, False, 12.0, "decode batch: 64 LIPs, 32Q/8KV heads, head_dim 128, bf16, page 16, "
                         "contexts U{512..4096}, 1 new token each"),

@@ -433,3 +433,44 @@ def test_offload_restore_bytes_state_and_pred(Hq, Hkv, D, dtype):
         sess.pred(sess.upload_batch(b))
     assert e.value.code == binding.SYM_EBUSY and sess.ctx.kv_len(sess.h[0]) == before
     sess.close()
+
+
+@pytest.mark.parametrize("pareto_index", [0.6, 3.0])
+def test_rag_driver_replayed_on_the_oracle(pareto_index):
+    """The RAG workload of the paper's section 5 in miniature (8 documents of 150 tokens, the 3 most
+    requested retained, 40 Poisson requests, batches fired by the library's controller): the run is
+    recorded, then replayed operation by operation on the CPU model.  Every batch's outputs must
+    match the oracle's and the final page tables / reference counts must be identical: prefill
+    chunks, decode rows, forks of cached documents, evictions and removals under allocator churn."""
+    from paper_2510_25412_amd import rag
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    cfg = rag.RagConfig(n_docs=8, doc_tokens=150, answer_tokens=5, retain=3, pareto_index=pareto_index, rate_per_s=20000.0,
+                        n_requests=40, prefill_chunk=64, max_batch=8, max_wait_us=200.0, seed=17)
+    n_pages = 1024
+    sess = drv.HipSession(shape, n_pages, max_lips=cfg.max_batch, max_tokens=cfg.max_batch * cfg.prefill_chunk + 64,
+                          max_entries=cfg.max_batch * 16 + 64, poison=True)
+    print(f"[case] rag pareto={pareto_index}", flush=True)
+    d = rag.RagDriver(sess, cfg, trace=True)
+    res = d.run()
+    assert res["requests"] == 40 and res["cached_topics"] <= 3 and 0 < res["mean_batch"] <= 8
+    assert res["pred_calls"] == 40 * 5 + (40 - round(res["hit_rate"] * 40)) * 3
+    osess = OracleSession(shape, n_pages)
+    it = iter(d.outputs)
+    worst = 0.0
+    for op in d.trace:
+        if op[0] == "pred":
+            T = sum(op[2])
+            ref = osess.pred(dict(files=op[1], n_tokens=op[2], q=d.q_host[:T], k_new=d.k_host[:T], v_new=d.v_host[:T]), dtype=np.float64)
+            worst = max(worst, check_outputs(next(it), ref))
+        else:
+            osess.setup([op])
+    assert set(d.h) == set(osess.h)
+    for fid in d.h:
+        assert sess.ctx.kv_pages(d.h[fid]) == osess.model.kv_pages(osess.h[fid])
+    assert sess.ctx.free_pages() == osess.model.free_pages()
+    osess.model.audit()
+    print(f"rag pareto {pareto_index}: {len(d.outputs)} batches, hit rate {res['hit_rate']:.2f}, worst scaled error {worst:.2e}")
+    d.close()
+    assert sess.ctx.free_pages() == n_pages
+    sess.close()
