@@ -38,6 +38,7 @@ struct sym_ctx {
   int32_t max_waves = 0, min_units = 4, range_cost = 3;
   int32_t decode_mode = 0;                           // 1 = decode ranges on the matrix cores
   int32_t share_min_lips = 4, share_min_pages = 8;   // decode LIPs / common full pages needed to read a prefix once
+  int32_t tile_rows = 256;                     // query rows of an MFMA tile: 128 or 256
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   int32_t row_tokens = 1;                      // new tokens of one LIP per decode row (bf16: up to 16 / G, at most 4)
   std::mutex mu;
@@ -189,6 +190,9 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.part_ml = part_ml;
   pa.tile_first = 0;
   pa.n_tiles = d.n_tiles;
+  pa.xcd_off = dw + H_XCD_OFF;
+  pa.tile_blocks = d.tile_blocks;
+  pa.tile_rows = d.tile_rows;
   pa.Hq = c->cfg.n_q_heads;
   pa.Hkv = c->cfg.n_kv_heads;
   pa.scale_log2e = c->scale_log2e;
@@ -381,7 +385,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
   c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
   c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));
-  c->tile_tokens = cfg->dtype == SYM_BF16 ? 128 / c->G : 0;   // a tile has 128 query rows
+  c->tile_rows = env_int("SYM_TILE_ROWS", 256) == 128 ? 128 : 256;
+  c->tile_tokens = cfg->dtype == SYM_BF16 ? c->tile_rows / c->G : 0;   // new tokens (or sharing members) per tile
   // a short draft (2 .. prefill_min - 1 new tokens) shares one pass over its file: 16 MFMA columns = tokens x heads
   c->row_tokens = cfg->dtype == SYM_BF16 ? std::max(1, std::min(env_int("SYM_ROW_TOKENS", ROW_TOKENS_MAX), std::min<int>(ROW_TOKENS_MAX, 16 / c->G))) : 1;
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units

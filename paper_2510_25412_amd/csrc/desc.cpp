@@ -11,8 +11,13 @@ namespace symkv {
 int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, const int64_t* len_after,
                const int32_t* const* tables, BatchDesc* out) {
   const int32_t P = prm.page_tokens, H = prm.n_kv_heads, G = prm.n_q_heads / H;
-  const int32_t TQ = prm.tile_tokens;
-  auto is_prefill = [&](int32_t b) { return TQ > 0 && n_tokens[b] >= prm.prefill_min; };
+  auto is_prefill = [&](int32_t b) { return prm.tile_tokens > 0 && n_tokens[b] >= prm.prefill_min; };
+  // Tiles of a batch with prefill chunks have prm.tile_tokens new tokens (256 query rows by default:
+  // eight wavefronts share one staging of K/V); a batch whose only tiles are shared prefixes (few
+  // members per group) keeps 128-row tiles, two workgroups per CU.
+  bool any_prefill = false;
+  for (int32_t b = 0; b < n_lips && !any_prefill; ++b) any_prefill = n_tokens[b] >= 1 && is_prefill(b);
+  const int32_t TQ = any_prefill ? prm.tile_tokens : std::min(prm.tile_tokens, 128 / G);
   // A decode row holds up to RT consecutive new tokens of one LIP (a short draft to verify):
   // they share one pass over the file's pages.
   const int32_t RT = std::max(1, std::min(prm.row_tokens, (int32_t)ROW_TOKENS_MAX));
@@ -51,7 +56,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   // of the row; the rest is split between the prefix partials of sharing groups and the
   // members' own ranges (one partial per (member, head), never more than the former).
   const int64_t shared_budget = std::max<int64_t>(0, ((int64_t)prm.max_partials - 2 * (int64_t)RT * prm.max_waves) / 2);
-  const int32_t tile_lips = TQ > 0 ? 128 / G : 0;           // a shared-prefix tile has 128 query rows
+  const int32_t tile_lips = TQ;                             // members of a shared-prefix tile (rows = members x G)
   if (prm.share_min_lips > 0 && tile_lips > 0) {
     auto& cand = out->by_first_page;
     cand.clear();
@@ -322,6 +327,68 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
         }
     }
   }
+  // ---- the tile list in 8 shares of equal cost, one per XCD
+  int32_t tile_blocks = 0;
+  {
+    int32_t* xo = w + H_XCD_OFF;
+    for (int x = 0; x <= 8; ++x) xo[x] = 0;
+    if (n_tiles > 0) {
+      auto cost = [&](const int32_t* t) -> int64_t {
+        return t[T_KIND] == TILE_SHARED ? (t[T_PAGE1] - t[T_PAGE0] + 1) / 2 + 1
+                                        : ((int64_t)t[T_LEN] + t[T_AUX] + t[T_COUNT] + 31) / 32 + 1;
+      };
+      // groups = runs of tiles with the same page table and kv head, split so that none exceeds 1/16 of the work
+      int64_t total = 0;
+      for (int64_t i = 0; i < n_tiles; ++i) total += cost(tiles + i * TILE_WORDS);
+      const int64_t cap = std::max<int64_t>(1, total / 16);
+      auto& groups = out->tile_groups;                    // (cost, first tile); the next group's first tile ends it
+      groups.clear();
+      int64_t acc = 0;
+      for (int64_t i = 0; i < n_tiles; ++i) {
+        const int32_t* t = tiles + i * TILE_WORDS;
+        const bool same = i > 0 && t[T_TBL] == t[-TILE_WORDS + T_TBL] && t[T_HEAD] == t[-TILE_WORDS + T_HEAD] && t[T_KIND] == t[-TILE_WORDS + T_KIND];
+        if (!same || acc >= cap) {
+          groups.emplace_back(0, (int32_t)i);
+          acc = 0;
+        }
+        acc += cost(t);
+        groups.back().first += cost(t);
+      }
+      const size_t ng = groups.size();
+      auto& order = out->tile_order;                      // group indices, heaviest first
+      order.resize(ng);
+      for (size_t i = 0; i < ng; ++i) order[i] = (int32_t)i;
+      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return groups[x].first > groups[y].first; });
+      int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      std::vector<int32_t> share_of(ng);
+      int32_t count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int32_t gi : order) {
+        int best = 0;
+        for (int x = 1; x < 8; ++x)
+          if (load[x] < load[best]) best = x;
+        share_of[gi] = best;
+        load[best] += groups[gi].first;
+        const int32_t gend = (size_t)gi + 1 < ng ? groups[gi + 1].second : (int32_t)n_tiles;
+        count[best] += gend - groups[gi].second;
+      }
+      for (int x = 0; x < 8; ++x) xo[x + 1] = xo[x] + count[x];
+      // rewrite the list share by share (groups in heaviest-first order inside a share)
+      auto& tmp = out->tile_tmp;
+      tmp.assign(tiles, tiles + n_tiles * TILE_WORDS);
+      int32_t pos[8];
+      for (int x = 0; x < 8; ++x) pos[x] = xo[x];
+      for (int32_t gi : order) {
+        const int32_t gend = (size_t)gi + 1 < ng ? groups[gi + 1].second : (int32_t)n_tiles;
+        const int32_t n = gend - groups[gi].second;
+        std::memcpy(tiles + (int64_t)pos[share_of[gi]] * TILE_WORDS, tmp.data() + (int64_t)groups[gi].second * TILE_WORDS,
+                    (size_t)n * TILE_WORDS * sizeof(int32_t));
+        pos[share_of[gi]] += n;
+      }
+      for (int x = 0; x < 8; ++x) tile_blocks = std::max(tile_blocks, 8 * count[x]);
+    }
+    w[H_TILE_BLOCKS] = tile_blocks;
+  }
+
   // every (member row, head): extra partials first + i * stride, i < count
   if (n_members > 0) {
     // merge entries are sorted by word 2 (q row * Hq + first head), as are the LIPs by q row
@@ -368,6 +435,8 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   out->n_tiles = (int32_t)n_tiles;
   out->total_units = total_units;
   out->max_row_tokens = max_nt;
+  out->tile_blocks = tile_blocks;
+  out->tile_rows = TQ * G;
   return SYM_OK;
 }
 

@@ -13,6 +13,10 @@
 //    A LIP that brings a few new tokens (a short draft to verify, paper section 4.1) packs up to
 //    row_tokens consecutive ones into one row: they share a single pass over the file, each
 //    with its own visible length.
+// Workgroups are handed to the 8 XCDs of the GPU round-robin, and each XCD has its own L2.  The
+// tile list is therefore cut into 8 shares of equal cost (32-token K/V blocks to walk): tiles that
+// read the same K/V (same file, same kv head) stay together in one share, longest first; workgroup
+// b runs tile b / 8 of share b % 8.
 // The work of the decode kernel is measured in units of one (page, kv head) = one 8 KiB K+V
 // slab; the units of all rows, ordered (row, kv head, page), are cut into n_waves contiguous
 // ranges of equal cost, one per wavefront, whatever the raggedness of the files.  A range
@@ -27,12 +31,14 @@
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 20, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 8, TILE_WORDS = 12 };
+enum { DESC_HEADER_WORDS = 32, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 8, TILE_WORDS = 12 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,
   H_OFF_ROWS, H_OFF_WAVES, H_OFF_MERGE, H_OFF_PT, H_OFF_PTOFF, H_OFF_TILES, H_TOTAL_WORDS,
-  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI, H_N_MERGE, H_OFF_MEMBERS, H_N_MEMBERS, H_N_SHARED_TILES
+  H_TOTAL_UNITS_LO, H_TOTAL_UNITS_HI, H_N_MERGE, H_OFF_MEMBERS, H_N_MEMBERS, H_N_SHARED_TILES,
+  H_TILE_BLOCKS = 18,     // workgroups of the tile part of the launch = 8 * (tiles of the fullest share)
+  H_XCD_OFF = 20          // 9 words: share x of the tile list is [H_XCD_OFF + x, H_XCD_OFF + x + 1)
 };
 // tile words
 enum { T_TBL = 0, T_LEN, T_QROW, T_COUNT, T_HEAD, T_AUX, T_KIND, T_PAGE0, T_PAGE1 };
@@ -48,10 +54,14 @@ struct BatchDesc {
   int32_t* words = nullptr;
   int64_t n_words = 0;
   int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
+  int32_t tile_blocks = 0;      // workgroups the tile part of the launch needs
+  int32_t tile_rows = 0;        // query rows of this batch's tiles (128 or 256)
   int32_t max_row_tokens = 1;   // > 1: some row holds several new tokens (needs the matrix-core decode kernel)
   int64_t total_units = 0;
   // scratch of the builder, kept between calls
   std::vector<std::pair<int32_t, int32_t>> by_first_page, lcp;
+  std::vector<int32_t> tile_tmp, tile_order;
+  std::vector<std::pair<int64_t, int32_t>> tile_groups;
   std::vector<int32_t> share_start, share_base, share_k, share_ml, share_nc, member_rows, shared_tiles, qrow_of, groups, grp_members;
 };
 

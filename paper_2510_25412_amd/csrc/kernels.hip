@@ -95,7 +95,7 @@ struct PageRegs {
 // wavefront 1 the V half, they exchange them through LDS (written and read in the same
 // lane-linear 1 KiB runs, so without bank conflicts), and every page is still read from HBM once.
 template <typename E, int GT, int G>
-__device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block, uint8_t (*plds)[kSlab]) {
+__device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block, uint8_t (*plds)[kSlab], const int wpb = kWavesPerBlock) {
   constexpr bool kPair = G < GT;
   const int hs = kPair ? (int)(threadIdx.x >> 6) : 0;      // which wavefront of the pair
   const int h0 = hs * G;                                    // first head (within the group) of this wavefront
@@ -103,7 +103,7 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
   constexpr int DPL = 2 * C;             // dims per lane
   constexpr int D = 16 * C;              // head dim
   const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(kPair ? block : block * kWavesPerBlock + (int)(threadIdx.x >> 6));
+  const int wv = __builtin_amdgcn_readfirstlane(kPair ? block : block * wpb + (int)(threadIdx.x >> 6));
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
@@ -405,22 +405,22 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-constexpr int kTileRows = 128;            // query rows per workgroup
 constexpr int kKvBlock = 32;              // tokens per K/V block
 constexpr int kKLds = kKvBlock * kRowBytes;      // 8 KiB: K block, 16-byte chunks, xor-swizzled
 constexpr int kVRow = 80;                 // bytes per dim row of V^T in LDS (64 + 16 pad: conflict-free reads)
 constexpr int kVLds = 128 * kVRow;        // 10 KiB
 
-template <int G, int CT>
+template <int G, int TW>
 __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block, uint8_t (*lds)[kKLds + kVLds]) {
-  // CT = 32-row column tiles per wavefront (a tile has 128*CT query rows); every K / V^T operand read
-  // from LDS feeds CT MFMAs.  CT = 2 was measured: it needs one wavefront per SIMD (~500 registers)
-  // and is 1.7x slower than CT = 1 with two, so CT = 1 is what runs.
-  // tiles that read the same K/V are neighbours in the list; blocks go round-robin over the 8
-  // XCDs, so give each XCD a contiguous run of the list (only locality depends on this)
-  const int per_xcd = (a.n_tiles + 7) / 8;
-  const int tile = (block % 8) * per_xcd + block / 8;
-  if (tile >= a.n_tiles) return;
+  // TW = wavefronts of the workgroup (4 or 8); a tile has 32 * TW query rows that share one staging
+  // of every K/V block, so K/V bytes read per flop (from L2, and written to LDS) halve with TW = 8.
+  // (Two 32-row column tiles per wavefront instead were measured: ~500 registers, one wavefront per
+  // SIMD, 1.7x slower.)
+  constexpr int CT = 1;
+  // workgroups go round-robin over the 8 XCDs; the tile list comes in 8 shares of equal cost in which
+  // tiles that read the same K/V are neighbours (one L2 per XCD), longest first
+  const int tile = a.xcd_off[block % 8] + block / 8;
+  if (tile >= a.xcd_off[block % 8 + 1]) return;
   const int32_t* tw = a.tiles + (int64_t)(a.tile_first + tile) * 12;
   const int tbl_off = tw[0], g = tw[4], count = tw[3];
   const bool shared = tw[6] != 0;
@@ -455,24 +455,40 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
   }
 
   // ---- staging roles
-  // K: thread copies chunks c = tid and tid + 256 of the block: token c/16, dim chunk c%16
-  // V: thread takes tokens (4*q4 + 2*up, +1) of page pg, dim chunk vc: 8 dims x 2 tokens
-  const int up = tid & 1, q4 = (tid >> 1) & 3, vc = (tid >> 3) & 15, pg = tid >> 7;
+  // K: thread copies chunk c = tid (and tid + 256 with four wavefronts) of the block: token c/16, dim chunk c%16
+  // V: thread takes tokens (4*q4 + 2*up, +1) of page pg, dim chunk vc: VD dims x 2 tokens
+  constexpr int VD = TW == 4 ? 8 : 4;                       // dims per thread
+  const int up = tid & 1, q4 = (tid >> 1) & 3, vc = (tid >> 3) & (128 / VD - 1), pg = tid >> (TW == 4 ? 7 : 8);
   // K/V of the blocks in flight (loaded three blocks ahead of their use): three register sets
   uint4 ka0, ka1, va0, va1, kb0r, kb1r, vb0, vb1, kc0, kc1, vc0, vc1;
   const uint8_t* slab = a.pool + (int64_t)g * kSlab;
-  auto k_src = [&](int kb, int c) {
-    const int t = c >> 4, dc = c & 15;
-    const int pi = min(2 * kb + (t >> 4), last_page);
-    return slab + (int64_t)tbl[pi] * a.page_bytes + (dc >> 3) * (kP * kHalfBytes) + (t & 15) * kHalfBytes + (dc & 7) * 16;
+  // Which of the block's two pages a thread stages is the same for its whole wavefront, so the page
+  // ids come through the scalar cache and the page base is scalar arithmetic; what differs per
+  // thread is a fixed offset inside the page, computed once.
+  const int wvu = __builtin_amdgcn_readfirstlane(wv);
+  const int k_page = TW == 4 ? 0 : (wvu >> 2);            // chunk tid: page of the block (chunk tid + 256: the other one)
+  const int v_page = TW == 4 ? (wvu >> 1) : (wvu >> 2);
+  const int kt = (tid >> 4) & 15, kdc = tid & 15;
+  const int k_off = (kdc >> 3) * (kP * kHalfBytes) + kt * kHalfBytes + (kdc & 7) * 16;
+  const int dbyte = vc * VD * 2;                            // byte offset of the thread's dims in the 256-byte row
+  const int v_off = kBlk + (dbyte >> 7) * (kP * kHalfBytes) + (4 * q4 + 2 * up) * kHalfBytes + (dbyte & 127);
+  auto page_base = [&](int pi) {
+    const int pid = __builtin_amdgcn_readfirstlane(tbl[min(pi, last_page)]);
+    return slab + (int64_t)pid * a.page_bytes;
   };
   auto issue_loads = [&](int kb, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
-    k0 = *(const uint4*)k_src(kb, tid);
-    k1 = *(const uint4*)k_src(kb, tid + 256);
-    const int pi = min(2 * kb + pg, last_page);
-    const uint8_t* p = slab + (int64_t)tbl[pi] * a.page_bytes + kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * q4 + 2 * up) * kHalfBytes + (vc & 7) * 16;
-    v0 = *(const uint4*)p;
-    v1 = *(const uint4*)(p + kHalfBytes);
+    const uint8_t* pk = page_base(2 * kb + k_page);
+    k0 = *(const uint4*)(pk + k_off);
+    if constexpr (TW == 4) k1 = *(const uint4*)(page_base(2 * kb + 1) + k_off);
+    const uint8_t* p = (TW == 4 ? page_base(2 * kb + v_page) : pk) + v_off;
+    if constexpr (TW == 4) {
+      v0 = *(const uint4*)p;
+      v1 = *(const uint4*)(p + kHalfBytes);
+    } else {
+      const uint2 x0 = *(const uint2*)p, x1 = *(const uint2*)(p + kHalfBytes);
+      v0.x = x0.x; v0.y = x0.y;
+      v1.x = x1.x; v1.y = x1.y;
+    }
   };
   auto k_dst = [&](uint8_t* base, int c) {
     const int t = c >> 4, dc = c & 15;
@@ -480,11 +496,13 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
   };
   auto store_lds = [&](int kb, uint8_t* base, const uint4& k0, const uint4& k1, const uint4& v0, const uint4& v1) {
     *(uint4*)k_dst(base, tid) = k0;
-    *(uint4*)k_dst(base, tid + 256) = k1;
-    // tokens past the end of what the tile may see are cleared (their weight is 0, 0 * NaN is not)
+    if constexpr (TW == 4) *(uint4*)k_dst(base, tid + 256) = k1;
+    // tokens past the end of what the tile may see are cleared (their weight is 0, 0 * NaN is not);
+    // only the last block can hold such tokens
     const int tok = kb * kKvBlock + pg * 16 + 4 * q4 + 2 * up;
-    const bool ok0 = tok < kv_end, ok1 = tok + 1 < kv_end;
-    uint8_t* vb = base + kKLds + (2 * pg + (q4 & 1)) * 16 + (q4 >> 1) * 8 + up * 4 + vc * 8 * kVRow;
+    const bool tail = kb * kKvBlock + kKvBlock > kv_end;
+    const bool ok0 = !tail || tok < kv_end, ok1 = !tail || tok + 1 < kv_end;
+    uint8_t* vb = base + kKLds + (2 * pg + (q4 & 1)) * 16 + (q4 >> 1) * 8 + up * 4 + vc * VD * kVRow;
     auto put = [&](int e, uint32_t lo_word0, uint32_t lo_word1, bool high) {
       const uint32_t x0 = high ? (lo_word0 & 0xffff0000u) : (lo_word0 << 16);
       const uint32_t x1 = high ? (lo_word1 & 0xffff0000u) : (lo_word1 << 16);
@@ -493,8 +511,10 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     };
     put(0, v0.x, v1.x, false); put(1, v0.x, v1.x, true);
     put(2, v0.y, v1.y, false); put(3, v0.y, v1.y, true);
-    put(4, v0.z, v1.z, false); put(5, v0.z, v1.z, true);
-    put(6, v0.w, v1.w, false); put(7, v0.w, v1.w, true);
+    if constexpr (TW == 4) {
+      put(4, v0.z, v1.z, false); put(5, v0.z, v1.z, true);
+      put(6, v0.w, v1.w, false); put(7, v0.w, v1.w, true);
+    }
   };
 
   f32x16_t O[CT][4];
@@ -520,23 +540,35 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     issue_loads(kb + 3, k0, k1, v0, v1);
     if (!wave_live) return;
 
-    // S^T = K Q^T for 32 tokens x 32 rows per column tile; each K operand read feeds CT MFMAs
+    // S^T = K Q^T for 32 tokens x 32 rows per column tile; each K operand read feeds CT MFMAs.
+    // All eight K operands are requested from LDS before the first MFMA, and all eight V^T operands
+    // before the softmax arithmetic (they reuse the K operands' registers), so the LDS latency is
+    // paid once per phase and not once per MFMA; the scheduling fences keep that order.
     f32x16_t S[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int v = 0; v < 16; ++v) S[ct][v] = 0.f;
+    bf16x8_t kk[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8_t kk = *(const bf16x8_t*)(base + (col * 16 + ((2 * ks + hf) ^ (col & 15))) * 16);
+    for (int ks = 0; ks < 8; ++ks) kk[ks] = *(const bf16x8_t*)(base + (col * 16 + ((2 * ks + hf) ^ (col & 15))) * 16);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) S[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, q[ct][ks], S[ct], 0, 0, 0);
-    }
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) S[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[ks], q[ct][ks], S[ct], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    const uint8_t* vbase = base + kKLds + col * kVRow + hf * 16;
+    f16x8_t vv[4][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) vv[db][ks] = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
+    __builtin_amdgcn_sched_barrier(0);
     // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
     // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
     const int tok0 = kb * kKvBlock + 4 * hf;
     const bool edge = kb * kKvBlock + kKvBlock > mask_from;      // the block reaches the causal edge of some row
-    f16x8_t P[CT][2];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       float mx = -__builtin_inff();
@@ -560,27 +592,25 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
           for (int v = 0; v < 16; ++v) O[ct][db][v] *= al;
         m[ct] = mn;
       }
-      uint32_t pw[8];
-#pragma unroll
-      for (int v = 0; v < 16; v += 2) {
-        const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v], a.scale_log2e, -m[ct])),
-                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v + 1], a.scale_log2e, -m[ct])));
-        l[ct] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[ct], false);
-        pw[v >> 1] = __builtin_bit_cast(uint32_t, pk);
-      }
-      P[ct][0] = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-      P[ct][1] = __builtin_bit_cast(f16x8_t, make_uint4(pw[4], pw[5], pw[6], pw[7]));
-    }
-    // O^T += V^T P^T; each V^T operand read feeds CT MFMAs
-    const uint8_t* vbase = base + kKLds + col * kVRow + hf * 16;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
+      // weights of the block's first 16 tokens, their O^T += V^T P^T MFMAs (four independent accumulators),
+      // then the second 16 tokens' weights while those MFMAs run
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const f16x8_t vv = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
+        uint32_t pw[4];
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) O[ct][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv, P[ct][ks], O[ct][db], 0, 0, 0);
+        for (int u = 0; u < 8; u += 2) {
+          const int v = 8 * ks + u;
+          const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v], a.scale_log2e, -m[ct])),
+                                                     __builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v + 1], a.scale_log2e, -m[ct])));
+          l[ct] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[ct], false);
+          pw[u >> 1] = __builtin_bit_cast(uint32_t, pk);
+        }
+        const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) O[ct][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv[db][ks], P, O[ct][db], 0, 0, 0);
       }
+    }
   };
 
   issue_loads(kb0, ka0, ka1, va0, va1);
@@ -852,16 +882,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs da) {
 // ranges, four wavefronts per workgroup.  One grid, so the two kinds of work fill the GPU
 // together and there is no launch boundary between them.
 // ---------------------------------------------------------------------------------------
-template <typename E, int G>
-__global__ __launch_bounds__(256, 2) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
+template <typename E, int G, int TW>
+__global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
   if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
     __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
     if ((int)blockIdx.x < tile_blocks) {
-      tile_block<G, 1>(pa, blockIdx.x, lds);
+      tile_block<G, TW>(pa, blockIdx.x, lds);
       return;
     }
   }
-  if constexpr (G < 8) decode_ranges<E, G, G>(da, blockIdx.x - tile_blocks, nullptr);
+  if constexpr (G < 8) decode_ranges<E, G, G>(da, blockIdx.x - tile_blocks, nullptr, TW);
 }
 
 // Decode ranges for 8 query heads per kv head: one workgroup of two wavefronts per range.
@@ -1096,16 +1126,22 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   const int mode = (E::kDimsPerChunk == 8 && decode_mode == 1) ? 1 : (G == 8 ? 2 : 0);
   PrefillArgs ps = pa;
   ps.tile_first = 0;
-  const int tile_blocks = ((ps.n_tiles + 7) / 8) * 8;
-  const int decode_blocks = mode == 0 ? (da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock : 0;
-  const dim3 grid(tile_blocks + decode_blocks), block(256);
+  const int tile_blocks = ps.n_tiles > 0 ? ps.tile_blocks : 0;
+  // eight-wavefront workgroups when the tiles have 256 query rows (and no tile is there: four)
+  const int tw = (ps.n_tiles > 0 && ps.tile_rows == 256) ? 8 : 4;
+  const int decode_blocks = mode == 0 ? (da.n_waves + tw - 1) / tw : 0;
+  const dim3 grid(tile_blocks + decode_blocks), block(256), block8(512);
+  if (ps.n_tiles > 0 && ps.tile_rows != 128 && ps.tile_rows != 256) return hipErrorInvalidValue;
+#define SYM_ATTN_CASE(GG) \
+  case GG: \
+    if (tw == 8) hipLaunchKernelGGL((attn_kernel<E, GG, 8>), grid, block8, 0, st, da, ps, tile_blocks); \
+    else hipLaunchKernelGGL((attn_kernel<E, GG, 4>), grid, block, 0, st, da, ps, tile_blocks); \
+    break;
   if (grid.x > 0) switch (G) {
-    case 1: hipLaunchKernelGGL((attn_kernel<E, 1>), grid, block, 0, st, da, ps, tile_blocks); break;
-    case 2: hipLaunchKernelGGL((attn_kernel<E, 2>), grid, block, 0, st, da, ps, tile_blocks); break;
-    case 4: hipLaunchKernelGGL((attn_kernel<E, 4>), grid, block, 0, st, da, ps, tile_blocks); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<E, 8>), grid, block, 0, st, da, ps, tile_blocks); break;
+    SYM_ATTN_CASE(1) SYM_ATTN_CASE(2) SYM_ATTN_CASE(4) SYM_ATTN_CASE(8)
     default: return hipErrorInvalidValue;
   }
+#undef SYM_ATTN_CASE
   if (da.n_waves > 0 && mode == 2) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);
   if (da.n_waves > 0 && mode == 1) {
     const dim3 dgrid((da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);

@@ -35,7 +35,10 @@ struct PrefillArgs {
   const int32_t* members;   // q rows of the members of shared-prefix tiles
   float* part_acc;          // partial results (shared-prefix tiles)
   float* part_ml;
+  const int32_t* xcd_off;   // [9]: workgroup b runs tile xcd_off[b % 8] + b / 8 if that is below xcd_off[b % 8 + 1]
+  int32_t tile_blocks;      // workgroups of the tile part of the launch (multiple of 8)
   int32_t tile_first, n_tiles;   // the launch covers tiles [tile_first, tile_first + n_tiles)
+  int32_t tile_rows;             // query rows per tile: 128 (four wavefronts per workgroup) or 256 (eight)
   int32_t Hq, Hkv;
   float scale_log2e;
 };

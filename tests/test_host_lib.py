@@ -321,9 +321,12 @@ def test_descriptor_rejects_bad_tables():
         c.build_desc([0], np.array([1], np.int32), [0, 1], [4])
 
 
-def test_descriptor_tiles_for_prefill_chunks():
-    """LIPs with 16+ new tokens become tiles (one per kv head and 32 new tokens at 4 heads per
-    group: 128 query rows); the others stay decode rows; q rows keep the batch's token order."""
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_descriptor_tiles_for_prefill_chunks(tile_rows, monkeypatch):
+    """LIPs with 16+ new tokens become tiles (one per kv head and tile_rows / 4 new tokens at 4 heads
+    per group); the others stay decode rows; q rows keep the batch's token order."""
+    monkeypatch.setenv("SYM_TILE_ROWS", str(tile_rows))
+    TQ = tile_rows // 4
     c = host_ctx(4096)
     lengths, n_tok = [100, 77, 40, 16], [70, 1, 3, 16]
     np_l = [-(-L // 16) for L in lengths]
@@ -332,14 +335,29 @@ def test_descriptor_tiles_for_prefill_chunks():
     words = c.build_desc(n_tok, flat, off, lengths)
     hdr = words[:20]
     n_rows, n_tiles = int(hdr[0]), int(hdr[4])
-    assert n_rows == 2 and n_tiles == (3 + 1) * 8            # the 3-token LIP is one row of three tokens
+    starts = list(range(0, 70, TQ))
+    assert n_rows == 2 and n_tiles == (len(starts) + 1) * 8      # the 3-token LIP is one row of three tokens
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
     assert rows[:, 2].tolist() == [70, 71] and rows[:, 0].tolist() == [int(off[1]), int(off[2])]
     assert rows[:, 1].tolist() == [77, 38] and rows[:, 3].tolist() == [0, 2 << 28]
     tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
-    exp = [(int(off[0]), 30, t0, min(32, 70 - t0), g, t0, 0) for g in range(8) for t0 in (0, 32, 64)]
+    exp = [(int(off[0]), 30, t0, min(TQ, 70 - t0), g, t0, 0) for g in range(8) for t0 in starts]
     exp += [(int(off[3]), 0, 74, 16, g, 0, 0) for g in range(8)]
-    assert [tuple(int(x) for x in t[:7]) for t in tiles] == exp
+    assert sorted(tuple(int(x) for x in t[:7]) for t in tiles) == sorted(exp)
+    # the list comes in 8 shares (one per XCD), tiles of one (file, kv head) together in one share, costs balanced
+    xo = words[20:29].tolist()
+    assert xo[0] == 0 and xo[8] == n_tiles and all(a <= b for a, b in zip(xo, xo[1:]))
+    assert int(words[18]) == 8 * max(b - a for a, b in zip(xo, xo[1:]))
+    cost = lambda t: -(-(int(t[1]) + int(t[5]) + int(t[3])) // 32) + 1
+    loads, where = [], {}
+    for x in range(8):
+        share = tiles[xo[x]:xo[x + 1]]
+        loads.append(sum(cost(t) for t in share))
+        for t in share:
+            where.setdefault((int(t[0]), int(t[4])), set()).add(x)
+    assert all(len(v) == 1 for v in where.values())
+    group_cost = max(sum(cost(t) for t in tiles if (int(t[0]), int(t[4])) == k) for k in where)
+    assert max(loads) - min(loads) <= group_cost
     # fp32 storage has no tile kernel: everything is a row
     c32 = host_ctx(4096, Hq=8, Hkv=8, D=64, dtype="f32")
     w32 = c32.build_desc(n_tok, flat, off, lengths)
