@@ -302,7 +302,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "long", "draft", "prune", "offload", "rag"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "fork", "mixed", "prefill", "long", "draft", "prune", "offload", "rag"], default="decode")
     ap.add_argument("--layers", type=int, default=None, help="independent layer pools rotated over (cache honesty)")
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
@@ -335,6 +335,8 @@ def main():
                       "private suffix U{1..256}, 32Q/8KV, bf16, 1 new token each"),
              "mixed": (synth.config4, 1, 20, 3, True, 0.0, "mixed: 32 LIPs x 512-token prefill chunk on U{0..8192} + 224 decode LIPs "
                        "U{1024..4096}, 32Q/8KV, bf16 (files truncated back after every step)"),
+             "prefill": (lambda: synth.config4(n_decode=0), 1, 20, 3, True, 0.0, "prefill only: the 32 prefill LIPs of the mixed batch (512-token chunk on "
+                         "U{0..8192}), 32Q/8KV, bf16 (files truncated back after every step)"),
              "draft": (lambda: synth.config2(n_new=4, slack_pages=4096), 4, 200, 20, False, 0.0, "draft verify: the decode batch (64 LIPs, 32Q/8KV, "
                        "bf16, contexts U{512..4096}) with 4 new tokens per LIP and call"),
              "long": (lambda: synth.config5(n_pages=args.pool_pages), 1, 50, 5, False, 0.0, "long context: 16 LIPs U{32768..131072}, "

@@ -529,97 +529,118 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
       for (int v = 0; v < 16; ++v) O[ct][db][v] = 0.f;
   }
 
-  // One block: its K/V (loaded three blocks ago) goes to LDS, the loads of the block three
-  // ahead are issued into the same registers, then the block is computed.  All loads and all
-  // blocks are unconditional: past the end the last pages are loaded again and every token is
-  // masked, so the loop (unrolled by three) has no control-flow join between a load and its use.
-  auto do_block = [&](const int kb, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
-    uint8_t* base = lds[kb & 1];
-    store_lds(kb, base, k0, k1, v0, v1);
-    __syncthreads();           // block kb is in LDS; everyone is done with the other buffer's previous block
-    issue_loads(kb + 3, k0, k1, v0, v1);
-    if (!wave_live) return;
-
-    // S^T = K Q^T for 32 tokens x 32 rows per column tile; each K operand read feeds CT MFMAs.
-    // All eight K operands are requested from LDS before the first MFMA, and all eight V^T operands
-    // before the softmax arithmetic (they reuse the K operands' registers), so the LDS latency is
-    // paid once per phase and not once per MFMA; the scheduling fences keep that order.
-    f32x16_t S[CT];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) S[ct][v] = 0.f;
-    bf16x8_t kk[8];
+  // The block loop is software-pipelined over three LDS buffers.  One step: block kb + 1 (loaded three
+  // steps ago) goes from registers to LDS, the loads of block kb + 4 are issued into the same
+  // registers, then the matrix cores start S^T = K Q^T of block kb + 1 while the vector units do the
+  // softmax arithmetic of block kb, and O^T += V^T P^T of block kb follows.  So the MFMAs of one block
+  // run under the vector work of its neighbour inside one wavefront, not only across wavefronts.
+  // All loads and all blocks are unconditional: past the end the last pages are loaded again and
+  // every token is masked, so the loop (unrolled by three) has no control-flow join between a load
+  // and its use.  One barrier per step: the buffer a step writes was last read two steps earlier.
+  auto k_operands = [&](const uint8_t* base, bf16x8_t (&kk)[8]) {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kk[ks] = *(const bf16x8_t*)(base + (col * 16 + ((2 * ks + hf) ^ (col & 15))) * 16);
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto scores = [&](const bf16x8_t (&kk)[8]) {
+    f32x16_t S;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int v = 0; v < 16; ++v) S[v] = 0.f;
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) S[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[ks], q[ct][ks], S[ct], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    const uint8_t* vbase = base + kKLds + col * kVRow + hf * 16;
+    for (int ks = 0; ks < 8; ++ks) S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[ks], q[0][ks], S, 0, 0, 0);
+    return S;
+  };
+  f32x16_t Sc;                   // scores of the current block (computed one step ahead)
+  auto step = [&](const int kb, uint8_t* cur, uint8_t* nxt, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
+    store_lds(kb + 1, nxt, k0, k1, v0, v1);
+    __syncthreads();           // block kb + 1 is in LDS; everyone is done with the block that was in `nxt` before
+    issue_loads(kb + 4, k0, k1, v0, v1);
+    if (!wave_live) return;
+
+    // operands of both MFMA phases are requested from LDS up front: the latency is paid once per step
+    bf16x8_t kk[8];
+    k_operands(nxt, kk);
+    const uint8_t* vbase = cur + kKLds + col * kVRow + hf * 16;
     f16x8_t vv[4][2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int db = 0; db < 4; ++db) vv[db][ks] = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
     __builtin_amdgcn_sched_barrier(0);
+
     // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
     // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
     const int tok0 = kb * kKvBlock + 4 * hf;
     const bool edge = kb * kKvBlock + kKvBlock > mask_from;      // the block reaches the causal edge of some row
+    float mx = -__builtin_inff();
+    if (edge) {
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-      float mx = -__builtin_inff();
-      if (edge) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int tok = tok0 + 8 * (v >> 2) + (v & 3);
-          S[ct][v] = tok < vis[ct] ? S[ct][v] : -__builtin_inff();
-        }
-      }
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[ct][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
-      if (__builtin_amdgcn_ballot_w64(mx > m[ct] + kTau) != 0) {     // rare after the first block
-        const float mn = fmaxf(m[ct], mx);
-        const float al = __builtin_amdgcn_exp2f(m[ct] - mn);
-        l[ct] *= al;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) O[ct][db][v] *= al;
-        m[ct] = mn;
-      }
-      // weights of the block's first 16 tokens, their O^T += V^T P^T MFMAs (four independent accumulators),
-      // then the second 16 tokens' weights while those MFMAs run
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        uint32_t pw[4];
-#pragma unroll
-        for (int u = 0; u < 8; u += 2) {
-          const int v = 8 * ks + u;
-          const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v], a.scale_log2e, -m[ct])),
-                                                     __builtin_amdgcn_exp2f(__builtin_fmaf(S[ct][v + 1], a.scale_log2e, -m[ct])));
-          l[ct] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[ct], false);
-          pw[u >> 1] = __builtin_bit_cast(uint32_t, pk);
-        }
-        const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) O[ct][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv[db][ks], P, O[ct][db], 0, 0, 0);
+      for (int v = 0; v < 16; ++v) {
+        const int tok = tok0 + 8 * (v >> 2) + (v & 3);
+        Sc[v] = tok < vis[0] ? Sc[v] : -__builtin_inff();
       }
     }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, Sc[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
+    if (__builtin_amdgcn_ballot_w64(mx > m[0] + kTau) != 0) {     // rare after the first block
+      const float mn = fmaxf(m[0], mx);
+      const float al = __builtin_amdgcn_exp2f(m[0] - mn);
+      l[0] *= al;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[0][db][v] *= al;
+      m[0] = mn;
+    }
+    // From here to the end of the step there is no branch: the scores of block kb + 1 (eight MFMAs)
+    // run under the exponentials of block kb; then the weights of the block's first 16 tokens, their
+    // O^T += V^T P^T MFMAs (four independent accumulators), and the second 16 tokens' weights while those run.
+    const f32x16_t Sn = scores(kk);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      uint32_t pw[4];
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        const int v = 8 * ks + u;
+        const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(Sc[v], a.scale_log2e, -m[0])),
+                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[v + 1], a.scale_log2e, -m[0])));
+        l[0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[0], false);
+        pw[u >> 1] = __builtin_bit_cast(uint32_t, pk);
+      }
+      const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+#pragma unroll
+      for (int db = 0; db < 4; ++db) O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vv[db][ks], P, O[0][db], 0, 0, 0);
+    }
+    // issue order of this stretch: one MFMA, then a few vector instructions, sixteen times (the first
+    // eight MFMAs are the scores of the next block, which depend on nothing computed here)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 4, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);
+    }
+    Sc = Sn;
   };
 
   issue_loads(kb0, ka0, ka1, va0, va1);
   issue_loads(kb0 + 1, kb0r, kb1r, vb0, vb1);
   issue_loads(kb0 + 2, kc0, kc1, vc0, vc1);
+  store_lds(kb0, lds[0], ka0, ka1, va0, va1);
+  __syncthreads();
+  issue_loads(kb0 + 3, ka0, ka1, va0, va1);
+  if (wave_live) {
+    bf16x8_t kk[8];
+    k_operands(lds[0], kk);
+    Sc = scores(kk);
+  }
   for (int kb = kb0; kb < nblk; kb += 3) {
-    do_block(kb, ka0, ka1, va0, va1);
-    do_block(kb + 1, kb0r, kb1r, vb0, vb1);
-    do_block(kb + 2, kc0, kc1, vc0, vc1);
+    step(kb, lds[0], lds[1], kb0r, kb1r, vb0, vb1);
+    step(kb + 1, lds[1], lds[2], kc0, kc1, vc0, vc1);
+    step(kb + 2, lds[2], lds[0], ka0, ka1, va0, va1);
   }
 
 #pragma unroll
@@ -885,7 +906,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs da) {
 template <typename E, int G, int TW>
 __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_blocks) {
   if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
-    __shared__ __align__(16) uint8_t lds[2][kKLds + kVLds];
+    __shared__ __align__(16) uint8_t lds[3][kKLds + kVLds];
     if ((int)blockIdx.x < tile_blocks) {
       tile_block<G, TW>(pa, blockIdx.x, lds);
       return;
