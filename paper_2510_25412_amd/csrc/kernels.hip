@@ -94,6 +94,284 @@ struct PageRegs {
 // per range, each with half of the heads; wavefront 0 fetches the K half of every page,
 // wavefront 1 the V half, they exchange them through LDS (written and read in the same
 // lane-linear 1 KiB runs, so without bank conflicts), and every page is still read from HBM once.
+// ---------------------------------------------------------------------------------------
+// Decode ranges as ONE page stream per wavefront (the VALU kernel for up to 4 query heads per kv
+// head).  A wavefront's units (row, kv head, page) are consecutive in the batch order, but they
+// belong to several (row, head) ranges when files are short; starting every range with its own
+// chain of dependent loads (row record -> page ids -> K/V) costs several memory latencies per
+// range, a third of the time at 10 pages per range.  Here a LOAD cursor runs two pages ahead of
+// the COMPUTE cursor through the same unit sequence, across range boundaries, so the K/V stream
+// never drains; the query rows of the next range are fetched one range ahead.  At a boundary the
+// compute side only combines its 8 token slots, writes the result and switches to the next
+// range's registers.
+// ---------------------------------------------------------------------------------------
+template <typename E, int G>
+__device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int block, const int wpb) {
+  constexpr int C = E::kDimsPerChunk;    // dims per 16-byte chunk
+  constexpr int DPL = 2 * C;             // dims per lane
+  constexpr int D = 16 * C;              // head dim
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(block * wpb + (int)(threadIdx.x >> 6));
+  if (wv >= a.n_waves) return;
+  const int r = lane >> 3, j = lane & 7;
+  auto sload = [&](const int32_t* ptr) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(*ptr); };
+
+  const int32_t* ww = a.waves + wv * 12;
+  // compute cursor: the range being accumulated
+  int row = sload(ww + 0), g = sload(ww + 1), p = sload(ww + 2);
+  int remaining = sload(ww + 3);
+  int part = sload(ww + 4);
+  int vis = sload(ww + 5), qrow = sload(ww + 6);
+  const int tbl0 = sload(ww + 7), pid_first = sload(ww + 8);
+  int pstart = sload(ww + 11) & 0x0fffffff;
+  int np = (vis + kP - 1) / kP;
+  // load cursor: the unit whose K/V is requested next (two pages ahead of the compute cursor)
+  int lrow = row, lg = g, lp = p, lnp = np, ltbl = tbl0, lpstart = pstart, lrem = remaining;
+  // record of the row after the load cursor's (fetched a whole row ahead of its use)
+  int n_tbl = 0, n_vis = 0, n_qrow = 0, n_pstart = 0;
+  auto fetch_next_row = [&](int rr) __attribute__((always_inline)) {      // rr may be one past the last row: the rows section is followed by valid words
+    n_tbl = sload(a.rows + rr * 4 + 0);
+    n_vis = sload(a.rows + rr * 4 + 1);
+    n_qrow = sload(a.rows + rr * 4 + 2);
+    n_pstart = sload(a.rows + rr * 4 + 3) & 0x0fffffff;
+  };
+  fetch_next_row(row + 1);
+  // (row, head) after the compute cursor's, for the query prefetch
+  int c_nqrow = 0, c_nvis = 0, c_npstart = 0;      // record of row + 1 as seen by the compute side
+
+  const uint8_t* pool_lane = a.pool + lane * 16;
+  // base address of the next unit to load, and advance the load cursor; past the last unit: page 0, head 0
+  int next_pid = pid_first;
+  auto next_base = [&]() __attribute__((always_inline)) -> const uint8_t* {
+    const bool valid = lrem > 0;
+    const uint8_t* base = pool_lane + (int64_t)(valid ? lg : 0) * kSlab + (int64_t)(valid ? next_pid : 0) * a.page_bytes;
+    if (valid) {
+      --lrem;
+      if (++lp == lnp) {
+        if (++lg == a.Hkv) {
+          lg = 0;
+          ++lrow;
+          ltbl = n_tbl;
+          lnp = (n_vis + kP - 1) / kP;
+          lpstart = n_pstart;
+          fetch_next_row(lrow + 1);
+        }
+        lp = lpstart;
+      }
+      next_pid = lrem > 0 ? sload(a.pt + ltbl + lp) : 0;     // id of the unit after this one, used one page later
+    }
+    return base;
+  };
+  auto load_page = [&](PageRegs& R, const uint8_t* base) __attribute__((always_inline)) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) R.k[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + x * 1024)));
+#pragma unroll
+    for (int x = 0; x < 4; ++x) R.v[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + kBlk + x * 1024)));
+  };
+
+  // q chunks of this lane for the G heads of the current range
+  u32x4_t q[G][2];
+  auto load_q = [&](u32x4_t (&dst)[G][2], int qr, int gg) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qr * a.Hq + gg * G + h) * kRowBytes + j * 16;
+      dst[h][0] = *(const u32x4_t*)qp;
+      dst[h][1] = *(const u32x4_t*)(qp + kHalfBytes);
+    }
+  };
+  auto fetch_compute_next_row = [&]() __attribute__((always_inline)) {
+    c_nvis = sload(a.rows + (row + 1) * 4 + 1);
+    c_nqrow = sload(a.rows + (row + 1) * 4 + 2);
+    c_npstart = sload(a.rows + (row + 1) * 4 + 3) & 0x0fffffff;
+  };
+  fetch_compute_next_row();
+  load_q(q, qrow, g);
+
+  float m[G], l[G], acc[G][DPL];
+  auto reset_state = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      m[h] = -1e30f;
+      l[h] = 0.f;
+#pragma unroll
+      for (int d = 0; d < DPL; ++d) acc[h][d] = 0.f;
+    }
+  };
+  reset_state();
+  int p_first = p;                                       // first page of the piece being accumulated
+
+  // tokens of page index pi (absolute, within the row) that exist: the row's last page may be ragged
+  auto compute = [&](PageRegs& R, int pi) __attribute__((always_inline)) {
+    const int nvalid = vis - pi * kP;          // >= 1; >= 16 for a full page
+    if (nvalid < kP) {
+      // ragged last page: slots past the file's end hold whatever was there before (possibly
+      // NaN patterns); their weight is 0, but 0 * NaN is NaN, so clear their V chunks
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+        if ((hf * 8 + r) >= nvalid) {
+          R.v[hf] = make_uint4(0, 0, 0, 0);
+          R.v[2 + hf] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    float s[2][G];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const bool valid = (hf * 8 + r) < nvalid;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float x = E::dot(R.k[hf], __builtin_bit_cast(uint4, q[h][0]), 0.f);
+        x = E::dot(R.k[2 + hf], __builtin_bit_cast(uint4, q[h][1]), x);
+        x = octet_sum(x) * a.scale_log2e;
+        s[hf][h] = valid ? x : -__builtin_inff();
+      }
+    }
+    bool need = false;
+#pragma unroll
+    for (int h = 0; h < G; ++h) need |= fmaxf(s[0][h], s[1][h]) > m[h] + kTau;
+    if (__builtin_amdgcn_ballot_w64(need) != 0) {     // rare after the first page
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float mn = fmaxf(m[h], fmaxf(s[0][h], s[1][h]));
+        const float al = __builtin_amdgcn_exp2f(m[h] - mn);
+        l[h] *= al;
+#pragma unroll
+        for (int d = 0; d < DPL; ++d) acc[h][d] *= al;
+        m[h] = mn;
+      }
+    }
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      float pw[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        pw[h] = __builtin_amdgcn_exp2f(s[hf][h] - m[h]);
+        l[h] += pw[h];
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float vf[C];
+        E::unpack(R.v[i * 2 + hf], vf);
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int e = 0; e < C; ++e) acc[h][i * C + e] = __builtin_fmaf(pw[h], vf[e], acc[h][i * C + e]);
+      }
+    }
+  };
+
+  // End of a piece of a (row, kv head) range: combine the 8 token slots (lanes with equal j).  Per head:
+  // common max M, rescale, total sum.  The G*DPL accumulators are then reduced with a halving exchange
+  // (lane bit 5, 4, 3 in turn: keep one half of the list, send the other), so lane (r, j) ends up owning the
+  // fully reduced values r*V/8 .. r*V/8 + V/8 - 1 of the list.  Then the compute cursor moves on.
+  auto finish_piece = [&]() __attribute__((always_inline)) {
+    const bool whole = (p_first == 0 && p == np);
+    // The range after (row, g): same row, next head; or head 0 of the next row (its record was fetched
+    // when the compute side entered this row).  Its query rows are requested now, so that they arrive
+    // while the exchange below runs (q is not needed any more for this piece).
+    const int64_t out_row = ((int64_t)qrow * a.Hq + g * G) * D;
+    const bool more = remaining > 0;
+    if (more) {
+      if (++g == a.Hkv) {
+        g = 0;
+        ++row;
+        vis = c_nvis;
+        qrow = c_nqrow;
+        pstart = c_npstart;
+        np = (vis + kP - 1) / kP;
+        fetch_compute_next_row();
+      }
+      load_q(q, qrow, g);
+    }
+    constexpr int V = G * DPL;
+    float vals[V];
+    float lsum[G], Mh[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float M = m[h];
+      M = fmaxf(M, row_xor8(M));
+      M = fmaxf(M, __shfl_xor(M, 16));
+      M = fmaxf(M, __shfl_xor(M, 32));
+      const float f = __builtin_amdgcn_exp2f(m[h] - M);
+      float ls = l[h] * f;
+      ls += row_xor8(ls);
+      ls += __shfl_xor(ls, 16);
+      ls += __shfl_xor(ls, 32);
+      lsum[h] = ls;
+      Mh[h] = M;
+#pragma unroll
+      for (int d = 0; d < DPL; ++d) vals[h * DPL + d] = acc[h][d] * f;
+    }
+    {
+      const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+#pragma unroll
+      for (int i = 0; i < V / 2; ++i) {
+        const float keep = b5 ? vals[i + V / 2] : vals[i], send = b5 ? vals[i] : vals[i + V / 2];
+        vals[i] = keep + __shfl_xor(send, 32);
+      }
+#pragma unroll
+      for (int i = 0; i < V / 4; ++i) {
+        const float keep = b4 ? vals[i + V / 4] : vals[i], send = b4 ? vals[i] : vals[i + V / 4];
+        vals[i] = keep + __shfl_xor(send, 16);
+      }
+#pragma unroll
+      for (int i = 0; i < V / 8; ++i) {
+        const float keep = b3 ? vals[i + V / 8] : vals[i], send = b3 ? vals[i] : vals[i + V / 8];
+        vals[i] = keep + row_xor8(send);
+      }
+    }
+    // lane (r, j) now holds list entries idx = r * V/8 + t: head idx / DPL, lane-local dim idx % DPL
+    if (whole) {
+#pragma unroll
+      for (int t = 0; t < V / 8; ++t) {
+        const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+        float ls = lsum[0];
+#pragma unroll
+        for (int hh = 1; hh < G; ++hh) ls = (h == hh) ? lsum[hh] : ls;
+        a.out[out_row + h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t] / ls;
+      }
+    } else {
+      float* pa = a.part_acc + (int64_t)part * G * D;
+#pragma unroll
+      for (int t = 0; t < V / 8; ++t) {
+        const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+        pa[h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t];
+      }
+      if (lane < G) {
+        float mm = Mh[0], ll = lsum[0];
+#pragma unroll
+        for (int hh = 1; hh < G; ++hh) {
+          mm = (lane == hh) ? Mh[hh] : mm;
+          ll = (lane == hh) ? lsum[hh] : ll;
+        }
+        a.part_ml[((int64_t)part * G + lane) * 2 + 0] = mm;
+        a.part_ml[((int64_t)part * G + lane) * 2 + 1] = ll;
+      }
+      ++part;
+    }
+    if (more) {                                          // the next range (the piece ended at its row's last page)
+      p = pstart;
+      p_first = p;
+      reset_state();
+    }
+  };
+  // one unit: accumulate the page, move the compute cursor, close the piece at the end of the range or of the wavefront's work
+  auto do_unit = [&](PageRegs& R) __attribute__((always_inline)) {
+    compute(R, p);
+    ++p;
+    --remaining;
+    if (p == np || remaining == 0) finish_piece();
+  };
+
+  PageRegs A, B;
+  load_page(A, next_base());
+  while (remaining > 0) {
+    load_page(B, next_base());
+    do_unit(A);
+    load_page(A, next_base());
+    if (remaining > 0) do_unit(B);
+  }
+}
+
 template <typename E, int GT, int G>
 __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int block, uint8_t (*plds)[kSlab], const int wpb = kWavesPerBlock) {
   constexpr bool kPair = G < GT;
@@ -912,7 +1190,7 @@ __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, Pr
       return;
     }
   }
-  if constexpr (G < 8) decode_ranges<E, G, G>(da, blockIdx.x - tile_blocks, nullptr, TW);
+  if constexpr (G < 8) decode_stream<E, G>(da, blockIdx.x - tile_blocks, TW);
 }
 
 // Decode ranges for 8 query heads per kv head: one workgroup of two wavefronts per range.
