@@ -16,6 +16,8 @@ Kvfs::Kvfs(int64_t n_pages, int32_t page_tokens, const int32_t* free_order)
     std::iota(order_.begin(), order_.end(), 0);
   }
   for (int64_t r = 0; r < n_pages; ++r) rank_[order_[r]] = (int32_t)r;
+  for (int s = 0; s < 16; ++s)
+    if ((1 << s) == page_tokens) page_shift_ = s;
   std::vector<int32_t> ranks(n_pages);
   std::iota(ranks.begin(), ranks.end(), 0);   // ascending = already a valid min-heap
   free_ranks_ = decltype(free_ranks_)(std::greater<int32_t>(), std::move(ranks));
@@ -275,13 +277,20 @@ int64_t Kvfs::gather_need(int32_t n_seg, const int32_t* seg_handle, const int64_
       if (err) *err = "extract/merge: bad segment bounds or result too long";
       return SYM_EINVAL;
     }
+    const size_t at = src.size();
+    src.resize(at + (size_t)(hi - lo));
+    int32_t* out = src.data() + at;
+    const int32_t* pages = f->pages.data();
+    const int64_t len = f->len;
+    const int sh = page_shift_;                            // page size is a power of two on the device path
     for (int64_t j = lo; j < hi; ++j) {
       const int64_t i = idx ? idx[j] : j;
-      if (i < 0 || i >= f->len) {
+      if ((uint64_t)i >= (uint64_t)len) {
+        src.resize(at);
         if (err) *err = "extract: token index outside the file";
         return SYM_EINVAL;
       }
-      src.push_back(f->pages[i / P_] * P_ + (int32_t)(i % P_));
+      *out++ = sh >= 0 ? (pages[i >> sh] << sh) + (int32_t)(i & (P_ - 1)) : pages[i / P_] * P_ + (int32_t)(i % P_);
     }
   }
   const int64_t n = (int64_t)(src.size() - s0), np = (n + P_ - 1) / P_;
@@ -317,9 +326,12 @@ int32_t Kvfs::gather_commit(GatherPlan* plan, int32_t k) {
       const int32_t dst = alloc_page();
       files_[id].pages.push_back(dst);
       const int64_t base = d * P_, c = std::min<int64_t>(P_, n - base);
+      const size_t at = plan->moves.size();
+      plan->moves.resize(at + (size_t)(2 * c));
+      int32_t* mv = plan->moves.data() + at;
       for (int64_t t = 0; t < c; ++t) {
-        plan->moves.push_back(src[base + t]);
-        plan->moves.push_back(dst * P_ + (int32_t)t);
+        mv[2 * t] = src[base + t];
+        mv[2 * t + 1] = dst * P_ + (int32_t)t;
       }
       tokens_moved += c;
     }

@@ -110,6 +110,7 @@ class Kvfs {
 
   int64_t n_pages_;
   int32_t P_;
+  int page_shift_ = -1;                     // log2(P_) when P_ is a power of two, else -1
   std::vector<uint32_t> refcount_;
   std::vector<int32_t> order_, rank_;       // rank -> page, page -> rank
   std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_ranks_;
