@@ -88,10 +88,10 @@ struct PageRegs {
 // combined once, when a (row, kv head) range ends; a range that is only part of its (row, kv
 // head) leaves a partial result for the merge kernel.
 // ---------------------------------------------------------------------------------------
-// GT = query heads per kv head, G = heads this wavefront handles.  G == GT: one wavefront per range,
-// pages double-buffered in registers.  G == GT/2 (used for 8 heads per kv head, whose 8 x 16
-// accumulators do not fit one wavefront's registers twice per SIMD): a workgroup of TWO wavefronts
-// per range, each with half of the heads; wavefront 0 fetches the K half of every page,
+// decode_stream (below) is the one-wavefront-per-range form.  decode_ranges is the form for 8
+// heads per kv head on the vector units (whose 8 x 16 accumulators do not fit one wavefront's
+// registers twice per SIMD): GT = query heads per kv head, G = GT / 2 = heads per wavefront, a
+// workgroup of TWO wavefronts per range; wavefront 0 fetches the K half of every page,
 // wavefront 1 the V half, they exchange them through LDS (written and read in the same
 // lane-linear 1 KiB runs, so without bank conflicts), and every page is still read from HBM once.
 // ---------------------------------------------------------------------------------------
@@ -128,11 +128,10 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
   // load cursor: the unit whose K/V is requested next (two pages ahead of the compute cursor)
   int lrow = row, lg = g, lp = p, lnp = np, ltbl = tbl0, lpstart = pstart, lrem = remaining;
   // record of the row after the load cursor's (fetched a whole row ahead of its use)
-  int n_tbl = 0, n_vis = 0, n_qrow = 0, n_pstart = 0;
+  int n_tbl = 0, n_vis = 0, n_pstart = 0;
   auto fetch_next_row = [&](int rr) __attribute__((always_inline)) {      // rr may be one past the last row: the rows section is followed by valid words
     n_tbl = sload(a.rows + rr * 4 + 0);
     n_vis = sload(a.rows + rr * 4 + 1);
-    n_qrow = sload(a.rows + rr * 4 + 2);
     n_pstart = sload(a.rows + rr * 4 + 3) & 0x0fffffff;
   };
   fetch_next_row(row + 1);
@@ -426,14 +425,6 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
     }
 
     const uint8_t* slab0 = a.pool + (int64_t)g * kSlab + lane * 16;
-    // K/V pages are read once per launch: stream them (nontemporal), 8 KiB per wave per page
-    auto load_page = [&](PageRegs& R, int pid) {
-      const uint8_t* base = slab0 + (int64_t)pid * a.page_bytes;
-#pragma unroll
-      for (int x = 0; x < 4; ++x) R.k[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + x * 1024)));
-#pragma unroll
-      for (int x = 0; x < 4; ++x) R.v[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + kBlk + x * 1024)));
-    };
     // tokens of page index pi (absolute, within the row) that exist: the row's last page may be ragged
     auto compute = [&](PageRegs& R, int pi) {
       const int nvalid = vis - pi * kP;          // >= 1; >= 16 for a full page
@@ -505,19 +496,8 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
       pid2 = tbl[min(2, last)];
     }
     first_range = false;
-    if constexpr (!kPair) {
-      int id1 = cnt > 1 ? pid1 : 0, id2 = cnt > 2 ? pid2 : 0;
-      PageRegs A, B;
-      load_page(A, pid0);
-      for (int k = 0; k < cnt; k += 2) {
-        load_page(B, id1);
-        id1 = k + 3 <= last ? tbl[k + 3] : 0;
-        compute(A, p + k);
-        load_page(A, id2);
-        id2 = k + 4 <= last ? tbl[k + 4] : 0;
-        if (k + 1 < cnt) compute(B, p + k + 1);
-      }
-    } else {
+    static_assert(kPair, "one wavefront per range is decode_stream's job");
+    {
       // this wavefront's half (K or V) of a page: 4 lane-linear 1 KiB runs -> registers -> LDS
       const uint8_t* half0 = slab0 + hs * kBlk;
       auto load_half = [&](uint4 (&st)[4], int pid) {
