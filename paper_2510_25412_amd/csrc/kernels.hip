@@ -672,8 +672,9 @@ template <int G, int TW>
 __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block, uint8_t (*lds)[kKLds + kVLds]) {
   // TW = wavefronts of the workgroup (4 or 8); a tile has 32 * TW query rows that share one staging
   // of every K/V block, so K/V bytes read per flop (from L2, and written to LDS) halve with TW = 8.
-  // (Two 32-row column tiles per wavefront instead were measured: ~500 registers, one wavefront per
-  // SIMD, 1.7x slower.)
+  // (Two 32-row column tiles per wavefront instead, four wavefronts per 256-row tile, halve the LDS
+  // reads per flop but need ~510 registers, one wavefront per SIMD: measured 1.5x slower, also with
+  // the pipelined block loop below.)
   constexpr int CT = 1;
   // workgroups go round-robin over the 8 XCDs; the tile list comes in 8 shares of equal cost in which
   // tiles that read the same K/V are neighbours (one L2 per XCD), longest first
