@@ -114,11 +114,26 @@ def test_config4_mixed_reduced():
     sess.close()
 
 
-def test_config5_long_context_scattered_sampled():
-    """Long contexts with pages scattered by a random allocation ranking over a 200k-page
-    (13 GB) pool; sampled LIPs checked against the oracle, all checked for finiteness."""
-    wl = synth.config5(n_lips=6, n_pages=200_000)
-    lips = [0, 3, 5]
+def test_config4_mixed_full_size_sampled():
+    """The mixed batch at its full size, in the launch configuration the benchmark times (256-row
+    tiles on eight-wavefront workgroups, XCD shares, decode ranges in the same grid): sampled prefill
+    and decode LIPs against the oracle, every output finite, state bit for bit."""
+    wl = synth.config4()
+    lips = [0, 7, 19, 31, 32, 100, 255]
+    got, sess, ref, osess = run_both(wl, only=lips)
+    check_outputs(got, ref, rows_of(wl, lips))
+    assert int((~np.isfinite(got)).sum()) == 0
+    check_state(wl, sess, osess)
+    sess.close()
+
+
+def test_config5_long_context_full_size_sampled():
+    """The long-context batch at its full size (16 LIPs of 32k..131k tokens, 64Q/8KV, pages scattered
+    by a random allocation ranking over a 3,000,000-page = 196 GB pool: byte offsets beyond 2^32,
+    8 query heads per kv head on the matrix cores); sampled LIPs checked against the oracle, all
+    checked for finiteness."""
+    wl = synth.config5()
+    lips = [0, 6, 11, 15]
     got, sess, ref, osess = run_both(wl, only=lips)
     check_outputs(got, ref, rows_of(wl, lips))
     assert int((~np.isfinite(got)).sum()) == 0
