@@ -310,7 +310,7 @@ def main():
     ap.add_argument("--rag-rate", type=float, default=6000.0, help="request arrivals per second of the rag workload")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path is single-GPU; see DESIGN.md for how it would shard); "
+        print("bench.py: this build runs on ONE GPU (the path is single-GPU: it would shard by LIP or by kv head, with no exchange inside attention); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
 
