@@ -209,23 +209,28 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
 
 /* The packed descriptor of the attention launch for a batch given by page tables (same
  * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.
- * Layout: words[0..19] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then word
+ * Layout: words[0..31] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then word
  * offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total words;
- * total units (lo, hi); n_merge; offset of the member list; n_members; n_shared_tiles}, then
+ * total units (lo, hi); n_merge; offset of the member list; n_members; n_shared_tiles;
+ * [18] workgroups of the tile part of the launch; [20..28] the 9 offsets that cut the tile list
+ * into 8 shares of equal cost, one per XCD (workgroup b runs tile b / 8 of share b % 8)}, then
  * the sections:
- *   rows      [n_rows][4]   page-table offset, visible tokens, q/out row, first page of the
- *                           row's own range (pages before it belong to a shared prefix)
+ *   rows      [n_rows][4]   page-table offset, tokens the row's first new token sees, its q/out
+ *                           row, and in one word: first page of the row's own range (low 28 bits;
+ *                           pages before it belong to a shared prefix) | (new tokens in the
+ *                           row - 1) << 28 (a row holds up to 4 consecutive draft tokens of a LIP)
  *   wave_work [n_waves][12] row, kv head, page, units, first partial, then of the first range:
  *                           visible tokens, q/out row, page-table offset, ids of its first
- *                           three pages, first page of the row's own range
+ *                           three pages, the row's fourth word
  *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
- *                           partials of the row's shared prefix: first, stride, count; 0, 0
+ *                           partials of the row's shared prefix: first, stride, count; then the
+ *                           distance between the own pieces (tokens in the row); 0
  *   page_table, pt_off [n_lips + 1]
  *   tiles     [n_tiles][12] page-table offset, file length before the call, first q/out row
  *                           (shared: offset into the member list), new tokens (shared: members)
  *                           in the tile, kv head, token offset in the chunk (shared: first
  *                           partial slot), kind (0 prefill chunk, 1 shared prefix), first page,
- *                           end page, 0, 0, 0
+ *                           end page, 0, 0, 0; ordered share by share
  *   members   [n_members]   q rows of the members of shared-prefix tiles
  * Returns the number of words (or a negative status); writes at most cap words.             */
 int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
