@@ -351,7 +351,11 @@ class Context:
         self._chk(self.lib.sym_kv_read(self.h, kv, start, n, _ptr(k_out), _ptr(v_out), stream))
 
     # ---- measurement ----
-    def profile_enable(self, mask):
+    def profile_enable(self, mask, stride=1):
+        """mask: bit k = time kernel id k; stride s: only every s-th launch of each id."""
+        return self._profile_enable(int(mask) | (int(stride) << 8))
+
+    def _profile_enable(self, mask):
         """mask: bit k = time kernel id k (K_ATTN ...); 0 = off."""
         self._chk(self.lib.sym_profile_enable(self.h, int(mask)))
 

@@ -60,7 +60,8 @@ struct sym_ctx {
   bool stage_pending[kStages] = {false, false, false, false};
   int stage_next = 0;
   // profiling
-  int prof_mask = 0;
+  int prof_mask = 0, prof_stride = 1;
+  int64_t prof_seen[SYM_K_COUNT] = {0, 0, 0, 0, 0};
   std::vector<hipEvent_t> ev_start[SYM_K_COUNT], ev_stop[SYM_K_COUNT];
   int ev_used[SYM_K_COUNT] = {0, 0, 0, 0, 0};
   // counters
@@ -137,6 +138,7 @@ struct Timed {
   Timed(sym_ctx* ctx, int kid, hipStream_t s) : c(ctx), id(kid), st(s), on(false) {
     ++c->kernel_launches;
     if (!((c->prof_mask >> id) & 1) || c->ev_used[id] >= kMaxTimed) return;
+    if (c->prof_seen[id]++ % c->prof_stride != 0) return;          // every prof_stride-th launch is timed
     if ((int)c->ev_start[id].size() <= c->ev_used[id]) {
       hipEvent_t a, b;
       if (hipEventCreate(&a) != hipSuccess) return;
@@ -787,7 +789,9 @@ int sym_sched_state(sym_sched* s, double* rate, double* target, double* a_us, do
 int sym_profile_enable(sym_ctx* c, int mask) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
-  c->prof_mask = mask;
+  c->prof_mask = mask & 0xff;
+  c->prof_stride = std::max(1, (mask >> 8) & 0xffff);
+  for (int k = 0; k < SYM_K_COUNT; ++k) c->prof_seen[k] = 0;
   return SYM_OK;
 }
 
