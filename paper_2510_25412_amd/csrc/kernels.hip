@@ -1186,7 +1186,7 @@ __global__ __launch_bounds__(128, 2) void decode_pair_kernel(DecodeArgs da) {
 //   out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M),  M = max_i m_i.
 // The G*D accumulator values of a piece form one flat list; lane owns entries e*64 + lane.  All
 // loads of a group of 4 pieces are issued before any is used (indices past the end re-read the
-// last piece with weight 0), so the kernel costs a few memory round trips.  A row that belongs
+// last piece with weight 0), so the kernel costs one memory round trip per group after the entry.  A row that belongs
 // to a shared-prefix group has extra pieces: the partials the tile kernel left for the prefix.
 // ---------------------------------------------------------------------------------------
 template <int G, int D>
@@ -1218,17 +1218,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a)
   }
 #pragma unroll
   for (int e = 0; e < VL; ++e) o[e] = 0.f;
-  for (int i0 = 0; i0 < pieces; i0 += 4) {
-    float mv[4][G];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int h = 0; h < G; ++h) mv[u][h] = ml0[(slot(i0 + u) * G + h) * 2];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int h = 0; h < G; ++h) Mx[h] = fmaxf(Mx[h], mv[u][h]);
-  }
+  // groups of 4 pieces: all their loads (max, sum, accumulator) are issued together, one memory round
+  // trip per group; the running maximum is carried from group to group (most rows have one group)
   for (int i0 = 0; i0 < pieces; i0 += 4) {
     float mv[4][G], lv[4][G], t[4][VL];
 #pragma unroll
@@ -1242,6 +1233,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void merge_kernel(MergeArgs a)
 #pragma unroll
       for (int e = 0; e < VL; ++e) t[u][e] = pa0[ii * G * D + e * 64];
     }
+    float sc[G];                                  // factor that brings what was summed so far to the new maximum
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float mn = Mx[h];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) mn = fmaxf(mn, mv[u][h]);
+      sc[h] = __builtin_amdgcn_exp2f(Mx[h] - mn);     // 0 for the first group (Mx = -inf)
+      Mx[h] = mn;
+      ls[h] *= sc[h];
+    }
+#pragma unroll
+    for (int e = 0; e < VL; ++e) o[e] *= sc[(e * 64) / D];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float w[G];
