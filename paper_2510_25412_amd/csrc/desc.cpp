@@ -173,7 +173,8 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
   // a merge entry per token of a cut (row, head) (at most one cut per wave boundary) and per (member row, head)
-  const int64_t off_pt = off_merge + (nw * max_nt + n_members * H) * MERGE_WORDS;
+  // (a cut (row, head) has a wave boundary inside it, and there are no more of them than (row, head)s)
+  const int64_t off_pt = off_merge + (std::min<int64_t>(nw, n_rows * H) * max_nt + n_members * H) * MERGE_WORDS;
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
   const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
