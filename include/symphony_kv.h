@@ -219,9 +219,8 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
  *                           row, and in one word: first page of the row's own range (low 28 bits;
  *                           pages before it belong to a shared prefix) | (new tokens in the
  *                           row - 1) << 28 (a row holds up to 4 consecutive draft tokens of a LIP)
- *   wave_work [n_waves][12] row, kv head, page, units, first partial, then of the first range:
- *                           visible tokens, q/out row, page-table offset, ids of its first
- *                           three pages, the row's fourth word
+ *   wave_work [n_waves][8]  row, kv head, page, units, first partial, ids of the first three
+ *                           pages of the first range (its first loads need no table lookup)
  *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
  *                           partials of the row's shared prefix: first, stride, count; then the
  *                           distance between the own pieces (tokens in the row); 0

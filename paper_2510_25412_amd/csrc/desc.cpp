@@ -265,15 +265,11 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     const int64_t erow = k + 1 < nw ? ww[WAVE_WORDS + 0] : n_rows;
     const int32_t eg = k + 1 < nw ? ww[WAVE_WORDS + 1] : 0, ep = k + 1 < nw ? ww[WAVE_WORDS + 2] : 0;
     ww[4] = part;
-    ww[5] = rows[row * ROW_WORDS + 1];
-    ww[6] = rows[row * ROW_WORDS + 2];
-    ww[7] = rows[row * ROW_WORDS + 0];
     {                                   // ids of the first pages: their loads need no table lookup
       const int32_t np0 = row_pages(row);
       const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
-      for (int i = 0; i < 3; ++i) ww[8 + i] = t0[std::min(p + i, np0 - 1)];
+      for (int i = 0; i < 3; ++i) ww[5 + i] = t0[std::min(p + i, np0 - 1)];
     }
-    ww[11] = rows[row * ROW_WORDS + 3];
     int64_t units = 0;
     while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
       const int32_t np = row_pages(row), p0 = row_first(row);

@@ -31,7 +31,7 @@
 
 namespace symkv {
 
-enum { DESC_HEADER_WORDS = 32, ROW_WORDS = 4, WAVE_WORDS = 12, MERGE_WORDS = 8, TILE_WORDS = 12 };
+enum { DESC_HEADER_WORDS = 32, ROW_WORDS = 4, WAVE_WORDS = 8, MERGE_WORDS = 8, TILE_WORDS = 12 };
 // header word indices
 enum {
   H_N_ROWS = 0, H_N_WAVES, H_N_PARTIALS, H_N_LIPS, H_N_TILES,

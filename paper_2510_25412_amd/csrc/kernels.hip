@@ -116,14 +116,16 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
   const int r = lane >> 3, j = lane & 7;
   auto sload = [&](const int32_t* ptr) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(*ptr); };
 
-  const int32_t* ww = a.waves + wv * 12;
-  // compute cursor: the range being accumulated
+  const int32_t* ww = a.waves + wv * 8;
+  // compute cursor: the range being accumulated.  The wave record carries the id of the first page, so the first
+  // K/V loads go out while the row record (one more scalar round trip) is still on its way.
   int row = sload(ww + 0), g = sload(ww + 1), p = sload(ww + 2);
   int remaining = sload(ww + 3);
   int part = sload(ww + 4);
-  int vis = sload(ww + 5), qrow = sload(ww + 6);
-  const int tbl0 = sload(ww + 7), pid_first = sload(ww + 8);
-  int pstart = sload(ww + 11) & 0x0fffffff;
+  const int pid_first = sload(ww + 5);
+  const int tbl0 = sload(a.rows + row * 4 + 0);
+  int vis = sload(a.rows + row * 4 + 1), qrow = sload(a.rows + row * 4 + 2);
+  int pstart = sload(a.rows + row * 4 + 3) & 0x0fffffff;
   int np = (vis + kP - 1) / kP;
   // load cursor: the unit whose K/V is requested next (two pages ahead of the compute cursor)
   int lrow = row, lg = g, lp = p, lnp = np, ltbl = tbl0, lpstart = pstart, lrem = remaining;
@@ -384,22 +386,21 @@ __device__ __forceinline__ void decode_ranges(const DecodeArgs& a, const int blo
   if (wv >= a.n_waves) return;
   const int r = lane >> 3, j = lane & 7;
 
-  const int32_t* ww = a.waves + wv * 12;
+  const int32_t* ww = a.waves + wv * 8;
   int row = __builtin_amdgcn_readfirstlane(ww[0]);
   int g = __builtin_amdgcn_readfirstlane(ww[1]);
   int p = __builtin_amdgcn_readfirstlane(ww[2]);
   int remaining = __builtin_amdgcn_readfirstlane(ww[3]);
   int part = __builtin_amdgcn_readfirstlane(ww[4]);
-  // row data of the first range travels with the wave's work item (one dependent load less)
-  int vis = __builtin_amdgcn_readfirstlane(ww[5]);
-  int qrow = __builtin_amdgcn_readfirstlane(ww[6]);
-  int tbl_off = __builtin_amdgcn_readfirstlane(ww[7]);
   // ids of the first range's first three pages (no table lookup before the first loads)
-  int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
-  int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
-  int pid2 = __builtin_amdgcn_readfirstlane(ww[10]);
-  int pstart = __builtin_amdgcn_readfirstlane(ww[11]);   // first page of the row's own range (pages before it are a
-                                                         // shared prefix handled by the tile kernel)
+  int pid0 = __builtin_amdgcn_readfirstlane(ww[5]);
+  int pid1 = __builtin_amdgcn_readfirstlane(ww[6]);
+  int pid2 = __builtin_amdgcn_readfirstlane(ww[7]);
+  int tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
+  int vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
+  int qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
+  int pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);   // first page of the row's own range (pages before it
+                                                                       // are a shared prefix handled by the tile kernel)
   bool first_range = true;
 
   while (remaining > 0) {
@@ -962,18 +963,18 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
   const int head = col % GT;                          // columns past nt * GT repeat earlier ones; their results are ignored
   const int vq4 = lane >> 4, vc = lane & 15;          // V staging role: tokens 4*vq4 .. +3 of a page, dim chunk vc
 
-  const int32_t* ww = a.waves + wv * 12;
+  const int32_t* ww = a.waves + wv * 8;
   int row = __builtin_amdgcn_readfirstlane(ww[0]);
   int g = __builtin_amdgcn_readfirstlane(ww[1]);
   int p = __builtin_amdgcn_readfirstlane(ww[2]);
   int remaining = __builtin_amdgcn_readfirstlane(ww[3]);
   int part = __builtin_amdgcn_readfirstlane(ww[4]);
-  int vis = __builtin_amdgcn_readfirstlane(ww[5]);
-  int qrow = __builtin_amdgcn_readfirstlane(ww[6]);
-  int tbl_off = __builtin_amdgcn_readfirstlane(ww[7]);
-  int pid0 = __builtin_amdgcn_readfirstlane(ww[8]);
-  int pid1 = __builtin_amdgcn_readfirstlane(ww[9]);
-  int pstart = __builtin_amdgcn_readfirstlane(ww[11]);
+  int pid0 = __builtin_amdgcn_readfirstlane(ww[5]);
+  int pid1 = __builtin_amdgcn_readfirstlane(ww[6]);
+  int tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
+  int vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
+  int qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
+  int pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
   int nt = (pstart >> 28) + 1;                        // new tokens in the row
   pstart &= 0x0fffffff;
   bool first_range = true;

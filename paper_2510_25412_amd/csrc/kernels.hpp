@@ -14,9 +14,8 @@ struct DecodeArgs {
   float* part_acc;          // [n_partials][G][D]
   float* part_ml;           // [n_partials][G][2] (max in log2 units, sum)
   const int32_t* rows;      // [n_rows][4]: page-table offset, visible tokens, q/out row, lip
-  const int32_t* waves;     // [n_waves][12]: row, kv head, page, units, first partial, then the
-                            //   first range's visible tokens, q/out row, page-table offset,
-                            //   ids of its first three pages, 0
+  const int32_t* waves;     // [n_waves][8]: row, kv head, page, units, first partial, ids of the first
+                            //   range's first three pages
   const int32_t* pt;        // flattened page tables
   int32_t n_waves, Hq, Hkv;
   float scale_log2e;        // softmax scale * log2(e)

@@ -219,7 +219,7 @@ def _walk_desc(words, Hkv, P=16):
     hdr = words[:20]
     n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
     rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
-    waves = words[hdr[6]:hdr[6] + 12 * n_waves].reshape(n_waves, 12)
+    waves = words[hdr[6]:hdr[6] + 8 * n_waves].reshape(n_waves, 8)
     merge = words[hdr[7]:hdr[7] + 8 * int(hdr[14])].reshape(int(hdr[14]), 8)
     pt = words[hdr[8]:hdr[9]]
     ptoff = words[hdr[9]:hdr[9] + n_lips + 1]
@@ -262,9 +262,8 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     pieces = {}
     for k in range(n_waves):
         row, g, p, rem, part = (int(x) for x in wv[k, :5])
-        assert wv[k, 5:8].tolist() == [int(rows[row, 1]), int(rows[row, 2]), int(rows[row, 0])]   # first range's row data
-        assert int(wv[k, 11]) == int(rows[row, 3])
-        assert wv[k, 8:11].tolist() == [int(pt[int(rows[row, 0]) + min(p + i, npgs[row] - 1)]) for i in range(3)]
+        # ids of the first range's first three pages travel with the wave record
+        assert wv[k, 5:8].tolist() == [int(pt[int(rows[row, 0]) + min(p + i, npgs[row] - 1)]) for i in range(3)]
         units.append(rem)
         starts.append(0)
         while rem > 0:
