@@ -18,9 +18,7 @@ Kvfs::Kvfs(int64_t n_pages, int32_t page_tokens, const int32_t* free_order)
   for (int64_t r = 0; r < n_pages; ++r) rank_[order_[r]] = (int32_t)r;
   for (int s = 0; s < 16; ++s)
     if ((1 << s) == page_tokens) page_shift_ = s;
-  std::vector<int32_t> ranks(n_pages);
-  std::iota(ranks.begin(), ranks.end(), 0);   // ascending = already a valid min-heap
-  free_ranks_ = decltype(free_ranks_)(std::greater<int32_t>(), std::move(ranks));
+  free_ranks_.fill(n_pages);
 }
 
 const KvFile* Kvfs::file_of(int32_t h) const {
@@ -29,15 +27,14 @@ const KvFile* Kvfs::file_of(int32_t h) const {
 }
 
 int32_t Kvfs::alloc_page() {
-  int32_t p = order_[free_ranks_.top()];   // lowest rank, whatever the release order
-  free_ranks_.pop();
+  int32_t p = order_[free_ranks_.pop_lowest()];   // lowest rank, whatever the release order
   refcount_[p] = 1;
   ++pages_allocated;
   return p;
 }
 
 void Kvfs::drop_ref(int32_t p) {
-  if (--refcount_[p] == 0) free_ranks_.push(rank_[p]);
+  if (--refcount_[p] == 0) free_ranks_.insert(rank_[p]);
 }
 
 namespace {
@@ -399,7 +396,7 @@ int Kvfs::offload(int32_t n, const int32_t* handles, SwapPlan* plan, std::string
       host_refs_[s] = std::move(w);
       waiters_.erase(p);
       refcount_[p] = 0;
-      free_ranks_.push(rank_[p]);
+      free_ranks_.insert(rank_[p]);
       plan->pairs.push_back(p);
       plan->pairs.push_back(s);
     }

@@ -1,5 +1,5 @@
 // Host-side state of the KV-cache file system (paper section 4.2): files as page lists,
-// per-page reference counts, copy-on-write forks, a ranked free-page heap.  Pure C++, no
+// per-page reference counts, copy-on-write forks, a ranked set of free pages.  Pure C++, no
 // HIP: the integer state is what tests compare bit for bit with the CPU model.
 #pragma once
 #include <cstdint>
@@ -19,6 +19,46 @@ struct KvFile {
   std::string name;
   bool named = false;
   bool alive = false;
+};
+
+// The set of free ranks with "take the lowest" in a few instructions: a bitmap of the ranks and
+// a summary bitmap with one bit per 64-rank word (a 3,000,000-page pool has 733 summary words; the
+// scan for the first non-empty one starts at a hint that only moves down when a rank is returned).
+class RankSet {
+ public:
+  void fill(int64_t n) {                      // ranks 0 .. n-1 all free
+    l0_.assign((size_t)((n + 63) / 64), ~0ull);
+    if (n % 64) l0_.back() = (1ull << (n % 64)) - 1;
+    l1_.assign((l0_.size() + 63) / 64, 0);
+    for (size_t w = 0; w < l0_.size(); ++w)
+      if (l0_[w]) l1_[w >> 6] |= 1ull << (w & 63);
+    count_ = n;
+    hint_ = 0;
+  }
+  int64_t size() const { return count_; }
+  int32_t pop_lowest() {                      // the caller has checked size() > 0
+    size_t i = hint_;
+    while (!l1_[i]) ++i;
+    hint_ = i;
+    const size_t w = i * 64 + (size_t)__builtin_ctzll(l1_[i]);
+    const int b = __builtin_ctzll(l0_[w]);
+    l0_[w] &= l0_[w] - 1;
+    if (!l0_[w]) l1_[i] &= ~(1ull << (w & 63));
+    --count_;
+    return (int32_t)(w * 64 + (size_t)b);
+  }
+  void insert(int32_t r) {
+    const size_t w = (size_t)r >> 6;
+    l0_[w] |= 1ull << (r & 63);
+    l1_[w >> 6] |= 1ull << (w & 63);
+    if ((w >> 6) < hint_) hint_ = w >> 6;
+    ++count_;
+  }
+
+ private:
+  std::vector<uint64_t> l0_, l1_;
+  int64_t count_ = 0;
+  size_t hint_ = 0;
 };
 
 // Result of planning a batch of appends (reused between calls: no per-call allocation once warm).
@@ -90,7 +130,7 @@ class Kvfs {
   int64_t host_slots_in_use() const { return (int64_t)host_refs_.size(); }
 
   int32_t refcount(int32_t page) const { return page < 0 || page >= n_pages_ ? -1 : (int32_t)refcount_[page]; }
-  int64_t free_pages() const { return (int64_t)free_ranks_.size(); }
+  int64_t free_pages() const { return free_ranks_.size(); }
   int64_t n_pages() const { return n_pages_; }
   int32_t page_tokens() const { return P_; }
 
@@ -113,7 +153,7 @@ class Kvfs {
   int page_shift_ = -1;                     // log2(P_) when P_ is a power of two, else -1
   std::vector<uint32_t> refcount_;
   std::vector<int32_t> order_, rank_;       // rank -> page, page -> rank
-  std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_ranks_;
+  RankSet free_ranks_;
   std::vector<KvFile> files_;
   std::vector<int32_t> free_file_ids_;
   std::vector<int32_t> handle_file_;        // handle -> file id or -1
