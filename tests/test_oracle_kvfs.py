@@ -446,3 +446,38 @@ def test_random_ops_with_offload_against_token_lists():
         check(h)
         m.kv_remove(h)
     assert m.free_pages() == 256 and m.host_refs == {} and m.waiters == {} and not getattr(pool, "host", {})
+
+
+def test_extract_offload_hand_trace_file():
+    """The hand-derived extract / merge / offload / restore trace under tests/golden (page size 4)."""
+    m = KVFSModel(16, 4)
+    for op, args, exp in load_trace("extract_offload_state_trace.txt"):
+        e = parse_expect(exp)
+        ints = lambda a: [] if a == "-" else [int(x) for x in a.split(",")]
+        if op == "open":
+            assert m.kv_open(None) == e["h"]
+        elif op == "fork":
+            assert m.kv_fork(int(args[0])) == e["h"]
+        elif op == "append":
+            h, n = int(args[0]), int(args[1])
+            cow, slots = m.append([(h, n)])
+            assert cow == e["cow"] and slots[0] == e["slots"] and m.kv_pages(h) == e["pages"]
+        elif op == "extract":
+            h, moves = m.kv_extract(int(args[0]), ints(args[1]))
+            assert h == e["h"] and m.kv_pages(h) == e["pages"] and moves == e["moves"]
+        elif op == "merge":
+            h, moves = m.kv_merge(ints(args[0]))
+            assert h == e["h"] and m.kv_pages(h) == e["pages"] and moves == e["moves"]
+        elif op == "offload":
+            assert m.kv_offload(ints(args[0])) == e["swaps"]
+        elif op == "restore":
+            assert m.kv_restore(ints(args[0])) == e["swaps"]
+        elif op == "pages":
+            assert m.kv_pages(int(args[0])) == e["pages"]
+        elif op == "remove":
+            m.kv_remove(int(args[0]))
+        if "rc" in e:
+            assert m.refcount.tolist()[:len(e["rc"])] == e["rc"], (op, args)
+        if "free" in e:
+            assert m.free_pages() == e["free"], (op, args)
+        m.audit()

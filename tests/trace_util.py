@@ -27,7 +27,12 @@ def parse_expect(exp):
     if "rc" in exp:
         out["rc"] = [int(x) for x in exp["rc"].split(",")]
     if "pages" in exp:
-        out["pages"] = [int(x) for x in exp["pages"].split(",")]
+        out["pages"] = [] if exp["pages"] == "-" else [int(x) for x in exp["pages"].split(",")]
+    if "moves" in exp:          # src page:slot > dst page:slot
+        out["moves"] = [] if exp["moves"] == "-" else [
+            tuple(int(y) for side in x.split(">") for y in side.split(":")) for x in exp["moves"].split(",")]
+    if "swaps" in exp:          # a>b pairs
+        out["swaps"] = [] if exp["swaps"] == "-" else [tuple(int(y) for y in x.split(">")) for x in exp["swaps"].split(",")]
     if "slots" in exp:
         out["slots"] = [tuple(int(y) for y in x.split(":")) for x in exp["slots"].split(",")]
     if "cow" in exp:
