@@ -279,7 +279,8 @@ int     sym_sched_state(sym_sched* s, double* rate_per_us, double* target_batch,
 #define SYM_K_COUNT    5
 /* sym_profile_enable(mask): bit k (k < 8) of mask set = launches of kernel id k are bracketed by
  * HIP events on the launch stream (at most 4096 timed launches are kept per kernel id, later
- * ones are not timed); bits 8..23 of mask = stride s (0 or 1: every launch; s > 1: every s-th
+ * ones are not timed).  For SYM_K_ATTN the two events are attached to the dispatches themselves
+ * (start of the first kernel of the attention launch, end of its last): kernel time only; bits 8..23 of mask = stride s (0 or 1: every launch; s > 1: every s-th
  * launch of each kernel id, so that the two event records do not stretch every step); mask 0 = off.
  * sym_profile_read synchronises on the recorded events and returns the summed duration in
  * milliseconds and the number of timed launches of one kernel id, then forgets them.     */

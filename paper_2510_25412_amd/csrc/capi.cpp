@@ -130,12 +130,17 @@ int stage_acquire(sym_ctx* c, int64_t words, int* idx) {
   return SYM_OK;
 }
 
+// Brackets a launch with a pair of events when the kernel id is being profiled.  attached = true: the
+// events are not recorded here but handed to the launch (start() / stop()), which attaches them to
+// the dispatch itself, so they bracket the kernel's execution and not its launch overhead.
 struct Timed {
   sym_ctx* c;
   int id;
   hipStream_t st;
-  bool on;
-  Timed(sym_ctx* ctx, int kid, hipStream_t s) : c(ctx), id(kid), st(s), on(false) {
+  bool on, attached;
+  hipEvent_t start() const { return on && attached ? c->ev_start[id][c->ev_used[id]] : nullptr; }
+  hipEvent_t stop() const { return on && attached ? c->ev_stop[id][c->ev_used[id]] : nullptr; }
+  Timed(sym_ctx* ctx, int kid, hipStream_t s, bool attach = false) : c(ctx), id(kid), st(s), on(false), attached(attach) {
     ++c->kernel_launches;
     if (!((c->prof_mask >> id) & 1) || c->ev_used[id] >= kMaxTimed) return;
     if (c->prof_seen[id]++ % c->prof_stride != 0) return;          // every prof_stride-th launch is timed
@@ -149,10 +154,10 @@ struct Timed {
       c->ev_start[id].push_back(a);
       c->ev_stop[id].push_back(b);
     }
-    on = hipEventRecord(c->ev_start[id][c->ev_used[id]], st) == hipSuccess;
+    on = attached || hipEventRecord(c->ev_start[id][c->ev_used[id]], st) == hipSuccess;
   }
   ~Timed() {
-    if (on && hipEventRecord(c->ev_stop[id][c->ev_used[id]], st) == hipSuccess) ++c->ev_used[id];
+    if (on && (attached || hipEventRecord(c->ev_stop[id][c->ev_used[id]], st) == hipSuccess)) ++c->ev_used[id];
   }
 };
 
@@ -199,9 +204,9 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.Hkv = c->cfg.n_kv_heads;
   pa.scale_log2e = c->scale_log2e;
   {
-    Timed t(c, SYM_K_ATTN, st);
+    Timed t(c, SYM_K_ATTN, st, true);
     // rows that hold several new tokens exist for the matrix-core decode kernel only
-    hipError_t e = launch_attn(a, pa, c->cfg.dtype, (c->decode_mode || d.max_row_tokens > 1) ? 1 : 0, st);
+    hipError_t e = launch_attn(a, pa, c->cfg.dtype, (c->decode_mode || d.max_row_tokens > 1) ? 1 : 0, st, t.start(), t.stop());
     if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {

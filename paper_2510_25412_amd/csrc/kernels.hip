@@ -1403,8 +1403,14 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(uint4* dst, const uint4
 }
 
 template <typename E>
-hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode_mode, hipStream_t st) {
+hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode_mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int G = da.Hq / da.Hkv;
+  // With events: they are attached to the dispatches themselves (start of the first kernel of the
+  // attention launch, end of the last), so the interval holds kernel time and nothing else.
+  auto launch = [&](auto kernel, dim3 g, dim3 b, hipEvent_t s, hipEvent_t e, auto... args) {
+    if (s || e) hipExtLaunchKernelGGL(kernel, g, b, 0, st, s, e, 0, args...);
+    else hipLaunchKernelGGL(kernel, g, b, 0, st, args...);
+  };
   // decode ranges: matrix cores (mode 1), the two-wavefront VALU kernel for 8 heads (mode 2), or the
   // VALU kernel fused into the tile launch (mode 0)
   const int mode = (E::kDimsPerChunk == 8 && decode_mode == 1) ? 1 : (G == 8 ? 2 : 0);
@@ -1416,24 +1422,27 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   const int decode_blocks = mode == 0 ? (da.n_waves + tw - 1) / tw : 0;
   const dim3 grid(tile_blocks + decode_blocks), block(256), block8(512);
   if (ps.n_tiles > 0 && ps.tile_rows != 128 && ps.tile_rows != 256) return hipErrorInvalidValue;
+  const bool second = da.n_waves > 0 && mode != 0;          // decode ranges in a launch of their own
+  const hipEvent_t e_first = second ? nullptr : ev1;
+  const hipEvent_t s_second = grid.x > 0 ? nullptr : ev0;
 #define SYM_ATTN_CASE(GG) \
   case GG: \
-    if (tw == 8) hipLaunchKernelGGL((attn_kernel<E, GG, 8>), grid, block8, 0, st, da, ps, tile_blocks); \
-    else hipLaunchKernelGGL((attn_kernel<E, GG, 4>), grid, block, 0, st, da, ps, tile_blocks); \
+    if (tw == 8) launch(attn_kernel<E, GG, 8>, grid, block8, ev0, e_first, da, ps, tile_blocks); \
+    else launch(attn_kernel<E, GG, 4>, grid, block, ev0, e_first, da, ps, tile_blocks); \
     break;
   if (grid.x > 0) switch (G) {
     SYM_ATTN_CASE(1) SYM_ATTN_CASE(2) SYM_ATTN_CASE(4) SYM_ATTN_CASE(8)
     default: return hipErrorInvalidValue;
   }
 #undef SYM_ATTN_CASE
-  if (da.n_waves > 0 && mode == 2) hipLaunchKernelGGL((decode_pair_kernel<E>), dim3(da.n_waves), dim3(128), 0, st, da);
+  if (da.n_waves > 0 && mode == 2) launch(decode_pair_kernel<E>, dim3(da.n_waves), dim3(128), s_second, ev1, da);
   if (da.n_waves > 0 && mode == 1) {
     const dim3 dgrid((da.n_waves + kWavesPerBlock - 1) / kWavesPerBlock);
     switch (G) {
-      case 1: hipLaunchKernelGGL((decode_mfma_kernel<1>), dgrid, block, 0, st, da); break;
-      case 2: hipLaunchKernelGGL((decode_mfma_kernel<2>), dgrid, block, 0, st, da); break;
-      case 4: hipLaunchKernelGGL((decode_mfma_kernel<4>), dgrid, block, 0, st, da); break;
-      case 8: hipLaunchKernelGGL((decode_mfma_kernel<8>), dgrid, block, 0, st, da); break;
+      case 1: launch(decode_mfma_kernel<1>, dgrid, block, s_second, ev1, da); break;
+      case 2: launch(decode_mfma_kernel<2>, dgrid, block, s_second, ev1, da); break;
+      case 4: launch(decode_mfma_kernel<4>, dgrid, block, s_second, ev1, da); break;
+      case 8: launch(decode_mfma_kernel<8>, dgrid, block, s_second, ev1, da); break;
       default: return hipErrorInvalidValue;
     }
   }
@@ -1442,10 +1451,10 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
 
 }  // namespace
 
-hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st) {
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (da.n_waves <= 0 && pa.n_tiles <= 0) return hipSuccess;
-  if (dtype == 0) return pa.n_tiles > 0 ? hipErrorInvalidValue : launch_attn_g<ElemF32>(da, pa, 0, st);
-  return launch_attn_g<ElemBF16>(da, pa, decode_mode, st);
+  if (dtype == 0) return pa.n_tiles > 0 ? hipErrorInvalidValue : launch_attn_g<ElemF32>(da, pa, 0, st, ev0, ev1);
+  return launch_attn_g<ElemBF16>(da, pa, decode_mode, st, ev0, ev1);
 }
 
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {

@@ -1,6 +1,7 @@
 // Argument blocks and launch functions of the HIP kernels (see kernels.hip).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 
@@ -89,7 +90,9 @@ struct SwapArgs {
 };
 
 // decode_mode: 0 = VALU decode kernel, 1 = decode ranges on the matrix cores (bf16 storage only)
-hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st);
+// ev0 / ev1 (both or neither): events attached to the first / last dispatch of the launch (kernel start, kernel end)
+hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st,
+                       hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st);
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st);
 hipError_t launch_gather(const GatherArgs& a, void* k_out, void* v_out, hipStream_t st);
