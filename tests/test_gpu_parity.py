@@ -489,3 +489,101 @@ def test_rag_driver_replayed_on_the_oracle(pareto_index):
     d.close()
     assert sess.ctx.free_pages() == n_pages
     sess.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 1), (64, 8, 128, synth.BF16, 2), (8, 8, 64, synth.F32, 3)])
+def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
+    """A seeded random program over the whole API (open, append, fork, extract, merge, truncate,
+    offload, restore, remove, pred batches that mix single tokens, drafts and prefill chunks) run
+    step by step on the library and on the oracle: same error codes, every pred's outputs within the
+    bar, page tables / reference counts / free pages equal after every step.  What a fixed scenario
+    does not think of (a fork of an extract that waits while its source is truncated, ...) shows up here."""
+    from oracle.kvfs_model import KVError
+    from paper_2510_25412_amd import binding
+    drv = _hip()
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    n_pages = 1536
+    sess = drv.HipSession(shape, n_pages, max_lips=16, max_tokens=1024, max_entries=1 << 15, poison=True)
+    osess = OracleSession(shape, n_pages)
+    rng = np.random.default_rng(1000 + seed)
+    print(f"[case] random program {Hq}/{Hkv} {dtype} seed {seed}", flush=True)
+
+    def data(n, heads):
+        x = rng.standard_normal((n, heads, D), dtype=np.float32)
+        return synth.bf16_round(x) if dtype == synth.BF16 else x
+
+    def both(op):
+        """The same setup operation on both sides: both succeed or both fail with the same code."""
+        try:
+            osess.setup([op])
+        except KVError as e:
+            with pytest.raises(binding.SymError) as ce:
+                sess.setup([op])
+            assert ce.value.code == e.code, op[0]
+            return False
+        sess.setup([op])
+        return True
+
+    next_fid, n_pred, worst = 0, 0, 0.0
+    for step in range(260):
+        fids = sorted(osess.h)
+        live = [f for f in fids if not osess.model.is_waiting(osess.h[f])]
+        r = rng.random()
+        if r < 0.08 or len(fids) < 3:
+            both(("open", next_fid))
+            both(("append", next_fid, data(n := int(rng.integers(1, 70)), Hkv), data(n, Hkv)))
+            next_fid += 1
+        elif r < 0.2 and live:
+            f = int(rng.choice(live))
+            both(("append", f, data(n := int(rng.integers(1, 50)), Hkv), data(n, Hkv)))
+        elif r < 0.3 and fids:
+            if both(("fork", next_fid, int(rng.choice(fids)))):
+                next_fid += 1
+        elif r < 0.37 and fids:
+            f = int(rng.choice(fids))
+            L = osess.model.kv_len(osess.h[f])
+            idx = np.flatnonzero(rng.random(L) < 0.7) if rng.random() < 0.7 else np.arange(L)[:int(rng.integers(0, L + 1))]
+            if both(("extract", next_fid, f, [int(i) for i in idx])):
+                next_fid += 1
+        elif r < 0.42 and len(fids) >= 2:
+            if both(("merge", next_fid, [int(x) for x in rng.choice(fids, size=2)])):
+                next_fid += 1
+        elif r < 0.47 and live:
+            f = int(rng.choice(live))
+            n = int(rng.integers(0, osess.model.kv_len(osess.h[f]) + 1))
+            osess.model.kv_truncate(osess.h[f], n)
+            sess.ctx.kv_truncate([sess.h[f]], [n])
+        elif r < 0.55 and fids:
+            both(("offload", [int(x) for x in rng.choice(fids, size=min(len(fids), int(rng.integers(1, 3))), replace=False)]))
+        elif r < 0.63 and fids:
+            both(("restore", [int(x) for x in rng.choice(fids, size=min(len(fids), int(rng.integers(1, 3))), replace=False)]))
+        elif r < 0.7 and len(fids) > 6:
+            f = int(rng.choice(fids))
+            osess.setup([("remove", f)])
+            sess.setup([("remove", f)])
+        elif live:
+            k = int(rng.integers(1, min(len(live), 10) + 1))
+            files = [int(x) for x in rng.choice(live, size=k, replace=False)]
+            nt = [int(rng.choice([1, 1, 1, 1, 2, 3, 5, 8, 17, 40])) for _ in files]
+            T = sum(nt)
+            b = dict(files=files, n_tokens=nt, q=data(T, Hq), k_new=data(T, Hkv), v_new=data(T, Hkv))
+            try:
+                ref = osess.pred(b, dtype=np.float64)
+            except KVError as e:
+                with pytest.raises(binding.SymError) as ce:
+                    sess.pred(sess.upload_batch(b))
+                assert ce.value.code == e.code
+            else:
+                got = sess.pred(sess.upload_batch(b)).cpu().numpy()
+                worst = max(worst, check_outputs(got, ref))
+                n_pred += 1
+        for f in osess.h:
+            assert sess.ctx.kv_pages(sess.h[f]) == osess.model.kv_pages(osess.h[f]), (step, f)
+        assert sess.ctx.free_pages() == osess.model.free_pages(), step
+    torch.cuda.synchronize()
+    used = sorted({p for f in osess.h for p in osess.model.kv_pages(osess.h[f]) if p >= 0})
+    assert [sess.ctx.page_refcount(p) for p in used] == [int(osess.model.refcount[p]) for p in used]
+    osess.model.audit()
+    assert n_pred > 40
+    print(f"random program: {n_pred} pred batches, worst scaled error {worst:.2e}")
+    sess.close()
