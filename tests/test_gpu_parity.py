@@ -491,7 +491,9 @@ def test_rag_driver_replayed_on_the_oracle(pareto_index):
     sess.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 1), (64, 8, 128, synth.BF16, 2), (8, 8, 64, synth.F32, 3)])
+@pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 1), (64, 8, 128, synth.BF16, 2), (8, 8, 64, synth.F32, 3),
+                                                 (16, 8, 128, synth.BF16, 4), (8, 8, 128, synth.BF16, 5), (32, 8, 128, synth.BF16, 6),
+                                                 (32, 8, 64, synth.F32, 7), (4, 1, 128, synth.BF16, 8)])
 def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
     """A seeded random program over the whole API (open, append, fork, extract, merge, truncate,
     offload, restore, remove, pred batches that mix single tokens, drafts and prefill chunks) run
