@@ -531,7 +531,13 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
         fids = sorted(osess.h)
         live = [f for f in fids if not osess.model.is_waiting(osess.h[f])]
         r = rng.random()
-        if r < 0.08 or len(fids) < 3:
+        if step % 60 == 5:                  # a long prefix forked five times: decode through shared-prefix tiles
+            both(("open", next_fid))
+            both(("append", next_fid, data(n := int(rng.integers(140, 400)), Hkv), data(n, Hkv)))
+            for i in range(1, 6):
+                both(("fork", next_fid + i, next_fid))
+            next_fid += 6
+        elif r < 0.08 or len(fids) < 3:
             both(("open", next_fid))
             both(("append", next_fid, data(n := int(rng.integers(1, 70)), Hkv), data(n, Hkv)))
             next_fid += 1
@@ -564,7 +570,7 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
             osess.setup([("remove", f)])
             sess.setup([("remove", f)])
         elif live:
-            k = int(rng.integers(1, min(len(live), 10) + 1))
+            k = int(rng.integers(1, min(len(live), 16) + 1))
             files = [int(x) for x in rng.choice(live, size=k, replace=False)]
             nt = [int(rng.choice([1, 1, 1, 1, 2, 3, 5, 8, 17, 40])) for _ in files]
             T = sum(nt)
