@@ -469,6 +469,20 @@ def main():
         binding.calib_copy(buf[1 << 30:], buf, 1 << 30, stream)
         torch.cuda.synchronize()
         del buf
+    mfma_sustained = None
+    if not args.no_calib and mfma_flops:
+        # what the matrix cores sustain on this part with nothing but MFMAs in the loop (two wavefronts
+        # per SIMD, operands in registers): the rate under the power limit, below the nominal peak
+        blocks = torch.cuda.get_device_properties(dev).multi_processor_count
+        sink = torch.empty(blocks * 512, dtype=torch.float32, device=dev)
+        binding.calib_mfma(sink, blocks, 2000, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = binding.calib_mfma(sink, blocks, 20000, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_sustained = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        del sink
 
     stats = sessions[0].ctx.get_stats()
     for s in sessions:
@@ -493,6 +507,8 @@ def main():
         "kernel_breakdown": breakdown,
         "stream_read_TBps": round(stream_read, 3) if stream_read else None,
         "frac_of_stream_read": round(hbm_ach / 1e3 / stream_read, 4) if stream_read else None,
+        "mfma_sustained_TFLOPs": round(mfma_sustained, 1) if mfma_sustained else None,
+        "frac_of_mfma_sustained": round(mfma_ach / mfma_sustained, 4) if mfma_sustained else None,
         "cpu_baseline": cpu,
         "host_us_per_step": {"plan_and_descriptor": round(stats["host_ns_plan"] / max(stats["pred_batches"], 1) / 1e3, 2),
                              "whole_call": round(stats["host_ns_pred"] / max(stats["pred_batches"], 1) / 1e3, 2)},

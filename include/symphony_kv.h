@@ -291,6 +291,12 @@ int sym_profile_read(sym_ctx* ctx, int kernel_id, double* total_ms, int64_t* lau
  * out8, 8 bytes) and a plain copy dst <- src.  bytes must be a multiple of 16.           */
 int sym_calib_read(const void* src, int64_t bytes, void* out8, void* stream);
 int sym_calib_copy(void* dst, const void* src, int64_t bytes, void* stream);
+/* Calibration of the matrix cores: `blocks` workgroups of 8 wavefronts (two per SIMD, the occupancy of
+ * the prefill tile kernel) issue nothing but 32x32x16 bf16 MFMAs on register operands, 16 per
+ * iteration and wavefront: blocks * 8 * iters * 16 * 32768 flops.  out: device, blocks * 512
+ * floats (one per thread, keeps the work alive).  Timed by the caller; what it sustains is
+ * the rate the part delivers under its power limit, below the nominal peak.                */
+int sym_calib_mfma(float* out, int32_t blocks, int32_t iters, void* stream);
 
 #ifdef __cplusplus
 }

@@ -81,6 +81,7 @@ _SIGNATURES = {
     "sym_profile_read": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), _I64P]),
     "sym_calib_read": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
     "sym_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
+    "sym_calib_mfma": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
 }
 
 
@@ -369,6 +370,14 @@ def calib_read(src, nbytes, out8, stream=None):
     rc = load().sym_calib_read(_ptr(src), nbytes, _ptr(out8), stream)
     if rc:
         raise SymError(rc, "calib_read")
+
+
+def calib_mfma(out, blocks, iters, stream=None):
+    """flops of the launch: blocks * 8 * iters * 16 * 32768."""
+    rc = load().sym_calib_mfma(_ptr(out), blocks, iters, stream)
+    if rc:
+        raise SymError(rc, "calib_mfma")
+    return blocks * 8 * iters * 16 * 32768
 
 
 def calib_copy(dst, src, nbytes, stream=None):

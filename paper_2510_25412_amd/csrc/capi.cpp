@@ -821,6 +821,10 @@ int sym_calib_read(const void* src, int64_t bytes, void* out8, void* stream) {
   if (!src || !out8 || bytes <= 0 || bytes % 16) return SYM_EINVAL;
   return launch_calib_read(src, bytes, out8, (hipStream_t)stream) == hipSuccess ? SYM_OK : SYM_EHIP;
 }
+int sym_calib_mfma(float* out, int32_t blocks, int32_t iters, void* stream) {
+  if (!out || blocks < 1 || blocks > 65536 || iters < 1) return SYM_EINVAL;
+  return launch_calib_mfma(out, blocks, iters, (hipStream_t)stream) == hipSuccess ? SYM_OK : SYM_EHIP;
+}
 int sym_calib_copy(void* dst, const void* src, int64_t bytes, void* stream) {
   if (!dst || !src || bytes <= 0 || bytes % 16) return SYM_EINVAL;
   return launch_calib_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? SYM_OK : SYM_EHIP;

@@ -1402,6 +1402,40 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(uint4* dst, const uint4
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Matrix-core rate that this part sustains: every wavefront (8 per workgroup, two per SIMD, as in the
+// tile kernel) issues 16 independent-enough 32x32x16 bf16 MFMAs per iteration on four accumulators,
+// operands in registers, nothing else in the loop.  flops = blocks * 8 * iters * 16 * 32768.
+__global__ __launch_bounds__(512, 1) void calib_mfma_kernel(float* out, int iters) {
+  const int lane = threadIdx.x & 63;
+  bf16x8_t x[4], y[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      // values of mixed sign and exponent, different in every lane and register
+      const uint32_t hsh = (uint32_t)(threadIdx.x * 8 + e + 131 * i + 977 * blockIdx.x) * 2654435761u;
+      x[i][e] = (__bf16)(((int)(hsh >> 20) - 2048) * (1.0f / 2048.0f));
+      y[i][e] = (__bf16)(((int)((hsh >> 8) & 4095) - 2048) * (1.0f / 2048.0f));
+    }
+  f32x16_t acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[(i + r) & 3], y[i], acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sum += acc[i][v];
+  out[(int64_t)blockIdx.x * 512 + threadIdx.x] = sum + (float)lane;
+}
+
 template <typename E>
 hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode_mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int G = da.Hq / da.Hkv;
@@ -1501,6 +1535,10 @@ hipError_t launch_swap(const SwapArgs& a, hipStream_t st) {
 
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st) {
   hipLaunchKernelGGL(calib_read_kernel, dim3(256 * 4), dim3(256), 0, st, (const u32x4_t*)src, bytes / 16, (unsigned long long*)out8);
+  return hipGetLastError();
+}
+hipError_t launch_calib_mfma(float* out, int blocks, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(calib_mfma_kernel, dim3(blocks), dim3(512), 0, st, out, iters);
   return hipGetLastError();
 }
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st) {

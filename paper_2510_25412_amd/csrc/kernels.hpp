@@ -100,5 +100,6 @@ hipError_t launch_move(const MoveArgs& a, hipStream_t st);
 hipError_t launch_swap(const SwapArgs& a, hipStream_t st);
 hipError_t launch_calib_read(const void* src, int64_t bytes, void* out8, hipStream_t st);
 hipError_t launch_calib_copy(void* dst, const void* src, int64_t bytes, hipStream_t st);
+hipError_t launch_calib_mfma(float* out, int blocks, int iters, hipStream_t st);
 
 }  // namespace symkv
