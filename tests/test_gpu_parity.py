@@ -595,3 +595,45 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
     assert n_pred > 40
     print(f"random program: {n_pred} pred batches, worst scaled error {worst:.2e}")
     sess.close()
+
+
+def test_calibration_kernels():
+    """The kernels that bench.py calibrates against do the work they are priced at: the copy copies
+    every byte, the streaming read leaves its checksum slot alone, and the MFMA loop's accumulators
+    hold the products of its operands (checked through a sum that needs only the MFMA operand layout:
+    lane l supplies row or column l % 32 and the 8 consecutive k from 8 * (l / 32))."""
+    from paper_2510_25412_amd import binding
+    assert torch.cuda.is_available()
+    dev = torch.device("cuda:0")
+    n = (1 << 20) + 48
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=dev)
+    dst = torch.zeros_like(src)
+    binding.calib_copy(dst, src, n)
+    out8 = torch.zeros(1, dtype=torch.int64, device=dev)
+    binding.calib_read(src, n, out8)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert int(out8.item()) in (0, 1)
+
+    blocks, iters = 3, 2
+    sink = torch.full((blocks * 512,), float("nan"), dtype=torch.float32, device=dev)
+    flops = binding.calib_mfma(sink, blocks, iters)
+    torch.cuda.synchronize()
+    assert flops == blocks * 8 * iters * 16 * 32768
+    got = sink.cpu().numpy().astype(np.float64).reshape(blocks, 8, 64)
+    tid = np.arange(512, dtype=np.uint64).reshape(8, 64, 1, 1)
+    e = np.arange(8, dtype=np.uint64).reshape(1, 1, 1, 8)
+    i = np.arange(4, dtype=np.uint64).reshape(1, 1, 4, 1)
+    for b in range(blocks):
+        hsh = ((tid * 8 + e + 131 * i + 977 * b) * 2654435761) & 0xFFFFFFFF          # [wave][lane][reg][elem]
+        x = ((hsh >> 20).astype(np.int64) - 2048) / 2048.0
+        y = (((hsh >> 8) & 4095).astype(np.int64) - 2048) / 2048.0
+        bf = lambda a: torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+        x, y = bf(x), bf(y)
+        # column sums of A and row sums of B over the 32 lanes that hold the same k: k = 8 * (lane / 32) + elem
+        sa = x.reshape(8, 2, 32, 4, 8).sum(axis=2).transpose(0, 2, 1, 3).reshape(8, 4, 16)   # [wave][reg][k]
+        sb = y.reshape(8, 2, 32, 4, 8).sum(axis=2).transpose(0, 2, 1, 3).reshape(8, 4, 16)
+        for w in range(8):
+            want = iters * sum(float(sa[w, (a + r) & 3] @ sb[w, a]) for a in range(4) for r in range(4))
+            have = got[b, w].sum() - 2016.0              # every thread adds its lane index
+            assert abs(have - want) <= 2e-2 + 1e-3 * abs(want), (b, w, have, want)     # fp32 sums of ~1e3 terms
