@@ -962,192 +962,242 @@ __device__ __forceinline__ void decode_mfma_ranges(const DecodeArgs& a, const in
   const int col = lane & 15, grp = lane >> 4;        // query column, lane group (tokens 4*grp .. 4*grp+3 of a page)
   const int head = col % GT;                          // columns past nt * GT repeat earlier ones; their results are ignored
   const int vq4 = lane >> 4, vc = lane & 15;          // V staging role: tokens 4*vq4 .. +3 of a page, dim chunk vc
+  auto sload = [&](const int32_t* ptr) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(*ptr); };
 
+  // As in the VALU kernel, the wavefront's units form ONE stream: a load cursor runs ahead of the compute
+  // cursor through the same sequence of (row, kv head) ranges, in steps of a pair of pages (a pair never
+  // straddles two ranges: the last pair of a range with an odd number of pages has one page), so the
+  // K/V loads of the next range are in flight while the current one is finished and written out.
   const int32_t* ww = a.waves + wv * 8;
-  int row = __builtin_amdgcn_readfirstlane(ww[0]);
-  int g = __builtin_amdgcn_readfirstlane(ww[1]);
-  int p = __builtin_amdgcn_readfirstlane(ww[2]);
-  int remaining = __builtin_amdgcn_readfirstlane(ww[3]);
-  int part = __builtin_amdgcn_readfirstlane(ww[4]);
-  int pid0 = __builtin_amdgcn_readfirstlane(ww[5]);
-  int pid1 = __builtin_amdgcn_readfirstlane(ww[6]);
-  int tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
-  int vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
-  int qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
-  int pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
+  // compute cursor: the range being accumulated
+  int row = sload(ww + 0), g = sload(ww + 1), p = sload(ww + 2);
+  int remaining = sload(ww + 3);
+  int part = sload(ww + 4);
+  const int tbl0 = sload(a.rows + row * 4 + 0);
+  int vis = sload(a.rows + row * 4 + 1), qrow = sload(a.rows + row * 4 + 2);
+  int pstart = sload(a.rows + row * 4 + 3);
   int nt = (pstart >> 28) + 1;                        // new tokens in the row
   pstart &= 0x0fffffff;
-  bool first_range = true;
+  int np = (vis + nt - 1 + kP - 1) / kP;              // pages the row's last token sees
+  // load cursor: the pair whose K/V is requested next
+  int lg = g, lrow = row, lp = p, lnp = np, ltbl = tbl0, lpstart = pstart, lrem = remaining;
+  int id0 = sload(ww + 5), id1 = sload(ww + 6);       // page ids of that pair (the first pair's come with the wave record)
+  // record of the row after the load cursor's, fetched a whole row ahead (one past the last row: valid words, never used)
+  int n_tbl = 0, n_np = 0, n_pstart = 0;
+  auto fetch_next_row = [&](int rr) __attribute__((always_inline)) {
+    n_tbl = sload(a.rows + rr * 4 + 0);
+    const int v = sload(a.rows + rr * 4 + 1), ps = sload(a.rows + rr * 4 + 3);
+    n_pstart = ps & 0x0fffffff;
+    n_np = (v + (ps >> 28) + kP - 1) / kP;
+  };
+  fetch_next_row(row + 1);
+  // record of row + 1 as the compute side needs it
+  int c_nvis = 0, c_nqrow = 0, c_nps = 0;
+  auto fetch_compute_next_row = [&]() __attribute__((always_inline)) {
+    c_nvis = sload(a.rows + (row + 1) * 4 + 1);
+    c_nqrow = sload(a.rows + (row + 1) * 4 + 2);
+    c_nps = sload(a.rows + (row + 1) * 4 + 3);
+  };
+  fetch_compute_next_row();
 
-  while (remaining > 0) {
-    const int np = (vis + nt - 1 + kP - 1) / kP;      // pages the row's last token sees
-    const int cnt = min(remaining, np - p);
-    const int32_t* tbl = a.pt + tbl_off + p;
-    const int last = cnt - 1;
-    const int tok = min(col / GT, nt - 1);            // this column's token within the row
-
-    // Q^T operand: this lane's (token, head), dims 32*ks + 8*grp .. +8 for the four k-steps
-    bf16x8_t q[4];
-    {
-      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)(qrow + tok) * a.Hq + g * GT + head) * kRowBytes + grp * 16;
+  // K of a page as the A operand: token col, chunk 4*ks + grp of its row (row half ks/2, chunk 4*(ks%2) + grp)
+  const int k_off = col * kHalfBytes + grp * 16;
+  // V of a page for the staging: tokens 4*vq4 + u, chunk vc
+  const int v_off = kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * vq4) * kHalfBytes + (vc & 7) * 16;
+  auto load_page = [&](uint4 (&kk)[4], uint4 (&vv)[4], const uint8_t* slab, int pid) __attribute__((always_inline)) {
+    const uint8_t* base = slab + (int64_t)pid * a.page_bytes;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 64));
+    for (int ks = 0; ks < 4; ++ks)
+      kk[ks] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + k_off + (ks >> 1) * (kP * kHalfBytes) + (ks & 1) * 64)));
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      vv[u] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + v_off + u * kHalfBytes)));
+  };
+  // Requests the next pair and moves the load cursor; every load is unconditional (a page that does not
+  // exist, also past the end of the wavefront's work, is page 0 of the pool and is never used).
+  auto load_next_pair = [&](uint4 (&k0)[4], uint4 (&v0)[4], uint4 (&k1)[4], uint4 (&v1)[4]) __attribute__((always_inline)) {
+    const int take = min(2, min(lrem, lnp - lp));
+    const uint8_t* slab = a.pool + (int64_t)(take > 0 ? lg : 0) * kSlab;
+    load_page(k0, v0, slab, take > 0 ? id0 : 0);
+    load_page(k1, v1, slab, take > 1 ? id1 : 0);
+    if (take > 0) {
+      lrem -= take;
+      lp += take;
+      if (lp == lnp) {                                 // the range after: next head of the row, or the next row
+        if (++lg == a.Hkv) {
+          lg = 0;
+          ++lrow;
+          ltbl = n_tbl;
+          lnp = n_np;
+          lpstart = n_pstart;
+          fetch_next_row(lrow + 1);
+        }
+        lp = lpstart;
+      }
+      const int t2 = min(2, min(lrem, lnp - lp));      // ids of the pair after this one, used one pair later
+      id0 = t2 > 0 ? sload(a.pt + ltbl + lp) : 0;
+      id1 = t2 > 1 ? sload(a.pt + ltbl + lp + 1) : 0;
     }
-    f32x4_t O[8];
+  };
+
+  // state of the range being accumulated
+  int tok = 0;                                        // this column's token within the row
+  bf16x8_t q[4];                                      // Q^T operand: this lane's (token, head), dims 32*ks + 8*grp .. +8
+  auto load_q = [&]() __attribute__((always_inline)) {
+    tok = min(col / GT, nt - 1);
+    const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)(qrow + tok) * a.Hq + g * GT + head) * kRowBytes + grp * 16;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) q[ks] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(qp + ks * 64));
+  };
+  f32x4_t O[8];
+  float m = -1e30f, l = 0.f;
+  auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int db = 0; db < 8; ++db) O[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m = -1e30f, l = 0.f;
+    m = -1e30f;
+    l = 0.f;
+  };
+  reset_state();
+  load_q();
+  int p_first = p;                                    // first page of the piece being accumulated
 
-    const uint8_t* slab = a.pool + (int64_t)g * kSlab;
-    // K of a page as the A operand: token col, chunk 4*ks + grp of its row (row half ks/2, chunk 4*(ks%2) + grp)
-    const int k_off = col * kHalfBytes + grp * 16;
-    // V of a page for the staging: tokens 4*vq4 + u, chunk vc
-    const int v_off = kBlk + (vc >> 3) * (kP * kHalfBytes) + (4 * vq4) * kHalfBytes + (vc & 7) * 16;
-    auto load_page = [&](uint4 (&kk)[4], uint4 (&vv)[4], int pid) {
-      const uint8_t* base = slab + (int64_t)pid * a.page_bytes;
+  // scores of one page: 4 tokens (4*grp + v) x this lane's head; tokens past nvalid masked
+  auto scores = [&](const uint4 (&kk)[4], int nvalid, float (&sc)[4]) __attribute__((always_inline)) {
+    f32x4_t S = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        kk[ks] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + k_off + (ks >> 1) * (kP * kHalfBytes) + (ks & 1) * 64)));
+    for (int ks = 0; ks < 4; ++ks) S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk[ks]), q[ks], S, 0, 0, 0);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        vv[u] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + v_off + u * kHalfBytes)));
-    };
-    // scores of one page: 4 tokens (4*grp + v) x this lane's head; tokens past nvalid masked
-    auto scores = [&](const uint4 (&kk)[4], int nvalid, float (&sc)[4]) {
-      f32x4_t S = {0.f, 0.f, 0.f, 0.f};
+    for (int v = 0; v < 4; ++v) sc[v] = (4 * grp + v) < nvalid ? S[v] : -__builtin_inff();
+  };
+  // V of one page -> fp16, transposed, into the wavefront's LDS buffer (half pg of every dim row)
+  auto stage_v = [&](const uint4 (&vv)[4], int nvalid, int pg) __attribute__((always_inline)) {
+    const uint32_t w[4][4] = {{vv[0].x, vv[0].y, vv[0].z, vv[0].w}, {vv[1].x, vv[1].y, vv[1].z, vv[1].w},
+                              {vv[2].x, vv[2].y, vv[2].z, vv[2].w}, {vv[3].x, vv[3].y, vv[3].z, vv[3].w}};
+    bool ok[4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kk[ks]), q[ks], S, 0, 0, 0);
+    for (int u = 0; u < 4; ++u) ok[u] = (4 * vq4 + u) < nvalid;      // slots past the file's end may hold anything
 #pragma unroll
-      for (int v = 0; v < 4; ++v) sc[v] = (4 * grp + v) < nvalid ? S[v] : -__builtin_inff();
-    };
-    // V of one page -> fp16, transposed, into the wavefront's LDS buffer (half pg of every dim row)
-    auto stage_v = [&](const uint4 (&vv)[4], int nvalid, int pg) {
-      const uint32_t w[4][4] = {{vv[0].x, vv[0].y, vv[0].z, vv[0].w}, {vv[1].x, vv[1].y, vv[1].z, vv[1].w},
-                                {vv[2].x, vv[2].y, vv[2].z, vv[2].w}, {vv[3].x, vv[3].y, vv[3].z, vv[3].w}};
-      bool ok[4];
+    for (int e = 0; e < 8; ++e) {
+      float f[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) ok[u] = (4 * vq4 + u) < nvalid;      // slots past the file's end may hold anything
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float f[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t x = (e & 1) ? (w[u][e >> 1] & 0xffff0000u) : (w[u][e >> 1] << 16);
-          f[u] = ok[u] ? as_f32(x) : 0.f;
-        }
-        const int d = vc * 8 + e;
-        uint2 pk;
-        pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[0], f[1]));
-        pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[2], f[3]));
-        *(uint2*)(vlds + d * kVtRow + ((vq4 ^ ((d >> 4) & 3)) * 16) + pg * 8) = pk;
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t x = (e & 1) ? (w[u][e >> 1] & 0xffff0000u) : (w[u][e >> 1] << 16);
+        f[u] = ok[u] ? as_f32(x) : 0.f;
       }
-    };
-    // two pages (32 tokens): scores, softmax weights, O^T += V^T P^T
-    auto compute2 = [&](const uint4 (&kA)[4], const uint4 (&vA)[4], const uint4 (&kB)[4], const uint4 (&vB)[4], int piA, bool haveB) {
-      // tokens of the page visible to this column's token; slots that hold file tokens at all
-      const int nvA = vis + tok - piA * kP, nvB = haveB ? nvA - kP : 0;
-      const int nsA = vis + nt - 1 - piA * kP, nsB = haveB ? nsA - kP : 0;
-      float sA[4], sB[4];
-      scores(kA, nvA, sA);
-      scores(kB, nvB, sB);
-      stage_v(vA, nsA, 0);
-      stage_v(vB, nsB, 1);
-      const float mx = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3]))) * a.scale_log2e;
-      if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {       // rare after the first pages
-        float mn = fmaxf(m, mx);
-        mn = fmaxf(mn, __shfl_xor(mn, 16));
-        mn = fmaxf(mn, __shfl_xor(mn, 32));                        // all four lane groups of the head agree
-        const float al = __builtin_amdgcn_exp2f(m - mn);
-        l *= al;
+      const int d = vc * 8 + e;
+      uint2 pk;
+      pk.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[0], f[1]));
+      pk.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(f[2], f[3]));
+      *(uint2*)(vlds + d * kVtRow + ((vq4 ^ ((d >> 4) & 3)) * 16) + pg * 8) = pk;
+    }
+  };
+  // two pages (32 tokens): scores, softmax weights, O^T += V^T P^T
+  auto compute2 = [&](const uint4 (&kA)[4], const uint4 (&vA)[4], const uint4 (&kB)[4], const uint4 (&vB)[4], int piA, bool haveB) __attribute__((always_inline)) {
+    // tokens of the page visible to this column's token; slots that hold file tokens at all
+    const int nvA = vis + tok - piA * kP, nvB = haveB ? nvA - kP : 0;
+    const int nsA = vis + nt - 1 - piA * kP, nsB = haveB ? nsA - kP : 0;
+    float sA[4], sB[4];
+    scores(kA, nvA, sA);
+    scores(kB, nvB, sB);
+    stage_v(vA, nsA, 0);
+    stage_v(vB, nsB, 1);
+    const float mx = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3]))) * a.scale_log2e;
+    if (__builtin_amdgcn_ballot_w64(mx > m + kTau) != 0) {       // rare after the first pages
+      float mn = fmaxf(m, mx);
+      mn = fmaxf(mn, __shfl_xor(mn, 16));
+      mn = fmaxf(mn, __shfl_xor(mn, 32));                        // all four lane groups of the head agree
+      const float al = __builtin_amdgcn_exp2f(m - mn);
+      l *= al;
 #pragma unroll
-        for (int db = 0; db < 8; ++db)
+      for (int db = 0; db < 8; ++db)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) O[db][v] *= al;
-        m = mn;
-      }
-      uint32_t pw[4];
+        for (int v = 0; v < 4; ++v) O[db][v] *= al;
+      m = mn;
+    }
+    uint32_t pw[4];
 #pragma unroll
-      for (int v = 0; v < 4; v += 2) {
-        const auto pa = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sA[v], a.scale_log2e, -m)),
-                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(sA[v + 1], a.scale_log2e, -m)));
-        const auto pb = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sB[v], a.scale_log2e, -m)),
-                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(sB[v + 1], a.scale_log2e, -m)));
-        l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pa), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
-        l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pb), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
-        pw[v >> 1] = __builtin_bit_cast(uint32_t, pa);
-        pw[2 + (v >> 1)] = __builtin_bit_cast(uint32_t, pb);
-      }
-      const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+    for (int v = 0; v < 4; v += 2) {
+      const auto pa = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sA[v], a.scale_log2e, -m)),
+                                                 __builtin_amdgcn_exp2f(__builtin_fmaf(sA[v + 1], a.scale_log2e, -m)));
+      const auto pb = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(sB[v], a.scale_log2e, -m)),
+                                                 __builtin_amdgcn_exp2f(__builtin_fmaf(sB[v + 1], a.scale_log2e, -m)));
+      l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pa), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
+      l = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pb), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l, false);
+      pw[v >> 1] = __builtin_bit_cast(uint32_t, pa);
+      pw[2 + (v >> 1)] = __builtin_bit_cast(uint32_t, pb);
+    }
+    const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pw[0], pw[1], pw[2], pw[3]));
 #pragma unroll
-      for (int db = 0; db < 8; ++db) {
-        const f16x8_t vt = *(const f16x8_t*)(vlds + (db * 16 + col) * kVtRow + ((grp ^ (db & 3)) * 16));
-        O[db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vt, P, O[db], 0, 0, 0);
-      }
-    };
+    for (int db = 0; db < 8; ++db) {
+      const f16x8_t vt = *(const f16x8_t*)(vlds + (db * 16 + col) * kVtRow + ((grp ^ (db & 3)) * 16));
+      O[db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vt, P, O[db], 0, 0, 0);
+    }
+  };
 
-    if (!first_range) {
-      pid0 = tbl[0];
-      pid1 = tbl[min(1, last)];
-    }
-    first_range = false;
-    // pages k, k+1 in registers while pages k+2, k+3 are in flight; every load is unconditional
-    // (past the end: page 0 of the pool, never used)
-    uint4 kA[4], vA[4], kB[4], vB[4], kC[4], vC[4], kD[4], vD[4];
-    int id2 = cnt > 2 ? tbl[2] : 0, id3 = cnt > 3 ? tbl[3] : 0;
-    load_page(kA, vA, pid0);
-    load_page(kB, vB, cnt > 1 ? pid1 : 0);
-    for (int k = 0; k < cnt; k += 4) {
-      load_page(kC, vC, id2);
-      load_page(kD, vD, id3);
-      id2 = k + 4 <= last ? tbl[k + 4] : 0;
-      id3 = k + 5 <= last ? tbl[k + 5] : 0;
-      compute2(kA, vA, kB, vB, p + k, k + 1 < cnt);
-      load_page(kA, vA, id2);
-      load_page(kB, vB, id3);
-      id2 = k + 6 <= last ? tbl[k + 6] : 0;
-      id3 = k + 7 <= last ? tbl[k + 7] : 0;
-      if (k + 2 < cnt) compute2(kC, vC, kD, vD, p + k + 2, k + 3 < cnt);
-    }
-
-    // ---- end of the range: the four lane groups of a head add up their sums; O^T is complete
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    const bool whole = (p == 0 && cnt == np);
-    if (col < nt * GT) {
-      if (whole) {
-        const float inv = 1.0f / l;
-        float* o = a.out + ((int64_t)(qrow + tok) * a.Hq + g * GT + head) * 128 + 4 * grp;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0] * inv, O[db][1] * inv, O[db][2] * inv, O[db][3] * inv);
-      } else {
-        const int64_t slot = (int64_t)(part + tok) * GT + head;   // a piece leaves one partial per token of the row
-        float* o = a.part_acc + slot * 128 + 4 * grp;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0], O[db][1], O[db][2], O[db][3]);
-        if (grp == 0) {
-          a.part_ml[slot * 2 + 0] = m;
-          a.part_ml[slot * 2 + 1] = l;
-        }
-      }
-    }
+  // End of a piece: the four lane groups of a head add up their sums, O^T is complete; the compute cursor
+  // moves to the next range first, so that its query rows are on their way while this piece is written.
+  auto finish_piece = [&]() __attribute__((always_inline)) {
+    const bool whole = (p_first == 0 && p == np);
+    const int64_t o_row = (int64_t)(qrow + tok) * a.Hq + g * GT + head;
+    const int64_t o_slot = (int64_t)(part + tok) * GT + head;     // a piece leaves one partial per token of the row
+    const bool o_live = col < nt * GT;
     if (!whole) part += nt;
-    remaining -= cnt;
-    p += cnt;
-    if (p == np) {
+    const bool more = remaining > 0;
+    if (more) {
       if (++g == a.Hkv) {
         g = 0;
         ++row;
-        if (remaining > 0) {
-          tbl_off = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 0]);
-          vis = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 1]);
-          qrow = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 2]);
-          pstart = __builtin_amdgcn_readfirstlane(a.rows[row * 4 + 3]);
-          nt = (pstart >> 28) + 1;
-          pstart &= 0x0fffffff;
+        vis = c_nvis;
+        qrow = c_nqrow;
+        nt = (c_nps >> 28) + 1;
+        pstart = c_nps & 0x0fffffff;
+        np = (vis + nt - 1 + kP - 1) / kP;
+        fetch_compute_next_row();
+      }
+      load_q();
+    }
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (o_live) {
+      if (whole) {
+        const float inv = 1.0f / l;
+        float* o = a.out + o_row * 128 + 4 * grp;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0] * inv, O[db][1] * inv, O[db][2] * inv, O[db][3] * inv);
+      } else {
+        float* o = a.part_acc + o_slot * 128 + 4 * grp;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *(float4*)(o + db * 16) = make_float4(O[db][0], O[db][1], O[db][2], O[db][3]);
+        if (grp == 0) {
+          a.part_ml[o_slot * 2 + 0] = m;
+          a.part_ml[o_slot * 2 + 1] = l;
         }
       }
-      p = pstart;
     }
+    if (more) {
+      p = pstart;
+      p_first = p;
+      reset_state();
+    }
+  };
+  // one pair of the stream: accumulate it, move the compute cursor, close the piece at the end of the range or of the wavefront's work
+  auto do_pair = [&](const uint4 (&kA)[4], const uint4 (&vA)[4], const uint4 (&kB)[4], const uint4 (&vB)[4]) __attribute__((always_inline)) {
+    const int took = max(1, min(2, min(remaining, np - p)));     // >= 1 whatever the descriptor says: the loop ends
+    compute2(kA, vA, kB, vB, p, took > 1);
+    p += took;
+    remaining -= took;
+    if (p == np || remaining == 0) finish_piece();
+  };
+
+  // pair k in registers while pair k + 1 is in flight
+  uint4 kA[4], vA[4], kB[4], vB[4], kC[4], vC[4], kD[4], vD[4];
+  load_next_pair(kA, vA, kB, vB);
+  load_next_pair(kC, vC, kD, vD);
+  while (remaining > 0) {
+    do_pair(kA, vA, kB, vB);
+    load_next_pair(kA, vA, kB, vB);
+    if (remaining > 0) do_pair(kC, vC, kD, vD);
+    load_next_pair(kC, vC, kD, vD);
   }
 }
 
