@@ -810,6 +810,28 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     return S;
   };
   f32x16_t Sc;                   // scores of the current block (computed one step ahead)
+  float mx_cur = 0.f;            // their row maximum in log2 units, both lanes of the row agreeing
+  // Causal mask and row maximum of the scores in Sc (block kb), done as soon as the scores exist, at the
+  // end of the step before the one that uses them: the exchange between the two lanes of a row goes
+  // through the LDS pipe, and there it must not queue behind the sixteen operand reads of its own step
+  // with the MFMAs waiting for the branch that needs it.
+  // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
+  // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
+  auto mask_and_max = [&](const int kb) __attribute__((always_inline)) {
+    const int tok0 = kb * kKvBlock + 4 * hf;
+    const bool edge = kb * kKvBlock + kKvBlock > mask_from;      // the block reaches the causal edge of some row
+    float mx = -__builtin_inff();
+    if (edge) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int tok = tok0 + 8 * (v >> 2) + (v & 3);
+        Sc[v] = tok < vis[0] ? Sc[v] : -__builtin_inff();
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, Sc[v]);
+    mx_cur = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
+  };
   auto step = [&](const int kb, uint8_t* cur, uint8_t* nxt, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
     store_lds(kb + 1, nxt, k0, k1, v0, v1);
     __syncthreads();           // block kb + 1 is in LDS; everyone is done with the block that was in `nxt` before
@@ -827,21 +849,8 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
       for (int db = 0; db < 4; ++db) vv[db][ks] = *(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32);
     __builtin_amdgcn_sched_barrier(0);
 
-    // value v of a lane is token 8*(v/4) + 4*hf + v%4 of the block
-    // scores stay unscaled; the scale (softmax scale * log2 e, positive) goes into one fma with the max
-    const int tok0 = kb * kKvBlock + 4 * hf;
-    const bool edge = kb * kKvBlock + kKvBlock > mask_from;      // the block reaches the causal edge of some row
-    float mx = -__builtin_inff();
-    if (edge) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int tok = tok0 + 8 * (v >> 2) + (v & 3);
-        Sc[v] = tok < vis[0] ? Sc[v] : -__builtin_inff();
-      }
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, Sc[v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2e;
+    // the block's row maximum was found at the end of the step before (mask_and_max)
+    const float mx = mx_cur;
     if (__builtin_amdgcn_ballot_w64(mx > m[0] + kTau) != 0) {     // rare after the first block
       const float mn = fmaxf(m[0], mx);
       const float al = __builtin_amdgcn_exp2f(m[0] - mn);
@@ -884,6 +893,7 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
       __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);
     }
     Sc = Sn;
+    mask_and_max(kb + 1);
   };
 
   issue_loads(kb0, ka0, ka1, va0, va1);
@@ -896,6 +906,7 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     bf16x8_t kk[8];
     k_operands(lds[0], kk);
     Sc = scores(kk);
+    mask_and_max(kb0);
   }
   for (int kb = kb0; kb < nblk; kb += 3) {
     step(kb, lds[0], lds[1], kb0r, kb1r, vb0, vb1);
