@@ -224,7 +224,11 @@ int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_
  *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
  *                           partials of the row's shared prefix: first, stride, count; then the
  *                           distance between the own pieces (tokens in the row); 0
- *   page_table, pt_off [n_lips + 1]
+ *   page_table, pt_off [n_lips + 1]   page ids file by file; a member of a shared-prefix group
+ *                           that is not the first member of a tile leaves out the common
+ *                           pages (nothing reads them through its table) and its offset,
+ *                           in rows and in pt_off, is moved back by their number, so that
+ *                           entry offset + i is page i for every i from its first own page on
  *   tiles     [n_tiles][12] page-table offset, file length before the call, first q/out row
  *                           (shared: offset into the member list), new tokens (shared: members)
  *                           in the tile, kv head, token offset in the chunk (shared: first

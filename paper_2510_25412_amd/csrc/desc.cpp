@@ -169,6 +169,19 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   if (total_units == 0) nw = 0;
   const int64_t n_members = (int64_t)member_rows.size();
 
+  // A member of a shared-prefix group reads only the pages after the common ones; those are read by
+  // the group's tiles through the table of each tile's first member.  So the common pages of every
+  // other member stay out of the descriptor (256 forks of 128-page prefixes: 128 KB that would
+  // cross PCIe for nothing); its table offset is moved back by the pages left out, so that page
+  // index i >= its first own page still finds entry i.
+  std::vector<uint8_t>& full_table = out->full_table;
+  full_table.assign((size_t)n_lips, 1);
+  for (int32_t b = 0; b < n_lips; ++b)
+    if (share_start[b] > 0) full_table[b] = 0;
+  for (size_t s = 0; s < stiles.size(); s += 6) full_table[stiles[s]] = 1;
+  for (int32_t b = 0; b < n_lips; ++b)
+    if (!full_table[b]) entries -= share_start[b];
+
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
@@ -193,11 +206,12 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int32_t* tiles = w + off_tiles;
   int64_t r = 0, e = 0, tok = 0, ti = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
-    ptoff[b] = (int32_t)e;
-    const int64_t e_lip = e;
+    const int64_t skip = full_table[b] ? 0 : share_start[b];      // leading pages left out (see above)
+    const int64_t e_lip = e - skip;
+    ptoff[b] = (int32_t)e_lip;
     int64_t np = (len_after[b] + P - 1) / P;
-    std::memcpy(pt + e, tables[b], (size_t)np * sizeof(int32_t));
-    e += np;
+    std::memcpy(pt + e, tables[b] + skip, (size_t)(np - skip) * sizeof(int32_t));
+    e += np - skip;
     if (is_prefill(b)) {
       // order (kv head, token tile): the tiles that read the same K/V are neighbours
       for (int32_t g = 0; g < H; ++g)

@@ -61,6 +61,7 @@ struct BatchDesc {
   // scratch of the builder, kept between calls
   std::vector<std::pair<int32_t, int32_t>> by_first_page, lcp;
   std::vector<int32_t> tile_tmp, tile_order;
+  std::vector<uint8_t> full_table;   // per LIP: its whole page table goes into the descriptor (see build_desc)
   std::vector<std::pair<int64_t, int32_t>> tile_groups;
   std::vector<int32_t> share_start, share_base, share_k, share_ml, share_nc, member_rows, shared_tiles, qrow_of, groups, grp_members;
 };

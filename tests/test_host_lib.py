@@ -402,6 +402,17 @@ def test_descriptor_shared_prefix_groups():
     assert rows[:, 3].tolist() == [40] * 6 + [0, 0]       # members start after the 40 common pages
     members = words[hdr[15]:hdr[15] + n_members].tolist()
     assert members == [0, 1, 2, 3, 4, 5]
+    # page-table section: the first member keeps its whole table (the tiles read the common pages
+    # through it); the other five leave the 40 common pages out, and their offsets are moved back by
+    # 40 so that page i of the file is still entry offset + i for every page of their own range
+    pt = words[hdr[8]:hdr[9]]
+    assert len(pt) == len(flat) - 5 * 40
+    for b in range(8):
+        first = int(rows[b, 3]) & 0x0fffffff if b in (1, 2, 3, 4, 5) else 0
+        for i in range(first, len(tables[b])):
+            assert int(pt[int(rows[b, 0]) + i]) == tables[b][i], (b, i)
+    ptoff = words[hdr[9]:hdr[9] + 9]
+    assert ptoff[:8].tolist() == rows[:, 0].tolist() and int(ptoff[8]) == len(pt)
     tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
     assert all(int(t[6]) == 1 and int(t[3]) == 6 and int(t[0]) == int(off[0]) for t in tiles)
     covered = {}
