@@ -637,3 +637,25 @@ def test_calibration_kernels():
             want = iters * sum(float(sa[w, (a + r) & 3] @ sb[w, a]) for a in range(4) for r in range(4))
             have = got[b, w].sum() - 2016.0              # every thread adds its lane index
             assert abs(have - want) <= 2e-2 + 1e-3 * abs(want), (b, w, have, want)     # fp32 sums of ~1e3 terms
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8)])
+def test_every_kind_of_work_in_one_batch(Hq, Hkv):
+    """Two fork groups (their members' page tables travel without the common pages), a prefill
+    chunk, plain single-token LIPs and drafts of 3 and 6 tokens in ONE batch: prefill and shared-prefix
+    tiles in one grid with the decode work, and, because of the drafts, every decode range (the
+    members' own ranges included) on the matrix-core decode kernel.  Few waves, so that ranges are
+    cut inside the members' rows too."""
+    shape = synth.Shape(Hq, Hkv, 128, 16, synth.BF16)
+    files = [("new", 700), ("new", 330), ("new", 1500), ("new", 64), ("new", 909)]
+    files += [("fork", 0, int(s)) for s in (5, 40, 0, 17, 90, 33)]          # files 5..10: forks of file 0
+    files += [("fork", 1, int(s)) for s in (1, 2, 3, 60, 7)]                # files 11..15: forks of file 1
+    batch = [(f, 1) for f in range(5, 16)] + [(2, 1), (3, 100), (4, 3), (0, 6), (1, 1)]
+    wl = synth.custom(f"allkinds_{Hq}_{Hkv}", shape, files, batch, 1024, seed=4242 + Hq)
+    for waves in (0, 40):
+        kw = dict(decode_waves=waves) if waves else {}
+        got, sess, ref, osess = run_both(wl, **kw)
+        worst = check_outputs(got, ref)
+        check_state(wl, sess, osess)
+        sess.close()
+        print(f"all kinds {Hq}/{Hkv} waves={waves}: worst scaled error {worst:.2e}")
