@@ -220,10 +220,9 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
 
 // One prologue launch for the staged words in c->stage[si]: the first copy_words words (the
 // descriptor) are copied to the start of the workspace; the copy list at cow_off and the slot
-// map at slots_off are read from the pinned buffer by the kernel itself.  Records the event
-// that lets the staging buffer be reused.
-int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off,
-                           int32_t n_tokens, const void* k, const void* v, hipStream_t st) {
+// map at slots_off are read from the pinned buffer by the kernel itself.
+int launch_prologue(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off, int32_t n_tokens,
+                    const void* k, const void* v, hipStream_t st) {
   PrologueArgs a;
   a.pool = (uint8_t*)c->cfg.pool;
   a.page_bytes = c->page_bytes;
@@ -238,11 +237,16 @@ int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_o
   a.Hkv = c->cfg.n_kv_heads;
   a.n_cow = n_cow;
   a.append_blocks = a.copy_blocks = 0;
-  {
-    Timed t(c, SYM_K_PROLOGUE, st);
-    hipError_t e = launch_prologue(a, st);
-    if (e != hipSuccess) return fail_hip(c, e, "prologue launch");
-  }
+  Timed t(c, SYM_K_PROLOGUE, st);
+  hipError_t e = symkv::launch_prologue(a, st);
+  if (e != hipSuccess) return fail_hip(c, e, "prologue launch");
+  return SYM_OK;
+}
+// The same, and records the event that lets the staging buffer be reused.
+int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off,
+                           int32_t n_tokens, const void* k, const void* v, hipStream_t st) {
+  const int rc = launch_prologue(c, si, copy_words, cow_off, n_cow, slots_off, n_tokens, k, v, st);
+  if (rc) return rc;
   hipError_t e = hipEventRecord(c->stage_ev[si], st);
   if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
   c->stage_pending[si] = true;
@@ -701,9 +705,12 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
   std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
   const auto t_planned = std::chrono::steady_clock::now();
-  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, (int)(c->plan.cow.size() / 3), slots_off, (int32_t)c->plan.slots.size(),
-                                   k_new, v_new, st)))
-    return rc;
+  int n_cow = (int)(c->plan.cow.size() / 3);
+  if (c->plan.copies_first) {       // an append of this batch overwrites slots that a copy of this batch reads: copies in a launch of their own
+    if ((rc = launch_prologue(c, si, 0, cow_off, n_cow, 0, 0, nullptr, nullptr, st))) return rc;
+    n_cow = 0;
+  }
+  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, n_cow, slots_off, (int32_t)c->plan.slots.size(), k_new, v_new, st))) return rc;
   ++c->pred_batches;
   rc = launch_attention(c, words, q, out, st);
   const auto t_end = std::chrono::steady_clock::now();

@@ -1580,7 +1580,7 @@ hipError_t launch_merge(const MergeArgs& a, int G, int D, hipStream_t st) {
 hipError_t launch_prologue(PrologueArgs a, hipStream_t st) {
   const int64_t total = (int64_t)a.n_tokens * a.Hkv * 32;
   a.append_blocks = (int32_t)((total + 255) / 256);
-  a.copy_blocks = a.copy_words > 0 ? (int32_t)std::min<int64_t>((a.copy_words / 4 + 255) / 256, 256) : 0;
+  a.copy_blocks = a.copy_words > 0 ? (int32_t)std::min<int64_t>(((a.copy_words + 3) / 4 + 255) / 256, 256) : 0;   // >= 1: also for one, two or three words
   const int64_t blocks = (int64_t)a.append_blocks + a.n_cow + a.copy_blocks;
   if (blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(prologue_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);

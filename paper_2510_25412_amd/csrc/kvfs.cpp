@@ -241,6 +241,15 @@ int Kvfs::append(int32_t n, const int32_t* handles, const int32_t* n_tokens, App
         plan->cow.push_back(dst);
         plan->cow.push_back(r);
       }
+    } else if (r != 0 && plan && !plan->copies_first) {
+      // appending in place into a partly filled page: were more of its slots than this file sees
+      // copied out earlier in this batch?
+      const int32_t page = f.pages.back();
+      for (size_t c = 0; c < plan->cow.size(); c += 3)
+        if (plan->cow[c] == page && plan->cow[c + 2] > r) {
+          plan->copies_first = true;
+          break;
+        }
     }
     for (int32_t i = 0; i < n_tokens[b]; ++i) {
       if (f.len % P_ == 0) f.pages.push_back(alloc_page());

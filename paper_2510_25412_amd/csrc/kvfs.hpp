@@ -65,7 +65,13 @@ class RankSet {
 struct AppendPlan {
   std::vector<int32_t> cow;       // (src, dst, r) triples: copy slots [0, r) of src into dst
   std::vector<int32_t> slots;     // per new token: page * P + slot
-  void clear() { cow.clear(); slots.clear(); }
+  // Copies and appends of one batch normally touch disjoint bytes (files that share a partly filled
+  // page see the same number of tokens in it: the copies take the slots below, the appends the slots
+  // from there on) and may run in any order.  Not so after a truncate or an extract left a sharer
+  // that sees FEWER tokens of the page: when the files that see more have copied the page and left,
+  // it appends in place, into slots that their copies still have to read.  Then the copies go first.
+  bool copies_first = false;
+  void clear() { cow.clear(); slots.clear(); copies_first = false; }
 };
 
 // Result of building a file out of tokens of existing files (extract / merge).

@@ -493,7 +493,8 @@ def test_rag_driver_replayed_on_the_oracle(pareto_index):
 
 @pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 1), (64, 8, 128, synth.BF16, 2), (8, 8, 64, synth.F32, 3),
                                                  (16, 8, 128, synth.BF16, 4), (8, 8, 128, synth.BF16, 5), (32, 8, 128, synth.BF16, 6),
-                                                 (32, 8, 64, synth.F32, 7), (4, 1, 128, synth.BF16, 8)])
+                                                 (32, 8, 64, synth.F32, 7), (4, 1, 128, synth.BF16, 8),
+                                                 (16, 8, 128, synth.BF16, 123), (32, 8, 128, synth.BF16, 126)])
 def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
     """A seeded random program over the whole API (open, append, fork, extract, merge, truncate,
     offload, restore, remove, pred batches that mix single tokens, drafts and prefill chunks) run
@@ -659,3 +660,92 @@ def test_every_kind_of_work_in_one_batch(Hq, Hkv):
         check_state(wl, sess, osess)
         sess.close()
         print(f"all kinds {Hq}/{Hkv} waves={waves}: worst scaled error {worst:.2e}")
+
+
+@pytest.mark.parametrize("how", ["truncate", "extract"])
+def test_copy_and_in_place_append_on_one_page_in_one_batch(how):
+    """Two files share a partly filled page but see different numbers of its tokens (a fork that
+    was truncated, or an extract of a leading part).  In one batch the file that sees more comes
+    first and copies the page; the other is then the only owner and appends in place, into slots
+    that the first one's copy must still read: the copies have to run before the appends.  (With
+    forks alone both see the same number of tokens and copies and appends are disjoint.)"""
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    sess = drv.HipSession(shape, 256, max_lips=8, max_tokens=256, max_entries=4096, poison=True)
+    osess = OracleSession(shape, 256)
+    rng = np.random.default_rng(31 + len(how))
+
+    def data(n, heads):
+        return synth.bf16_round(rng.standard_normal((n, heads, 128), dtype=np.float32))
+
+    def both(op):
+        osess.setup([op])
+        sess.setup([op])
+
+    both(("open", 0))
+    both(("append", 0, data(239, 8), data(239, 8)))          # 14 full pages + 15 tokens
+    if how == "truncate":
+        both(("fork", 1, 0))
+        osess.model.kv_truncate(osess.h[1], 232)             # the fork sees 8 tokens of the shared last page
+        sess.ctx.kv_truncate([sess.h[1]], [232])
+    else:
+        both(("extract", 1, 0, list(range(232))))
+    assert sess.ctx.kv_pages(sess.h[1])[-1] == sess.ctx.kv_pages(sess.h[0])[-1]      # the last page is shared
+    for files, nt in (([0, 1], [2, 8]), ([1, 0], [3, 1])):
+        T = sum(nt)
+        b = dict(files=files, n_tokens=nt, q=data(T, 32), k_new=data(T, 8), v_new=data(T, 8))
+        ref = osess.pred(b, dtype=np.float64)
+        got = sess.pred(sess.upload_batch(b)).cpu().numpy()
+        check_outputs(got, ref)
+        for f in (0, 1):
+            assert sess.ctx.kv_pages(sess.h[f]) == osess.model.kv_pages(osess.h[f])
+    # every stored token of both files, bit for bit
+    from oracle.attention import gather_file
+    for f in (0, 1):
+        n = osess.model.kv_len(osess.h[f])
+        k = torch.empty((n, 8, 128), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        sess.ctx.kv_read(sess.h[f], 0, n, k, v, sess.stream)
+        torch.cuda.synchronize()
+        Ko, Vo = gather_file(osess.pool, osess.model.kv_pages(osess.h[f]), n)
+        assert np.array_equal(k.float().cpu().numpy(), Ko) and np.array_equal(v.float().cpu().numpy(), Vo), f
+    sess.close()
+
+
+@pytest.mark.parametrize("n_moved", [1, 2, 3, 5])
+def test_extract_of_very_few_tokens(n_moved):
+    """An extract or merge that has to copy one, two or three tokens: the list of moves is shorter than
+    one 16-byte unit of the copy that brings it to the device.  The new file and every other file
+    read back bit for bit (a move list that did not arrive would move whatever the workspace held)."""
+    from oracle.attention import gather_file
+    drv = _hip()
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    sess = drv.HipSession(shape, 128, max_lips=8, max_tokens=256, max_entries=4096, poison=True)
+    osess = OracleSession(shape, 128)
+    rng = np.random.default_rng(900 + n_moved)
+
+    def data(n, heads):
+        return synth.bf16_round(rng.standard_normal((n, heads, 128), dtype=np.float32))
+
+    def both(op):
+        osess.setup([op])
+        sess.setup([op])
+
+    for f, n in ((0, 70), (1, 33), (2, 5)):
+        both(("open", f))
+        both(("append", f, data(n, 8), data(n, 8)))
+    # a pred first, so that the workspace holds a descriptor when the move list is due
+    b = dict(files=[0, 1, 2], n_tokens=[1, 1, 1], q=data(3, 32), k_new=data(3, 8), v_new=data(3, 8))
+    check_outputs(sess.pred(sess.upload_batch(b)).cpu().numpy(), osess.pred(b, dtype=np.float64))
+    both(("extract", 3, 0, [int(i) for i in rng.choice(71, size=n_moved, replace=False)]))
+    both(("extract", 4, 2, [1 + i for i in range(min(n_moved, 5))]))
+    for f in range(5):
+        n = osess.model.kv_len(osess.h[f])
+        k = torch.empty((n, 8, 128), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        sess.ctx.kv_read(sess.h[f], 0, n, k, v, sess.stream)
+        torch.cuda.synchronize()
+        Ko, Vo = gather_file(osess.pool, osess.model.kv_pages(osess.h[f]), n)
+        assert np.array_equal(k.float().cpu().numpy(), Ko) and np.array_equal(v.float().cpu().numpy(), Vo), f
+        assert sess.ctx.kv_pages(sess.h[f]) == osess.model.kv_pages(osess.h[f])
+    sess.close()
