@@ -496,6 +496,17 @@ def test_rag_driver_replayed_on_the_oracle(pareto_index):
                                                  (32, 8, 64, synth.F32, 7), (4, 1, 128, synth.BF16, 8),
                                                  (16, 8, 128, synth.BF16, 123), (32, 8, 128, synth.BF16, 126)])
 def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
+    _random_program(Hq, Hkv, D, dtype, seed, big=False)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 4), (64, 8, 128, synth.BF16, 1)])
+def test_random_program_large(Hq, Hkv, D, dtype, seed):
+    """The same at sizes where prefill chunks span several tiles, prefixes of up to 3000 tokens are
+    shared by twelve files and batches hold up to 48 LIPs."""
+    _random_program(Hq, Hkv, D, dtype, seed, big=True)
+
+
+def _random_program(Hq, Hkv, D, dtype, seed, big):
     """A seeded random program over the whole API (open, append, fork, extract, merge, truncate,
     offload, restore, remove, pred batches that mix single tokens, drafts and prefill chunks) run
     step by step on the library and on the oracle: same error codes, every pred's outputs within the
@@ -505,8 +516,14 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
     from paper_2510_25412_amd import binding
     drv = _hip()
     shape = synth.Shape(Hq, Hkv, D, 16, dtype)
-    n_pages = 1536
-    sess = drv.HipSession(shape, n_pages, max_lips=16, max_tokens=1024, max_entries=1 << 15, poison=True)
+    # sizes: steps, pool pages, LIPs per batch, tokens per batch, forks of a long prefix, its length, file and append lengths, chunk sizes
+    if big:
+        n_steps, n_pages, max_lips, max_tok, n_forks, pre_lo, pre_hi, new_hi, app_hi, keep = 110, 16384, 48, 8192, 11, 600, 3000, 1500, 400, 40
+        chunks = [1, 1, 1, 1, 1, 1, 2, 3, 5, 8, 17, 40, 130, 300]
+    else:
+        n_steps, n_pages, max_lips, max_tok, n_forks, pre_lo, pre_hi, new_hi, app_hi, keep = 260, 1536, 16, 1024, 5, 140, 400, 70, 50, 6
+        chunks = [1, 1, 1, 1, 2, 3, 5, 8, 17, 40]
+    sess = drv.HipSession(shape, n_pages, max_lips=max_lips, max_tokens=max_tok, max_entries=1 << 18, poison=True)
     osess = OracleSession(shape, n_pages)
     rng = np.random.default_rng(1000 + seed)
     print(f"[case] random program {Hq}/{Hkv} {dtype} seed {seed}", flush=True)
@@ -528,23 +545,23 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
         return True
 
     next_fid, n_pred, worst = 0, 0, 0.0
-    for step in range(260):
+    for step in range(n_steps):
         fids = sorted(osess.h)
         live = [f for f in fids if not osess.model.is_waiting(osess.h[f])]
         r = rng.random()
         if step % 60 == 5:                  # a long prefix forked five times: decode through shared-prefix tiles
             both(("open", next_fid))
-            both(("append", next_fid, data(n := int(rng.integers(140, 400)), Hkv), data(n, Hkv)))
-            for i in range(1, 6):
+            both(("append", next_fid, data(n := int(rng.integers(pre_lo, pre_hi)), Hkv), data(n, Hkv)))
+            for i in range(1, n_forks + 1):
                 both(("fork", next_fid + i, next_fid))
-            next_fid += 6
+            next_fid += n_forks + 1
         elif r < 0.08 or len(fids) < 3:
             both(("open", next_fid))
-            both(("append", next_fid, data(n := int(rng.integers(1, 70)), Hkv), data(n, Hkv)))
+            both(("append", next_fid, data(n := int(rng.integers(1, new_hi)), Hkv), data(n, Hkv)))
             next_fid += 1
         elif r < 0.2 and live:
             f = int(rng.choice(live))
-            both(("append", f, data(n := int(rng.integers(1, 50)), Hkv), data(n, Hkv)))
+            both(("append", f, data(n := int(rng.integers(1, app_hi)), Hkv), data(n, Hkv)))
         elif r < 0.3 and fids:
             if both(("fork", next_fid, int(rng.choice(fids)))):
                 next_fid += 1
@@ -566,14 +583,14 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
             both(("offload", [int(x) for x in rng.choice(fids, size=min(len(fids), int(rng.integers(1, 3))), replace=False)]))
         elif r < 0.63 and fids:
             both(("restore", [int(x) for x in rng.choice(fids, size=min(len(fids), int(rng.integers(1, 3))), replace=False)]))
-        elif r < 0.7 and len(fids) > 6:
+        elif r < 0.7 and len(fids) > keep:
             f = int(rng.choice(fids))
             osess.setup([("remove", f)])
             sess.setup([("remove", f)])
         elif live:
-            k = int(rng.integers(1, min(len(live), 16) + 1))
+            k = int(rng.integers(1, min(len(live), max_lips) + 1))
             files = [int(x) for x in rng.choice(live, size=k, replace=False)]
-            nt = [int(rng.choice([1, 1, 1, 1, 2, 3, 5, 8, 17, 40])) for _ in files]
+            nt = [int(rng.choice(chunks)) for _ in files]
             T = sum(nt)
             b = dict(files=files, n_tokens=nt, q=data(T, Hq), k_new=data(T, Hkv), v_new=data(T, Hkv))
             try:
@@ -593,7 +610,7 @@ def test_random_program_against_oracle(Hq, Hkv, D, dtype, seed):
     used = sorted({p for f in osess.h for p in osess.model.kv_pages(osess.h[f]) if p >= 0})
     assert [sess.ctx.page_refcount(p) for p in used] == [int(osess.model.refcount[p]) for p in used]
     osess.model.audit()
-    assert n_pred > 40
+    assert n_pred > (10 if big else 40)
     print(f"random program: {n_pred} pred batches, worst scaled error {worst:.2e}")
     sess.close()
 
