@@ -206,6 +206,13 @@ int     sym_get_stats(sym_ctx* ctx, sym_stats* out);
  * *n_cow receives the number of copies.  Either output may be NULL.                      */
 int sym_plan_append(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
                     int32_t* cow_out, int64_t cow_cap, int32_t* n_cow, int32_t* slots_out);
+/* 1 if the last planned batch (sym_plan_append, sym_pred_batch, sym_kv_append) has to run its
+ * page copies before its appends, 0 if they may run in any order.  Copies take the slots of a
+ * shared, partly filled page below what the copying file sees, appends the slots from what
+ * the appending file sees on: disjoint when both see the same, as forks do; after a truncate
+ * or an extract a sharer may see less, and once the others have copied and left it appends
+ * in place into slots that their copies still read.                                        */
+int sym_plan_copies_first(sym_ctx* ctx);
 
 /* The packed descriptor of the attention launch for a batch given by page tables (same
  * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.

@@ -66,6 +66,7 @@ _SIGNATURES = {
     "sym_free_pages": (C.c_int64, [C.c_void_p]),
     "sym_get_stats": (C.c_int, [C.c_void_p, C.POINTER(SymStats)]),
     "sym_plan_append": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_int64, _I32P, _I32P]),
+    "sym_plan_copies_first": (C.c_int, [C.c_void_p]),
     "sym_build_desc": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, _I32P, C.c_int64]),
     "sym_kv_read": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_sched_create": (C.c_void_p, [C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double]),
@@ -337,6 +338,9 @@ class Context:
                                            C.byref(n_cow), slots.ctypes.data_as(_I32P)))
         T = int(nt_a.sum())
         return [tuple(int(x) for x in cow[3 * i:3 * i + 3]) for i in range(n_cow.value)], slots[:T].copy()
+
+    def plan_copies_first(self):
+        return bool(self._chk(self.lib.sym_plan_copies_first(self.h)))
 
     def build_desc(self, n_tokens, page_table_flat, pt_offsets, lengths):
         nt_a, nt_p = _i32(n_tokens)

@@ -540,6 +540,12 @@ int sym_plan_append(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t*
   return SYM_OK;
 }
 
+int sym_plan_copies_first(sym_ctx* c) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->plan.copies_first ? 1 : 0;
+}
+
 int64_t sym_build_desc(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
                        const int64_t* pt_offsets, const int64_t* lengths, int32_t* words_out, int64_t cap) {
   if (!c || n_lips < 0 || (n_lips > 0 && (!n_tokens || !page_table_flat || !pt_offsets || !lengths))) return SYM_EINVAL;

@@ -440,6 +440,42 @@ def test_descriptor_shared_prefix_groups():
     assert all(int(by_out[k][5]) == 0 for k in by_out if k // 32 >= 6)
 
 
+def test_copies_before_appends_only_when_they_overlap():
+    """A batch's page copies and appends may run in any order on the device unless an append lands
+    in a slot that a copy of the same batch reads: a fork that was truncated (or an extract of a
+    leading part) sees fewer tokens of the shared last page than its source; when the source comes
+    first in the batch, copies the page and leaves, the other appends in place from its own end."""
+    def scenario(how):
+        c = host_ctx(64)
+        a = c.kv_open()
+        c.plan_append([a], [39])                       # 2 full pages + 7 tokens in page 2
+        if how == "fork":
+            b = c.kv_fork(a)
+        elif how == "truncate":
+            b = c.kv_fork(a)
+            c.kv_truncate([b], [35])                   # sees 3 tokens of page 2
+        else:
+            b = c.kv_extract(a, np.arange(35))         # page 2 referenced, 3 tokens seen
+        assert c.kv_pages(b)[-1] == c.kv_pages(a)[-1] == 2
+        return c, a, b
+
+    for how in ("truncate", "extract"):
+        c, a, b = scenario(how)
+        cow, slots = c.plan_append([a, b], [1, 2])     # a copies slots 0..6 of page 2; b, then alone, writes slots 3 and 4 of it
+        assert cow == [(2, 3, 7)] and slots.tolist() == [3 * 16 + 7, 2 * 16 + 3, 2 * 16 + 4]
+        assert c.plan_copies_first()
+        c, a, b = scenario(how)
+        cow, slots = c.plan_append([b, a], [2, 1])     # b copies slots 0..2; a, then alone, writes slot 7: disjoint
+        assert cow == [(2, 3, 3)] and slots.tolist() == [3 * 16 + 3, 3 * 16 + 4, 2 * 16 + 7]
+        assert not c.plan_copies_first()
+    c, a, b = scenario("fork")
+    cow, slots = c.plan_append([a, b], [1, 2])         # both see 7 tokens: copy takes slots 0..6, the append slots 7 and 8
+    assert cow == [(2, 3, 7)] and slots.tolist() == [3 * 16 + 7, 2 * 16 + 7, 2 * 16 + 8]
+    assert not c.plan_copies_first()
+    cow, slots = c.plan_append([a], [5])               # the flag belongs to the last plan
+    assert cow == [] and not c.plan_copies_first()
+
+
 def test_offload_restore_hand_trace_library():
     """The model's hand-worked offload / restore trace at page size 16, on the library."""
     c = host_ctx(16)
@@ -523,6 +559,9 @@ def test_random_ops_with_offload_match_oracle_model_bit_exact():
             a, b = both(lambda: m.append(list(zip(hs, ns))), lambda: c.plan_append(hs, ns))
             if a is not None:
                 assert b[0] == a[0] and b[1].tolist() == [p * 16 + s for mine in a[1] for p, s in mine]
+                # copies before appends exactly when an append of the batch lands in a slot that a copy reads
+                overlap = any(p == src and s < cnt for src, _, cnt in a[0] for mine in a[1] for p, s in mine)
+                assert c.plan_copies_first() == overlap
         elif r < 0.78:
             k = min(len(live), int(rng.integers(1, 4)))
             hs = [int(x) for x in rng.choice(live, size=k, replace=False)]
