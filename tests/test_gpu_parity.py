@@ -766,3 +766,67 @@ def test_extract_of_very_few_tokens(n_moved):
         assert np.array_equal(k.float().cpu().numpy(), Ko) and np.array_equal(v.float().cpu().numpy(), Vo), f
         assert sess.ctx.kv_pages(sess.h[f]) == osess.model.kv_pages(osess.h[f])
     sess.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,dtype,seed", [(32, 8, 128, synth.BF16, 3), (64, 8, 128, synth.BF16, 4), (8, 8, 64, synth.F32, 5)])
+def test_raw_entry_on_arbitrary_page_tables(Hq, Hkv, D, dtype, seed):
+    """sym_pred_batch_raw with page tables that no allocator would produce: pages repeated within a
+    table, identical tables, prefixes shared in whole or in part by some LIPs, ragged last pages,
+    single tokens, drafts and chunks, against dense attention over the gathered pages."""
+    from oracle.attention import gather_file, dense_attention
+    from paper_2510_25412_amd.driver import to_device
+    drv = _hip()
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    NP = 400
+    sess = drv.HipSession(shape, NP, max_lips=40, max_tokens=4096, max_entries=1 << 16, poison=True)
+    osess = OracleSession(shape, NP)
+    rng = np.random.default_rng(7000 + seed)
+
+    def data(n, heads):
+        x = rng.standard_normal((n, heads, D), dtype=np.float32)
+        return synth.bf16_round(x) if dtype == synth.BF16 else x
+
+    fill = ("append", 0, data(NP * 16, Hkv), data(NP * 16, Hkv))     # defined data in every page, on both sides
+    for s in (sess, osess):
+        s.setup([("open", 0)])
+        s.setup([fill])
+    assert sess.ctx.kv_pages(sess.h[0]) == list(range(NP))
+    worst = 0.0
+    for it in range(12):
+        n_lips = int(rng.integers(1, 33))
+        tables, lengths, nts = [], [], []
+        prefixes = [rng.permutation(NP)[:int(rng.integers(2, 60))].tolist() for _ in range(3)]
+        for b in range(n_lips):
+            kind = rng.random()
+            if kind < 0.45:                # one of the prefixes, whole or in part, then private pages (or none)
+                pre = prefixes[int(rng.integers(3))]
+                pre = pre[:int(rng.integers(1, len(pre) + 1))] if rng.random() < 0.3 else pre
+                t = pre + rng.permutation(NP)[:int(rng.integers(0, 12))].tolist()
+            elif kind < 0.55 and tables:   # the same table as another LIP
+                t = list(tables[int(rng.integers(len(tables)))])
+            else:                          # any pages, repeats allowed
+                t = rng.integers(0, NP, size=int(rng.integers(1, 70))).tolist()
+            nt = int(rng.choice([1, 1, 1, 1, 1, 2, 3, 4, 6, 17, 40]))
+            if nt > len(t) * 16:
+                nt = 1
+            tables.append(t)
+            lengths.append(int(rng.integers(max(nt, (len(t) - 1) * 16 + 1), len(t) * 16 + 1)))
+            nts.append(nt)
+        T = sum(nts)
+        q = data(T, Hq)
+        flat = np.concatenate(tables).astype(np.int32)
+        off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+        out = torch.empty((T, Hq, D), dtype=torch.float32, device=sess.device)
+        sess.ctx.pred_batch_raw(nts, flat, off, lengths, to_device(q, sess.device), out, sess.stream)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        ref = np.empty_like(got, dtype=np.float64)
+        row = 0
+        for t, L, nt in zip(tables, lengths, nts):
+            K, V = gather_file(osess.pool, t, L)
+            ref[row:row + nt] = dense_attention(widen(q[row:row + nt]).astype(np.float64), widen(K).astype(np.float64),
+                                                widen(V).astype(np.float64), L - nt, dtype=np.float64)
+            row += nt
+        worst = max(worst, check_outputs(got, ref))
+    sess.close()
+    print(f"raw entry, arbitrary tables {Hq}/{Hkv}: worst scaled error {worst:.2e}")
