@@ -418,6 +418,7 @@ def main():
     ms_per_step = wall / steps * 1e3
     tbps = step_bytes / (wall / steps) / 1e12
     G = shape.n_q_heads // shape.n_kv_heads
+    model_layers = 80 if shape.n_q_heads == 64 else 32      # layers of the Llama model with this attention shape (70B / 8B)
 
     # the attention kernel against both roofs; the one it sits closer to is reported as its bound
     hbm_ach = step_bytes / (attn_ms * 1e-3) / 1e9
@@ -449,6 +450,17 @@ def main():
         breakdown[name + "_us"] = round(tot / cnt * 1e3, 2) if cnt else None
     for s in sessions:
         s.ctx.profile_enable(0)
+    # ---- spread of the step time (untimed extra pass): an event on the stream between every two steps
+    n_dist = min(100, steps)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_dist + 1)]
+    evs[0].record()
+    for i in range(n_dist):
+        step(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_dist))
+    spread = {"steps": n_dist, "p10": round(per_step[n_dist // 10], 2), "median": round(per_step[n_dist // 2], 2),
+              "p90": round(per_step[min(n_dist - 1, (9 * n_dist) // 10)], 2)}
     stream_read = None
     if not args.no_calib:
         nbytes = 4 << 30
@@ -502,6 +514,9 @@ def main():
         "pct_hbm_peak": round(100 * tbps / HBM_PEAK_TBPS, 2),
         "effective_TBps_logical": round(logical_bytes / (wall / steps) / 1e12, 4),
         "lip_steps_per_s": round(n_lips / (wall / steps), 1),
+        # attention only: what this layer's rate allows a model of that many layers (nothing else of the model is built)
+        "lip_steps_per_s_all_layers": {"layers": model_layers, "value": round(n_lips / (wall / steps) / model_layers, 1)},
+        "step_us_spread": spread,
         "roofline": dominant,
         "roofline_other": other if mfma_flops else None,
         "kernel_breakdown": breakdown,
