@@ -168,6 +168,47 @@ def test_fork_cow_append_invariance():
     s_f.model.audit()
 
 
+@pytest.mark.parametrize("how", ["truncate", "extract"])
+def test_a_copy_takes_the_page_as_it_was_before_the_batch(how):
+    """One batch in which a page is both copied and appended to in place: file A (6 tokens, pages of
+    4) shares its partly filled page with a file B that sees only ONE token of it (a fork truncated
+    to 5 tokens, or an extract of the first 5).  A appends first and copies slots 0 and 1 away; B, now
+    alone on the page, appends into slot 1.  A must keep ITS token 5 in slot 1 of the copy, whatever B
+    wrote there: every file reads back exactly the rows that were appended to it (section 4.2: a fork
+    shares tensors, it never lets one file's writes show in another)."""
+    rng = np.random.default_rng(21)
+    Hkv, D, P = 2, 4, 4
+    m, pool = KVFSModel(16, P), PagePool(Hkv, P, D)
+    rows = {}                                           # file handle -> the K rows it must hold
+
+    def append(items):
+        k = [_rand(rng, n, Hkv, D) for _, n in items]
+        v = [_rand(rng, n, Hkv, D) for _, n in items]
+        cow, slots = m.append(items)
+        pool.apply(cow, slots, np.concatenate(k), np.concatenate(v))
+        for (h, _), kk in zip(items, k):
+            rows[h] = np.concatenate([rows[h], kk]) if h in rows else kk
+        return cow
+
+    a = m.kv_open()
+    append([(a, 6)])
+    if how == "truncate":
+        b = m.kv_fork(a)
+        m.kv_truncate(b, 5)
+    else:
+        b, moves = m.kv_extract(a, list(range(5)))
+        assert moves == []                              # slots 0.. of existing pages: referenced, not copied
+    rows[b] = rows[a][:5]
+    assert m.kv_pages(a) == m.kv_pages(b) and m.refcount[m.kv_pages(a)[1]] == 2
+    shared = m.kv_pages(a)[1]
+    cow = append([(a, 1), (b, 2)])
+    assert cow == [(shared, m.kv_pages(a)[1], 2)] and m.kv_pages(b)[1] == shared    # A copied two slots, B stayed
+    for h in (a, b):
+        K, _ = gather_file(pool, m.kv_pages(h), m.kv_len(h))
+        assert np.array_equal(K, rows[h]), "file %d does not read back what was appended to it" % h
+    m.audit()
+
+
 def test_chunk_equals_sequential():
     """One n-token pred equals n one-token preds (pins the in-chunk causal mask and the
     append order)."""

@@ -115,6 +115,43 @@ def test_lowest_rank_allocation_and_handle_reuse():
     m.audit()
 
 
+def test_names_handles_and_what_close_and_remove_free():
+    """Section 4.2: a file can be shared across LIPs by name; remove deletes it; close gives up a
+    handle.  This build's reading: a second open of a name is a second handle to the SAME file; a named
+    file outlives its handles; an anonymous file goes with its last handle; remove takes the name along."""
+    m = KVFSModel(8, 4)
+    h0 = m.kv_open("doc")
+    m.append([(h0, 5)])
+    h1 = m.kv_open("doc")
+    assert h1 != h0 and m.kv_pages(h1) == m.kv_pages(h0) == [0, 1] and m.kv_len(h1) == 5
+    assert m.refcount.tolist()[:2] == [1, 1]                       # one file, not a fork
+    m.append([(h1, 1)])
+    assert m.kv_len(h0) == 6                                       # written through one handle, seen through the other
+    m.kv_close(h0)
+    assert m.free_pages() == 6 and m.kv_len(h1) == 6              # still there
+    with pytest.raises(KVError) as e:
+        m.kv_len(h0)
+    assert e.value.code == EBADF
+    m.kv_close(h1)
+    assert m.free_pages() == 6                                     # a named file outlives its handles
+    h2 = m.kv_open("doc")
+    assert m.kv_len(h2) == 6 and m.kv_pages(h2) == [0, 1]
+    m.kv_remove(h2)
+    assert m.free_pages() == 8
+    h3 = m.kv_open("doc")                                          # the name went with the file: a new, empty one
+    assert m.kv_len(h3) == 0 and m.kv_pages(h3) == []
+    # anonymous: gone with its last handle, pages and all
+    x = m.kv_open()
+    m.append([(x, 9)])
+    y = m.kv_fork(x)
+    assert m.free_pages() == 5
+    m.kv_close(x)
+    assert m.free_pages() == 5 and m.kv_len(y) == 9               # the fork still holds every page
+    m.kv_close(y)
+    assert m.free_pages() == 8 and not m.refcount.any()
+    m.audit()
+
+
 def test_random_ops_keep_invariants():
     rng = np.random.default_rng(7)
     m = KVFSModel(256, 8, rng.permutation(256))

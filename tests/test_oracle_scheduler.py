@@ -89,3 +89,4 @@ def test_deadline_fires_a_short_batch_when_arrivals_stop():
     assert t.decide(500.0) == 2                                   # 100 us left < (12.5 - 2) / 0.1: the target is out of reach
     assert t.decide(600.0) == 2
     assert t.decide(410.0, gpu_idle=False) == 0
+    assert t.decide(600.0, gpu_idle=False) == 0                   # nothing is fired into a busy GPU, deadline or not
