@@ -209,6 +209,28 @@ def test_a_copy_takes_the_page_as_it_was_before_the_batch(how):
     m.audit()
 
 
+def test_sampled_outputs_equal_the_full_run():
+    """The full-size GPU tests ask the oracle for the outputs of a few LIPs of a batch only: those
+    rows must be the rows of the full run, bit for bit, every other row NaN, and the file-system state
+    the same (the append is carried out for every LIP either way)."""
+    shape = synth.Shape(4, 2, 8, 4, synth.BF16)
+    wl = synth.custom("sampled", shape, [("new", 9), ("new", 0), ("fork", 0, 3), ("new", 30), ("fork", 3, 0)],
+                      [(0, 1), (1, 5), (2, 2), (3, 1), (4, 7)], 64, seed=5)
+    full, s_full = run_workload(wl)
+    part, s_part = run_workload(wl, only=[1, 4, 2])
+    starts = np.concatenate([[0], np.cumsum([1, 5, 2, 1, 7])])
+    for b in range(5):
+        rows = slice(starts[b], starts[b + 1])
+        if b in (1, 2, 4):
+            assert np.array_equal(part[rows], full[rows]), b
+        else:
+            assert np.isnan(part[rows]).all(), b
+    assert not np.isnan(full).any()
+    for f in range(5):
+        assert s_part.model.kv_pages(s_part.h[f]) == s_full.model.kv_pages(s_full.h[f])
+    assert np.array_equal(s_part.model.refcount, s_full.model.refcount)
+
+
 def test_chunk_equals_sequential():
     """One n-token pred equals n one-token preds (pins the in-chunk causal mask and the
     append order)."""

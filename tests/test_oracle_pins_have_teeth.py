@@ -88,6 +88,7 @@ def test_unmodified_oracle_passes_under_the_harness():
     assert _failing_pins("attention.py", [], _ATTN_PINS) == []
     assert _failing_pins("kvfs_model.py", [], _KVFS_PINS) == []
     assert _failing_pins("scheduler.py", [], _SCHED_PINS) == []
+    assert _failing_pins("driver.py", [], _ATTN_PINS) == []
 
 
 @pytest.mark.parametrize("what,edits", [
@@ -168,5 +169,19 @@ def test_a_mistake_in_the_state_model_fails_a_pin(what, edits):
 ])
 def test_a_mistake_in_the_scheduler_oracle_fails_a_pin(what, edits):
     failed = _failing_pins("scheduler.py", edits, _SCHED_PINS)
+    print(f"[{what}] caught by: {', '.join(failed)}")
+    assert failed, f"no pin notices: {what}"
+
+
+@pytest.mark.parametrize("what,edits", [
+    ("bf16 patterns widened into the wrong bits", [("<< np.uint32(16)", "<< np.uint32(15)")]),
+    ("sampled rows start at the LIP's index", [("            out[starts[b]:starts[b] + n] = dense_attention(q[starts[b]:starts[b] + n]", "            out[b:b + n] = dense_attention(q[b:b + n]")]),
+    ("sampled LIPs read the first LIP's file", [("K, V = gather_file(self.pool, self.model.kv_pages(h), before[b] + n)", "K, V = gather_file(self.pool, self.model.kv_pages(items[0][0]), before[b] + n)")]),
+    ("a fork is a fork of the newest file", [("self.h[op[1]] = self.model.kv_fork(self.h[op[2]])", "self.h[op[1]] = self.model.kv_fork(self.h[max(self.h)])")]),
+    ("extract moves are not carried out", [("                self.h[op[1]], moves = self.model.kv_extract(self.h[op[2]], op[3])\n                self.pool.move_tokens(moves)\n", "                self.h[op[1]], moves = self.model.kv_extract(self.h[op[2]], op[3])\n")]),
+])
+@pytest.mark.filterwarnings("ignore::RuntimeWarning")
+def test_a_mistake_in_the_oracle_driver_fails_a_pin(what, edits):
+    failed = _failing_pins("driver.py", edits, _ATTN_PINS)
     print(f"[{what}] caught by: {', '.join(failed)}")
     assert failed, f"no pin notices: {what}"
