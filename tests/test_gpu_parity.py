@@ -830,3 +830,40 @@ def test_raw_entry_on_arbitrary_page_tables(Hq, Hkv, D, dtype, seed):
         worst = max(worst, check_outputs(got, ref))
     sess.close()
     print(f"raw entry, arbitrary tables {Hq}/{Hkv}: worst scaled error {worst:.2e}")
+
+
+# ---- do these parity tests notice when the two sides differ? ------------------------------------
+# A mistake is written into a COPY of the oracle's source (on the CPU; the kernels run unchanged),
+# a few quick parity tests above are run against the copy, and at least one must fail: the
+# comparisons are real ones, with a bar tight enough for a wrong scale, head mapping, mask, page
+# choice or copy.
+_QUICK = ["test_config1_tiny_fp32_all_outputs", "test_edge_cases", "test_chunk_equals_sequential_on_gpu", "test_prefill_chunk_equals_sequential",
+          "test_copy_and_in_place_append_on_one_page_in_one_batch", "test_extract_of_very_few_tokens", "test_config4_mixed_reduced"]
+
+
+def test_quick_parity_tests_pass_under_the_harness_without_a_mistake():
+    from test_oracle_pins_have_teeth import _failing_pins
+    assert _failing_pins("attention.py", [], ["test_gpu_parity.py"], only=_QUICK) == []
+
+
+@pytest.mark.parametrize("module_file,what,edits", [
+    ("attention.py", "scale dropped", [("@ K[:, g, :].T) * scale", "@ K[:, g, :].T)")]),
+    ("attention.py", "heads interleaved instead of grouped", [("g = h // G", "g = h % Hkv")]),
+    ("attention.py", "a token does not see itself", [("<= (len_before + np.arange(n))", "< (len_before + np.arange(n))")]),
+    ("attention.py", "a token sees one token too many", [("<= (len_before + np.arange(n))", "<= (len_before + 1 + np.arange(n))")]),
+    ("attention.py", "K and V swapped in the gather", [("K[lo:lo + n] = pg[0,", "K[lo:lo + n] = pg[1,"), ("V[lo:lo + n] = pg[1,", "V[lo:lo + n] = pg[0,")]),
+    ("attention.py", "weighted sum of K", [("out[:, h, :] = p @ V[:, g, :]", "out[:, h, :] = p @ K[:, g, :]")]),
+    ("kvfs_model.py", "highest rank first", [("heapq.heappop(self.free_ranks)", "self.free_ranks.pop(self.free_ranks.index(max(self.free_ranks)))")]),
+    ("kvfs_model.py", "shared partial page written in place", [("if r != 0 and self.refcount[f.pages[-1]] > 1:", "if False:")]),
+    ("kvfs_model.py", "copy takes one slot too few", [("cow.append((src, dst, r))", "cow.append((src, dst, r - 1))")]),
+    ("kvfs_model.py", "copies after the appends", [("        for src, dst, r in cow:\n            self.copy_slots(src, dst, r)\n        t = 0\n", "        t = 0\n"),
+                                                   ("        assert t == len(k_new)\n", "        assert t == len(k_new)\n        for src, dst, r in cow:\n            self.copy_slots(src, dst, r)\n")]),
+    ("kvfs_model.py", "extract: nothing is ever shared", [("same = all(pg == toks[0][0] and sl == k for k, (pg, sl) in enumerate(toks))", "same = False")]),
+    ("kvfs_model.py", "extract: destination slots shifted", [("moves.append((pg, sl, dst, k))", "moves.append((pg, sl, dst, (k + 1) % P))")]),
+])
+@pytest.mark.filterwarnings("ignore::RuntimeWarning")
+def test_parity_tests_notice_a_wrong_oracle(module_file, what, edits):
+    from test_oracle_pins_have_teeth import _failing_pins
+    print(f"[case] oracle with a planted mistake: {what}", flush=True)
+    failed = _failing_pins(module_file, edits, ["test_gpu_parity.py"], only=_QUICK, first=True)
+    assert failed, f"no parity test notices an oracle with: {what}"

@@ -38,8 +38,9 @@ def _cases(fn):
     return [tuple(v) if len(names) > 1 else (v,) for v in marks[0].args[1]]
 
 
-def _failing_pins(module_file, edits, pin_files):
-    """Pins (function names) that fail when `module_file` of the oracle carries `edits`."""
+def _failing_pins(module_file, edits, pin_files, only=None, first=False):
+    """Pins (function names) that fail when `module_file` of the oracle carries `edits`.
+    only: run just these functions; first: stop at the first one that fails."""
     path = os.path.join(_ROOT, "oracle", module_file)
     text = open(path).read()
     for old, new in edits:
@@ -58,8 +59,10 @@ def _failing_pins(module_file, edits, pin_files):
         for pf in pin_files:
             pins = _load("pins_under_mutation_" + pf[:-3], os.path.join(_TESTS, pf))
             for name, fn in sorted(vars(pins).items()):
-                if not name.startswith("test_") or not callable(fn):
+                if not name.startswith("test_") or not callable(fn) or (only is not None and name not in only):
                     continue
+                if first and failed:
+                    break
                 for args in _cases(fn):
                     try:
                         fn(*args)
