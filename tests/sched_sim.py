@@ -13,7 +13,7 @@ def poisson_arrivals(rate_per_us, n, seed):
 def simulate(timer, arrivals, a_us, c_us, log=None):
     """timer: object with arrive/decide/fired/done/next_deadline.  The GPU serves a batch of b calls in
     a_us + c_us * b.  Returns dict(waits, batches, busy_us, end_us).  `log`, if a list, receives every
-    (time, decision) pair, waits included."""
+    (time, decision, decision with a busy GPU) triple, waits included."""
     now, k, n = 0.0, 0, len(arrivals)
     pending = []
     waits, batches, busy = [], [], 0.0
@@ -24,7 +24,7 @@ def simulate(timer, arrivals, a_us, c_us, log=None):
             k += 1
         fire = timer.decide(now, True)
         if log is not None:
-            log.append((now, fire))
+            log.append((now, fire, timer.decide(now, False)))      # and what it would do were the GPU busy
         if fire > 0:
             timer.fired(fire)
             waits += [now - t for t in pending[:fire]]

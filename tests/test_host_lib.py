@@ -68,6 +68,76 @@ def test_fig1_hand_trace_library():
             assert c.free_pages() == e["free"]
 
 
+def test_random_ops_with_names_handles_and_bad_batches_match_oracle_model():
+    """Names, second handles, close, remove through any handle, stale handles and batches that name a
+    file twice (also through two handles): every call returns the same handle or the same error on both
+    sides, and after every step every handle number answers kv_len alike."""
+    rng = np.random.default_rng(77)
+    m = KVFSModel(256, 16)
+    c = host_ctx(256)
+    names = ["doc%d" % i for i in range(5)]
+    top = 0                                              # handle numbers 0 .. top have been seen
+
+    def both(call_m, call_c):
+        try:
+            a = call_m()
+        except KVError as e:
+            with pytest.raises(binding.SymError) as ce:
+                call_c()
+            assert ce.value.code == e.code
+            return None
+        b = call_c()
+        return a, b
+
+    n_busy = n_stale = 0
+    for step in range(1200):
+        r = rng.random()
+        h = int(rng.integers(0, top + 2))                # any number: live, closed, never issued
+        if r < 0.15:
+            res = both(lambda: m.kv_open(None), lambda: c.kv_open(None))
+        elif r < 0.35:
+            nm = names[int(rng.integers(len(names)))]
+            res = both(lambda: m.kv_open(nm), lambda: c.kv_open(nm))
+        elif r < 0.45:
+            res = both(lambda: m.kv_fork(h), lambda: c.kv_fork(h))
+        elif r < 0.60:
+            res = both(lambda: m.kv_close(h), lambda: c.kv_close(h))
+            n_stale += res is None
+            res = None
+        elif r < 0.68:
+            both(lambda: m.kv_remove(h), lambda: c.kv_remove(h))
+            res = None
+        else:
+            k = int(rng.integers(1, 5))
+            hs = [int(x) for x in rng.integers(0, top + 1, size=k)]        # repeats and two handles of one file happen
+            ns = [int(rng.integers(1, 30)) for _ in hs]
+            try:
+                cow, slots = m.append(list(zip(hs, ns)))
+            except KVError as e:
+                with pytest.raises(binding.SymError) as ce:
+                    c.plan_append(hs, ns)
+                assert ce.value.code == e.code
+                n_busy += e.code == binding.SYM_EBUSY
+            else:
+                ccow, cslots = c.plan_append(hs, ns)
+                assert ccow == cow and cslots.tolist() == [p * 16 + s for mine in slots for p, s in mine]
+            res = None
+        if res is not None:
+            assert res[0] == res[1]
+            top = max(top, res[0])
+        for hh in range(top + 2):
+            lens = both(lambda: m.kv_len(hh), lambda: c.kv_len(hh))
+            if lens is not None:
+                assert lens[0] == lens[1]
+                if step % 40 == 0:
+                    assert c.kv_pages(hh) == m.kv_pages(hh)
+        if step % 40 == 0:
+            assert c.free_pages() == m.free_pages()
+            assert [c.page_refcount(p) for p in range(256)] == m.refcount.tolist()
+    assert n_busy > 10 and n_stale > 10                  # the program did name files twice and did use stale handles
+    m.audit()
+
+
 def test_random_ops_match_oracle_model_bit_exact():
     rng = np.random.default_rng(2024)
     order = rng.permutation(512).astype(np.int32)
@@ -618,3 +688,29 @@ def test_batch_timer_rejects_bad_arguments():
     t.arrive(5.0)
     assert t.decide(5.0) == 1 and t.decide(5.0, gpu_idle=False) == 0 and t.next_deadline() == 105.0
     t.close()
+
+
+# ---- do the comparisons above notice when library and model differ? -----------------------------
+@pytest.mark.parametrize("module_file,what,edits", [
+    ("kvfs_model.py", "highest rank first", [("heapq.heappop(self.free_ranks)", "self.free_ranks.pop(self.free_ranks.index(max(self.free_ranks)))")]),
+    ("kvfs_model.py", "shared partial page written in place", [("if r != 0 and self.refcount[f.pages[-1]] > 1:", "if False:")]),
+    ("kvfs_model.py", "copy takes one slot too few", [("cow.append((src, dst, r))", "cow.append((src, dst, r - 1))")]),
+    ("kvfs_model.py", "truncate keeps one page too few", [("keep=-(-new_len // self.P))", "keep=new_len // self.P)")]),
+    ("kvfs_model.py", "extract: nothing is ever shared", [("same = all(pg == toks[0][0] and sl == k for k, (pg, sl) in enumerate(toks))", "same = False")]),
+    ("kvfs_model.py", "extract: destination slots shifted", [("moves.append((pg, sl, dst, k))", "moves.append((pg, sl, dst, (k + 1) % P))")]),
+    ("kvfs_model.py", "offload: a page leaves as soon as one reader waits", [("if len(self.waiters[p]) == self.refcount[p]:", "if True:")]),
+    ("kvfs_model.py", "offload: host slots never reused", [("                    if self.free_slots:\n", "                    if False:\n")]),
+    ("kvfs_model.py", "restore: count of the new page is 1", [("self.refcount[q] = len(refs)", "self.refcount[q] = 1")]),
+    ("kvfs_model.py", "same file twice in a batch allowed", [("            if any(f is g for g in files):\n                raise KVError(EBUSY, \"same file twice in a batch\")\n", "")]),
+    ("kvfs_model.py", "close of the last handle keeps an anonymous file", [("if f.name is None and not f.handles:", "if False:")]),
+    ("kvfs_model.py", "second open of a name makes a new file", [("if name is not None and name in self.names:", "if False:")]),
+    ("scheduler.py", "target ignores the per-call cost", [("t = lam * self.a / (1.0 - load)", "t = lam * self.a")]),
+    ("scheduler.py", "new gaps ignored", [("self.mean_gap = self.mean_gap + self.w * (gap - self.mean_gap)", "pass")]),
+    ("scheduler.py", "fires while the GPU is busy", [("if not gpu_idle or not self.pending:", "if not self.pending:")]),
+])
+def test_library_against_model_tests_notice_a_wrong_model(module_file, what, edits):
+    """The library's host state is pinned by comparing it with the oracle's model; here the model is
+    made wrong on purpose (in a copy of its source) and the comparisons in this file must fail."""
+    from test_oracle_pins_have_teeth import _failing_pins
+    me = "test_library_against_model_tests_notice_a_wrong_model"
+    assert _failing_pins(module_file, edits, ["test_host_lib.py"], first=True, skip=(me,)), f"no test notices a model with: {what}"
