@@ -832,6 +832,43 @@ def test_raw_entry_on_arbitrary_page_tables(Hq, Hkv, D, dtype, seed):
     print(f"raw entry, arbitrary tables {Hq}/{Hkv}: worst scaled error {worst:.2e}")
 
 
+def test_two_contexts_on_two_threads_and_streams():
+    """Two contexts driven at the same time from two host threads, each on a stream of its own
+    (default priority): the library keeps no state outside a context, so both must produce what they
+    produce alone (ctypes releases the interpreter lock during the calls, so the calls do overlap)."""
+    import threading
+    drv = _hip()
+    wls = [synth.config2(n_lips=24, lo=100, hi=900, slack_pages=64),
+           synth.config3(n_roots=3, n_children=6, prefix=400, suffix_hi=60, slack_pages=64)]
+    refs = [run_oracle(wl, dtype=np.float64) for wl in wls]
+    results, errors = [None, None], []
+
+    def work(i):
+        try:
+            st = torch.cuda.Stream(device="cuda:0")
+            with torch.cuda.stream(st):
+                for rep in range(4):
+                    got, sess = drv.run_workload(wls[i], poison=True)
+                    results[i] = (got, [sess.pages(f) for f in sorted(sess.h)], sess.ctx.free_pages())
+                    sess.close()
+        except Exception as e:                      # reported by the main thread
+            errors.append((i, repr(e)))
+
+    print("[case] two contexts, two threads, two streams", flush=True)
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a worker thread did not finish"
+    assert not errors, errors
+    for i, (wl, (ref, osess)) in enumerate(zip(wls, refs)):
+        got, pages, free = results[i]
+        check_outputs(got, ref)
+        assert pages == [osess.model.kv_pages(osess.h[f]) for f in sorted(osess.h)]
+        assert free == osess.model.free_pages()
+
+
 # ---- do these parity tests notice when the two sides differ? ------------------------------------
 # A mistake is written into a COPY of the oracle's source (on the CPU; the kernels run unchanged),
 # a few quick parity tests above are run against the copy, and at least one must fail: the
