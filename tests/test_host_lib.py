@@ -690,6 +690,57 @@ def test_batch_timer_rejects_bad_arguments():
     t.close()
 
 
+def test_one_context_from_four_threads():
+    """The header promises one mutex per context: four threads work on files of their own in ONE
+    context at the same time (ctypes releases the interpreter lock during a call).  Afterwards every
+    page is free again, no count is off, and each thread has seen exactly its own tokens."""
+    import threading
+    c = host_ctx(4096)
+    errors = []
+
+    def work(seed):
+        try:
+            rng = np.random.default_rng(seed)
+            mine = {}                                    # handle -> tokens
+            for _ in range(1500):
+                r = rng.random()
+                if r < 0.25 or not mine:
+                    mine[c.kv_open()] = 0
+                elif r < 0.45:
+                    p = int(rng.choice(list(mine)))
+                    mine[c.kv_fork(p)] = mine[p]
+                elif r < 0.85:
+                    hs = [int(h) for h in rng.choice(list(mine), size=min(len(mine), 3), replace=False)]
+                    ns = [int(rng.integers(1, 20)) for _ in hs]
+                    c.plan_append(hs, ns)
+                    for h, n in zip(hs, ns):
+                        mine[h] += n
+                else:
+                    h = int(rng.choice(list(mine)))
+                    c.kv_remove(h)
+                    del mine[h]
+                if len(mine) > 12:
+                    h = next(iter(mine))
+                    c.kv_remove(h)
+                    del mine[h]
+            for h, n in mine.items():
+                assert c.kv_len(h) == n and len(c.kv_pages(h)) == -(-n // 16)
+            for h in list(mine):
+                c.kv_remove(h)
+        except Exception as e:
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(s,)) for s in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=60)
+    assert not any(t.is_alive() for t in threads) and not errors, errors
+    st = c.get_stats()
+    assert c.free_pages() == 4096 and st["files"] == 0 and st["handles"] == 0 and st["pages_shared"] == 0
+    assert all(c.page_refcount(p) == 0 for p in range(0, 4096, 7))
+
+
 # ---- do the comparisons above notice when library and model differ? -----------------------------
 @pytest.mark.parametrize("module_file,what,edits", [
     ("kvfs_model.py", "highest rank first", [("heapq.heappop(self.free_ranks)", "self.free_ranks.pop(self.free_ranks.index(max(self.free_ranks)))")]),
