@@ -203,6 +203,7 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.Hq = c->cfg.n_q_heads;
   pa.Hkv = c->cfg.n_kv_heads;
   pa.scale_log2e = c->scale_log2e;
+  pa.small_shared_only = d.small_shared_only;
   {
     Timed t(c, SYM_K_ATTN, st, true);
     // rows that hold several new tokens exist for the matrix-core decode kernel only

@@ -317,6 +317,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
 
   // ---- shared-prefix tiles and the extra partials of their members' merge entries
   const int32_t shared_base = part;
+  int32_t max_shared_rows = 0;
   if (!stiles.empty()) {
     int32_t* members = w + off_members;
     std::memcpy(members, member_rows.data(), member_rows.size() * sizeof(int32_t));
@@ -330,6 +331,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
           t[T_TBL] = ptoff[b0];
           t[T_QROW] = moff;                                    // offset into the member list
           t[T_COUNT] = k;
+          max_shared_rows = std::max(max_shared_rows, k * G);
           t[T_HEAD] = g;
           t[T_AUX] = shared_base + base + (g * nc + c) * k;    // first partial of this tile
           t[T_KIND] = TILE_SHARED;
@@ -448,6 +450,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   out->max_row_tokens = max_nt;
   out->tile_blocks = tile_blocks;
   out->tile_rows = TQ * G;
+  out->small_shared_only = (n_tiles > 0 && !any_prefill && max_shared_rows > 0 && max_shared_rows <= 64) ? 1 : 0;
   return SYM_OK;
 }
 

@@ -56,6 +56,7 @@ struct BatchDesc {
   int32_t n_rows = 0, n_waves = 0, n_partials = 0, n_lips = 0, n_merge = 0, n_tiles = 0;
   int32_t tile_blocks = 0;      // workgroups the tile part of the launch needs
   int32_t tile_rows = 0;        // query rows of this batch's tiles (128 or 256)
+  int32_t small_shared_only = 0;   // 1: every tile is a shared-prefix tile with at most 64 live rows
   int32_t max_row_tokens = 1;   // > 1: some row holds several new tokens (needs the matrix-core decode kernel)
   int64_t total_units = 0;
   // scratch of the builder, kept between calls

@@ -669,7 +669,7 @@ constexpr int kKLds = kKvBlock * kRowBytes;      // 8 KiB: K block, 16-byte chun
 constexpr int kVRow = 80;                 // bytes per dim row of V^T in LDS (64 + 16 pad: conflict-free reads)
 constexpr int kVLds = 128 * kVRow;        // 10 KiB
 
-template <int G, int TW>
+template <int G, int TW, bool SPLIT>
 __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block, uint8_t (*lds)[kKLds + kVLds]) {
   // TW = wavefronts of the workgroup (4 or 8); a tile has 32 * TW query rows that share one staging
   // of every K/V block, so K/V bytes read per flop (from L2, and written to LDS) halve with TW = 8.
@@ -697,13 +697,25 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
   const int kb0 = shared ? tw[7] / 2 : 0;                        // first 32-token block (page0 is even)
   const int nblk = (kv_end + kKvBlock - 1) / kKvBlock;
   const int last_page = max((kv_end + kP - 1) / kP - 1, 0);
-  const bool wave_live = wv * 32 * CT < count * G;               // a wavefront whose rows are all padding only stages
+  // A shared-prefix tile of four wavefronts with at most 64 live rows would keep two of them busy, each alone
+  // with the whole chain of a block (operand reads, eight chained score MFMAs, weights, PV) in every step.
+  // Such a tile is split by key block instead: wavefronts 0 and 1 take the rows for the even blocks,
+  // wavefronts 2 and 3 the same rows for the odd blocks, and each does half of a block's chain per
+  // step (scores and weights of its block in one step, PV in the next); the two halves are combined
+  // through LDS at the end like two pieces of a split range.
+  // (A kernel of its own, chosen by the host when every tile of the batch is such a tile: with both block
+  // loops in one kernel the register allocator spills inside them.)
+  static_assert(!SPLIT || TW == 4, "only four-wavefront tiles are split");
+  constexpr bool split = SPLIT;
+  const int pair = split ? (wv >> 1) : 0;
+  const int wvr = split ? (wv & 1) : wv;                         // which 32 rows of the tile
+  const bool wave_live = wvr * 32 * CT < count * G;              // a wavefront whose rows are all padding only stages
 
   int tl[CT], h[CT], qrow[CT], vis[CT];
   bf16x8_t q[CT][8];             // Q of this lane's rows: 8 k-steps of 16 dims, this lane supplies dims 16*ks + 8*hf .. +8
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
-    const int rho = (wv * CT + ct) * 32 + col;     // query row of this lane inside the tile
+    const int rho = (wvr * CT + ct) * 32 + col;    // query row of this lane inside the tile
     tl[ct] = rho / G;                              // token (prefill) or member (shared prefix) of the row
     h[ct] = rho % G;
     const int tlc = min(tl[ct], count - 1);        // rows past the tile's last token/member repeat it (never written)
@@ -896,6 +908,102 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     mask_and_max(kb + 1);
   };
 
+  // A tile split by key block (see `split` above).  The pair whose block it is computes scores, maximum and
+  // weights of block kb + 1 (K in `nxt`) in step kb and the PV product of that block (V^T then in `cur`) in
+  // step kb + 1, while the other pair does the same one block later: the buffers are read in the same steps
+  // as in the unsplit loop, so three of them and one barrier per step still do.
+  uint32_t pwc[2][4] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+  auto first_half = [&](const int kb, const uint8_t* kbuf) {
+    bf16x8_t kk[8];
+    k_operands(kbuf, kk);
+    Sc = scores(kk);
+    mask_and_max(kb);
+    const float mx = mx_cur;
+    if (__builtin_amdgcn_ballot_w64(mx > m[0] + kTau) != 0) {
+      const float mn = fmaxf(m[0], mx);
+      const float al = __builtin_amdgcn_exp2f(m[0] - mn);
+      l[0] *= al;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[0][db][v] *= al;
+      m[0] = mn;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        const int v = 8 * ks + u;
+        const auto pk = __builtin_amdgcn_cvt_pkrtz(__builtin_amdgcn_exp2f(__builtin_fmaf(Sc[v], a.scale_log2e, -m[0])),
+                                                   __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[v + 1], a.scale_log2e, -m[0])));
+        l[0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk), f16x2_t{(_Float16)1.0f, (_Float16)1.0f}, l[0], false);
+        pwc[ks][u >> 1] = __builtin_bit_cast(uint32_t, pk);
+      }
+  };
+  auto second_half = [&](const uint8_t* vbuf) {
+    const uint8_t* vbase = vbuf + kKLds + col * kVRow + hf * 16;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const f16x8_t P = __builtin_bit_cast(f16x8_t, make_uint4(pwc[ks][0], pwc[ks][1], pwc[ks][2], pwc[ks][3]));
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8_t*)(vbase + db * 32 * kVRow + ks * 32), P, O[0][db], 0, 0, 0);
+    }
+  };
+  auto step_split = [&](const int kb, const uint8_t* cur, uint8_t* nxt, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
+    store_lds(kb + 1, nxt, k0, k1, v0, v1);
+    __syncthreads();
+    issue_loads(kb + 5, k0, k1, v0, v1);
+    if (!wave_live) return;
+    if (((kb - kb0) & 1) == pair) second_half(cur);
+    else first_half(kb + 1, nxt);
+  };
+
+  if constexpr (SPLIT) {
+    // This kernel has registers to spare: a fourth set of staging registers (and a fourth LDS buffer, so that
+    // the loop unrolled by four addresses them statically) puts the loads four blocks ahead of their use.
+    // These tiles each stream K/V of their own, and what bounds them is the bytes in flight.
+    uint4 kd0, kd1, vd0, vd1;
+    issue_loads(kb0, ka0, ka1, va0, va1);
+    issue_loads(kb0 + 1, kb0r, kb1r, vb0, vb1);
+    issue_loads(kb0 + 2, kc0, kc1, vc0, vc1);
+    issue_loads(kb0 + 3, kd0, kd1, vd0, vd1);
+    store_lds(kb0, lds[0], ka0, ka1, va0, va1);
+    __syncthreads();
+    issue_loads(kb0 + 4, ka0, ka1, va0, va1);
+    if (wave_live && pair == 0) first_half(kb0, lds[0]);
+    for (int kb = kb0; kb < nblk; kb += 4) {
+      step_split(kb, lds[0], lds[1], kb0r, kb1r, vb0, vb1);
+      step_split(kb + 1, lds[1], lds[2], kc0, kc1, vc0, vc1);
+      step_split(kb + 2, lds[2], lds[3], kd0, kd1, vd0, vd1);
+      step_split(kb + 3, lds[3], lds[0], ka0, ka1, va0, va1);
+    }
+    // the odd blocks' half (wavefronts 2, 3) goes to the even blocks' (wavefronts 0, 1) through LDS: per
+    // lane maximum, sum and the 64 accumulator values
+    __syncthreads();
+    float* xch = (float*)lds[0] + (wvr * 66) * 64 + lane;
+    if (pair == 1) {
+      xch[0] = m[0];
+      xch[64] = l[0];
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xch[(2 + db * 16 + v) * 64] = O[0][db][v];
+    }
+    __syncthreads();
+    if (pair == 1) return;
+    {
+      const float m1 = xch[0], l1 = xch[64];
+      const float mn = fmaxf(m[0], m1);
+      const float a0 = __builtin_amdgcn_exp2f(m[0] - mn), a1 = __builtin_amdgcn_exp2f(m1 - mn);
+      l[0] = l[0] * a0 + l1 * a1;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[0][db][v] = O[0][db][v] * a0 + xch[(2 + db * 16 + v) * 64] * a1;
+      m[0] = mn;
+    }
+  } else {
   issue_loads(kb0, ka0, ka1, va0, va1);
   issue_loads(kb0 + 1, kb0r, kb1r, vb0, vb1);
   issue_loads(kb0 + 2, kc0, kc1, vc0, vc1);
@@ -912,6 +1020,7 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
     step(kb, lds[0], lds[1], kb0r, kb1r, vb0, vb1);
     step(kb + 1, lds[1], lds[2], kc0, kc1, vc0, vc1);
     step(kb + 2, lds[2], lds[0], ka0, ka1, va0, va1);
+  }
   }
 
 #pragma unroll
@@ -1223,7 +1332,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs da) {
 // and workgroups that run decode ranges (one wavefront per range) in ONE grid, so the two kinds of
 // work fill the GPU together and there is no launch boundary between them.
 // ---------------------------------------------------------------------------------------
-template <typename E, int G, int TW>
+template <typename E, int G, int TW, bool SPLIT = false>
 __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_groups, int decode_groups) {
   // Workgroups come in groups of eight (one per XCD, which the tile order relies on).  Decode groups
   // are spread among the tile groups, so that some CUs stream K/V from HBM for decode ranges while
@@ -1238,9 +1347,9 @@ __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, Pr
   const uint32_t d0 = j < gs ? (uint32_t)((uint64_t)j * (uint64_t)decode_groups / gs) : (uint32_t)decode_groups;   // decode groups before group j
   const bool is_decode = j < gs && (uint32_t)((uint64_t)(j + 1) * (uint64_t)decode_groups / gs) > d0;
   if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
-    __shared__ __align__(16) uint8_t lds[3][kKLds + kVLds];
+    __shared__ __align__(16) uint8_t lds[SPLIT ? 4 : 3][kKLds + kVLds];
     if (!is_decode) {
-      tile_block<G, TW>(pa, (int)((j - d0) * 8 + x), lds);
+      tile_block<G, TW, SPLIT>(pa, (int)((j - d0) * 8 + x), lds);
       return;
     }
   }
@@ -1527,6 +1636,8 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   const int tile_blocks = ps.n_tiles > 0 ? ps.tile_blocks : 0;
   // eight-wavefront workgroups when the tiles have 256 query rows (and no tile is there: four)
   const int tw = (ps.n_tiles > 0 && ps.tile_rows == 256) ? 8 : 4;
+  // every tile a shared-prefix tile with at most 64 live rows: the kernel that splits them by key block
+  const bool split_tiles = E::kDimsPerChunk == 8 && tw == 4 && ps.n_tiles > 0 && ps.small_shared_only != 0;
   const int decode_blocks = mode == 0 ? (da.n_waves + tw - 1) / tw : 0;
   const int tile_groups = (tile_blocks + 7) / 8, decode_groups = (decode_blocks + 7) / 8;
   const dim3 grid((tile_groups + decode_groups) * 8), block(256), block8(512);
@@ -1537,6 +1648,7 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
 #define SYM_ATTN_CASE(GG) \
   case GG: \
     if (tw == 8) launch(attn_kernel<E, GG, 8>, grid, block8, ev0, e_first, da, ps, tile_groups, decode_groups); \
+    else if (split_tiles) launch(attn_kernel<E, GG, 4, true>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
     else launch(attn_kernel<E, GG, 4>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
     break;
   if (grid.x > 0) switch (G) {

@@ -41,6 +41,7 @@ struct PrefillArgs {
   int32_t tile_rows;             // query rows per tile: 128 (four wavefronts per workgroup) or 256 (eight)
   int32_t Hq, Hkv;
   float scale_log2e;
+  int32_t small_shared_only;     // every tile is a shared-prefix tile of at most 64 query rows (members x heads per kv head)
 };
 
 struct MergeArgs {
