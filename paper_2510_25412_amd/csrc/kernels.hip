@@ -750,12 +750,18 @@ __device__ __forceinline__ void tile_block(const PrefillArgs& a, const int block
   };
   auto issue_loads = [&](int kb, uint4& k0, uint4& k1, uint4& v0, uint4& v1) {
     const uint8_t* pk = page_base(2 * kb + k_page);
-    k0 = *(const uint4*)(pk + k_off);
-    if constexpr (TW == 4) k1 = *(const uint4*)(page_base(2 * kb + 1) + k_off);
+    // four-wavefront tiles are shared-prefix tiles, and each of those streams K/V of its own (nobody reads a
+    // line twice): nontemporal loads.  Prefill tiles share their stream with seven neighbours through L2.
+    auto ld16 = [&](const uint8_t* q16) {
+      if constexpr (TW == 4) return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)q16));
+      else return *(const uint4*)q16;
+    };
+    k0 = ld16(pk + k_off);
+    if constexpr (TW == 4) k1 = ld16(page_base(2 * kb + 1) + k_off);
     const uint8_t* p = (TW == 4 ? page_base(2 * kb + v_page) : pk) + v_off;
     if constexpr (TW == 4) {
-      v0 = *(const uint4*)p;
-      v1 = *(const uint4*)(p + kHalfBytes);
+      v0 = ld16(p);
+      v1 = ld16(p + kHalfBytes);
     } else {
       const uint2 x0 = *(const uint2*)p, x1 = *(const uint2*)(p + kHalfBytes);
       v0.x = x0.x; v0.y = x0.y;
