@@ -319,6 +319,34 @@ def test_shared_prefix_groups(Hq, Hkv, monkeypatch):
     check_outputs(got, plain, tol=1e-3)     # the tile kernel rounds softmax weights to fp16, the decode kernel does not
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8)])
+@pytest.mark.parametrize("prefix_pages", [1, 2, 3, 4, 5, 7, 9, 16, 41])
+def test_small_shared_prefix_tiles_split_by_key_block(Hq, Hkv, prefix_pages, monkeypatch):
+    """Batches whose shared-prefix tiles all have at most 64 rows run the kernel that splits a tile by
+    key block over its two pairs of wavefronts: prefixes of one block (the second pair gets nothing),
+    of an odd and an even number of blocks, with a half block at the end (odd page counts), groups of
+    fewer than 32 rows (one wavefront per pair) and of exactly 64, members with and without tokens of
+    their own.  The sharing thresholds are turned down so that even a one-page prefix is shared."""
+    monkeypatch.setenv("SYM_SHARE_MIN_LIPS", "2")
+    monkeypatch.setenv("SYM_SHARE_MIN_PAGES", "1")
+    G = Hq // Hkv
+    shape = synth.Shape(Hq, Hkv, 128, 16, synth.BF16)
+    n_big = 64 // G                                      # members of a 64-row group
+    files = [("new", 16 * prefix_pages + 5), ("new", 16 * prefix_pages)]
+    files += [("fork", 0, int(s)) for s in (0, 1, 17)]                                  # 3 members: 3 * G rows
+    files += [("fork", 1, (7 * i) % 40) for i in range(n_big)]                           # exactly 64 rows
+    batch = [(f, 1) for f in range(2, len(files))]
+    wl = synth.custom(f"split_{Hq}_{Hkv}_{prefix_pages}", shape, files, batch, 1024, seed=300 + prefix_pages + Hq)
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+    monkeypatch.setenv("SYM_SHARE_MIN_LIPS", "0")
+    plain, sess2 = _hip().run_workload(wl, poison=True)
+    sess2.close()
+    check_outputs(got, plain, tol=1e-3)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 8)])
 @pytest.mark.parametrize("waves", [0, 24])
 def test_draft_verify_rows(Hq, Hkv, waves, monkeypatch):
