@@ -128,7 +128,12 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     }
     if (!groups.empty()) {
       const int64_t target = 512;                             // about two workgroups per CU
-      const int32_t nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, (target + base_tiles - 1) / base_tiles));
+      int32_t nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, (target + base_tiles - 1) / base_tiles));
+      // every member leaves one partial per kv head and key chunk: the same number of chunks for all groups
+      // that the partial slots can hold (not the wanted number for the first groups and none for the last)
+      int64_t members_total = 0;
+      for (size_t gi = 0; gi < groups.size(); gi += 3) members_total += groups[gi + 1];
+      nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nc_want, shared_budget / std::max<int64_t>(1, members_total * H)));
       for (size_t gi = 0; gi < groups.size(); gi += 3) {
         const int32_t lo = groups[gi], K = groups[gi + 1], C = groups[gi + 2];
         int32_t nc = std::max(1, std::min(nc_want, C / 8));

@@ -510,6 +510,33 @@ def test_descriptor_shared_prefix_groups():
     assert all(int(by_out[k][5]) == 0 for k in by_out if k // 32 >= 6)
 
 
+def test_descriptor_shares_the_partial_slots_between_groups():
+    """Every member of a shared-prefix group leaves one partial per kv head and key chunk.  When the
+    wanted number of key chunks does not fit into the partial slots for all groups, all groups get fewer
+    chunks; the first groups must not take what they want and leave the last ones to read their whole
+    prefix member by member."""
+    c = host_ctx(8192, decode_waves=64)                  # few wave slots: few partial slots
+    tables, lengths = [], []
+    for gidx in range(5):                                # five groups of six forks of a 64-page prefix
+        prefix = list(range(1000 * gidx + 100, 1000 * gidx + 164))
+        for i in range(6):
+            tables.append(prefix + [1000 * gidx + 500 + i])
+            lengths.append(16 * 64 + 1 + i)
+    flat = np.concatenate(tables).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+    words = c.build_desc([1] * 30, flat, off, lengths)
+    hdr = words[:20]
+    n_rows, n_tiles, n_members, n_shared = int(hdr[0]), int(hdr[4]), int(hdr[16]), int(hdr[17])
+    rows = words[hdr[5]:hdr[5] + 4 * n_rows].reshape(n_rows, 4)
+    assert n_members == 30, "every group is shared"
+    assert (rows[:, 3] & 0x0fffffff).tolist() == [64] * 30   # every member's own range starts after the prefix
+    tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
+    per_group = {}
+    for t in tiles:
+        per_group[int(t[0])] = per_group.get(int(t[0]), 0) + 1
+    assert len(per_group) == 5 and len(set(per_group.values())) == 1     # the same number of tiles (chunks x heads) for every group
+
+
 def test_copies_before_appends_only_when_they_overlap():
     """A batch's page copies and appends may run in any order on the device unless an append lands
     in a slot that a copy of the same batch reads: a fork that was truncated (or an extract of a
