@@ -319,7 +319,7 @@ def test_shared_prefix_groups(Hq, Hkv, monkeypatch):
     check_outputs(got, plain, tol=1e-3)     # the tile kernel rounds softmax weights to fp16, the decode kernel does not
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8)])
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 8)])
 @pytest.mark.parametrize("prefix_pages", [1, 2, 3, 4, 5, 7, 9, 16, 41])
 def test_small_shared_prefix_tiles_split_by_key_block(Hq, Hkv, prefix_pages, monkeypatch):
     """Batches whose shared-prefix tiles all have at most 64 rows run the kernel that splits a tile by
