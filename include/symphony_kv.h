@@ -9,7 +9,11 @@
  *
  * Conventions
  *  - Every function returns an int status unless stated: 0 = SYM_OK, negative = error.
- *    On any error the host state is unchanged (all-or-nothing).  No exception or abort
+ *    On an error the host state is unchanged (all-or-nothing): arguments are validated, pool
+ *    space is counted and pinned staging memory is reserved before anything is committed.  The
+ *    one exception: SYM_EHIP from a kernel launch or from a wait on the device (reported AFTER
+ *    the commit) means the device is in an unknown state; the files of the call may then be
+ *    longer than their data, and the context should be destroyed.  No exception or abort
  *    crosses this boundary.  sym_strerror() returns the last message of the context.
  *  - "device" pointers are HIP device memory owned by the CALLER (e.g. a torch tensor's
  *    data_ptr()).  The library allocates no device memory, never synchronises `stream`
@@ -105,7 +109,7 @@ const char* sym_strerror(sym_ctx* ctx);   /* valid until the next call on ctx */
 sym_kv  sym_kv_open(sym_ctx* ctx, const char* name);
 /* kv_fork: new anonymous file with a copy of the parent's page list; every page's
  * reference count goes up by one; no tensor is copied, no page allocated, no device work
- * ("without duplicating the actual tensors", section 4.2).                               */
+ * (section 4.2: a fork must not duplicate the tensors).                                  */
 sym_kv  sym_kv_fork(sym_ctx* ctx, sym_kv parent);
 /* kv_remove: delete the file: every page's count goes down by one, pages reaching zero
  * return to the free set; all handles of the file become invalid (Fig. 1).               */
@@ -120,14 +124,14 @@ int64_t sym_kv_len(sym_ctx* ctx, sym_kv kv);
  * section 4.1, rolls the rejected ones back).  Host-only: pages no longer needed lose one
  * reference; K/V bytes are not touched.  kv, new_len: host.  All or nothing.              */
 int     sym_kv_truncate(sym_ctx* ctx, int32_t n, const sym_kv* kv, const int64_t* new_len);
-/* kv_append: the "file is updated with new tensors" half of pred (section 4.1) on its own:
+/* kv_append: the half of pred (section 4.1) that adds the new tokens' tensors to the file, on its own:
  * append n >= 1 token rows.  k, v: device, [n][Hkv][D] in the storage dtype.  Allocates
  * pages as needed; a shared, partly filled last page is first copied (copy-on-write).    */
 int     sym_kv_append(sym_ctx* ctx, sym_kv kv, int32_t n, const void* k, const void* v,
                       void* stream);
 
-/* kv_extract, kv_merge (section 4.2: "create new files from existing ones by extracting
- * specific token indices" / "merging existing files into one", e.g. to prune a context).
+/* kv_extract, kv_merge (section 4.2: a new file from chosen token indices of an existing one, and
+ * a new file that is several existing files joined, e.g. to prune a context).
  * Both make NEW anonymous files; the source files are not modified.
  *   sym_kv_extract: for n_files files at once (one launch): token j of new file i is token
  *     idx[idx_off[i] + j] of src[i], j < idx_off[i+1] - idx_off[i].  src, idx_off [n_files + 1],
@@ -153,8 +157,8 @@ int64_t sym_last_moves(sym_ctx* ctx, int32_t* out, int64_t cap);
  * the GPU to CPU memory and is restored when the I/O completes).  kv: host, n distinct handles.
  *   sym_kv_offload: the files start to wait.  A waiting file cannot be read or written (pred,
  *     append, fork, truncate, extract, merge, read: SYM_EBUSY) but can be removed or closed.  A
- *     page leaves the GPU when EVERY reference to it belongs to a waiting file ("a shared page
- *     leaves only when all sharers wait"): it is copied into pinned host memory owned by the
+ *     page leaves the GPU when EVERY reference to it belongs to a waiting file (a page that a
+ *     running file still shares stays): it is copied into pinned host memory owned by the
  *     context (host slots, lowest free first, allocated with hipHostMalloc as needed, kept until
  *     sym_destroy), every table entry that referenced it becomes -(slot + 1) (as sym_kv_pages
  *     shows), and the page returns to the free set.  Other pages stay where they are.
@@ -183,6 +187,28 @@ int64_t sym_last_swaps(sym_ctx* ctx, int32_t* out, int64_t cap);
 int sym_pred_batch(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
                    const void* q, const void* k_new, const void* v_new, float* out,
                    void* stream);
+
+/* sym_pred_batch for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same result, same state changes as
+ * sym_pred_batch, but the device scratch of the batch (descriptor words, partial results of cut
+ * ranges and shared prefixes) is a file-scope device array inside the library instead of the
+ * workspace of sym_config, and the call allocates nothing on the way: no device memory, no pinned
+ * memory (the staging buffers sym_init made are used as they are), no events (launches of this
+ * entry point are not profiled).  The array has sym_static_scratch_bytes() = 64 MiB and lives on
+ * every GPU the library has been used on until the process ends; its address on the context's
+ * device is looked up once, by sym_init.  Limits, refused with SYM_ENOSPC before anything changes:
+ * the descriptor blob of the batch (its upper bound: about 40 words per wavefront slot + 21 per new
+ * token + one per page-table entry + about 1000 per LIP at 8 kv heads) must not exceed 1 Mi words,
+ * and the partial results this shape needs at least (2 x tokens per row x wavefront slots + 1 slots of
+ * G x (head_dim + 2) floats) must fit behind it; with fewer slots than the workspace would have,
+ * fewer shared prefixes are read once (results are the same to rounding).  The array is shared by
+ * EVERY context and stream on the GPU and keeps the last call's contents (nothing in it has to
+ * start at zero: each launch writes every slot it reads): two calls of this entry point that
+ * overlap on one GPU, from different streams or contexts, race; order them.                   */
+int sym_pred_batch_static(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
+                          const void* q, const void* k_new, const void* v_new, float* out,
+                          void* stream);
+int64_t sym_static_scratch_bytes(void);
 
 /* Kernel-level entry without the allocator: attention only, over page tables the caller
  * supplies.  K/V of every token (new ones included) must already be in the pool.
@@ -252,10 +278,17 @@ int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
 int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out,
                 void* stream);
 
+/* Test hook: the next `count` reservations of pinned staging memory on this context fail with
+ * SYM_EHIP (as if the runtime had no pinned memory left).  Every call that changes file-system
+ * state reserves its staging memory BEFORE the change, so such a failure must leave page tables,
+ * lengths, reference counts and the free set exactly as they were; tests check that.  Works in a
+ * host-only context too (whose calls stage nothing but still pass through the reservation).  */
+int sym_test_fail_staging(sym_ctx* ctx, int32_t count);
+
 /* ---- inference scheduler: when to fire a batch (section 4.4) ------------------------- */
 /* The controller that decides WHEN the pending pred calls go to the GPU as one batch.  The
  * paper states the trade-off (too early wastes the GPU, too late makes threads wait) and that
- * the batch size follows the average call frequency via "models like Poisson process"; the
+ * the batch size follows the average call frequency through an arrival model such as a Poisson process; the
  * formulas are this library's: arrival rate lambda = 1 / (exponentially weighted mean gap);
  * service time S(b) = a + c*b fitted to the batches reported with sym_sched_done; target batch
  * b* = lambda*a / (1 - lambda*c) (the fixed point b = lambda*S(b): expected arrivals during one

@@ -8,7 +8,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsymphony_kv.so")
+# SYMPHONY_KV_LIB: another build of the same library (the host-only sanitizer builds of the CPU tests)
+LIB_PATH = os.environ.get("SYMPHONY_KV_LIB") or os.path.join(_HERE, "libsymphony_kv.so")
 
 SYM_OK, SYM_EINVAL, SYM_EBADF, SYM_ENOSPC, SYM_ENOENT, SYM_EEXIST, SYM_EBUSY, SYM_EHIP = 0, -1, -2, -3, -4, -5, -6, -7
 SYM_F32, SYM_BF16 = 0, 1
@@ -60,6 +61,9 @@ _SIGNATURES = {
     "sym_kv_waiting": (C.c_int, [C.c_void_p, C.c_int32]),
     "sym_last_swaps": (C.c_int64, [C.c_void_p, _I32P, C.c_int64]),
     "sym_pred_batch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_pred_batch_static": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_static_scratch_bytes": (C.c_int64, []),
+    "sym_test_fail_staging": (C.c_int, [C.c_void_p, C.c_int32]),
     "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_kv_pages": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, C.c_int64]),
     "sym_page_refcount": (C.c_int32, [C.c_void_p, C.c_int32]),
@@ -288,6 +292,14 @@ class Context:
         kv_a, kv_p = _i32(kv)
         nt_a, nt_p = _i32(n_tokens)
         self._chk(self.lib.sym_pred_batch(self.h, len(kv_a), kv_p, nt_p, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream))
+
+    def pred_batch_static(self, kv, n_tokens, q, k_new, v_new, out, stream=None):
+        kv_a, kv_p = _i32(kv)
+        nt_a, nt_p = _i32(n_tokens)
+        self._chk(self.lib.sym_pred_batch_static(self.h, len(kv_a), kv_p, nt_p, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream))
+
+    def test_fail_staging(self, count):
+        self._chk(self.lib.sym_test_fail_staging(self.h, count))
 
     def prepare_batch(self, kv, n_tokens, q, k_new, v_new, out):
         """Marshals the arguments of pred_batch once, for callers that issue the same batch many

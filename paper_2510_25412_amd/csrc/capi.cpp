@@ -23,7 +23,13 @@ using namespace symkv;
 namespace {
 constexpr int kStages = 4;          // pinned staging buffers in rotation
 constexpr int kMaxTimed = 4096;     // timed launches kept per kernel id
+constexpr int64_t kStaticBlobWords = 1 << 20;      // largest descriptor blob (32-bit words) sym_pred_batch_static accepts; every staging
+                                                  // buffer of a device context has this size from sym_init on
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+// memcpy of `bytes` bytes that tolerates an empty source (the data() of an empty vector may be null)
+inline void copy_bytes(void* dst, const void* src, size_t bytes) {
+  if (bytes) std::memcpy(dst, src, bytes);
+}
 inline int env_int(const char* name, int dflt) {
   const char* s = std::getenv(name);
   return (s && *s) ? std::atoi(s) : dflt;
@@ -59,6 +65,8 @@ struct sym_ctx {
   hipEvent_t stage_ev[kStages];
   bool stage_pending[kStages] = {false, false, false, false};
   int stage_next = 0;
+  int fail_staging = 0;                // test hook: this many coming staging reservations fail (sym_test_fail_staging)
+  uint8_t* static_scratch = nullptr;   // this device's copy of the library's file-scope scratch array (sym_pred_batch_static)
   // profiling
   int prof_mask = 0, prof_stride = 1;
   int64_t prof_seen[SYM_K_COUNT] = {0, 0, 0, 0, 0};
@@ -99,33 +107,66 @@ int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t en
 // pieces per wave, each a partial per token of the row); the rest is for the partials of
 // shared-prefix tiles and of their members' own ranges.
 int64_t partial_slots(const sym_ctx* c) { return (2 * ROW_TOKENS_MAX + 10) * (int64_t)c->max_waves + 1; }
-DescParams desc_params(const sym_ctx* c) {
-  return DescParams{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min,
-                    c->tile_tokens, c->share_min_lips, c->share_min_pages, (int32_t)partial_slots(c), c->row_tokens};
-}
-int64_t partial_bytes(const sym_ctx* c) {
-  const int64_t np = partial_slots(c);
+// The fewest slots with which every batch can be described: the cut pieces alone.
+int64_t min_partial_slots(const sym_ctx* c) { return 2 * (int64_t)c->row_tokens * c->max_waves + 1; }
+int64_t partial_bytes_for(const sym_ctx* c, int64_t np) {
   return align_up(np * c->G * 2 * 4, 256) + align_up(np * c->G * c->cfg.head_dim * 4, 256);
 }
+int64_t partial_bytes(const sym_ctx* c) { return partial_bytes_for(c, partial_slots(c)); }
 
-// Reserve the next pinned staging buffer with room for `words`; waits for the copy that last used it.
+// Device scratch of one batch: [descriptor words][partial max/sum][partial accumulators].  Either the
+// caller's workspace (as many partial slots as partial_slots says) or the library's static array
+// (as many as fit behind the descriptor).
+struct Scratch {
+  uint8_t* base;
+  int64_t bytes;
+  int64_t partials;
+};
+Scratch workspace_of(const sym_ctx* c) { return Scratch{(uint8_t*)c->cfg.workspace, c->cfg.workspace_bytes, partial_slots(c)}; }
+DescParams desc_params(const sym_ctx* c, int64_t partials) {
+  return DescParams{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min,
+                    c->tile_tokens, c->share_min_lips, c->share_min_pages, (int32_t)std::min<int64_t>(partials, 0x7fffffff), c->row_tokens};
+}
+
+// Pinned staging.  A call that changes host state first RESERVES room for the most it may stage
+// (stage_reserve: every buffer of the ring grows to that size now), then commits, then takes the
+// ring's next buffer (stage_acquire): no allocation can fail after the commit, so a call that
+// fails for want of pinned memory leaves the file system as it was.
+// may_alloc = false: never allocates; buffers that are too small are SYM_ENOSPC.
+int stage_reserve(sym_ctx* c, int64_t words, bool may_alloc = true) {
+  if (c->fail_staging > 0) {           // test hook (sym_test_fail_staging)
+    --c->fail_staging;
+    return fail(c, SYM_EHIP, "staging reservation failed (test hook)");
+  }
+  if (c->cfg.device < 0) return SYM_OK;          // host-only context: nothing is staged
+  for (int i = 0; i < kStages; ++i) {
+    if (c->stage_words[i] >= words) continue;
+    if (!may_alloc) return fail(c, SYM_ENOSPC, "batch too large for the preallocated staging buffers");
+    if (c->stage_pending[i]) {
+      hipError_t e = hipEventSynchronize(c->stage_ev[i]);
+      if (e != hipSuccess) return fail_hip(c, e, "hipEventSynchronize(stage)");
+      c->stage_pending[i] = false;
+    }
+    const int64_t cap = std::max<int64_t>(words * 3 / 2, 1 << 16);
+    int32_t* fresh = nullptr;
+    hipError_t e = hipHostMalloc((void**)&fresh, (size_t)cap * 4, hipHostMallocDefault);
+    if (e != hipSuccess) return fail_hip(c, e, "hipHostMalloc(stage)");
+    if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+    c->stage[i] = fresh;
+    c->stage_words[i] = cap;
+  }
+  return SYM_OK;
+}
+// The ring's next buffer (reserved before: it has room for `words`); waits for the copy that last used it.
 int stage_acquire(sym_ctx* c, int64_t words, int* idx) {
   const int i = c->stage_next;
-  c->stage_next = (i + 1) % kStages;
+  if (c->stage_words[i] < words) return fail(c, SYM_EINVAL, "staging buffer was not reserved");      // a bug of the caller
   if (c->stage_pending[i]) {
     hipError_t e = hipEventSynchronize(c->stage_ev[i]);
     if (e != hipSuccess) return fail_hip(c, e, "hipEventSynchronize(stage)");
     c->stage_pending[i] = false;
   }
-  if (c->stage_words[i] < words) {
-    if (c->stage[i]) (void)hipHostFree(c->stage[i]);
-    c->stage[i] = nullptr;
-    c->stage_words[i] = 0;
-    const int64_t cap = std::max<int64_t>(words * 3 / 2, 1 << 16);
-    hipError_t e = hipHostMalloc((void**)&c->stage[i], (size_t)cap * 4, hipHostMallocDefault);
-    if (e != hipSuccess) return fail_hip(c, e, "hipHostMalloc(stage)");
-    c->stage_words[i] = cap;
-  }
+  c->stage_next = (i + 1) % kStages;
   *idx = i;
   return SYM_OK;
 }
@@ -140,9 +181,9 @@ struct Timed {
   bool on, attached;
   hipEvent_t start() const { return on && attached ? c->ev_start[id][c->ev_used[id]] : nullptr; }
   hipEvent_t stop() const { return on && attached ? c->ev_stop[id][c->ev_used[id]] : nullptr; }
-  Timed(sym_ctx* ctx, int kid, hipStream_t s, bool attach = false) : c(ctx), id(kid), st(s), on(false), attached(attach) {
+  Timed(sym_ctx* ctx, int kid, hipStream_t s, bool attach = false, bool allow = true) : c(ctx), id(kid), st(s), on(false), attached(attach) {
     ++c->kernel_launches;
-    if (!((c->prof_mask >> id) & 1) || c->ev_used[id] >= kMaxTimed) return;
+    if (!allow || !((c->prof_mask >> id) & 1) || c->ev_used[id] >= kMaxTimed) return;
     if (c->prof_seen[id]++ % c->prof_stride != 0) return;          // every prof_stride-th launch is timed
     if ((int)c->ev_start[id].size() <= c->ev_used[id]) {
       hipEvent_t a, b;
@@ -161,14 +202,15 @@ struct Timed {
   }
 };
 
-// Launches attention (decode + merge) for the descriptor in c->desc, already copied to the workspace.
-int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, hipStream_t st) {
+// Launches attention (decode + merge) for the descriptor in c->desc, already copied to the scratch `ws`.
+// timed = false: no profiling events (they are created on demand, and this call may not allocate).
+int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const void* q, float* out, hipStream_t st, bool timed = true) {
   const BatchDesc& d = c->desc;
   if (d.n_waves == 0 && d.n_tiles == 0) return SYM_OK;
-  // workspace: [descriptor words][partial max/sum][partial accumulators]
-  const int32_t* dw = (const int32_t*)c->cfg.workspace;
-  uint8_t* base = (uint8_t*)c->cfg.workspace + align_up(blob_words * 4, 256);
-  const int64_t np = partial_slots(c);
+  // scratch: [descriptor words][partial max/sum][partial accumulators]
+  const int32_t* dw = (const int32_t*)ws.base;
+  uint8_t* base = ws.base + align_up(blob_words * 4, 256);
+  const int64_t np = ws.partials;
   float* part_ml = (float*)base;
   float* part_acc = (float*)(base + align_up(np * c->G * 2 * 4, 256));
   DecodeArgs a;
@@ -205,14 +247,14 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
   pa.scale_log2e = c->scale_log2e;
   pa.small_shared_only = d.small_shared_only;
   {
-    Timed t(c, SYM_K_ATTN, st, true);
+    Timed t(c, SYM_K_ATTN, st, true, timed);
     // rows that hold several new tokens exist for the matrix-core decode kernel only
     hipError_t e = launch_attn(a, pa, c->cfg.dtype, (c->decode_mode || d.max_row_tokens > 1) ? 1 : 0, st, t.start(), t.stop());
     if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {
     MergeArgs m{part_acc, part_ml, dw + d.words[H_OFF_MERGE], out, d.n_merge};
-    Timed t(c, SYM_K_MERGE, st);
+    Timed t(c, SYM_K_MERGE, st, false, timed);
     hipError_t e = launch_merge(m, c->G, c->cfg.head_dim, st);
     if (e != hipSuccess) return fail_hip(c, e, "merge launch");
   }
@@ -223,7 +265,7 @@ int launch_attention(sym_ctx* c, int64_t blob_words, const void* q, float* out, 
 // descriptor) are copied to the start of the workspace; the copy list at cow_off and the slot
 // map at slots_off are read from the pinned buffer by the kernel itself.
 int launch_prologue(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off, int32_t n_tokens,
-                    const void* k, const void* v, hipStream_t st) {
+                    const void* k, const void* v, hipStream_t st, uint8_t* dev_words = nullptr, bool timed = true) {
   PrologueArgs a;
   a.pool = (uint8_t*)c->cfg.pool;
   a.page_bytes = c->page_bytes;
@@ -232,21 +274,22 @@ int launch_prologue(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int
   a.slots = c->stage[si] + slots_off;
   a.cow = c->stage[si] + cow_off;
   a.host_words = c->stage[si];
-  a.dev_words = (int32_t*)c->cfg.workspace;
+  a.dev_words = (int32_t*)(dev_words ? dev_words : (uint8_t*)c->cfg.workspace);
   a.copy_words = copy_words;
   a.n_tokens = n_tokens;
   a.Hkv = c->cfg.n_kv_heads;
   a.n_cow = n_cow;
   a.append_blocks = a.copy_blocks = 0;
-  Timed t(c, SYM_K_PROLOGUE, st);
+  Timed t(c, SYM_K_PROLOGUE, st, false, timed);
   hipError_t e = symkv::launch_prologue(a, st);
   if (e != hipSuccess) return fail_hip(c, e, "prologue launch");
   return SYM_OK;
 }
 // The same, and records the event that lets the staging buffer be reused.
 int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off,
-                           int32_t n_tokens, const void* k, const void* v, hipStream_t st) {
-  const int rc = launch_prologue(c, si, copy_words, cow_off, n_cow, slots_off, n_tokens, k, v, st);
+                           int32_t n_tokens, const void* k, const void* v, hipStream_t st, uint8_t* dev_words = nullptr,
+                           bool timed = true) {
+  const int rc = launch_prologue(c, si, copy_words, cow_off, n_cow, slots_off, n_tokens, k, v, st, dev_words, timed);
   if (rc) return rc;
   hipError_t e = hipEventRecord(c->stage_ev[si], st);
   if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
@@ -267,11 +310,16 @@ int ensure_host_slots(sym_ctx* c, int64_t n_slots) {
 }
 uint8_t* host_slot(const sym_ctx* c, int32_t s) { return c->host_chunks[s / kHostChunk] + (int64_t)(s % kHostChunk) * c->page_bytes; }
 
+constexpr int64_t kSwapChunk = 1 << 18;                               // pages per swap launch
+int64_t swap_stage_words(int64_t pages) { return 4 * std::min(pages, kSwapChunk); }
+int64_t move_chunk(const sym_ctx* c) { return std::min<int64_t>((c->cfg.workspace_bytes / 4 - 64) / 2, 1 << 20); }   // tokens per move launch
+int64_t move_stage_words(const sym_ctx* c, int64_t tokens) { return 2 * std::min(tokens, std::max<int64_t>(move_chunk(c), 0)) + 4; }
+
 // Carries out the page copies of c->splan ((page, slot) pairs when to_host, (slot, page) otherwise).
 int run_swaps(sym_ctx* c, bool to_host, hipStream_t st) {
   const std::vector<int32_t>& pr = c->splan.pairs;
   const int64_t n = (int64_t)pr.size() / 2;
-  const int64_t cap = 1 << 18;                                        // pages per launch
+  const int64_t cap = kSwapChunk;
   for (int64_t off = 0; off < n; off += cap) {
     const int64_t cnt = std::min(cap, n - off);
     int si, rc;
@@ -301,12 +349,12 @@ int run_swaps(sym_ctx* c, bool to_host, hipStream_t st) {
 int run_moves(sym_ctx* c, hipStream_t st) {
   const std::vector<int32_t>& mv = c->gplan.moves;
   const int64_t n = (int64_t)mv.size() / 2;
-  const int64_t cap = std::min<int64_t>((c->cfg.workspace_bytes / 4 - 64) / 2, 1 << 20);   // tokens per chunk
+  const int64_t cap = move_chunk(c);
   for (int64_t off = 0; off < n; off += cap) {
     const int64_t cnt = std::min(cap, n - off);
     int si, rc;
     if ((rc = stage_acquire(c, 2 * cnt + 4, &si))) return rc;
-    std::memcpy(c->stage[si], mv.data() + 2 * off, (size_t)cnt * 8);
+    copy_bytes(c->stage[si], mv.data() + 2 * off, (size_t)cnt * 8);
     if ((rc = launch_prologue_staged(c, si, 2 * cnt, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
     MoveArgs ma{(uint8_t*)c->cfg.pool, c->page_bytes, (const int32_t*)c->cfg.workspace, cnt, c->cfg.n_kv_heads};
     Timed t(c, SYM_K_MOVE, st);
@@ -328,12 +376,77 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     for (int64_t i = 0; i < np; ++i)
       if (c->tables[b][i] < 0 || c->tables[b][i] >= c->cfg.n_pages) return fail(c, SYM_EINVAL, "page id out of range");
   }
-  const DescParams prm = desc_params(c);
+  const DescParams prm = desc_params(c, partial_slots(c));
   c->desc.alloc = alloc;
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   c->desc.alloc = nullptr;
   if (rc) return fail(c, rc, "build_desc: bad batch or no room for the descriptor");
   return c->desc.n_words;
+}
+
+// sym_pred_batch and sym_pred_batch_static (lock held, arguments checked): `ws` is the device scratch
+// the batch uses; no_alloc = true: nothing is allocated on the way (staging buffers as sym_init made
+// them, no profiling events) and a batch that does not fit is refused before anything changes.
+int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q, const void* k_new,
+                      const void* v_new, float* out, hipStream_t st, const Scratch& ws, bool no_alloc) {
+  const auto t_begin = std::chrono::steady_clock::now();
+  const int P = c->cfg.page_tokens;
+  // sizes after the append, for the checks that must precede any state change
+  int64_t T = 0, entries = 0;
+  for (int32_t b = 0; b < n_lips; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    if (!f) return fail(c, SYM_EBADF, "pred_batch: bad file handle");
+    if (n_tokens[b] < 1) return fail(c, SYM_EINVAL, "pred_batch: n_tokens must be >= 1");
+    T += n_tokens[b];
+    entries += (f->len + n_tokens[b] + P - 1) / P;
+  }
+  const int64_t bound = blob_words_bound(c, n_lips, T, entries);
+  if (no_alloc && bound > kStaticBlobWords) return fail(c, SYM_ENOSPC, "pred_batch_static: batch too large (descriptor beyond the static limit)");
+  if (align_up(bound * 4, 256) + partial_bytes_for(c, ws.partials) > ws.bytes) return fail(c, SYM_ENOSPC, "workspace too small for this batch");
+  int rc;
+  if ((rc = stage_reserve(c, bound, !no_alloc))) return rc;      // the last thing that can fail for want of memory
+  c->plan.clear();
+  if ((rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err))) return rc;
+  c->tables.resize(n_lips);
+  c->len_after.resize(n_lips);
+  for (int32_t b = 0; b < n_lips; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    c->tables[b] = f->pages.data();
+    c->len_after[b] = f->len;
+  }
+  const DescParams prm = desc_params(c, ws.partials);
+  // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
+  const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
+  int si = -1;
+  int64_t wait_ns = 0;
+  c->desc.alloc = [&](int64_t words) -> int32_t* {
+    const auto w0 = std::chrono::steady_clock::now();
+    if (stage_acquire(c, words + tail_words, &si)) return nullptr;      // may wait for the GPU: not host work
+    wait_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - w0).count();
+    return c->stage[si];
+  };
+  rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
+  c->desc.alloc = nullptr;
+  if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // not reached: sizes were checked against their bounds above
+  const int64_t dwords = align_up(c->desc.n_words, 4);
+  const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
+  const int64_t words = slots_off + (int64_t)c->plan.slots.size();
+  copy_bytes(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
+  copy_bytes(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
+  const auto t_planned = std::chrono::steady_clock::now();
+  int n_cow = (int)(c->plan.cow.size() / 3);
+  if (c->plan.copies_first) {       // an append of this batch overwrites slots that a copy of this batch reads: copies in a launch of their own
+    if ((rc = launch_prologue(c, si, 0, cow_off, n_cow, 0, 0, nullptr, nullptr, st, ws.base, !no_alloc))) return rc;
+    n_cow = 0;
+  }
+  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, n_cow, slots_off, (int32_t)c->plan.slots.size(), k_new, v_new, st, ws.base, !no_alloc))) return rc;
+  ++c->pred_batches;
+  rc = launch_attention(c, ws, words, q, out, st, !no_alloc);
+  const auto t_end = std::chrono::steady_clock::now();
+  const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
+  c->host_ns_plan += ns(t_planned - t_begin) - wait_ns;
+  c->host_ns_pred += ns(t_end - t_begin) - wait_ns;
+  return rc;
 }
 
 }  // namespace
@@ -380,8 +493,20 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
     hipError_t e = hipSetDevice(cfg->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device);
-    for (int i = 0; i < kStages && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming);
+    int n_ev = 0;                                  // staging events created so far
+    while (n_ev < kStages && e == hipSuccess)
+      if ((e = hipEventCreateWithFlags(&c->stage_ev[n_ev], hipEventDisableTiming)) == hipSuccess) ++n_ev;
+    // for the entry point that allocates nothing: this device's address of the library's static scratch
+    // array (the device is current here), and staging buffers that hold its largest descriptor
+    if (e == hipSuccess) e = static_scratch_address(cfg->device, &c->static_scratch);
+    for (int i = 0; i < kStages && e == hipSuccess; ++i) {
+      e = hipHostMalloc((void**)&c->stage[i], (size_t)kStaticBlobWords * 4, hipHostMallocDefault);
+      if (e == hipSuccess) c->stage_words[i] = kStaticBlobWords;
+    }
     if (e != hipSuccess) {
+      for (int i = 0; i < kStages; ++i)
+        if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+      for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(c->stage_ev[i]);
       delete c->fs;
       delete c;
       return SYM_EHIP;
@@ -488,7 +613,7 @@ int64_t sym_kv_pages(sym_ctx* c, sym_kv kv, int32_t* out, int64_t cap) {
   const KvFile* f = c->fs->file_of(kv);
   if (!f) return fail(c, SYM_EBADF, "kv_pages: bad handle");
   const int64_t n = (int64_t)f->pages.size();
-  if (out) std::memcpy(out, f->pages.data(), (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
+  if (out) copy_bytes(out, f->pages.data(), (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
   return n;
 }
 
@@ -536,8 +661,8 @@ int sym_plan_append(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t*
   const int rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err);
   if (rc) return rc;
   if (n_cow) *n_cow = (int32_t)(c->plan.cow.size() / 3);
-  if (cow_out) std::memcpy(cow_out, c->plan.cow.data(), c->plan.cow.size() * 4);
-  if (slots_out) std::memcpy(slots_out, c->plan.slots.data(), c->plan.slots.size() * 4);
+  if (cow_out) copy_bytes(cow_out, c->plan.cow.data(), c->plan.cow.size() * 4);
+  if (slots_out) copy_bytes(slots_out, c->plan.slots.data(), c->plan.slots.size() * 4);
   return SYM_OK;
 }
 
@@ -556,7 +681,7 @@ int64_t sym_build_desc(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
     return c->scratch_words.data();
   });
   if (n < 0) return n;
-  if (words_out) std::memcpy(words_out, c->desc.words, (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
+  if (words_out) copy_bytes(words_out, c->desc.words, (size_t)std::min(n, std::max<int64_t>(cap, 0)) * 4);
   return n;
 }
 
@@ -566,14 +691,15 @@ int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
   hipStream_t st = (hipStream_t)stream;
   if ((int64_t)n + 3 + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
+  int rc;
+  if ((rc = stage_reserve(c, (int64_t)std::max(n, 0) + 3))) return rc;      // before any state change
   c->plan.clear();
-  int rc = c->fs->append(1, &kv, &n, &c->plan, &c->err);
-  if (rc) return rc;
+  if ((rc = c->fs->append(1, &kv, &n, &c->plan, &c->err))) return rc;
   const int64_t words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size();
   int si;
   if ((rc = stage_acquire(c, words, &si))) return rc;
-  std::memcpy(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
-  std::memcpy(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
+  copy_bytes(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
+  copy_bytes(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
   return launch_prologue_staged(c, si, 0, 0, (int)(c->plan.cow.size() / 3), (int64_t)c->plan.cow.size(), n, k, v, st);
 }
 
@@ -593,6 +719,7 @@ int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t
     need += k;
   }
   if (need > c->fs->free_pages()) return fail(c, SYM_ENOSPC, "page pool exhausted");
+  if (int rc = stage_reserve(c, move_stage_words(c, idx_off[n_files] - idx_off[0]))) return rc;      // before any state change
   for (int32_t i = 0; i < n_files; ++i) out[i] = c->fs->gather_commit(&c->gplan, i);
   return c->cfg.device < 0 ? SYM_OK : run_moves(c, (hipStream_t)stream);
 }
@@ -600,6 +727,9 @@ int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t
 sym_kv sym_kv_merge(sym_ctx* c, int32_t m, const sym_kv* files, void* stream) {
   if (!c || m < 0 || (m > 0 && !files)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  int64_t tokens = 0;
+  for (int32_t i = 0; i < m; ++i) tokens += std::max<int64_t>(c->fs->len(files[i]), 0);
+  if (int rc = stage_reserve(c, move_stage_words(c, tokens))) return rc;      // before any state change
   const sym_kv h = c->fs->gather(m, files, nullptr, nullptr, &c->gplan, &c->err);
   if (h < 0 || c->cfg.device < 0) return h;
   const int rc = run_moves(c, (hipStream_t)stream);
@@ -610,16 +740,15 @@ int sym_kv_offload(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
   if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   int rc;
-  if (c->cfg.device >= 0) {
-    // Host memory first, so that running out of it changes nothing: at most every page of the
-    // files leaves, into the lowest free slots.
-    int64_t pages = 0;
-    for (int32_t b = 0; b < n; ++b) {
-      const KvFile* f = c->fs->file_of(kv[b]);
-      if (f) pages += (int64_t)f->pages.size();
-    }
-    if ((rc = ensure_host_slots(c, std::max(c->fs->host_slots(), c->fs->host_slots_in_use() + pages)))) return rc;
+  // Host memory and staging first, so that running out of either changes nothing: at most every
+  // page of the files leaves, into the lowest free slots.
+  int64_t pages = 0;
+  for (int32_t b = 0; b < n; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    if (f) pages += (int64_t)f->pages.size();
   }
+  if ((rc = stage_reserve(c, swap_stage_words(pages)))) return rc;
+  if (c->cfg.device >= 0 && (rc = ensure_host_slots(c, std::max(c->fs->host_slots(), c->fs->host_slots_in_use() + pages)))) return rc;
   if ((rc = c->fs->offload(n, kv, &c->splan, &c->err))) return rc;
   if (c->cfg.device < 0) {
     c->pages_offloaded += (int64_t)c->splan.pairs.size() / 2;
@@ -631,6 +760,12 @@ int sym_kv_offload(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
 int sym_kv_restore(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
   if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  int64_t pages = 0;
+  for (int32_t b = 0; b < n; ++b) {
+    const KvFile* f = c->fs->file_of(kv[b]);
+    if (f) pages += (int64_t)f->pages.size();
+  }
+  if (int rs = stage_reserve(c, swap_stage_words(pages))) return rs;      // before any state change
   const int rc = c->fs->restore(n, kv, &c->splan, &c->err);
   if (rc || c->cfg.device < 0) {
     if (!rc) c->pages_restored += (int64_t)c->splan.pairs.size() / 2;
@@ -649,7 +784,7 @@ int64_t sym_last_swaps(sym_ctx* c, int32_t* out, int64_t cap) {
   if (!c || cap < 0) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   const int64_t n = (int64_t)c->splan.pairs.size() / 2;
-  if (out) std::memcpy(out, c->splan.pairs.data(), (size_t)std::min(n, cap) * 8);
+  if (out) copy_bytes(out, c->splan.pairs.data(), (size_t)std::min(n, cap) * 8);
   return n;
 }
 
@@ -657,7 +792,7 @@ int64_t sym_last_moves(sym_ctx* c, int32_t* out, int64_t cap) {
   if (!c || cap < 0) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   const int64_t n = (int64_t)c->gplan.moves.size() / 2;
-  if (out) std::memcpy(out, c->gplan.moves.data(), (size_t)std::min(n, cap) * 8);
+  if (out) copy_bytes(out, c->gplan.moves.data(), (size_t)std::min(n, cap) * 8);
   return n;
 }
 
@@ -668,64 +803,26 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   if (!kv || !n_tokens || !q || !k_new || !v_new || !out) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
-  const auto t_begin = std::chrono::steady_clock::now();
-  hipStream_t st = (hipStream_t)stream;
-  const int P = c->cfg.page_tokens;
-  // sizes after the append, for the workspace check that must precede any state change
-  int64_t T = 0, entries = 0;
-  for (int32_t b = 0; b < n_lips; ++b) {
-    const KvFile* f = c->fs->file_of(kv[b]);
-    if (!f) return fail(c, SYM_EBADF, "pred_batch: bad file handle");
-    if (n_tokens[b] < 1) return fail(c, SYM_EINVAL, "pred_batch: n_tokens must be >= 1");
-    T += n_tokens[b];
-    entries += (f->len + n_tokens[b] + P - 1) / P;
-  }
-  if (align_up(blob_words_bound(c, n_lips, T, entries) * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes)
-    return fail(c, SYM_ENOSPC, "workspace too small for this batch");
-  c->plan.clear();
-  int rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err);
-  if (rc) return rc;
-  c->tables.resize(n_lips);
-  c->len_after.resize(n_lips);
-  for (int32_t b = 0; b < n_lips; ++b) {
-    const KvFile* f = c->fs->file_of(kv[b]);
-    c->tables[b] = f->pages.data();
-    c->len_after[b] = f->len;
-  }
-  const DescParams prm = desc_params(c);
-  // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
-  const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
-  int si = -1;
-  int64_t wait_ns = 0;
-  c->desc.alloc = [&](int64_t words) -> int32_t* {
-    const auto w0 = std::chrono::steady_clock::now();
-    if (stage_acquire(c, words + tail_words, &si)) return nullptr;      // may wait for the GPU: not host work
-    wait_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - w0).count();
-    return c->stage[si];
-  };
-  rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
-  c->desc.alloc = nullptr;
-  if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // unreachable after the checks above
-  const int64_t dwords = align_up(c->desc.n_words, 4);
-  const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
-  const int64_t words = slots_off + (int64_t)c->plan.slots.size();
-  std::memcpy(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
-  std::memcpy(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
-  const auto t_planned = std::chrono::steady_clock::now();
-  int n_cow = (int)(c->plan.cow.size() / 3);
-  if (c->plan.copies_first) {       // an append of this batch overwrites slots that a copy of this batch reads: copies in a launch of their own
-    if ((rc = launch_prologue(c, si, 0, cow_off, n_cow, 0, 0, nullptr, nullptr, st))) return rc;
-    n_cow = 0;
-  }
-  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, n_cow, slots_off, (int32_t)c->plan.slots.size(), k_new, v_new, st))) return rc;
-  ++c->pred_batches;
-  rc = launch_attention(c, words, q, out, st);
-  const auto t_end = std::chrono::steady_clock::now();
-  const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
-  c->host_ns_plan += ns(t_planned - t_begin) - wait_ns;
-  c->host_ns_pred += ns(t_end - t_begin) - wait_ns;
-  return rc;
+  return pred_batch_locked(c, n_lips, kv, n_tokens, q, k_new, v_new, out, (hipStream_t)stream, workspace_of(c), false);
 }
+
+int sym_pred_batch_static(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q,
+                          const void* k_new, const void* v_new, float* out, void* stream) {
+  if (!c || n_lips < 0) return SYM_EINVAL;
+  if (n_lips == 0) return SYM_OK;
+  if (!kv || !n_tokens || !q || !k_new || !v_new || !out) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  if (!c->static_scratch) return fail(c, SYM_EHIP, "the static scratch array has no address on this device");
+  // partial slots: what fits behind the largest descriptor this entry point accepts
+  Scratch ws{c->static_scratch, kStaticScratchBytes, 0};
+  const int64_t slot_bytes = (int64_t)c->G * (2 + c->cfg.head_dim) * 4;
+  ws.partials = (ws.bytes - kStaticBlobWords * 4 - 1024) / slot_bytes;
+  if (ws.partials < min_partial_slots(c)) return fail(c, SYM_ENOSPC, "pred_batch_static: this shape's partial results do not fit the static scratch");
+  return pred_batch_locked(c, n_lips, kv, n_tokens, q, k_new, v_new, out, (hipStream_t)stream, ws, true);
+}
+
+int64_t sym_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, const int32_t* page_table_flat,
                        const int64_t* pt_offsets, const int64_t* lengths, const void* q, float* out, void* stream) {
@@ -737,14 +834,21 @@ int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   int si = -1;
   const int64_t dwords = desc_from_flat(c, n_lips, n_tokens, page_table_flat, pt_offsets, lengths, [&](int64_t words) -> int32_t* {
     if (align_up(words * 4, 256) + partial_bytes(c) > c->cfg.workspace_bytes) return nullptr;
-    return stage_acquire(c, words + 4, &si) ? nullptr : c->stage[si];
+    return (stage_reserve(c, words + 4) || stage_acquire(c, words + 4, &si)) ? nullptr : c->stage[si];
   });
   if (dwords < 0) return (int)dwords;
   hipStream_t st = (hipStream_t)stream;
   int rc;
   if ((rc = launch_prologue_staged(c, si, dwords, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
   ++c->pred_batches;
-  return launch_attention(c, dwords, q, out, st);
+  return launch_attention(c, workspace_of(c), dwords, q, out, st);
+}
+
+int sym_test_fail_staging(sym_ctx* c, int32_t count) {
+  if (!c || count < 0) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  c->fail_staging = count;
+  return SYM_OK;
 }
 
 int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out, void* stream) {
@@ -759,7 +863,7 @@ int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, vo
   if ((int64_t)n + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
   const int P = c->cfg.page_tokens;
   int si, rc;
-  if ((rc = stage_acquire(c, n, &si))) return rc;
+  if ((rc = stage_reserve(c, n)) || (rc = stage_acquire(c, n, &si))) return rc;
   for (int32_t i = 0; i < n; ++i) {
     const int64_t t = start + i;
     c->stage[si][i] = f->pages[t / P] * P + (int32_t)(t % P);

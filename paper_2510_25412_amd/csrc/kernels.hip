@@ -6,9 +6,11 @@
 // one token and one kv head is 256 bytes; a (page, kv head) slab is [K|V][row half 0|1]
 // [16 tokens][128 bytes], 8 KiB, so 8 tokens of one row half are 1 KiB contiguous.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstdint>
+#include <mutex>
 
 #include "kernels.hpp"
 
@@ -1676,7 +1678,38 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Scratch memory of the entry point that allocates nothing (sym_pred_batch_static): descriptor
+// words + partial results live in this file-scope array instead of the caller's workspace.
+// Every GPU the library runs on holds its own copy at its own address, until the process ends;
+// host code never uses the array's name as an address: it asks the runtime once per device for
+// the address and passes that to the kernels like any other workspace.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
 }  // namespace
+
+hipError_t static_scratch_address(int device, uint8_t** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static uint8_t* addr[kMaxDevices] = {};
+  if (device < 0 || device >= kMaxDevices || !ptr) return hipErrorInvalidValue;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!addr[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (cur != device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[device] = (uint8_t*)p;
+  }
+  *ptr = addr[device];
+  return hipSuccess;
+}
 
 hipError_t launch_attn(const DecodeArgs& da, const PrefillArgs& pa, int dtype, int decode_mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (da.n_waves <= 0 && pa.n_tiles <= 0) return hipSuccess;

@@ -1,7 +1,6 @@
 // Argument blocks and launch functions of the HIP kernels (see kernels.hip).
 #pragma once
 #include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
 
 #include <cstdint>
 
@@ -89,6 +88,11 @@ struct SwapArgs {
   int32_t n_pages;
   int32_t to_host;              // 1 = pool -> host slots, 0 = host slots -> pool
 };
+
+// Size of the file-scope device array that stands in for the workspace in sym_pred_batch_static, and
+// its address on `device` (looked up once per device, with that device current during the lookup).
+constexpr int64_t kStaticScratchBytes = 64ll << 20;
+hipError_t static_scratch_address(int device, uint8_t** ptr);
 
 // decode_mode: 0 = VALU decode kernel, 1 = decode ranges on the matrix cores (bf16 storage only)
 // ev0 / ev1 (both or neither): events attached to the first / last dispatch of the launch (kernel start, kernel end)
