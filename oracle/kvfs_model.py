@@ -1,7 +1,7 @@
 """State model of the KV-cache file system (test infrastructure, CPU only).
 
 The paper (section 4.2) says only that KV tensors live in fixed-size pages of GPU
-memory, that files can be opened, forked "without duplicating the actual tensors",
+memory, that files can be opened, forked without the tensors being duplicated,
 removed and closed, and (section 4.1) that `pred` appends the new tokens' tensors to
 the file.  Everything finer than that is a convention of this build, written out here
 step by step so that the library's integer state can be compared bit for bit:

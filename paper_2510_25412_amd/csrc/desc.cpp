@@ -136,8 +136,11 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(nc_want, shared_budget / std::max<int64_t>(1, members_total * H)));
       for (size_t gi = 0; gi < groups.size(); gi += 3) {
         const int32_t lo = groups[gi], K = groups[gi + 1], C = groups[gi + 2];
-        int32_t nc = std::max(1, std::min(nc_want, C / 8));
-        while (nc > 1 && n_shared_partials + (int64_t)K * H * nc > shared_budget) --nc;   // partial slots must fit
+        // pages per key chunk are even (whole 32-token blocks): rounding up can leave the last chunks empty
+        // (66 pages in 8 chunks of 10: the 8th would be [66, 66)), so the count follows from the size
+        auto chunks_of = [C](int32_t n) { const int32_t cp = ((C + n - 1) / n + 1) & ~1; return (C + cp - 1) / cp; };
+        int32_t nc = chunks_of(std::max(1, std::min(nc_want, C / 8)));
+        while (nc > 1 && n_shared_partials + (int64_t)K * H * nc > shared_budget) nc = chunks_of(nc - 1);   // partial slots must fit
         if (n_shared_partials + (int64_t)K * H * nc > shared_budget) continue;            // no room: plain rows
         for (int32_t i = 0; i < K; i += tile_lips) {
           const int32_t k = std::min(tile_lips, K - i);
@@ -215,7 +218,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
     const int64_t e_lip = e - skip;
     ptoff[b] = (int32_t)e_lip;
     int64_t np = (len_after[b] + P - 1) / P;
-    std::memcpy(pt + e, tables[b] + skip, (size_t)(np - skip) * sizeof(int32_t));
+    if (np > skip) std::memcpy(pt + e, tables[b] + skip, (size_t)(np - skip) * sizeof(int32_t));
     e += np - skip;
     if (is_prefill(b)) {
       // order (kv head, token tile): the tiles that read the same K/V are neighbours

@@ -2,8 +2,8 @@
 a population of identical LIPs, each answering one request about a topic whose document (3000
 tokens in the paper, 100 documents) must be in its KV file before the answer is decoded.  The
 LIP logic is the paper's prompt caching: the KV files of the `retain` most requested topics are
-kept and forked for every later request of the topic ("retaining the KV cache for the top 20 most
-popular topics and discarding it for others"); other topics are prefilled from scratch and
+kept and forked for every later request of the topic (the paper keeps the caches of its 20 most
+popular topics and drops the rest); other topics are prefilled from scratch and
 their file is removed with the request.  Topic popularity is skewed by a Pareto index (smaller
 index = a few topics get most requests).
 

@@ -285,6 +285,73 @@ def test_error_codes_and_all_or_nothing():
         c.kv_append(n2, 1, 1, 1)
 
 
+def test_extract_of_no_tokens_same_codes_as_the_model():
+    """An extract of no tokens makes an empty file from a usable source and is refused, with the model's
+    code and without a new file, from a stale handle (EBADF) or a waiting file (EBUSY)."""
+    m, c = KVFSModel(32, 16), host_ctx(32)
+    a, b = c.kv_open(), c.kv_open()
+    ma, mb = m.kv_open(), m.kv_open()
+    c.plan_append([a, b], [20, 5])
+    m.append([(ma, 20), (mb, 5)])
+    assert c.kv_extract(a, []) == m.kv_extract(ma, [])[0]
+    c.kv_offload([b])
+    m.kv_offload([mb])
+    files = c.get_stats()["files"]
+    for h in (b, 99, -1):
+        with pytest.raises(KVError) as em:
+            m.kv_extract(h, [])
+        with pytest.raises(binding.SymError) as ec:
+            c.kv_extract(h, [])
+        assert ec.value.code == em.value.code
+    assert c.get_stats()["files"] == files and c.free_pages() == m.free_pages()
+
+
+def _state(c, handles, n_pages):
+    return ([c.page_refcount(p) for p in range(n_pages)], [(c.kv_len(h), c.kv_pages(h), c.kv_waiting(h)) for h in handles],
+            c.free_pages(), c.get_stats()["files"], c.get_stats()["host_slots"])
+
+
+def test_a_failed_staging_reservation_changes_nothing():
+    """Calls that change file-system state reserve their pinned staging memory first: when that
+    reservation fails (forced by the test hook), the call returns SYM_EHIP and page tables, lengths,
+    reference counts, free pages, file count and host slots are what they were; the same call then
+    succeeds and leaves the state the model predicts."""
+    m = KVFSModel(32, 16)
+    c = host_ctx(32)
+    a, b = c.kv_open(), c.kv_open()
+    ma, mb = m.kv_open(), m.kv_open()
+    c.plan_append([a, b], [40, 21])
+    m.append([(ma, 40), (mb, 21)])
+    f = c.kv_fork(a)
+    mf = m.kv_fork(ma)
+    hs = [a, b, f]
+
+    def failing(call):
+        snap = _state(c, hs, 32)
+        c.test_fail_staging(1)
+        with pytest.raises(binding.SymError) as e:
+            call()
+        assert e.value.code == binding.SYM_EHIP
+        assert _state(c, hs, 32) == snap
+        # the hook was used up by the failed call: it does not linger
+        return call()
+
+    x = failing(lambda: c.kv_extract(a, [0, 1, 2, 17, 39]))
+    mx, _ = m.kv_extract(ma, [0, 1, 2, 17, 39])
+    assert c.kv_pages(x) == m.kv_pages(mx)
+    y = failing(lambda: c.kv_merge([b, a]))
+    my, _ = m.kv_merge([mb, ma])
+    assert c.kv_pages(y) == m.kv_pages(my)
+    failing(lambda: c.kv_offload([b]))
+    m.kv_offload([mb])
+    assert c.kv_pages(b) == m.kv_pages(mb) and c.kv_waiting(b)
+    failing(lambda: c.kv_restore([b]))
+    m.kv_restore([mb])
+    assert c.kv_pages(b) == m.kv_pages(mb) and not c.kv_waiting(b)
+    assert [c.page_refcount(p) for p in range(32)] == [int(r) for r in m.refcount]
+    assert c.free_pages() == m.free_pages()
+
+
 def _walk_desc(words, Hkv, P=16):
     hdr = words[:20]
     n_rows, n_waves, n_partials, n_lips = (int(x) for x in hdr[:4])
@@ -508,6 +575,34 @@ def test_descriptor_shared_prefix_groups():
     assert max(used) < n_partials
     # the unrelated file and the 3-page sharer are ordinary rows
     assert all(int(by_out[k][5]) == 0 for k in by_out if k // 32 >= 6)
+
+
+def test_descriptor_shared_prefix_chunks_are_never_empty():
+    """Common prefixes of 16 .. 200 pages, few and many members: every shared tile covers at least one page, and per kv
+    head the key chunks cover the common pages exactly once, in order (pages per chunk are rounded up to whole
+    32-token blocks, which must shorten the list of chunks, not leave empty ones at its end)."""
+    c = host_ctx(1 << 16)
+    for members in (4, 16):
+        for C in range(16, 201, 2):
+            tables = [list(range(100, 100 + C)) + [5000 + 8 * i, 5001 + 8 * i] for i in range(members)]
+            lengths = [16 * C + 17 + i for i in range(members)]
+            flat = np.concatenate(tables).astype(np.int32)
+            off = np.concatenate([[0], np.cumsum([len(t) for t in tables])]).astype(np.int64)
+            words = c.build_desc([1] * members, flat, off, lengths)
+            hdr = words[:20]
+            n_tiles, n_shared = int(hdr[4]), int(hdr[17])
+            assert n_tiles == n_shared and n_shared % 8 == 0 and n_shared > 0
+            tiles = words[hdr[10]:hdr[10] + 12 * n_tiles].reshape(n_tiles, 12)
+            spans = {}
+            for t in tiles:
+                assert int(t[7]) < int(t[8]), (members, C, t[:9].tolist())
+                spans.setdefault(int(t[4]), []).append((int(t[7]), int(t[8])))
+            for g in range(8):
+                sp = sorted(spans[g])
+                assert sp[0][0] == 0 and sp[-1][1] == C and all(a[1] == b[0] for a, b in zip(sp, sp[1:])), (members, C, sp)
+            # the members' merge entries count exactly the chunks that exist
+            merge = words[hdr[7]:hdr[7] + 8 * int(hdr[14])].reshape(int(hdr[14]), 8)
+            assert set(merge[:, 5].tolist()) == {n_shared // 8}
 
 
 def test_descriptor_shares_the_partial_slots_between_groups():

@@ -272,6 +272,31 @@ def test_extract_errors_change_nothing():
     m.audit()
 
 
+def test_extract_of_no_tokens_still_needs_a_usable_source():
+    """kv_extract with an empty index list makes an empty file, but only from a source that exists and
+    does not wait: a stale handle is EBADF and a waiting file EBUSY like any other read of it (a waiting
+    file refuses every call but remove and close, the reading of paper section 4.3 taken here), and
+    neither creates a file or a handle."""
+    m = KVFSModel(8, 4)
+    a, b = m.kv_open(), m.kv_open()
+    m.append([(a, 6), (b, 3)])
+    e0, moves = m.kv_extract(a, [])
+    assert m.kv_len(e0) == 0 and m.kv_pages(e0) == [] and moves == []
+    m.kv_offload([b])
+    gone = m.kv_open()
+    m.kv_remove(gone)
+    snap = (m.refcount.copy(), m.free_pages(), dict(m.handles), m.kv_pages(b))
+    with pytest.raises(KVError) as e:
+        m.kv_extract(b, [])
+    assert e.value.code == EBUSY
+    for bad in (gone, 99, -1):
+        with pytest.raises(KVError) as e:
+            m.kv_extract(bad, [])
+        assert e.value.code == EBADF
+    assert np.array_equal(snap[0], m.refcount) and snap[1:] == (m.free_pages(), m.handles, m.kv_pages(b))
+    m.audit()
+
+
 def test_random_ops_with_extract_merge_against_token_lists():
     """Every file is shadowed by a plain Python list of unique token ids; each token's K row holds its
     id.  After any mix of append / fork / extract / merge / truncate / remove, reading a file

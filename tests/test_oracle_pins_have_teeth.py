@@ -143,6 +143,7 @@ def test_a_mistake_in_the_attention_oracle_fails_a_pin(what, edits):
     ("extract: nothing is ever shared", [("same = all(pg == toks[0][0] and sl == k for k, (pg, sl) in enumerate(toks))", "same = False")]),
     ("extract: shared page not counted", [("            if s is not None:\n                self.refcount[s] += 1\n", "            if s is not None:\n")]),
     ("extract: destination slots shifted", [("moves.append((pg, sl, dst, k))", "moves.append((pg, sl, dst, (k + 1) % P))")]),
+    ("extract of no tokens skips the check of its source", [("        self._file(h, usable=True)                        # the source must exist and not wait, even for no tokens\n", "")]),
     ("extract: index past the end allowed", [("if i < 0 or i >= f.length:", "if i < 0 or i > f.length:")]),
     ("merge: second file first", [("for h in handles for i in range(", "for h in reversed(handles) for i in range(")]),
     ("offload: a page leaves as soon as one reader waits", [("if len(self.waiters[p]) == self.refcount[p]:", "if True:")]),
