@@ -73,6 +73,9 @@ typedef struct sym_config {
                               NULL = identity.  Copied by sym_init.                      */
   float   softmax_scale;   /* 0 = 1/sqrt(D)                                              */
   int32_t decode_waves;    /* wavefront slots the decode kernel is cut into; 0 = auto    */
+  int32_t n_layers;        /* attention layers that share the files' page tables; 0 or 1 =
+                              one.  The pool then holds n_layers * n_pages pages, layer after
+                              layer: page p of layer l is page l * n_pages + p of the pool.   */
 } sym_config;
 
 typedef struct sym_stats {
@@ -210,6 +213,34 @@ int sym_pred_batch_static(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const 
                           void* stream);
 int64_t sym_static_scratch_bytes(void);
 
+/* pred over the layers of a model (section 4.1: one pred is a forward pass, and every attention
+ * layer of it sees the same files, page tables and batch).  In a context with n_layers layers a
+ * page id names one page in EVERY layer; the file calls act on all layers at once:
+ *   sym_kv_append:  k, v are [n_layers][n][Hkv][D];
+ *   sym_kv_extract / sym_kv_merge / sym_kv_offload / sym_kv_restore and the copy-on-write copies
+ *     move the rows or pages of every layer (a host slot holds a page's bytes of all layers);
+ *   sym_kv_read reads layer 0, sym_kv_read_layer any layer.
+ * A batch runs in two steps:
+ *   sym_pred_begin:  the host half, once per batch: plans and commits the append of
+ *     n_tokens[b] rows to file kv[b] (same rules and errors as sym_pred_batch), builds the batch
+ *     descriptor and copies it to the workspace (one small launch on `stream`).
+ *   sym_pred_layer:  the device half, once per layer, in any order, on the same stream: appends
+ *     this layer's rows k_new, v_new [T][Hkv][D] and computes this layer's attention for q
+ *     [T][Hq][D] into out [T][Hq][D] float32, against layer `layer` of the pool: the attention
+ *     launch (plain decode batches: this one launch appends the rows as well), preceded by a
+ *     launch for page copies and the rows of multi-token LIPs when the batch has any, followed
+ *     by the merge of partial results when ranges were divided.
+ * Between sym_pred_begin and the last of the n_layers sym_pred_layer calls (or sym_pred_end,
+ * which abandons the layers not yet run: their new rows stay unwritten) every call that changes
+ * file-system state or reads files is refused with SYM_EBUSY; kv_open, kv_len, kv_pages and
+ * the other introspection calls work.  A single-layer context may use either these calls or
+ * sym_pred_batch; a context with several layers only these.                               */
+int sym_pred_begin(sym_ctx* ctx, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens,
+                   void* stream);
+int sym_pred_layer(sym_ctx* ctx, int32_t layer, const void* q, const void* k_new,
+                   const void* v_new, float* out, void* stream);
+int sym_pred_end(sym_ctx* ctx);
+
 /* Kernel-level entry without the allocator: attention only, over page tables the caller
  * supplies.  K/V of every token (new ones included) must already be in the pool.
  * page_table_flat: host int32, LIP b's page ids at [pt_offsets[b], pt_offsets[b+1]);
@@ -277,6 +308,8 @@ int64_t sym_build_desc(sym_ctx* ctx, int32_t n_lips, const int32_t* n_tokens,
  * device arrays k_out, v_out [n][Hkv][D] (storage dtype).                                */
 int sym_kv_read(sym_ctx* ctx, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out,
                 void* stream);
+int sym_kv_read_layer(sym_ctx* ctx, sym_kv kv, int32_t layer, int64_t start, int32_t n,
+                      void* k_out, void* v_out, void* stream);
 
 /* Test hook: the next `count` reservations of pinned staging memory on this context fail with
  * SYM_EHIP (as if the runtime had no pinned memory left).  Every call that changes file-system

@@ -21,7 +21,7 @@ class SymConfig(C.Structure):
                 ("page_tokens", C.c_int32), ("dtype", C.c_int32), ("device", C.c_int32),
                 ("n_pages", C.c_int64), ("pool", C.c_void_p), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_int64), ("free_order", C.POINTER(C.c_int32)),
-                ("softmax_scale", C.c_float), ("decode_waves", C.c_int32)]
+                ("softmax_scale", C.c_float), ("decode_waves", C.c_int32), ("n_layers", C.c_int32)]
 
 
 class SymStats(C.Structure):
@@ -64,6 +64,10 @@ _SIGNATURES = {
     "sym_pred_batch_static": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_static_scratch_bytes": (C.c_int64, []),
     "sym_test_fail_staging": (C.c_int, [C.c_void_p, C.c_int32]),
+    "sym_pred_begin": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p]),
+    "sym_pred_layer": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sym_pred_end": (C.c_int, [C.c_void_p]),
+    "sym_kv_read_layer": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_pred_batch_raw": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I64P, _I64P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sym_kv_pages": (C.c_int64, [C.c_void_p, C.c_int32, _I32P, C.c_int64]),
     "sym_page_refcount": (C.c_int32, [C.c_void_p, C.c_int32]),
@@ -125,7 +129,7 @@ def _ptr(t):
 
 
 def make_config(n_q_heads, n_kv_heads, head_dim, page_tokens, dtype, n_pages, device=-1, pool=None, workspace=None,
-                workspace_bytes=0, free_order=None, softmax_scale=0.0, decode_waves=0):
+                workspace_bytes=0, free_order=None, softmax_scale=0.0, decode_waves=0, n_layers=1):
     cfg = SymConfig()
     cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_tokens = n_q_heads, n_kv_heads, head_dim, page_tokens
     cfg.dtype = {"f32": SYM_F32, "bf16": SYM_BF16}.get(dtype, dtype)
@@ -135,7 +139,7 @@ def make_config(n_q_heads, n_kv_heads, head_dim, page_tokens, dtype, n_pages, de
     if free_order is not None:
         keep, p = _i32(free_order)
         cfg.free_order = p
-    cfg.softmax_scale, cfg.decode_waves = softmax_scale, decode_waves
+    cfg.softmax_scale, cfg.decode_waves, cfg.n_layers = softmax_scale, decode_waves, n_layers
     cfg._keep = keep
     return cfg
 
@@ -293,6 +297,19 @@ class Context:
         nt_a, nt_p = _i32(n_tokens)
         self._chk(self.lib.sym_pred_batch(self.h, len(kv_a), kv_p, nt_p, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream))
 
+    def pred_begin(self, kv, n_tokens, stream=None):
+        kv_a, kv_p = _i32(kv)
+        nt_a, nt_p = _i32(n_tokens)
+        self._chk(self.lib.sym_pred_begin(self.h, len(kv_a), kv_p, nt_p, stream))
+
+    def pred_layer(self, layer, q, k_new, v_new, out, stream=None):
+        rc = self.lib.sym_pred_layer(self.h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream)
+        if rc < 0:
+            self._chk(rc)
+
+    def pred_end(self):
+        self._chk(self.lib.sym_pred_end(self.h))
+
     def pred_batch_static(self, kv, n_tokens, q, k_new, v_new, out, stream=None):
         kv_a, kv_p = _i32(kv)
         nt_a, nt_p = _i32(n_tokens)
@@ -364,8 +381,8 @@ class Context:
         self._chk(self.lib.sym_build_desc(self.h, len(nt_a), nt_p, pt_p, po_p, ln_p, out.ctypes.data_as(_I32P), n))
         return out
 
-    def kv_read(self, kv, start, n, k_out, v_out, stream=None):
-        self._chk(self.lib.sym_kv_read(self.h, kv, start, n, _ptr(k_out), _ptr(v_out), stream))
+    def kv_read(self, kv, start, n, k_out, v_out, stream=None, layer=0):
+        self._chk(self.lib.sym_kv_read_layer(self.h, kv, layer, start, n, _ptr(k_out), _ptr(v_out), stream))
 
     # ---- measurement ----
     def profile_enable(self, mask, stride=1):

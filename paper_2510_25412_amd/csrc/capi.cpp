@@ -36,9 +36,22 @@ inline int env_int(const char* name, int dflt) {
 }
 }  // namespace
 
+// A batch planned by sym_pred_begin: where its parts lie in the device copy of the blob, until every layer has run.
+struct OpenPred {
+  bool open = false;
+  int64_t words = 0, cow_off = 0, slots_off = 0;   // blob size; offsets of the copy list and of the slot map in it
+  int32_t n_cow = 0, n_append = 0;                 // page copies; rows for the append kernel (0 when the attention kernel appends them all)
+  bool copies_first = false;
+  std::vector<uint8_t> done;                       // per layer: sym_pred_layer has run
+  int32_t n_done = 0;
+};
+
 struct sym_ctx {
   sym_config cfg;
   int32_t G = 1;
+  int32_t n_layers = 1;
+  int64_t layer_bytes = 0;            // bytes of one layer of the pool: n_pages * page_bytes
+  OpenPred pred;
   int64_t page_bytes = 0;
   float scale_log2e = 0.f;
   int32_t max_waves = 0, min_units = 4, range_cost = 3;
@@ -47,6 +60,9 @@ struct sym_ctx {
   int32_t tile_rows = 256;                     // query rows of an MFMA tile: 128 or 256
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   int32_t row_tokens = 1;                      // new tokens of one LIP per decode row (bf16: up to 16 / G, at most 4)
+  int32_t fuse_append = 1;                     // 1: the attention kernel appends the tokens of single-token LIPs itself
+  int32_t bin_waves = 8;                       // wavefronts per decode bin (workgroup) of a batch without tiles: 4 or 8
+  int32_t bin_tolerance = 3;                   // percent of imbalance between the decode bins that is accepted before ranges are split
   std::mutex mu;
   std::string err;
   Kvfs* fs = nullptr;
@@ -56,6 +72,7 @@ struct sym_ctx {
   std::vector<uint8_t*> host_chunks;   // pinned memory of the host slots, kHostChunk pages each
   int64_t pages_offloaded = 0, pages_restored = 0;
   BatchDesc desc;
+  int32_t desc_hdr[DESC_HEADER_WORDS] = {};   // header of the last descriptor built for a launch (its words lie in pinned memory)
   std::vector<const int32_t*> tables;
   std::vector<int64_t> len_after;
   std::vector<int32_t> scratch_words;
@@ -88,6 +105,14 @@ int fail_hip(sym_ctx* c, hipError_t e, const char* what) {
   return SYM_EHIP;
 }
 
+uint8_t* pool_of(const sym_ctx* c, int32_t layer) { return (uint8_t*)c->cfg.pool + (int64_t)layer * c->layer_bytes; }
+// Calls that change file-system state (or stage anything) are refused between sym_pred_begin and the batch's last layer:
+// the descriptor on the device describes the files as they are.
+int refuse_if_open(sym_ctx* c, const char* what) {
+  if (!c->pred.open) return SYM_OK;
+  return fail(c, SYM_EBUSY, std::string(what) + ": a batch begun with sym_pred_begin has layers left (run them, or sym_pred_end)");
+}
+
 bool shape_ok(const sym_config* cfg) {
   if (!cfg) return false;
   const int es = cfg->dtype == SYM_F32 ? 4 : cfg->dtype == SYM_BF16 ? 2 : 0;
@@ -99,7 +124,11 @@ bool shape_ok(const sym_config* cfg) {
 
 // 32-bit words of the host-to-device blob of one batch: descriptor + copies + slots.
 int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t entries) {
-  return DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + ROW_TOKENS_MAX * MERGE_WORDS) + entries +
+  // bins: a segment (and at most one merge entry) per (row, kv head) and per piece of a split range (no more pieces than
+  // partial slots for them: 2 * tokens per row * wavefront slots), an in-bin merge list per workgroup of at least 4 wavefronts
+  const int64_t bins = (T * c->cfg.n_kv_heads + 2 * (int64_t)c->row_tokens * c->max_waves + 2) * (SEG_WORDS + MERGE_WORDS) +
+                       ((int64_t)c->max_waves / 4 + 1) * LMERGE_WORDS;
+  return bins + DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + ROW_TOKENS_MAX * MERGE_WORDS) + entries +
          (T + 8 * n_lips) * c->cfg.n_kv_heads * 2 + n_lips * (1 + c->cfg.n_kv_heads * (MERGE_WORDS + 8 * TILE_WORDS)) +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
@@ -123,9 +152,15 @@ struct Scratch {
   int64_t partials;
 };
 Scratch workspace_of(const sym_ctx* c) { return Scratch{(uint8_t*)c->cfg.workspace, c->cfg.workspace_bytes, partial_slots(c)}; }
-DescParams desc_params(const sym_ctx* c, int64_t partials) {
-  return DescParams{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min,
-                    c->tile_tokens, c->share_min_lips, c->share_min_pages, (int32_t)std::min<int64_t>(partials, 0x7fffffff), c->row_tokens};
+// fuse_append: the batch's single-token LIPs are appended by the attention kernel itself (bins only)
+DescParams desc_params(const sym_ctx* c, int64_t partials, bool fuse_append = false) {
+  DescParams p{c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.page_tokens, c->max_waves, c->min_units, c->range_cost, c->prefill_min,
+               c->tile_tokens, c->share_min_lips, c->share_min_pages, (int32_t)std::min<int64_t>(partials, 0x7fffffff), c->row_tokens};
+  // the vector-unit decode kernel (up to 4 query heads per kv head, unless the matrix cores are asked for) works on bins
+  p.bin_waves = (c->G < 8 && !c->decode_mode) ? c->bin_waves : 0;
+  p.fuse_append = (fuse_append && p.bin_waves && c->fuse_append) ? 1 : 0;
+  p.bin_tolerance = c->bin_tolerance;
+  return p;
 }
 
 // Pinned staging.  A call that changes host state first RESERVES room for the most it may stage
@@ -204,9 +239,11 @@ struct Timed {
 
 // Launches attention (decode + merge) for the descriptor in c->desc, already copied to the scratch `ws`.
 // timed = false: no profiling events (they are created on demand, and this call may not allocate).
-int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const void* q, float* out, hipStream_t st, bool timed = true) {
+int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const void* q, float* out, hipStream_t st, bool timed = true,
+                     const void* k_new = nullptr, const void* v_new = nullptr, int32_t layer = 0) {
   const BatchDesc& d = c->desc;
   if (d.n_waves == 0 && d.n_tiles == 0) return SYM_OK;
+  const int32_t* hdr = c->desc_hdr;
   // scratch: [descriptor words][partial max/sum][partial accumulators]
   const int32_t* dw = (const int32_t*)ws.base;
   uint8_t* base = ws.base + align_up(blob_words * 4, 256);
@@ -214,27 +251,36 @@ int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const vo
   float* part_ml = (float*)base;
   float* part_acc = (float*)(base + align_up(np * c->G * 2 * 4, 256));
   DecodeArgs a;
-  a.pool = (const uint8_t*)c->cfg.pool;
+  a.pool = pool_of(c, layer);
   a.page_bytes = c->page_bytes;
   a.q = q;
   a.out = out;
   a.part_acc = part_acc;
   a.part_ml = part_ml;
-  a.rows = dw + d.words[H_OFF_ROWS];
-  a.waves = dw + d.words[H_OFF_WAVES];
-  a.pt = dw + d.words[H_OFF_PT];
+  a.rows = dw + hdr[H_OFF_ROWS];
+  a.waves = dw + hdr[H_OFF_WAVES];
+  a.pt = dw + hdr[H_OFF_PT];
   a.n_waves = d.n_waves;
   a.Hq = c->cfg.n_q_heads;
   a.Hkv = c->cfg.n_kv_heads;
   a.scale_log2e = c->scale_log2e;
+  a.segs = dw + hdr[H_OFF_SEGS];
+  a.lmerge = dw + hdr[H_OFF_LMERGE];
+  a.n_bins = d.n_bins;
+  a.bin_waves = d.bin_waves;
+  // the attention kernel requests a chunk of these rows with every segment's query rows, used or not: when it appends
+  // nothing, the query rows (no smaller) stand in
+  a.k_new = d.n_fused > 0 ? k_new : q;
+  a.v_new = d.n_fused > 0 ? v_new : q;
+  if (d.n_fused > 0 && (!k_new || !v_new)) return fail(c, SYM_EINVAL, "attention launch: rows to append are missing");
   PrefillArgs pa;
-  pa.pool = (const uint8_t*)c->cfg.pool;
+  pa.pool = pool_of(c, layer);
   pa.page_bytes = c->page_bytes;
   pa.q = q;
   pa.out = out;
-  pa.tiles = dw + d.words[H_OFF_TILES];
-  pa.pt = dw + d.words[H_OFF_PT];
-  pa.members = dw + d.words[H_OFF_MEMBERS];
+  pa.tiles = dw + hdr[H_OFF_TILES];
+  pa.pt = dw + hdr[H_OFF_PT];
+  pa.members = dw + hdr[H_OFF_MEMBERS];
   pa.part_acc = part_acc;
   pa.part_ml = part_ml;
   pa.tile_first = 0;
@@ -253,7 +299,7 @@ int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const vo
     if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   }
   if (d.n_merge > 0) {
-    MergeArgs m{part_acc, part_ml, dw + d.words[H_OFF_MERGE], out, d.n_merge};
+    MergeArgs m{part_acc, part_ml, dw + hdr[H_OFF_MERGE], out, d.n_merge};
     Timed t(c, SYM_K_MERGE, st, false, timed);
     hipError_t e = launch_merge(m, c->G, c->cfg.head_dim, st);
     if (e != hipSuccess) return fail_hip(c, e, "merge launch");
@@ -261,19 +307,19 @@ int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const vo
   return SYM_OK;
 }
 
-// One prologue launch for the staged words in c->stage[si]: the first copy_words words (the
-// descriptor) are copied to the start of the workspace; the copy list at cow_off and the slot
-// map at slots_off are read from the pinned buffer by the kernel itself.
-int launch_prologue(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off, int32_t n_tokens,
-                    const void* k, const void* v, hipStream_t st, uint8_t* dev_words = nullptr, bool timed = true) {
+// One prologue launch: the first copy_words words of the pinned buffer c->stage[si] (the descriptor, or the whole blob of
+// a batch) are copied to `dev_words` (default: the start of the workspace); `n_cow` page copies from the list `cow` and the
+// append of `n_tokens` rows k, v by the slot map `slots` (both lists in pinned or device memory) go to layer `layer`.
+int launch_prologue(sym_ctx* c, int si, int64_t copy_words, const int32_t* cow, int n_cow, const int32_t* slots, int32_t n_tokens,
+                    const void* k, const void* v, hipStream_t st, uint8_t* dev_words = nullptr, bool timed = true, int32_t layer = 0) {
   PrologueArgs a;
-  a.pool = (uint8_t*)c->cfg.pool;
+  a.pool = pool_of(c, layer);
   a.page_bytes = c->page_bytes;
   a.k_new = k;
   a.v_new = v;
-  a.slots = c->stage[si] + slots_off;
-  a.cow = c->stage[si] + cow_off;
-  a.host_words = c->stage[si];
+  a.slots = slots;
+  a.cow = cow;
+  a.host_words = si >= 0 ? c->stage[si] : nullptr;
   a.dev_words = (int32_t*)(dev_words ? dev_words : (uint8_t*)c->cfg.workspace);
   a.copy_words = copy_words;
   a.n_tokens = n_tokens;
@@ -285,12 +331,8 @@ int launch_prologue(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int
   if (e != hipSuccess) return fail_hip(c, e, "prologue launch");
   return SYM_OK;
 }
-// The same, and records the event that lets the staging buffer be reused.
-int launch_prologue_staged(sym_ctx* c, int si, int64_t copy_words, int64_t cow_off, int n_cow, int64_t slots_off,
-                           int32_t n_tokens, const void* k, const void* v, hipStream_t st, uint8_t* dev_words = nullptr,
-                           bool timed = true) {
-  const int rc = launch_prologue(c, si, copy_words, cow_off, n_cow, slots_off, n_tokens, k, v, st, dev_words, timed);
-  if (rc) return rc;
+// Records the event that lets the staging buffer be reused.
+int stage_release(sym_ctx* c, int si, hipStream_t st) {
   hipError_t e = hipEventRecord(c->stage_ev[si], st);
   if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
   c->stage_pending[si] = true;
@@ -302,13 +344,14 @@ constexpr int64_t kHostChunk = 1024;
 int ensure_host_slots(sym_ctx* c, int64_t n_slots) {
   while ((int64_t)c->host_chunks.size() * kHostChunk < n_slots) {
     uint8_t* p = nullptr;
-    hipError_t e = hipHostMalloc((void**)&p, (size_t)(kHostChunk * c->page_bytes), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void**)&p, (size_t)(kHostChunk * c->page_bytes * c->n_layers), hipHostMallocDefault);
     if (e != hipSuccess) return fail_hip(c, e, "hipHostMalloc(host slots)");
     c->host_chunks.push_back(p);
   }
   return SYM_OK;
 }
-uint8_t* host_slot(const sym_ctx* c, int32_t s) { return c->host_chunks[s / kHostChunk] + (int64_t)(s % kHostChunk) * c->page_bytes; }
+// a host slot holds the page's bytes of every layer, layer after layer
+uint8_t* host_slot(const sym_ctx* c, int32_t s) { return c->host_chunks[s / kHostChunk] + (int64_t)(s % kHostChunk) * c->page_bytes * c->n_layers; }
 
 constexpr int64_t kSwapChunk = 1 << 18;                               // pages per swap launch
 int64_t swap_stage_words(int64_t pages) { return 4 * std::min(pages, kSwapChunk); }
@@ -330,15 +373,13 @@ int run_swaps(sym_ctx* c, bool to_host, hipStream_t st) {
       list[2 * i] = (uint64_t)(to_host ? a : b);
       list[2 * i + 1] = (uint64_t)(uintptr_t)host_slot(c, to_host ? b : a);
     }
-    SwapArgs sa{(uint8_t*)c->cfg.pool, c->page_bytes, list, (int32_t)cnt, to_host ? 1 : 0};
-    {
+    for (int32_t l = 0; l < c->n_layers; ++l) {
+      SwapArgs sa{pool_of(c, l), c->page_bytes, list, (int32_t)cnt, to_host ? 1 : 0, (int64_t)l * c->page_bytes};
       Timed t(c, SYM_K_SWAP, st);
       hipError_t e = launch_swap(sa, st);
       if (e != hipSuccess) return fail_hip(c, e, "swap launch");
     }
-    hipError_t e = hipEventRecord(c->stage_ev[si], st);
-    if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
-    c->stage_pending[si] = true;
+    if ((rc = stage_release(c, si, st))) return rc;
   }
   (to_host ? c->pages_offloaded : c->pages_restored) += n;
   return SYM_OK;
@@ -355,11 +396,13 @@ int run_moves(sym_ctx* c, hipStream_t st) {
     int si, rc;
     if ((rc = stage_acquire(c, 2 * cnt + 4, &si))) return rc;
     copy_bytes(c->stage[si], mv.data() + 2 * off, (size_t)cnt * 8);
-    if ((rc = launch_prologue_staged(c, si, 2 * cnt, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
-    MoveArgs ma{(uint8_t*)c->cfg.pool, c->page_bytes, (const int32_t*)c->cfg.workspace, cnt, c->cfg.n_kv_heads};
-    Timed t(c, SYM_K_MOVE, st);
-    hipError_t e = launch_move(ma, st);
-    if (e != hipSuccess) return fail_hip(c, e, "move launch");
+    if ((rc = launch_prologue(c, si, 2 * cnt, nullptr, 0, nullptr, 0, nullptr, nullptr, st)) || (rc = stage_release(c, si, st))) return rc;
+    for (int32_t l = 0; l < c->n_layers; ++l) {
+      MoveArgs ma{pool_of(c, l), c->page_bytes, (const int32_t*)c->cfg.workspace, cnt, c->cfg.n_kv_heads};
+      Timed t(c, SYM_K_MOVE, st);
+      hipError_t e = launch_move(ma, st);
+      if (e != hipSuccess) return fail_hip(c, e, "move launch");
+    }
   }
   return SYM_OK;
 }
@@ -381,15 +424,22 @@ int64_t desc_from_flat(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   const int rc = build_desc(prm, n_lips, n_tokens, lengths, c->tables.data(), &c->desc);
   c->desc.alloc = nullptr;
   if (rc) return fail(c, rc, "build_desc: bad batch or no room for the descriptor");
+  std::memcpy(c->desc_hdr, c->desc.words, sizeof(c->desc_hdr));
   return c->desc.n_words;
 }
 
-// sym_pred_batch and sym_pred_batch_static (lock held, arguments checked): `ws` is the device scratch
-// the batch uses; no_alloc = true: nothing is allocated on the way (staging buffers as sym_init made
-// them, no profiling events) and a batch that does not fit is refused before anything changes.
-int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q, const void* k_new,
-                      const void* v_new, float* out, hipStream_t st, const Scratch& ws, bool no_alloc) {
-  const auto t_begin = std::chrono::steady_clock::now();
+// The host half of a batch (lock held, arguments checked): validates, reserves staging, commits the append, builds the
+// descriptor straight into a pinned staging buffer with copy list and slot map behind it.  `ws` is the device scratch
+// the batch will use; no_alloc = true: nothing is allocated on the way (staging buffers as sym_init made them) and a
+// batch that does not fit is refused before anything changes.
+struct PlannedBatch {
+  int si = -1;
+  int64_t dwords = 0, words = 0, cow_off = 0, slots_off = 0;
+  int32_t n_cow = 0, n_append = 0;
+  int64_t wait_ns = 0;
+};
+int pred_plan_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const Scratch& ws, bool no_alloc,
+                     PlannedBatch* pb) {
   const int P = c->cfg.page_tokens;
   // sizes after the append, for the checks that must precede any state change
   int64_t T = 0, entries = 0;
@@ -414,38 +464,64 @@ int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  const DescParams prm = desc_params(c, ws.partials);
+  const DescParams prm = desc_params(c, ws.partials, true);
   // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
   const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
   int si = -1;
-  int64_t wait_ns = 0;
   c->desc.alloc = [&](int64_t words) -> int32_t* {
     const auto w0 = std::chrono::steady_clock::now();
     if (stage_acquire(c, words + tail_words, &si)) return nullptr;      // may wait for the GPU: not host work
-    wait_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - w0).count();
+    pb->wait_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - w0).count();
     return c->stage[si];
   };
   rc = build_desc(prm, n_lips, n_tokens, c->len_after.data(), c->tables.data(), &c->desc);
   c->desc.alloc = nullptr;
   if (rc) return fail(c, rc, "pred_batch: descriptor build failed");   // not reached: sizes were checked against their bounds above
-  const int64_t dwords = align_up(c->desc.n_words, 4);
-  const int64_t cow_off = dwords, slots_off = cow_off + (int64_t)c->plan.cow.size();
-  const int64_t words = slots_off + (int64_t)c->plan.slots.size();
-  copy_bytes(c->stage[si] + cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
-  copy_bytes(c->stage[si] + slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
+  std::memcpy(c->desc_hdr, c->desc.words, sizeof(c->desc_hdr));
+  pb->si = si;
+  pb->dwords = align_up(c->desc.n_words, 4);
+  pb->cow_off = pb->dwords;
+  pb->slots_off = pb->cow_off + (int64_t)c->plan.cow.size();
+  pb->words = pb->slots_off + (int64_t)c->plan.slots.size();
+  copy_bytes(c->stage[si] + pb->cow_off, c->plan.cow.data(), c->plan.cow.size() * 4);
+  copy_bytes(c->stage[si] + pb->slots_off, c->plan.slots.data(), c->plan.slots.size() * 4);
+  if (c->desc.n_fused > 0) {           // tokens that the attention kernel appends itself: the append kernel skips them
+    int32_t* sl = c->stage[si] + pb->slots_off;
+    int64_t t = 0;
+    for (int32_t b = 0; b < n_lips; t += n_tokens[b], ++b)
+      if (c->desc.fused[b]) sl[t] = -1;
+  }
+  pb->n_cow = (int)(c->plan.cow.size() / 3);
+  // rows for the append kernel: none when the attention kernel appends every token of the batch itself
+  pb->n_append = c->desc.n_fused == (int32_t)c->plan.slots.size() ? 0 : (int32_t)c->plan.slots.size();
+  return SYM_OK;
+}
+
+// sym_pred_batch and sym_pred_batch_static (lock held, arguments checked): one layer, one call.
+int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const void* q, const void* k_new,
+                      const void* v_new, float* out, hipStream_t st, const Scratch& ws, bool no_alloc) {
+  const auto t_begin = std::chrono::steady_clock::now();
+  PlannedBatch pb;
+  int rc;
+  if ((rc = pred_plan_locked(c, n_lips, kv, n_tokens, ws, no_alloc, &pb))) return rc;
   const auto t_planned = std::chrono::steady_clock::now();
-  int n_cow = (int)(c->plan.cow.size() / 3);
+  const int32_t* cow = c->stage[pb.si] + pb.cow_off;
+  const int32_t* slots = c->stage[pb.si] + pb.slots_off;
+  int n_cow = pb.n_cow;
   if (c->plan.copies_first) {       // an append of this batch overwrites slots that a copy of this batch reads: copies in a launch of their own
-    if ((rc = launch_prologue(c, si, 0, cow_off, n_cow, 0, 0, nullptr, nullptr, st, ws.base, !no_alloc))) return rc;
+    if ((rc = launch_prologue(c, pb.si, 0, cow, n_cow, nullptr, 0, nullptr, nullptr, st, ws.base, !no_alloc))) return rc;
     n_cow = 0;
   }
-  if ((rc = launch_prologue_staged(c, si, dwords, cow_off, n_cow, slots_off, (int32_t)c->plan.slots.size(), k_new, v_new, st, ws.base, !no_alloc))) return rc;
+  // descriptor to the device; page copies and the appends the attention kernel does not do itself, read from the pinned buffer
+  if ((rc = launch_prologue(c, pb.si, pb.dwords, cow, n_cow, slots, pb.n_append, k_new, v_new, st, ws.base, !no_alloc)) ||
+      (rc = stage_release(c, pb.si, st)))
+    return rc;
   ++c->pred_batches;
-  rc = launch_attention(c, ws, words, q, out, st, !no_alloc);
+  rc = launch_attention(c, ws, pb.words, q, out, st, !no_alloc, k_new, v_new);
   const auto t_end = std::chrono::steady_clock::now();
   const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
-  c->host_ns_plan += ns(t_planned - t_begin) - wait_ns;
-  c->host_ns_pred += ns(t_end - t_begin) - wait_ns;
+  c->host_ns_plan += ns(t_planned - t_begin) - pb.wait_ns;
+  c->host_ns_pred += ns(t_end - t_begin) - pb.wait_ns;
   return rc;
 }
 
@@ -464,13 +540,14 @@ int64_t sym_workspace_bytes(const sym_config* cfg, int64_t max_lips, int64_t max
   tmp.cfg = *cfg;
   tmp.G = cfg->n_q_heads / cfg->n_kv_heads;
   tmp.max_waves = cfg->decode_waves > 0 ? cfg->decode_waves : 8192;
+  tmp.row_tokens = ROW_TOKENS_MAX;
   return align_up(blob_words_bound(&tmp, max_lips, max_tokens, max_table_entries) * 4, 256) + partial_bytes(&tmp) + 256;
 }
 
 int sym_init(const sym_config* cfg, sym_ctx** out) {
   if (!out) return SYM_EINVAL;
   *out = nullptr;
-  if (!shape_ok(cfg) || cfg->n_pages < 1 || cfg->n_pages >= (1LL << 27)) return SYM_EINVAL;
+  if (!shape_ok(cfg) || cfg->n_pages < 1 || cfg->n_pages >= (1LL << 27) || cfg->n_layers < 0 || cfg->n_layers > 1024) return SYM_EINVAL;
   if (cfg->device >= 0 && (!cfg->pool || !cfg->workspace || cfg->workspace_bytes < 4096)) return SYM_EINVAL;
   if (cfg->free_order) {   // must be a permutation
     std::vector<uint8_t> seen((size_t)cfg->n_pages, 0);
@@ -485,6 +562,8 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->cfg.free_order = nullptr;
   c->G = cfg->n_q_heads / cfg->n_kv_heads;
   c->page_bytes = sym_page_bytes(cfg);
+  c->n_layers = std::max(1, cfg->n_layers);
+  c->layer_bytes = cfg->n_pages * c->page_bytes;
   const float scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   c->scale_log2e = scale * 1.4426950408889634f;
   c->fs = new Kvfs(cfg->n_pages, cfg->page_tokens, cfg->free_order);
@@ -527,6 +606,9 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   // a short draft (2 .. prefill_min - 1 new tokens) shares one pass over its file: 16 MFMA columns = tokens x heads
   c->row_tokens = cfg->dtype == SYM_BF16 ? std::max(1, std::min(env_int("SYM_ROW_TOKENS", ROW_TOKENS_MAX), std::min<int>(ROW_TOKENS_MAX, 16 / c->G))) : 1;
   c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
+  c->bin_tolerance = std::max(0, env_int("SYM_BIN_TOL", 3));
+  c->bin_waves = env_int("SYM_BIN_WAVES", 8) == 4 ? 4 : 8;
+  c->fuse_append = env_int("SYM_FUSE_APPEND", 1) ? 1 : 0;
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
     return SYM_ENOSPC;
@@ -565,6 +647,7 @@ sym_kv sym_kv_open(sym_ctx* c, const char* name) {
 sym_kv sym_kv_fork(sym_ctx* c, sym_kv parent) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_fork")) return busy;
   const int32_t h = c->fs->fork(parent);
   if (h < 0) c->err = h == SYM_EBUSY ? "kv_fork: file is offloaded" : "kv_fork: bad handle";
   return h;
@@ -573,6 +656,7 @@ sym_kv sym_kv_fork(sym_ctx* c, sym_kv parent) {
 int sym_kv_remove(sym_ctx* c, sym_kv kv) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_remove")) return busy;
   const int rc = c->fs->remove(kv);
   if (rc) c->err = "kv_remove: bad handle";
   return rc;
@@ -581,6 +665,7 @@ int sym_kv_remove(sym_ctx* c, sym_kv kv) {
 int sym_kv_close(sym_ctx* c, sym_kv kv) {
   if (!c) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_close")) return busy;
   const int rc = c->fs->close(kv);
   if (rc) c->err = "kv_close: bad handle";
   return rc;
@@ -595,6 +680,7 @@ int64_t sym_kv_len(sym_ctx* c, sym_kv kv) {
 int sym_kv_truncate(sym_ctx* c, int32_t n, const sym_kv* kv, const int64_t* new_len) {
   if (!c || n < 0 || (n > 0 && (!kv || !new_len))) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_truncate")) return busy;
   for (int32_t i = 0; i < n; ++i) {          // validate everything first: all or nothing
     const KvFile* f = c->fs->file_of(kv[i]);
     if (!f) return fail(c, SYM_EBADF, "kv_truncate: bad handle");
@@ -656,6 +742,7 @@ int sym_plan_append(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t*
                     int64_t cow_cap, int32_t* n_cow, int32_t* slots_out) {
   if (!c || n_lips < 0 || (n_lips > 0 && (!kv || !n_tokens))) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "plan_append")) return busy;
   if (cow_out && cow_cap < n_lips) return fail(c, SYM_EINVAL, "plan_append: cow_cap must be >= n_lips");
   c->plan.clear();
   const int rc = c->fs->append(n_lips, kv, n_tokens, &c->plan, &c->err);
@@ -689,9 +776,10 @@ int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v
   if (!c || !k || !v) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  int rc;
+  if ((rc = refuse_if_open(c, "kv_append"))) return rc;
   hipStream_t st = (hipStream_t)stream;
   if ((int64_t)n + 3 + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
-  int rc;
   if ((rc = stage_reserve(c, (int64_t)std::max(n, 0) + 3))) return rc;      // before any state change
   c->plan.clear();
   if ((rc = c->fs->append(1, &kv, &n, &c->plan, &c->err))) return rc;
@@ -700,7 +788,12 @@ int sym_kv_append(sym_ctx* c, sym_kv kv, int32_t n, const void* k, const void* v
   if ((rc = stage_acquire(c, words, &si))) return rc;
   copy_bytes(c->stage[si], c->plan.cow.data(), c->plan.cow.size() * 4);
   copy_bytes(c->stage[si] + c->plan.cow.size(), c->plan.slots.data(), c->plan.slots.size() * 4);
-  return launch_prologue_staged(c, si, 0, 0, (int)(c->plan.cow.size() / 3), (int64_t)c->plan.cow.size(), n, k, v, st);
+  const int64_t layer_rows = (int64_t)n * c->cfg.n_kv_heads * 256;           // bytes of one layer's rows in k and in v
+  for (int32_t l = 0; l < c->n_layers; ++l)
+    if ((rc = launch_prologue(c, si, 0, c->stage[si], (int)(c->plan.cow.size() / 3), c->stage[si] + c->plan.cow.size(), n,
+                              (const uint8_t*)k + l * layer_rows, (const uint8_t*)v + l * layer_rows, st, nullptr, true, l)))
+      return rc;
+  return stage_release(c, si, st);
 }
 
 int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t* idx_off, const int64_t* idx, sym_kv* out,
@@ -709,6 +802,7 @@ int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t
   if (n_files == 0) return SYM_OK;
   if (!src || !idx_off || !out || (idx_off[n_files] > 0 && !idx)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_extract")) return busy;
   const int64_t none = 0;
   if (!idx) idx = &none;
   int64_t need = 0;                                       // all files or none: plan them all, count the fresh pages
@@ -727,6 +821,7 @@ int sym_kv_extract(sym_ctx* c, int32_t n_files, const sym_kv* src, const int64_t
 sym_kv sym_kv_merge(sym_ctx* c, int32_t m, const sym_kv* files, void* stream) {
   if (!c || m < 0 || (m > 0 && !files)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_merge")) return busy;
   int64_t tokens = 0;
   for (int32_t i = 0; i < m; ++i) tokens += std::max<int64_t>(c->fs->len(files[i]), 0);
   if (int rc = stage_reserve(c, move_stage_words(c, tokens))) return rc;      // before any state change
@@ -739,6 +834,7 @@ sym_kv sym_kv_merge(sym_ctx* c, int32_t m, const sym_kv* files, void* stream) {
 int sym_kv_offload(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
   if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_offload")) return busy;
   int rc;
   // Host memory and staging first, so that running out of either changes nothing: at most every
   // page of the files leaves, into the lowest free slots.
@@ -760,6 +856,7 @@ int sym_kv_offload(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
 int sym_kv_restore(sym_ctx* c, int32_t n, const sym_kv* kv, void* stream) {
   if (!c || n < 0 || (n > 0 && !kv)) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
+  if (int busy = refuse_if_open(c, "kv_restore")) return busy;
   int64_t pages = 0;
   for (int32_t b = 0; b < n; ++b) {
     const KvFile* f = c->fs->file_of(kv[b]);
@@ -803,6 +900,8 @@ int sym_pred_batch(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   if (!kv || !n_tokens || !q || !k_new || !v_new || !out) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  if (c->n_layers != 1) return fail(c, SYM_EINVAL, "pred_batch: a context with several layers runs its batches with sym_pred_begin / sym_pred_layer");
+  if (int busy = refuse_if_open(c, "pred_batch")) return busy;
   return pred_batch_locked(c, n_lips, kv, n_tokens, q, k_new, v_new, out, (hipStream_t)stream, workspace_of(c), false);
 }
 
@@ -814,6 +913,8 @@ int sym_pred_batch_static(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const in
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
   if (!c->static_scratch) return fail(c, SYM_EHIP, "the static scratch array has no address on this device");
+  if (c->n_layers != 1) return fail(c, SYM_EINVAL, "pred_batch_static: single-layer contexts only");
+  if (int busy = refuse_if_open(c, "pred_batch_static")) return busy;
   // partial slots: what fits behind the largest descriptor this entry point accepts
   Scratch ws{c->static_scratch, kStaticScratchBytes, 0};
   const int64_t slot_bytes = (int64_t)c->G * (2 + c->cfg.head_dim) * 4;
@@ -839,9 +940,72 @@ int sym_pred_batch_raw(sym_ctx* c, int32_t n_lips, const int32_t* n_tokens, cons
   if (dwords < 0) return (int)dwords;
   hipStream_t st = (hipStream_t)stream;
   int rc;
-  if ((rc = launch_prologue_staged(c, si, dwords, 0, 0, 0, 0, nullptr, nullptr, st))) return rc;
+  if ((rc = launch_prologue(c, si, dwords, nullptr, 0, nullptr, 0, nullptr, nullptr, st)) || (rc = stage_release(c, si, st))) return rc;
   ++c->pred_batches;
   return launch_attention(c, workspace_of(c), dwords, q, out, st);
+}
+
+int sym_pred_begin(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, void* stream) {
+  if (!c || n_lips < 1 || !kv || !n_tokens) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  int rc;
+  if ((rc = refuse_if_open(c, "pred_begin"))) return rc;
+  const auto t_begin = std::chrono::steady_clock::now();
+  PlannedBatch pb;
+  if ((rc = pred_plan_locked(c, n_lips, kv, n_tokens, workspace_of(c), false, &pb))) return rc;
+  // the whole blob (descriptor, copy list, slot map) goes to the device once; the layers read it there
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = launch_prologue(c, pb.si, pb.words, nullptr, 0, nullptr, 0, nullptr, nullptr, st)) || (rc = stage_release(c, pb.si, st))) return rc;
+  OpenPred& o = c->pred;
+  o.open = true;
+  o.words = pb.words;
+  o.cow_off = pb.cow_off;
+  o.slots_off = pb.slots_off;
+  o.n_cow = pb.n_cow;
+  o.n_append = pb.n_append;
+  o.copies_first = c->plan.copies_first;
+  o.done.assign((size_t)c->n_layers, 0);
+  o.n_done = 0;
+  ++c->pred_batches;
+  const int64_t ns = std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t_begin).count() - pb.wait_ns;
+  c->host_ns_plan += ns;
+  c->host_ns_pred += ns;
+  return SYM_OK;
+}
+
+int sym_pred_layer(sym_ctx* c, int32_t layer, const void* q, const void* k_new, const void* v_new, float* out, void* stream) {
+  if (!c || !q || !k_new || !v_new || !out) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  OpenPred& o = c->pred;
+  if (!o.open) return fail(c, SYM_EINVAL, "pred_layer: no batch is open (sym_pred_begin first)");
+  if (layer < 0 || layer >= c->n_layers) return fail(c, SYM_EINVAL, "pred_layer: no such layer");
+  if (o.done[layer]) return fail(c, SYM_EBUSY, "pred_layer: this layer of the batch has already run");
+  const auto t_begin = std::chrono::steady_clock::now();
+  hipStream_t st = (hipStream_t)stream;
+  const Scratch ws = workspace_of(c);
+  const int32_t* cow = (const int32_t*)ws.base + o.cow_off;          // the device copy of the blob
+  const int32_t* slots = (const int32_t*)ws.base + o.slots_off;
+  int rc, n_cow = o.n_cow;
+  if (o.copies_first && n_cow > 0) {
+    if ((rc = launch_prologue(c, -1, 0, cow, n_cow, nullptr, 0, nullptr, nullptr, st, nullptr, true, layer))) return rc;
+    n_cow = 0;
+  }
+  if (n_cow > 0 || o.n_append > 0)
+    if ((rc = launch_prologue(c, -1, 0, cow, n_cow, slots, o.n_append, k_new, v_new, st, nullptr, true, layer))) return rc;
+  rc = launch_attention(c, ws, o.words, q, out, st, true, k_new, v_new, layer);
+  if (rc) return rc;
+  o.done[layer] = 1;
+  if (++o.n_done == c->n_layers) o.open = false;                      // the batch is complete
+  c->host_ns_pred += std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t_begin).count();
+  return SYM_OK;
+}
+
+int sym_pred_end(sym_ctx* c) {
+  if (!c) return SYM_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  c->pred.open = false;
+  return SYM_OK;
 }
 
 int sym_test_fail_staging(sym_ctx* c, int32_t count) {
@@ -851,15 +1015,17 @@ int sym_test_fail_staging(sym_ctx* c, int32_t count) {
   return SYM_OK;
 }
 
-int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out, void* stream) {
+int sym_kv_read_layer(sym_ctx* c, sym_kv kv, int32_t layer, int64_t start, int32_t n, void* k_out, void* v_out, void* stream) {
   if (!c || !k_out || !v_out || n < 0 || start < 0) return SYM_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   if (c->cfg.device < 0) return fail(c, SYM_EINVAL, "host-only context");
+  if (layer < 0 || layer >= c->n_layers) return fail(c, SYM_EINVAL, "kv_read: no such layer");
   const KvFile* f = c->fs->file_of(kv);
   if (!f) return fail(c, SYM_EBADF, "kv_read: bad handle");
   if (f->waiting) return fail(c, SYM_EBUSY, "kv_read: file is offloaded");
   if (start + n > f->len) return fail(c, SYM_EINVAL, "kv_read: range beyond the file");
   if (n == 0) return SYM_OK;
+  if (int busy = refuse_if_open(c, "kv_read")) return busy;
   if ((int64_t)n + 64 > c->cfg.workspace_bytes / 4) return fail(c, SYM_ENOSPC, "workspace too small");
   const int P = c->cfg.page_tokens;
   int si, rc;
@@ -869,13 +1035,14 @@ int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, vo
     c->stage[si][i] = f->pages[t / P] * P + (int32_t)(t % P);
   }
   hipStream_t st = (hipStream_t)stream;
-  GatherArgs ga{(const uint8_t*)c->cfg.pool, c->page_bytes, c->stage[si], n, c->cfg.n_kv_heads};
+  GatherArgs ga{pool_of(c, layer), c->page_bytes, c->stage[si], n, c->cfg.n_kv_heads};
   hipError_t e = launch_gather(ga, k_out, v_out, st);
   if (e != hipSuccess) return fail_hip(c, e, "gather launch");
-  e = hipEventRecord(c->stage_ev[si], st);
-  if (e != hipSuccess) return fail_hip(c, e, "hipEventRecord(stage)");
-  c->stage_pending[si] = true;
-  return SYM_OK;
+  return stage_release(c, si, st);
+}
+
+int sym_kv_read(sym_ctx* c, sym_kv kv, int64_t start, int32_t n, void* k_out, void* v_out, void* stream) {
+  return sym_kv_read_layer(c, kv, 0, start, n, k_out, v_out, stream);
 }
 
 sym_sched* sym_sched_create(int32_t max_batch, double max_wait_us, double weight, double a_us, double c_us) {

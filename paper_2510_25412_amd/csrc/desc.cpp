@@ -172,9 +172,21 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       total_units += ((vis_last + P - 1) / P - share_start[b]) * H;
     }
   }
+  // bins (whole ranges per workgroup, pieces combined through LDS) for the vector-unit kernel; the global
+  // cut for the matrix-core decode kernel, which rows of several tokens need
+  const bool bins = prm.bin_waves > 0 && max_nt == 1 && total_units > 0;
+  // a bin is a workgroup: eight wavefronts, or four when the launch has tiles of 128 query rows (four-wavefront workgroups)
+  const int32_t W = !bins ? 0 : n_tiles > 0 ? (TQ * G != 256 ? 4 : 8) : (prm.bin_waves == 4 ? 4 : 8);
+  const int64_t max_bins = std::max<int64_t>(1, prm.max_waves / std::max(W, 1));
   int64_t nw = (total_units + prm.min_units_per_wave - 1) / prm.min_units_per_wave;
   nw = std::max<int64_t>(1, std::min<int64_t>(nw, prm.max_waves));
   if (total_units == 0) nw = 0;
+  int64_t n_bins = 0;
+  if (bins) {
+    n_bins = (total_units + (int64_t)prm.min_units_per_wave * W - 1) / ((int64_t)prm.min_units_per_wave * W);
+    n_bins = std::max<int64_t>(1, std::min<int64_t>(n_bins, max_bins));
+    nw = n_bins * W;
+  }
   const int64_t n_members = (int64_t)member_rows.size();
 
   // A member of a shared-prefix group reads only the pages after the common ones; those are read by
@@ -190,16 +202,182 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   for (int32_t b = 0; b < n_lips; ++b)
     if (!full_table[b]) entries -= share_start[b];
 
+  // ---- rows, planned before the allocation (the bins are made of them)
+  std::vector<int32_t>& rows_tmp = out->rows_tmp;
+  rows_tmp.resize((size_t)n_rows * ROW_WORDS);
+  out->fused.assign((size_t)n_lips, 0);
+  int32_t n_fused = 0;
+  {
+    int64_t r = 0, e = 0, tok = 0;
+    for (int32_t b = 0; b < n_lips; ++b) {
+      const int64_t skip = full_table[b] ? 0 : share_start[b];
+      const int64_t e_lip = e - skip;
+      e += (len_after[b] + P - 1) / P - skip;
+      if (!is_prefill(b)) {
+        for (int32_t i = 0; i < n_tokens[b]; i += RT, ++r) {
+          const int32_t nt = std::min(RT, n_tokens[b] - i);
+          rows_tmp[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
+          rows_tmp[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // tokens the row's first token sees
+          rows_tmp[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row of its first token
+          rows_tmp[r * ROW_WORDS + 3] = share_start[b] | ((nt - 1) << ROW_NT_SHIFT);      // first page of the row's own range; tokens - 1
+        }
+        // the attention kernel can append a LIP's token itself when it is the LIP's only one (nobody else reads it in this launch)
+        if (bins && prm.fuse_append && n_tokens[b] == 1) {
+          out->fused[b] = 1;
+          ++n_fused;
+        }
+      }
+      tok += n_tokens[b];
+    }
+  }
+  out->row_lip.clear();
+  if (bins && n_fused > 0) {
+    out->row_lip.reserve((size_t)n_rows);
+    for (int32_t b = 0; b < n_lips; ++b)
+      if (!is_prefill(b))
+        for (int32_t i = 0; i < n_tokens[b]; i += RT) out->row_lip.push_back(b);
+  }
+  auto trow_nt = [&](int64_t rr) { return (rows_tmp[rr * ROW_WORDS + 3] >> ROW_NT_SHIFT) + 1; };
+  auto trow_pages = [&](int64_t rr) { return (rows_tmp[rr * ROW_WORDS + 1] + trow_nt(rr) - 1 + P - 1) / P; };   // pages its last token sees
+  auto trow_first = [&](int64_t rr) { return rows_tmp[rr * ROW_WORDS + 3] & ROW_PAGE_MASK; };
+
+  // ---- bins: segments (whole ranges, or pieces of ranges too long for a bin), handed to the bins longest first
+  std::vector<int32_t>& seg_tmp = out->seg_tmp;          // SEG_WORDS per segment, in (row, head, page) order
+  std::vector<int32_t>& item_bin = out->item_bin;        // bin of every segment
+  int64_t n_segs = 0, n_split_partials = 0, n_split_merge = 0;
+  const int64_t alpha = prm.range_cost;
+  if (bins) {
+    const int64_t total_cost = total_units + alpha * n_rows * H;
+    auto& order = out->item_order;
+    auto& heap = out->bin_heap;
+    auto emit = [&](int64_t row, int32_t g, int32_t pb, int32_t pe, int32_t np, int32_t dest, int32_t bin) {
+      const int32_t rec[SEG_WORDS] = {rows_tmp[row * ROW_WORDS + 0], g, pb, pe, rows_tmp[row * ROW_WORDS + 1], rows_tmp[row * ROW_WORDS + 2] * prm.n_q_heads + g * G, dest,
+                                      (pe == np && !out->row_lip.empty() && out->fused[out->row_lip[row]]) ? (rows_tmp[row * ROW_WORDS + 1] - 1) % P : -1};
+      seg_tmp.insert(seg_tmp.end(), rec, rec + SEG_WORDS);
+      item_bin.push_back(bin);
+    };
+    // Plan A, when there are several ranges per bin (short files, the members of forked prefixes): whole ranges, handed to
+    // the bins longest first; nothing is split, so no range leaves partials in device memory because of the bins.
+    bool planned = false;
+    if (n_rows * H >= 3 * n_bins) {
+      seg_tmp.clear();
+      item_bin.clear();
+      n_split_partials = n_split_merge = 0;
+      for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t np = trow_pages(row), p0 = trow_first(row);
+        for (int32_t g = 0; g < H; ++g) {
+          emit(row, g, p0, np, np, p0 > 0 ? (int32_t)n_split_partials : -1, 0);        // the members of a shared prefix always leave partials
+          if (p0 > 0) {
+            ++n_split_partials;
+            ++n_split_merge;
+          }
+        }
+      }
+      n_segs = (int64_t)seg_tmp.size() / SEG_WORDS;
+      // longest first by counting sort on the page count (rows come in, the H ranges of a row are equal)
+      int32_t longest = 0;
+      for (int64_t row = 0; row < n_rows; ++row) longest = std::max(longest, trow_pages(row) - trow_first(row));
+      order.assign((size_t)longest + 2, 0);                    // order[c] = rows with more than c pages, after the prefix sum
+      for (int64_t row = 0; row < n_rows; ++row) ++order[longest - (trow_pages(row) - trow_first(row)) + 1];
+      for (int32_t c = 0; c <= longest; ++c) order[c + 1] += order[c];
+      auto& sorted = out->tile_tmp;                            // rows, longest first (scratch that the tile list reuses later)
+      sorted.resize((size_t)n_rows);
+      for (int64_t row = 0; row < n_rows; ++row) sorted[order[longest - (trow_pages(row) - trow_first(row))]++] = (int32_t)row;
+      heap.clear();
+      for (int64_t b = 0; b < n_bins; ++b) heap.emplace_back(0, (int32_t)b);
+      auto worse = [](const std::pair<int64_t, int32_t>& x, const std::pair<int64_t, int32_t>& y) { return x > y; };   // min-heap on (load, bin)
+      int64_t worst = 0;
+      for (int32_t row : sorted) {
+        const int64_t c = trow_pages(row) - trow_first(row) + alpha;
+        for (int32_t g = 0; g < H; ++g) {
+          std::pop_heap(heap.begin(), heap.end(), worse);
+          heap.back().first += c;
+          item_bin[(size_t)row * H + g] = heap.back().second;
+          worst = std::max(worst, heap.back().first);
+          std::push_heap(heap.begin(), heap.end(), worse);
+        }
+      }
+      planned = worst * n_bins * 100 <= total_cost * (100 + prm.bin_tolerance);
+    }
+    // Plan B: the units in (row, head, page) order are cut into n_bins * W contiguous ranges of equal cost, one per wavefront,
+    // exactly like the global cut (on a virtual axis where every range occupies range_cost + pages, wavefront k starts at
+    // total * k / (n_bins * W); a start inside the overhead part of a range snaps to its first page), and every W consecutive
+    // wavefronts are a bin.  A range that a BIN boundary divides becomes one segment per part, each leaving a partial in
+    // device memory (at most n_bins - 1 ranges); what the wavefront boundaries inside a bin divide is combined through LDS.
+    out->wave_pos.clear();
+    if (!planned && n_bins > 1) {
+      seg_tmp.clear();
+      item_bin.clear();
+      n_split_partials = n_split_merge = 0;
+      auto& wpos = out->wave_pos;                        // (segment, page) where every wavefront starts
+      wpos.reserve((size_t)nw * 2);
+      int64_t k = 0, vstart = 0;
+      int32_t bin = 0;
+      for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t np = trow_pages(row), p0 = trow_first(row);
+        for (int32_t g = 0; g < H; ++g) {
+          const int64_t vend = vstart + alpha + (np - p0);
+          const size_t first_seg = seg_tmp.size() / SEG_WORDS;
+          int32_t pb = p0;
+          for (; k < nw && total_cost * k / nw < vend; ++k) {
+            const int32_t at = p0 + (int32_t)std::max<int64_t>(0, total_cost * k / nw - vstart - alpha);
+            if (k % W == 0) {                            // a bin begins here
+              if (at > pb) {
+                emit(row, g, pb, at, np, 0, bin);
+                pb = at;
+              }
+              bin = (int32_t)(k / W);
+            }
+            wpos.push_back((int32_t)(seg_tmp.size() / SEG_WORDS));      // the segment that is emitted next holds page `at`
+            wpos.push_back(at);
+          }
+          emit(row, g, pb, np, np, 0, bin);
+          const size_t n_here = seg_tmp.size() / SEG_WORDS - first_seg;
+          const bool partial = n_here > 1 || p0 > 0;
+          for (size_t i = 0; i < n_here; ++i) seg_tmp[(first_seg + i) * SEG_WORDS + S_DEST] = partial ? (int32_t)(n_split_partials + i) : -1;
+          if (partial) {
+            n_split_partials += (int64_t)n_here;
+            ++n_split_merge;
+          }
+          vstart = vend;
+        }
+      }
+      n_segs = (int64_t)seg_tmp.size() / SEG_WORDS;
+      planned = true;
+    }
+    // One bin (a small batch): every range is a segment of it, cut between its wavefronts only.
+    if (!planned) {
+      seg_tmp.clear();
+      item_bin.clear();
+      n_split_partials = n_split_merge = 0;
+      for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t np = trow_pages(row), p0 = trow_first(row);
+        for (int32_t g = 0; g < H; ++g) {
+          emit(row, g, p0, np, np, p0 > 0 ? (int32_t)n_split_partials : -1, 0);
+          if (p0 > 0) {
+            ++n_split_partials;
+            ++n_split_merge;
+          }
+        }
+      }
+      n_segs = (int64_t)seg_tmp.size() / SEG_WORDS;
+    }
+  }
+
   const int64_t off_rows = DESC_HEADER_WORDS;
   const int64_t off_waves = off_rows + n_rows * ROW_WORDS;
   const int64_t off_merge = off_waves + nw * WAVE_WORDS;
   // a merge entry per token of a cut (row, head) (at most one cut per wave boundary) and per (member row, head)
-  // (a cut (row, head) has a wave boundary inside it, and there are no more of them than (row, head)s)
-  const int64_t off_pt = off_merge + (std::min<int64_t>(nw, n_rows * H) * max_nt + n_members * H) * MERGE_WORDS;
+  // (a cut (row, head) has a wave boundary inside it, and there are no more of them than (row, head)s);
+  // with bins: one per (row, head) that is split between bins or belongs to a shared prefix
+  const int64_t merge_cap = bins ? n_split_merge : std::min<int64_t>(nw, n_rows * H) * max_nt + n_members * H;
+  const int64_t off_pt = off_merge + merge_cap * MERGE_WORDS;
   const int64_t off_ptoff = off_pt + entries;
   const int64_t off_tiles = off_ptoff + n_lips + 1;
   const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
-  const int64_t total = off_members + n_members;
+  const int64_t off_segs = off_members + n_members;
+  const int64_t off_lmerge = off_segs + (bins ? (n_segs + 2) * SEG_WORDS : 0);       // two spare records: the kernel looks ahead
+  const int64_t total = off_lmerge + (bins ? n_bins * LMERGE_WORDS : 0);
   if (total > 0x7fffffff) return SYM_EINVAL;
   int32_t* const w = out->alloc ? out->alloc(total) : nullptr;   // the caller's buffer (pinned staging memory on the GPU path)
   if (!w) return SYM_ENOSPC;
@@ -212,7 +390,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   int32_t* pt = w + off_pt;
   int32_t* ptoff = w + off_ptoff;
   int32_t* tiles = w + off_tiles;
-  int64_t r = 0, e = 0, tok = 0, ti = 0;
+  int64_t e = 0, tok = 0, ti = 0;
   for (int32_t b = 0; b < n_lips; ++b) {
     const int64_t skip = full_table[b] ? 0 : share_start[b];      // leading pages left out (see above)
     const int64_t e_lip = e - skip;
@@ -234,18 +412,11 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
           t[T_AUX] = t0;                                            // token offset inside the chunk
           t[T_KIND] = TILE_PREFILL;
         }
-    } else {
-      for (int32_t i = 0; i < n_tokens[b]; i += RT, ++r) {
-        const int32_t nt = std::min(RT, n_tokens[b] - i);
-        rows[r * ROW_WORDS + 0] = (int32_t)e_lip;                                    // page-table offset
-        rows[r * ROW_WORDS + 1] = (int32_t)(len_after[b] - n_tokens[b] + i + 1);   // tokens the row's first token sees
-        rows[r * ROW_WORDS + 2] = (int32_t)(tok + i);                               // q / out row of its first token
-        rows[r * ROW_WORDS + 3] = share_start[b] | ((nt - 1) << ROW_NT_SHIFT);      // first page of the row's own range; tokens - 1
-      }
     }
     tok += n_tokens[b];
   }
   ptoff[n_lips] = (int32_t)e;
+  if (n_rows > 0) std::memcpy(rows, rows_tmp.data(), (size_t)n_rows * ROW_WORDS * sizeof(int32_t));
 
   // ---- cut the unit sequence into nw ranges of equal cost; number the partial results.
   // Cost of a range = its units + range_cost per (row, head) it starts in (the end-of-range
@@ -257,70 +428,173 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   auto row_nt = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 3] >> ROW_NT_SHIFT) + 1; };
   auto row_pages = [&](int64_t rr) { return (rows[rr * ROW_WORDS + 1] + row_nt(rr) - 1 + P - 1) / P; };   // pages its last token sees
   auto row_first = [&](int64_t rr) { return rows[rr * ROW_WORDS + 3] & ROW_PAGE_MASK; };
-  const int64_t alpha = prm.range_cost;
-  const int64_t vtotal = total_units + alpha * n_rows * H;
-  {
-    int64_t k = 0, vstart = 0;     // next boundary to place; virtual start of the current (row, head)
-    for (int64_t row = 0; row < n_rows && k < nw; ++row) {
-      const int32_t np = row_pages(row), p0 = row_first(row);
-      for (int32_t g = 0; g < H && k < nw; ++g) {
-        const int64_t vend = vstart + alpha + (np - p0);
-        while (k < nw && vtotal * k / nw < vend) {
-          const int64_t o = vtotal * k / nw - vstart;
-          int32_t* ww = waves + k * WAVE_WORDS;
-          ww[0] = (int32_t)row;
-          ww[1] = g;
-          ww[2] = p0 + (int32_t)std::max<int64_t>(0, o - alpha);
+  int32_t part = 0;
+  int32_t n_merge = 0;        // (row, head) ranges that need a merge
+  if (bins) {
+    // ---- bins: segment list bin by bin, wave records, in-bin merge lists, merge entries of split ranges
+    int32_t* segs = w + off_segs;
+    int32_t* lmerge = w + off_lmerge;
+    std::memset(lmerge, 0, (size_t)n_bins * LMERGE_WORDS * sizeof(int32_t));
+    auto& first = out->bin_first;                         // first segment of every bin in the final order
+    first.assign((size_t)n_bins + 1, 0);
+    for (int64_t i = 0; i < n_segs; ++i) ++first[item_bin[i] + 1];
+    for (int64_t b = 0; b < n_bins; ++b) first[b + 1] += first[b];
+    auto& pos = out->item_order;                          // reused: next free place of every bin
+    pos.assign(first.begin(), first.end() - 1);
+    for (int64_t i = 0; i < n_segs; ++i)                  // (row, head, page) order is kept inside a bin
+      std::memcpy(segs + (int64_t)pos[item_bin[i]]++ * SEG_WORDS, seg_tmp.data() + i * SEG_WORDS, SEG_WORDS * sizeof(int32_t));
+    std::memset(segs + n_segs * SEG_WORDS, 0, 2 * SEG_WORDS * sizeof(int32_t));
+    // merge entries of the ranges that leave partials, in (row, head) order = the order of their partial numbers
+    for (int64_t i = 0; i < n_segs; ++i) {
+      const int32_t* sg = seg_tmp.data() + i * SEG_WORDS;
+      if (sg[S_DEST] < 0) continue;
+      const bool first_piece = i == 0 || sg[-SEG_WORDS + S_DEST] < 0 || sg[-SEG_WORDS + S_QROW] != sg[S_QROW];
+      if (first_piece) {
+        int32_t* it = merge + (int64_t)n_merge++ * MERGE_WORDS;
+        std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
+        it[0] = sg[S_DEST];
+        it[2] = sg[S_QROW];
+        it[6] = 1;
+      }
+      ++merge[(int64_t)(n_merge - 1) * MERGE_WORDS + 1];
+    }
+    part = (int32_t)n_split_partials;
+    // Inside a bin the wavefronts cut the bin's segments like the global cut does the batch: on a virtual axis where every
+    // segment occupies range_cost + pages, wavefront k of the Wb that get work starts at total * k / Wb (snapped to the
+    // segment's first page inside the overhead part).  Wb <= pages of the bin, so no two cuts fall on one page and the
+    // pieces of a cut segment lie in consecutive wavefronts.  A piece that is not its whole segment goes to an LDS slot:
+    // 2 * wavefront for a wavefront's first piece, 2 * wavefront + 1 for its last; the list of cut segments (segment,
+    // slot of the first piece, its wavefront, pieces) tells the workgroup what to combine when all are done.
+    for (int64_t b = 0; b < n_bins; ++b) {
+      const int64_t s0 = first[b], s1 = first[b + 1];
+      int64_t pages = 0;
+      for (int64_t i = s0; i < s1; ++i) pages += segs[i * SEG_WORDS + S_PE] - segs[i * SEG_WORDS + S_PB];
+      const int64_t vt = pages + alpha * (s1 - s0);
+      const int64_t Wb = out->wave_pos.empty() ? std::min<int64_t>(W, pages) : W;
+      int32_t* bw = waves + b * W * WAVE_WORDS;
+      std::memset(bw, 0, (size_t)W * WAVE_WORDS * sizeof(int32_t));
+      int32_t* lm = lmerge + b * LMERGE_WORDS;
+      lm[1] = (int32_t)s0;                              // the bin's segments (the kernel walks them for the appends that ride along)
+      lm[2] = (int32_t)s1;
+      int64_t k = 0, vstart = 0;
+      if (!out->wave_pos.empty()) {                     // the wavefronts' starts come from the cut of the whole batch
+        for (; k < W; ++k) {
+          bw[k * WAVE_WORDS + 0] = out->wave_pos[(size_t)(b * W + k) * 2];
+          bw[k * WAVE_WORDS + 1] = out->wave_pos[(size_t)(b * W + k) * 2 + 1];
+        }
+      }
+      for (int64_t i = s0; i < s1 && k < Wb; ++i) {
+        const int32_t pb = segs[i * SEG_WORDS + S_PB], pe = segs[i * SEG_WORDS + S_PE];
+        const int64_t vend = vstart + alpha + (pe - pb);
+        while (k < Wb && vt * k / Wb < vend) {
+          const int64_t o = vt * k / Wb - vstart;
+          int32_t* ww = bw + k * WAVE_WORDS;
+          ww[0] = (int32_t)i;
+          ww[1] = pb + (int32_t)std::max<int64_t>(0, o - alpha);
           ++k;
         }
         vstart = vend;
       }
-    }
-  }
-  int32_t part = 0;
-  int32_t n_merge = 0;        // (row, head) ranges that need a merge
-  for (int64_t k = 0; k < nw; ++k) {
-    int32_t* ww = waves + k * WAVE_WORDS;
-    int64_t row = ww[0];
-    int32_t g = ww[1], p = ww[2];
-    // the range ends where the next one starts (or at the end of the batch)
-    const int64_t erow = k + 1 < nw ? ww[WAVE_WORDS + 0] : n_rows;
-    const int32_t eg = k + 1 < nw ? ww[WAVE_WORDS + 1] : 0, ep = k + 1 < nw ? ww[WAVE_WORDS + 2] : 0;
-    ww[4] = part;
-    {                                   // ids of the first pages: their loads need no table lookup
-      const int32_t np0 = row_pages(row);
-      const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
-      for (int i = 0; i < 3; ++i) ww[5 + i] = t0[std::min(p + i, np0 - 1)];
-    }
-    int64_t units = 0;
-    while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
-      const int32_t np = row_pages(row), p0 = row_first(row);
-      const int32_t cnt = (row == erow && g == eg) ? ep - p : np - p;
-      if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
-        const int32_t nt = row_nt(row);                        // a piece leaves one partial per token of the row
-        if (p == p0) {                                         // first piece of this (row, g)
-          for (int32_t t = 0; t < nt; ++t, ++n_merge) {
-            int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
-            std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
-            it[0] = part + t;
-            it[2] = (rows[row * ROW_WORDS + 2] + t) * prm.n_q_heads + g * G;
-            it[6] = nt;                                        // distance between the token's pieces
+      for (int64_t kk = 0; kk < Wb; ++kk) {
+        int32_t* ww = bw + kk * WAVE_WORDS;
+        int64_t i = ww[0];
+        int32_t p = ww[1];
+        const int64_t ei = kk + 1 < Wb ? ww[WAVE_WORDS + 0] : s1;
+        const int32_t ep = kk + 1 < Wb ? ww[WAVE_WORDS + 1] : 0;
+        {                                   // ids of the first pages: their loads need no table lookup
+          const int32_t* sg = segs + i * SEG_WORDS;
+          for (int t = 0; t < 3; ++t) ww[4 + t] = pt[sg[S_TBL] + std::min(p + t, sg[S_PE] - 1)];
+        }
+        int64_t units = 0;
+        int32_t piece = 0;
+        while (i < s1) {
+          const int32_t* sg = segs + i * SEG_WORDS;
+          const int32_t end = (i == ei) ? ep : sg[S_PE];      // the next wavefront may start inside this segment
+          if (end > p) {
+            if (!(p == sg[S_PB] && end == sg[S_PE])) {        // a piece of a cut segment
+              if (p == sg[S_PB]) {                             // its first piece: a new entry
+                int32_t* en = lm + 4 + 4 * lm[0]++;
+                en[0] = (int32_t)i;
+                en[1] = (int32_t)(piece == 0 ? 2 * kk : 2 * kk + 1);
+                en[2] = (int32_t)kk;
+                en[3] = 0;
+              }
+              ++lm[4 + 4 * (lm[0] - 1) + 3];
+            }
+            units += end - p;
+            ++piece;
           }
+          if (i == ei) break;
+          ++i;
+          p = i < s1 ? segs[i * SEG_WORDS + S_PB] : 0;
         }
-        for (int32_t t = 0; t < nt; ++t) ++merge[(int64_t)(n_merge - 1 - t) * MERGE_WORDS + 1];
-        part += nt;
-      }
-      units += cnt;
-      p += cnt;
-      if (p == np) {
-        if (++g == H) {
-          g = 0;
-          ++row;
-        }
-        p = row < n_rows ? row_first(row) : 0;
+        ww[2] = (int32_t)units;
       }
     }
-    ww[3] = (int32_t)units;
+  } else {
+    const int64_t vtotal = total_units + alpha * n_rows * H;
+    {
+      int64_t k = 0, vstart = 0;     // next boundary to place; virtual start of the current (row, head)
+      for (int64_t row = 0; row < n_rows && k < nw; ++row) {
+        const int32_t np = row_pages(row), p0 = row_first(row);
+        for (int32_t g = 0; g < H && k < nw; ++g) {
+          const int64_t vend = vstart + alpha + (np - p0);
+          while (k < nw && vtotal * k / nw < vend) {
+            const int64_t o = vtotal * k / nw - vstart;
+            int32_t* ww = waves + k * WAVE_WORDS;
+            ww[0] = (int32_t)row;
+            ww[1] = g;
+            ww[2] = p0 + (int32_t)std::max<int64_t>(0, o - alpha);
+            ++k;
+          }
+          vstart = vend;
+        }
+      }
+    }
+    for (int64_t k = 0; k < nw; ++k) {
+      int32_t* ww = waves + k * WAVE_WORDS;
+      int64_t row = ww[0];
+      int32_t g = ww[1], p = ww[2];
+      // the range ends where the next one starts (or at the end of the batch)
+      const int64_t erow = k + 1 < nw ? ww[WAVE_WORDS + 0] : n_rows;
+      const int32_t eg = k + 1 < nw ? ww[WAVE_WORDS + 1] : 0, ep = k + 1 < nw ? ww[WAVE_WORDS + 2] : 0;
+      ww[4] = part;
+      {                                   // ids of the first pages: their loads need no table lookup
+        const int32_t np0 = row_pages(row);
+        const int32_t* t0 = pt + rows[row * ROW_WORDS + 0];
+        for (int i = 0; i < 3; ++i) ww[5 + i] = t0[std::min(p + i, np0 - 1)];
+      }
+      int64_t units = 0;
+      while (row < erow || (row == erow && (g < eg || (g == eg && p < ep)))) {
+        const int32_t np = row_pages(row), p0 = row_first(row);
+        const int32_t cnt = (row == erow && g == eg) ? ep - p : np - p;
+        if (!(p == 0 && cnt == np)) {                            // a whole (row, g) needs no partial
+          const int32_t nt = row_nt(row);                        // a piece leaves one partial per token of the row
+          if (p == p0) {                                         // first piece of this (row, g)
+            for (int32_t t = 0; t < nt; ++t, ++n_merge) {
+              int32_t* it = merge + (int64_t)n_merge * MERGE_WORDS;
+              std::memset(it, 0, MERGE_WORDS * sizeof(int32_t));
+              it[0] = part + t;
+              it[2] = (rows[row * ROW_WORDS + 2] + t) * prm.n_q_heads + g * G;
+              it[6] = nt;                                        // distance between the token's pieces
+            }
+          }
+          for (int32_t t = 0; t < nt; ++t) ++merge[(int64_t)(n_merge - 1 - t) * MERGE_WORDS + 1];
+          part += nt;
+        }
+        units += cnt;
+        p += cnt;
+        if (p == np) {
+          if (++g == H) {
+            g = 0;
+            ++row;
+          }
+          p = row < n_rows ? row_first(row) : 0;
+        }
+      }
+      ww[3] = (int32_t)units;
+    }
+
   }
 
   // ---- shared-prefix tiles and the extra partials of their members' merge entries
@@ -448,6 +722,15 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   w[H_TOTAL_WORDS] = (int32_t)total;
   w[H_TOTAL_UNITS_LO] = (int32_t)(total_units & 0xffffffff);
   w[H_TOTAL_UNITS_HI] = (int32_t)(total_units >> 32);
+  w[H_N_SEGS] = (int32_t)(bins ? n_segs : 0);
+  w[H_OFF_SEGS] = (int32_t)off_segs;
+  w[H_N_BINS] = (int32_t)n_bins;
+  w[H_BIN_WAVES] = W;
+  w[H_OFF_LMERGE] = (int32_t)off_lmerge;
+  out->n_bins = (int32_t)n_bins;
+  out->bin_waves = W;
+  out->n_segs = (int32_t)(bins ? n_segs : 0);
+  out->n_fused = n_fused;
   out->n_rows = (int32_t)n_rows;
   out->n_waves = (int32_t)nw;
   out->n_partials = n_partials;

@@ -90,105 +90,191 @@ struct PageRegs {
 // combined once, when a (row, kv head) range ends; a range that is only part of its (row, kv
 // head) leaves a partial result for the merge kernel.
 // ---------------------------------------------------------------------------------------
-// decode_stream (below) is the one-wavefront-per-range form.  decode_ranges is the form for 8
+// decode_bins (below) is the form for up to 4 query heads per kv head.  decode_ranges is the form for 8
 // heads per kv head on the vector units (whose 8 x 16 accumulators do not fit one wavefront's
 // registers twice per SIMD): GT = query heads per kv head, G = GT / 2 = heads per wavefront, a
 // workgroup of TWO wavefronts per range; wavefront 0 fetches the K half of every page,
 // wavefront 1 the V half, they exchange them through LDS (written and read in the same
 // lane-linear 1 KiB runs, so without bank conflicts), and every page is still read from HBM once.
 // ---------------------------------------------------------------------------------------
-// Decode ranges as ONE page stream per wavefront (the VALU kernel for up to 4 query heads per kv
-// head).  A wavefront's units (row, kv head, page) are consecutive in the batch order, but they
-// belong to several (row, head) ranges when files are short; starting every range with its own
-// chain of dependent loads (row record -> page ids -> K/V) costs several memory latencies per
-// range, a third of the time at 10 pages per range.  Here a LOAD cursor runs two pages ahead of
-// the COMPUTE cursor through the same unit sequence, across range boundaries, so the K/V stream
-// never drains; the query rows of the next range are fetched one range ahead.  At a boundary the
-// compute side only combines its 8 token slots, writes the result and switches to the next
-// range's registers.
+// Decode ranges in bins (the VALU kernel for up to 4 query heads per kv head).  A workgroup of W
+// wavefronts is a bin: the host hands it a list of segments (whole (row, kv head) ranges, or pieces of
+// ranges too long for one bin) and cuts that list into W contiguous parts of equal cost, one per
+// wavefront.  A wavefront walks its part as ONE page stream: a LOAD cursor runs two pages ahead of the
+// COMPUTE cursor through the same unit sequence, across segment boundaries (starting every segment
+// with its own chain of dependent loads, segment record -> page ids -> K/V, would cost several memory
+// latencies per segment, a third of the time at 10 pages per range), so the K/V stream never drains;
+// the query rows of the next segment are fetched one segment ahead.  At a boundary the compute side only
+// combines its 8 token slots, hands the result on and switches to the next segment's registers.
+// Where a result goes: a piece that is its whole segment writes the segment's destination (the final
+// output rows, or a partial slot in device memory when the segment is only part of its range or the row has a
+// shared prefix); a piece of a segment that the bin's cut divided goes to an LDS slot, and when all
+// wavefronts of the bin are done they combine those pieces (merge_bin_pieces) into the destination.
+// The append of a row's new token can ride along (segment word S_APPEND): the wavefront that reads
+// the row's last page replaces the token's slot in its registers with the rows of k_new / v_new and
+// writes them into the pool afterwards; nobody else reads that page in this launch.
 // ---------------------------------------------------------------------------------------
 template <typename E, int G>
-__device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int block, const int wpb) {
+struct BinLds {
+  static constexpr int kAcc = G * 16 * E::kDimsPerChunk;      // accumulator floats of a piece: G heads x D dims
+  static constexpr int kSlot = kAcc + 2 * G;                   // + (max, sum) per head
+};
+
+// After the barrier: wavefront `wib` of the bin combines the pieces of cut segments wib, wib + W, ... of the bin's list.
+// Lane owns accumulator entries e * 64 + lane of the G * D values (head = entry / D).
+template <typename E, int G>
+__device__ __forceinline__ void merge_bin_pieces(const DecodeArgs& a, const int bin, const int W, const int wib, const float* lds) {
+  constexpr int D = 16 * E::kDimsPerChunk, VL = G * D / 64, SLOT = BinLds<E, G>::kSlot, ACC = BinLds<E, G>::kAcc;
+  const int lane = threadIdx.x & 63;
+  const int32_t* lm = a.lmerge + (int64_t)bin * 32;
+  const int cnt = __builtin_amdgcn_readfirstlane(lm[0]);
+  for (int k = wib; k < cnt; k += W) {
+    const int seg = __builtin_amdgcn_readfirstlane(lm[4 + 4 * k + 0]);
+    const int s0 = __builtin_amdgcn_readfirstlane(lm[4 + 4 * k + 1]);
+    const int w0 = __builtin_amdgcn_readfirstlane(lm[4 + 4 * k + 2]);
+    const int n = __builtin_amdgcn_readfirstlane(lm[4 + 4 * k + 3]);
+    const int32_t* sr = a.segs + (int64_t)seg * 8;
+    const int qh = __builtin_amdgcn_readfirstlane(sr[5]);        // q row * Hq + first query head
+    const int dest = __builtin_amdgcn_readfirstlane(sr[6]);
+    float M[G], ls[G], o[VL];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      M[h] = -__builtin_inff();
+      ls[h] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < VL; ++e) o[e] = 0.f;
+    for (int i = 0; i < n; ++i) {
+      const float* sl = lds + (int64_t)(i == 0 ? s0 : 2 * (w0 + i)) * SLOT;
+      float sc[G], wt[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float mi = sl[ACC + 2 * h], li = sl[ACC + 2 * h + 1];
+        const float mn = fmaxf(M[h], mi);
+        sc[h] = __builtin_amdgcn_exp2f(M[h] - mn);      // 0 for the first piece (M = -inf)
+        wt[h] = __builtin_amdgcn_exp2f(mi - mn);
+        ls[h] = ls[h] * sc[h] + li * wt[h];
+        M[h] = mn;
+      }
+#pragma unroll
+      for (int e = 0; e < VL; ++e) o[e] = o[e] * sc[(e * 64) / D] + sl[e * 64 + lane] * wt[(e * 64) / D];
+    }
+    if (dest < 0) {
+      float* out = a.out + (int64_t)qh * D;
+#pragma unroll
+      for (int e = 0; e < VL; ++e) out[e * 64 + lane] = o[e] / ls[(e * 64) / D];
+    } else {
+      float* pa = a.part_acc + (int64_t)dest * G * D;
+#pragma unroll
+      for (int e = 0; e < VL; ++e) pa[e * 64 + lane] = o[e];
+      if (lane < G) {
+        float mm = M[0], ll = ls[0];
+#pragma unroll
+        for (int hh = 1; hh < G; ++hh) {
+          mm = (lane == hh) ? M[hh] : mm;
+          ll = (lane == hh) ? ls[hh] : ll;
+        }
+        a.part_ml[((int64_t)dest * G + lane) * 2 + 0] = mm;
+        a.part_ml[((int64_t)dest * G + lane) * 2 + 1] = ll;
+      }
+    }
+  }
+}
+
+template <typename E, int G>
+__device__ __forceinline__ void decode_bins(const DecodeArgs& a, const int bin, const int W, float* lds) {
   constexpr int C = E::kDimsPerChunk;    // dims per 16-byte chunk
   constexpr int DPL = 2 * C;             // dims per lane
   constexpr int D = 16 * C;              // head dim
+  constexpr int SLOT = BinLds<E, G>::kSlot, ACC = BinLds<E, G>::kAcc;
+  if (bin >= a.n_bins) return;           // the whole workgroup
   const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(block * wpb + (int)(threadIdx.x >> 6));
-  if (wv >= a.n_waves) return;
+  const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // wavefront within the bin
   const int r = lane >> 3, j = lane & 7;
   auto sload = [&](const int32_t* ptr) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(*ptr); };
+  const int32_t* ww = a.waves + ((int64_t)bin * W + wib) * 8;
+  int remaining = sload(ww + 2);
 
-  const int32_t* ww = a.waves + wv * 8;
-  // compute cursor: the range being accumulated.  The wave record carries the id of the first page, so the first
-  // K/V loads go out while the row record (one more scalar round trip) is still on its way.
-  int row = sload(ww + 0), g = sload(ww + 1), p = sload(ww + 2);
-  int remaining = sload(ww + 3);
-  int part = sload(ww + 4);
-  const int pid_first = sload(ww + 5);
-  const int tbl0 = sload(a.rows + row * 4 + 0);
-  int vis = sload(a.rows + row * 4 + 1), qrow = sload(a.rows + row * 4 + 2);
-  int pstart = sload(a.rows + row * 4 + 3) & 0x0fffffff;
-  int np = (vis + kP - 1) / kP;
+  if (remaining > 0) {
+  // Segment record: [0] page-table offset, [1] kv head, [2] first page, [3] end page (what the load side needs),
+  // [4] tokens the row sees, [5] q row * Hq + first query head, [6] destination, [7] slot of the appended token or -1.
+  // compute cursor: the segment being accumulated.  The wave record carries the id of the first page, so the first
+  // K/V loads go out while the segment record (one more scalar round trip) is still on its way.
+  int seg = sload(ww + 0), p = sload(ww + 1);
+  const int pid_first = sload(ww + 4);
+  const int32_t* sr = a.segs + (int64_t)seg * 8;
+  int pe = sload(sr + 3), vis = sload(sr + 4), qh = sload(sr + 5);
+  int dest = sload(sr + 6), app = sload(sr + 7), tbl = sload(sr + 0);
+  bool from_start = p == sload(sr + 2);                  // the piece begins where its segment begins
   // load cursor: the unit whose K/V is requested next (two pages ahead of the compute cursor)
-  int lrow = row, lg = g, lp = p, lnp = np, ltbl = tbl0, lpstart = pstart, lrem = remaining;
-  // record of the row after the load cursor's (fetched a whole row ahead of its use)
-  int n_tbl = 0, n_vis = 0, n_pstart = 0;
-  auto fetch_next_row = [&](int rr) __attribute__((always_inline)) {      // rr may be one past the last row: the rows section is followed by valid words
-    n_tbl = sload(a.rows + rr * 4 + 0);
-    n_vis = sload(a.rows + rr * 4 + 1);
-    n_pstart = sload(a.rows + rr * 4 + 3) & 0x0fffffff;
+  int lseg = seg, lg = sload(sr + 1), lp = p, lpe = pe, ltbl = sload(sr + 0), lrem = remaining;
+  // record of the segment after the load cursor's (fetched a whole segment ahead of its use; the list ends with spare records)
+  int n_tbl = 0, n_g = 0, n_pb = 0, n_pe = 0;
+  auto fetch_next_seg = [&](int ss) __attribute__((always_inline)) {
+    const int32_t* q4 = a.segs + (int64_t)ss * 8;
+    n_tbl = sload(q4 + 0);
+    n_g = sload(q4 + 1);
+    n_pb = sload(q4 + 2);
+    n_pe = sload(q4 + 3);
   };
-  fetch_next_row(row + 1);
-  // (row, head) after the compute cursor's, for the query prefetch
-  int c_nqrow = 0, c_nvis = 0, c_npstart = 0;      // record of row + 1 as seen by the compute side
+  fetch_next_seg(lseg + 1);
+  // record of segment seg + 1 as the compute side needs it
+  int c_pe = 0, c_vis = 0, c_qh = 0, c_dest = 0, c_app = 0, c_tbl = 0;
+  auto fetch_compute_next_seg = [&]() __attribute__((always_inline)) {
+    const int32_t* q8 = a.segs + (int64_t)(seg + 1) * 8;
+    c_pe = sload(q8 + 3);
+    c_vis = sload(q8 + 4);
+    c_qh = sload(q8 + 5);
+    c_dest = sload(q8 + 6);
+    c_app = sload(q8 + 7);
+    c_tbl = sload(q8 + 0);
+  };
 
   const uint8_t* pool_lane = a.pool + lane * 16;
-  // base address of the next unit to load, and advance the load cursor; past the last unit: page 0, head 0
+  // Requests the K/V of the next unit into R and advances the load cursor; past the last unit: page 0, head 0 (valid
+  // memory that every wavefront touches, never used).
   int next_pid = pid_first;
-  auto next_base = [&]() __attribute__((always_inline)) -> const uint8_t* {
+  auto load_next = [&](PageRegs& R) __attribute__((always_inline)) {
     const bool valid = lrem > 0;
     const uint8_t* base = pool_lane + (int64_t)(valid ? lg : 0) * kSlab + (int64_t)(valid ? next_pid : 0) * a.page_bytes;
     if (valid) {
       --lrem;
-      if (++lp == lnp) {
-        if (++lg == a.Hkv) {
-          lg = 0;
-          ++lrow;
-          ltbl = n_tbl;
-          lnp = (n_vis + kP - 1) / kP;
-          lpstart = n_pstart;
-          fetch_next_row(lrow + 1);
-        }
-        lp = lpstart;
+      if (++lp == lpe) {
+        ++lseg;
+        ltbl = n_tbl;
+        lg = n_g;
+        lp = n_pb;
+        lpe = n_pe;
+        fetch_next_seg(lseg + 1);
       }
       next_pid = lrem > 0 ? sload(a.pt + ltbl + lp) : 0;     // id of the unit after this one, used one page later
     }
-    return base;
-  };
-  auto load_page = [&](PageRegs& R, const uint8_t* base) __attribute__((always_inline)) {
+    // every load is unconditional and off one base address: no control-flow join between a load and its use, so the
+    // waits can be for exactly the older page while the newer one is in flight
 #pragma unroll
     for (int x = 0; x < 4; ++x) R.k[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + x * 1024)));
 #pragma unroll
     for (int x = 0; x < 4; ++x) R.v[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)(base + kBlk + x * 1024)));
   };
 
-  // q chunks of this lane for the G heads of the current range
+  // q chunks of this lane for the G heads of the current segment
   u32x4_t q[G][2];
-  auto load_q = [&](u32x4_t (&dst)[G][2], int qr, int gg) {
+  // The append that rides along: the K and V rows of the row's new token (2 x 256 bytes in k_new / v_new) are requested
+  // with the query rows, one 16-byte chunk per lane (lanes 0..15: K, 16..31: V; the upper half of the wavefront repeats
+  // them), whenever a segment begins: the load is unconditional like every load of the stream (for a segment that appends
+  // nothing the chunk is never used; k_new / v_new then point at the query rows, which are no smaller).
+  u32x4_t nr;
+  auto load_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const uint8_t* qp = (const uint8_t*)a.q + ((int64_t)qr * a.Hq + gg * G + h) * kRowBytes + j * 16;
-      dst[h][0] = *(const u32x4_t*)qp;
-      dst[h][1] = *(const u32x4_t*)(qp + kHalfBytes);
+      const uint8_t* qp = (const uint8_t*)a.q + (int64_t)(qh + h) * kRowBytes + j * 16;
+      q[h][0] = *(const u32x4_t*)qp;
+      q[h][1] = *(const u32x4_t*)(qp + kHalfBytes);
     }
+    nr = *(const u32x4_t*)((const uint8_t*)((lane & 16) ? a.v_new : a.k_new) + (int64_t)(qh / G) * kRowBytes + (lane & 15) * 16);
   };
-  auto fetch_compute_next_row = [&]() __attribute__((always_inline)) {
-    c_nvis = sload(a.rows + (row + 1) * 4 + 1);
-    c_nqrow = sload(a.rows + (row + 1) * 4 + 2);
-    c_npstart = sload(a.rows + (row + 1) * 4 + 3) & 0x0fffffff;
-  };
-  fetch_compute_next_row();
-  load_q(q, qrow, g);
+  fetch_compute_next_seg();
+  load_q();
 
   float m[G], l[G], acc[G][DPL];
   auto reset_state = [&]() __attribute__((always_inline)) {
@@ -201,7 +287,7 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
     }
   };
   reset_state();
-  int p_first = p;                                       // first page of the piece being accumulated
+  int piece = 0;                                         // pieces this wavefront has finished
 
   // tokens of page index pi (absolute, within the row) that exist: the row's last page may be ragged
   auto compute = [&](PageRegs& R, int pi) __attribute__((always_inline)) {
@@ -262,28 +348,27 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
     }
   };
 
-  // End of a piece of a (row, kv head) range: combine the 8 token slots (lanes with equal j).  Per head:
-  // common max M, rescale, total sum.  The G*DPL accumulators are then reduced with a halving exchange
-  // (lane bit 5, 4, 3 in turn: keep one half of the list, send the other), so lane (r, j) ends up owning the
-  // fully reduced values r*V/8 .. r*V/8 + V/8 - 1 of the list.  Then the compute cursor moves on.
+  // End of a piece: combine the 8 token slots (lanes with equal j).  Per head: common max M, rescale, total sum.  The
+  // G*DPL accumulators are then reduced with a halving exchange (lane bit 5, 4, 3 in turn: keep one half of the list,
+  // send the other), so lane (r, j) ends up owning the fully reduced values r*V/8 .. r*V/8 + V/8 - 1 of the list.
+  // Then the compute cursor moves on.
   auto finish_piece = [&]() __attribute__((always_inline)) {
-    const bool whole = (p_first == 0 && p == np);
-    // The range after (row, g): same row, next head; or head 0 of the next row (its record was fetched
-    // when the compute side entered this row).  Its query rows are requested now, so that they arrive
-    // while the exchange below runs (q is not needed any more for this piece).
-    const int64_t out_row = ((int64_t)qrow * a.Hq + g * G) * D;
+    const bool whole = from_start && p == pe;            // the piece is its whole segment
+    const int64_t out_row = (int64_t)qh * D;
+    const int f_dest = dest;
+    // The segment after this one: its query rows are requested now, so that they arrive while the exchange
+    // below runs (q is not needed any more for this piece).
     const bool more = remaining > 0;
     if (more) {
-      if (++g == a.Hkv) {
-        g = 0;
-        ++row;
-        vis = c_nvis;
-        qrow = c_nqrow;
-        pstart = c_npstart;
-        np = (vis + kP - 1) / kP;
-        fetch_compute_next_row();
-      }
-      load_q(q, qrow, g);
+      ++seg;
+      pe = c_pe;
+      vis = c_vis;
+      qh = c_qh;
+      dest = c_dest;
+      app = c_app;
+      tbl = c_tbl;
+      fetch_compute_next_seg();
+      load_q();
     }
     constexpr int V = G * DPL;
     float vals[V];
@@ -323,7 +408,7 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
       }
     }
     // lane (r, j) now holds list entries idx = r * V/8 + t: head idx / DPL, lane-local dim idx % DPL
-    if (whole) {
+    if (whole && f_dest < 0) {
 #pragma unroll
       for (int t = 0; t < V / 8; ++t) {
         const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
@@ -333,46 +418,88 @@ __device__ __forceinline__ void decode_stream(const DecodeArgs& a, const int blo
         a.out[out_row + h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t] / ls;
       }
     } else {
-      float* pa = a.part_acc + (int64_t)part * G * D;
+      // unnormalised accumulator, max and sum: to the segment's partial slot in device memory, or to this wavefront's LDS
+      // slot (two separate stretches of code: one pointer that may be either would make every store a flat store, and
+      // with flat stores outstanding the waits for the K/V loads could no longer count)
+      float mm = Mh[0], ll = lsum[0];
 #pragma unroll
-      for (int t = 0; t < V / 8; ++t) {
-        const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
-        pa[h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t];
+      for (int hh = 1; hh < G; ++hh) {
+        mm = (lane == hh) ? Mh[hh] : mm;
+        ll = (lane == hh) ? lsum[hh] : ll;
       }
-      if (lane < G) {
-        float mm = Mh[0], ll = lsum[0];
+      if (whole) {
+        float* pa = a.part_acc + (int64_t)f_dest * G * D;
 #pragma unroll
-        for (int hh = 1; hh < G; ++hh) {
-          mm = (lane == hh) ? Mh[hh] : mm;
-          ll = (lane == hh) ? lsum[hh] : ll;
+        for (int t = 0; t < V / 8; ++t) {
+          const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+          pa[h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t];
         }
-        a.part_ml[((int64_t)part * G + lane) * 2 + 0] = mm;
-        a.part_ml[((int64_t)part * G + lane) * 2 + 1] = ll;
+        if (lane < G) {
+          a.part_ml[((int64_t)f_dest * G + lane) * 2 + 0] = mm;
+          a.part_ml[((int64_t)f_dest * G + lane) * 2 + 1] = ll;
+        }
+      } else {
+        float* pl = lds + (piece == 0 ? 2 * wib : 2 * wib + 1) * SLOT;
+#pragma unroll
+        for (int t = 0; t < V / 8; ++t) {
+          const int idx = r * (V / 8) + t, h = idx / DPL, dl = idx % DPL;
+          pl[h * D + (dl / C) * (D / 2) + j * C + (dl % C)] = vals[t];
+        }
+        if (lane < G) {
+          pl[ACC + lane * 2 + 0] = mm;
+          pl[ACC + lane * 2 + 1] = ll;
+        }
       }
-      ++part;
     }
-    if (more) {                                          // the next range (the piece ended at its row's last page)
-      p = pstart;
-      p_first = p;
+    ++piece;
+    if (more) {                                          // the next segment (the piece ended with its own)
+      p = sload(a.segs + (int64_t)seg * 8 + 2);
+      from_start = true;
       reset_state();
     }
   };
-  // one unit: accumulate the page, move the compute cursor, close the piece at the end of the range or of the wavefront's work
+  // one unit: accumulate the page, move the compute cursor, close the piece at the end of the segment or of the wavefront's work
   auto do_unit = [&](PageRegs& R) __attribute__((always_inline)) {
+    if (app >= 0 && p + 1 == pe) {
+      // The segment's last page is the row's last page, and its slot `app` is the new token's, still unwritten in the pool:
+      // the lanes that hold that slot take the token's chunks (K row halves from lanes j and 8 + j of `nr`, V from
+      // 16 + j and 24 + j) and write them into the pool, where this wavefront is the page's only reader in this launch.
+      const u32x4_t k0 = {(uint32_t)__shfl((int)nr.x, j), (uint32_t)__shfl((int)nr.y, j), (uint32_t)__shfl((int)nr.z, j), (uint32_t)__shfl((int)nr.w, j)};
+      const u32x4_t k1 = {(uint32_t)__shfl((int)nr.x, 8 + j), (uint32_t)__shfl((int)nr.y, 8 + j), (uint32_t)__shfl((int)nr.z, 8 + j), (uint32_t)__shfl((int)nr.w, 8 + j)};
+      const u32x4_t v0 = {(uint32_t)__shfl((int)nr.x, 16 + j), (uint32_t)__shfl((int)nr.y, 16 + j), (uint32_t)__shfl((int)nr.z, 16 + j), (uint32_t)__shfl((int)nr.w, 16 + j)};
+      const u32x4_t v1 = {(uint32_t)__shfl((int)nr.x, 24 + j), (uint32_t)__shfl((int)nr.y, 24 + j), (uint32_t)__shfl((int)nr.z, 24 + j), (uint32_t)__shfl((int)nr.w, 24 + j)};
+      uint8_t* dst = const_cast<uint8_t*>(a.pool) + (int64_t)sload(a.pt + tbl + p) * a.page_bytes + (int64_t)(qh / G % a.Hkv) * kSlab +
+                     app * kHalfBytes + j * 16;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)                     // (register indices stay compile-time constants)
+        if ((app >> 3) == hf && r == (app & 7)) {
+          R.k[hf] = __builtin_bit_cast(uint4, k0);
+          R.k[2 + hf] = __builtin_bit_cast(uint4, k1);
+          R.v[hf] = __builtin_bit_cast(uint4, v0);
+          R.v[2 + hf] = __builtin_bit_cast(uint4, v1);
+          *(u32x4_t*)dst = k0;
+          *(u32x4_t*)(dst + kP * kHalfBytes) = k1;
+          *(u32x4_t*)(dst + kBlk) = v0;
+          *(u32x4_t*)(dst + kBlk + kP * kHalfBytes) = v1;
+        }
+    }
     compute(R, p);
     ++p;
     --remaining;
-    if (p == np || remaining == 0) finish_piece();
+    if (p == pe || remaining == 0) finish_piece();
   };
 
   PageRegs A, B;
-  load_page(A, next_base());
+  load_next(A);
   while (remaining > 0) {
-    load_page(B, next_base());
+    load_next(B);
     do_unit(A);
-    load_page(A, next_base());
+    load_next(A);
     if (remaining > 0) do_unit(B);
   }
+  }
+  __syncthreads();                                       // every piece of the bin is in LDS (or went straight to its destination)
+  merge_bin_pieces<E, G>(a, bin, W, wib, lds);
 }
 
 template <typename E, int GT, int G>
@@ -1354,16 +1481,27 @@ __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, Pr
   const uint64_t gs = (uint64_t)((tile_groups + 1) / 2) + (uint64_t)decode_groups;     // groups of the mixed stretch
   const uint32_t d0 = j < gs ? (uint32_t)((uint64_t)j * (uint64_t)decode_groups / gs) : (uint32_t)decode_groups;   // decode groups before group j
   const bool is_decode = j < gs && (uint32_t)((uint64_t)(j + 1) * (uint64_t)decode_groups / gs) > d0;
-  if constexpr (E::kDimsPerChunk == 8) {           // tiles exist for bf16 storage only
-    __shared__ __align__(16) uint8_t lds[SPLIT ? 4 : 3][kKLds + kVLds];
+  // LDS: the K/V buffers of a tile workgroup, or the piece slots of a decode bin (a workgroup is one or the other)
+  constexpr int kTileLds = E::kDimsPerChunk == 8 ? (SPLIT ? 4 : 3) * (kKLds + kVLds) : 0;      // tiles exist for bf16 storage only
+  constexpr int kBinLds = G < 8 ? 2 * TW * BinLds<E, G < 8 ? G : 1>::kSlot * 4 : 0;
+  constexpr int kLds = kTileLds > kBinLds ? kTileLds : (kBinLds > 16 ? kBinLds : 16);
+  __shared__ __align__(16) uint8_t lds[kLds];
+  if constexpr (E::kDimsPerChunk == 8) {
     if (!is_decode) {
-      tile_block<G, TW, SPLIT>(pa, (int)((j - d0) * 8 + x), lds);
+      tile_block<G, TW, SPLIT>(pa, (int)((j - d0) * 8 + x), (uint8_t(*)[kKLds + kVLds])lds);
       return;
     }
   }
   if constexpr (G < 8) {
-    if (is_decode) decode_stream<E, G>(da, (int)(d0 * 8 + x), TW);
+    if (is_decode) decode_bins<E, G>(da, (int)(d0 * 8 + x), TW, (float*)lds);
   }
+}
+
+// A batch without tiles (plain decode): the decode bins alone, W wavefronts per bin.
+template <typename E, int G, int W>
+__global__ __launch_bounds__(64 * W, 8 / W) void decode_only_kernel(DecodeArgs da) {
+  __shared__ __align__(16) float lds[2 * W * BinLds<E, G>::kSlot];
+  decode_bins<E, G>(da, (int)blockIdx.x, W, lds);
 }
 
 // Decode ranges for 8 query heads per kv head: one workgroup of two wavefronts per range.
@@ -1474,6 +1612,7 @@ __global__ __launch_bounds__(256) void prologue_kernel(PrologueArgs a) {
     const int g = (int)(th % a.Hkv);
     const int64_t t = th / a.Hkv;
     const int slot = a.slots[t];
+    if (slot < 0) return;                   // this token is appended by the attention kernel
     const int page = slot / kP, ts = slot % kP;
     const uint8_t* src = (const uint8_t*)(kv ? a.v_new : a.k_new) + th * kRowBytes + c * 16;
     uint8_t* dst = a.pool + (int64_t)page * a.page_bytes + (int64_t)g * kSlab + kv * kBlk +
@@ -1544,7 +1683,7 @@ constexpr int kSwapSplit = 4;
 __global__ __launch_bounds__(256) void swap_kernel(SwapArgs a) {
   const int e = blockIdx.x / kSwapSplit, part = blockIdx.x % kSwapSplit;
   const int64_t page = (int64_t)a.list[2 * e];
-  uint8_t* host = (uint8_t*)a.list[2 * e + 1];
+  uint8_t* host = (uint8_t*)a.list[2 * e + 1] + a.host_offset;
   uint8_t* dev = a.pool + page * a.page_bytes;
   const int64_t n16 = a.page_bytes / 16, per = (n16 + kSwapSplit - 1) / kSwapSplit;
   const int64_t lo = part * per, hi = min(n16, lo + per);
@@ -1646,7 +1785,9 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   const int tw = (ps.n_tiles > 0 && ps.tile_rows == 256) ? 8 : 4;
   // every tile a shared-prefix tile with at most 64 live rows: the kernel that splits them by key block
   const bool split_tiles = E::kDimsPerChunk == 8 && tw == 4 && ps.n_tiles > 0 && ps.small_shared_only != 0;
-  const int decode_blocks = mode == 0 ? (da.n_waves + tw - 1) / tw : 0;
+  // mode 0: one workgroup per bin; the host made the bins for workgroups of this size
+  if (mode == 0 && da.n_bins > 0 && (tile_blocks > 0 ? da.bin_waves != tw : (da.bin_waves != 4 && da.bin_waves != 8))) return hipErrorInvalidValue;
+  const int decode_blocks = mode == 0 ? da.n_bins : 0;
   const int tile_groups = (tile_blocks + 7) / 8, decode_groups = (decode_blocks + 7) / 8;
   const dim3 grid((tile_groups + decode_groups) * 8), block(256), block8(512);
   if (ps.n_tiles > 0 && ps.tile_rows != 128 && ps.tile_rows != 256) return hipErrorInvalidValue;
@@ -1659,6 +1800,20 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
     else if (split_tiles) launch(attn_kernel<E, GG, 4, true>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
     else launch(attn_kernel<E, GG, 4>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
     break;
+  if (tile_blocks == 0 && mode == 0 && da.n_bins > 0) {      // plain decode: the lean kernel
+    const dim3 dgrid(da.n_bins), dblock(64 * da.bin_waves);
+#define SYM_DECODE_CASE(GG) \
+  case GG: \
+    if (da.bin_waves == 8) launch(decode_only_kernel<E, GG, 8>, dgrid, dblock, ev0, ev1, da); \
+    else launch(decode_only_kernel<E, GG, 4>, dgrid, dblock, ev0, ev1, da); \
+    break;
+    switch (G) {
+      SYM_DECODE_CASE(1) SYM_DECODE_CASE(2) SYM_DECODE_CASE(4)
+      default: return hipErrorInvalidValue;
+    }
+#undef SYM_DECODE_CASE
+    return hipGetLastError();
+  }
   if (grid.x > 0) switch (G) {
     SYM_ATTN_CASE(1) SYM_ATTN_CASE(2) SYM_ATTN_CASE(4) SYM_ATTN_CASE(8)
     default: return hipErrorInvalidValue;

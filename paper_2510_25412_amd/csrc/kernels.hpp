@@ -19,6 +19,15 @@ struct DecodeArgs {
   const int32_t* pt;        // flattened page tables
   int32_t n_waves, Hq, Hkv;
   float scale_log2e;        // softmax scale * log2(e)
+  // bins (the vector-unit decode kernel): `waves` then holds bin_waves records per bin: first segment, first
+  // page, units, 0, ids of the first three pages
+  const int32_t* segs;      // [n_segs + 2][8]: page-table offset, kv head, first page, end page, visible tokens,
+                            //   q/out row * Hq + first query head, destination (-1 output, else partial slot), slot of the appended token or -1
+  const int32_t* lmerge;    // [n_bins][32]: count, then (segment, LDS slot of its first piece, that piece's wavefront,
+                            //   pieces) per segment the bin's cut divided, from word 4 on
+  int32_t n_bins, bin_waves;
+  const void* k_new;        // [rows][Hkv][D]: rows of the new tokens, for segments that append (else unused)
+  const void* v_new;
 };
 
 struct PrefillArgs {
@@ -87,6 +96,7 @@ struct SwapArgs {
   const uint64_t* list;         // pinned host [n_pages][2]: page id, address of the page's host slot
   int32_t n_pages;
   int32_t to_host;              // 1 = pool -> host slots, 0 = host slots -> pool
+  int64_t host_offset;          // byte offset inside every host slot (a slot holds the page's bytes of every layer)
 };
 
 // Size of the file-scope device array that stands in for the workspace in sym_pred_batch_static, and

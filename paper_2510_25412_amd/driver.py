@@ -14,19 +14,21 @@ def to_device(a, device):
 
 
 class HipSession:
-    """Device pool + workspace + library context for one workload shape."""
+    """Device pool + workspace + library context for one workload shape.  n_layers > 1: the pool holds that many
+    layers of every page; setup() appends the same rows to every layer unless an op carries rows per layer."""
 
     def __init__(self, shape, n_pages, free_order=None, device="cuda:0", max_lips=4096, max_tokens=1 << 16,
-                 max_entries=1 << 21, decode_waves=0, poison=False):
+                 max_entries=1 << 21, decode_waves=0, poison=False, n_layers=1):
         self.shape = shape
+        self.n_layers = n_layers
         self.device = torch.device(device)
         cfg = binding.make_config(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.page_tokens, shape.dtype, n_pages,
-                                  device=self.device.index or 0, free_order=free_order, decode_waves=decode_waves)
+                                  device=self.device.index or 0, free_order=free_order, decode_waves=decode_waves, n_layers=n_layers)
         pb = binding.page_bytes(cfg)
         assert pb > 0, "unsupported shape"
         self.page_bytes = pb
         wb = binding.workspace_bytes(cfg, max_lips, max_tokens, max_entries)
-        self.pool = torch.empty(n_pages * pb, dtype=torch.uint8, device=self.device)
+        self.pool = torch.empty(n_layers * n_pages * pb, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
         if poison:          # every never-written slot reads as NaN (tests: stale slots must not leak)
             self.pool.fill_(0xFF)
@@ -46,8 +48,11 @@ class HipSession:
                 self.h[op[1]] = self.ctx.kv_fork(self.h[op[2]])
             elif op[0] == "append":
                 _, fid, K, V = op
+                n = K.shape[-3]
                 k, v = to_device(K, self.device), to_device(V, self.device)
-                self.ctx.kv_append(self.h[fid], len(K), k, v, self.stream)
+                if self.n_layers > 1 and K.ndim == 3:          # the same rows for every layer
+                    k, v = k.expand(self.n_layers, *k.shape).contiguous(), v.expand(self.n_layers, *v.shape).contiguous()
+                self.ctx.kv_append(self.h[fid], n, k, v, self.stream)
                 torch.cuda.current_stream(self.device).synchronize()   # k, v are freed on return
             elif op[0] == "remove":
                 self.ctx.kv_remove(self.h.pop(op[1]))

@@ -727,6 +727,72 @@ def test_every_kind_of_work_in_one_batch(Hq, Hkv):
         print(f"all kinds {Hq}/{Hkv} waves={waves}: worst scaled error {worst:.2e}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,dtype,multi", [(32, 8, 128, synth.BF16, 1), (32, 8, 128, synth.BF16, 3), (8, 8, 64, synth.F32, 3),
+                                                  (64, 8, 128, synth.BF16, 1), (16, 8, 128, synth.BF16, 1)])
+def test_layered_pred_layer_by_layer_against_the_oracle(Hq, Hkv, D, dtype, multi):
+    """A context with three layers: one page table, three layers of every page.  The files are built with different rows
+    in every layer (forks, a copy-on-write, an extract, an offload and restore: every layer must move), then one batch
+    (decode LIPs, forks of one prefix, a LIP with several new tokens, a prefill chunk where tiles exist) runs as
+    sym_pred_begin + one sym_pred_layer per layer, in shuffled layer order.  Per layer: outputs against an oracle that
+    was given that layer's rows; afterwards every file of every layer is read back and compared bit for bit with the
+    oracle's pages (the appends that ride in the attention kernel included); the state calls refused while layers are
+    left are checked on the way."""
+    drv = _hip()
+    from paper_2510_25412_amd import binding
+    L = 3
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    files = [("new", 45), ("fork", 0, 7), ("fork", 0, 0), ("new", 300), ("new", 16), ("extract", 3, list(range(0, 300, 3))),
+             ("new", 700)] + [("fork", 6, int(x)) for x in (3, 0, 18, 40, 1)]
+    # (a bf16 batch with a LIP of 2..15 new tokens runs all its decode rows on the matrix cores; without one, the vector-unit
+    # kernel runs them in bins and appends the single tokens itself)
+    batch = [(0, 1), (1, 1), (2, multi), (3, 1), (4, 40 if dtype == synth.BF16 else 5), (5, 1)] + [(f, 1) for f in range(7, 12)]
+    wls = [synth.custom(f"layered{l}", shape, files, batch, 256, seed=900 + 17 * l, then=[("offload", [3, 5]), ("restore", [3, 5])])
+           for l in range(L)]
+    sess = drv.HipSession(shape, 256, device="cuda:0", max_lips=len(batch), max_tokens=1024, max_entries=4096, poison=True,
+                          n_layers=L, decode_waves=24)
+    # the same program on every layer's rows: append ops carry [L, n, Hkv, D]
+    for ops in zip(*[list(w.setup_ops()) for w in wls]):
+        op = ops[0]
+        if op[0] == "append":
+            op = ("append", op[1], np.stack([o[2] for o in ops]), np.stack([o[3] for o in ops]))
+        sess.setup([op])
+    refs, osessions = zip(*[run_oracle(w, dtype=np.float64) for w in wls])
+    bs = [w.batch() for w in wls]
+    dbs = [sess.upload_batch(b) for b in bs]
+    kv, nt = dbs[0]["kv"], dbs[0]["n_tokens"]
+    with pytest.raises(binding.SymError) as e:                 # no batch is open yet
+        sess.ctx.pred_layer(0, dbs[0]["q"], dbs[0]["k_new"], dbs[0]["v_new"], dbs[0]["out"], sess.stream)
+    assert e.value.code == binding.SYM_EINVAL
+    sess.ctx.pred_begin(kv, nt, sess.stream)
+    for l in (2, 0):
+        sess.ctx.pred_layer(l, dbs[l]["q"], dbs[l]["k_new"], dbs[l]["v_new"], dbs[l]["out"], sess.stream)
+    for call in (lambda: sess.ctx.kv_fork(kv[0]), lambda: sess.ctx.kv_remove(kv[0]), lambda: sess.ctx.pred_begin(kv, nt, sess.stream),
+                 lambda: sess.ctx.kv_truncate([kv[0]], [3]), lambda: sess.ctx.kv_offload([kv[0]], sess.stream),
+                 lambda: sess.ctx.pred_layer(2, dbs[2]["q"], dbs[2]["k_new"], dbs[2]["v_new"], dbs[2]["out"], sess.stream)):
+        with pytest.raises(binding.SymError) as e:             # one layer is left: nothing may change the files
+            call()
+        assert e.value.code == binding.SYM_EBUSY
+    sess.ctx.pred_layer(1, dbs[1]["q"], dbs[1]["k_new"], dbs[1]["v_new"], dbs[1]["out"], sess.stream)
+    torch.cuda.synchronize()
+    for l in range(L):
+        worst = check_outputs(dbs[l]["out"].cpu().numpy(), refs[l])
+        print(f"layer {l}: worst scaled error {worst:.2e}")
+    check_state(wls[0], sess, osessions[0])
+    from oracle.attention import gather_file
+    tdt = torch.float32 if dtype == synth.F32 else torch.bfloat16
+    for l in range(L):
+        for f in range(len(files)):
+            n = sess.ctx.kv_len(sess.h[f])
+            k = torch.empty((n, Hkv, D), dtype=tdt, device="cuda")
+            v = torch.empty_like(k)
+            sess.ctx.kv_read(sess.h[f], 0, n, k, v, sess.stream, layer=l)
+            torch.cuda.synchronize()
+            K, V = gather_file(osessions[l].pool, osessions[l].model.kv_pages(osessions[l].h[f]), n)
+            assert np.array_equal(k.float().cpu().numpy(), K) and np.array_equal(v.float().cpu().numpy(), V), (l, f)
+    sess.ctx.kv_fork(kv[0])                                       # the batch is complete: the files can change again
+    sess.close()
+
+
 @pytest.mark.parametrize("how", ["truncate", "extract"])
 def test_copy_and_in_place_append_on_one_page_in_one_batch(how):
     """Two files share a partly filled page but see different numbers of its tokens (a fork that

@@ -374,6 +374,7 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
     Hkv = 8
     monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
     monkeypatch.setenv("SYM_ROW_TOKENS", str(row_tokens))
+    monkeypatch.setenv("SYM_DECODE_MFMA", "1")          # the global cut of the matrix-core decode kernel (else: bins, below)
     c = host_ctx(4096, decode_waves=waves)
     rng = np.random.default_rng(1)
     np_l = [-(-L // 16) for L in lengths]
@@ -445,6 +446,120 @@ def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves
                 seen_parts += [x + t for x in ps]
     assert not items
     assert sorted(seen_parts) == list(range(n_partials)) and n_partials <= 2 * n_waves * row_tokens
+
+
+def _walk_bins(words, P=16):
+    """Walks the bins of a descriptor the way the vector-unit decode kernel does.  Returns per bin the cost, and
+    checks on the way: every wavefront's pieces, the LDS slots they use, the in-bin merge lists."""
+    hdr = words[:48]
+    n_segs, off_segs, n_bins, W, off_lm = (int(hdr[i]) for i in (32, 33, 34, 35, 36))
+    segs = words[off_segs:off_segs + 8 * n_segs].reshape(n_segs, 8)
+    assert not words[off_segs + 8 * n_segs:off_segs + 8 * (n_segs + 2)].any()       # the spare records the kernel may read ahead
+    waves = words[hdr[6]:hdr[6] + 8 * n_bins * W].reshape(n_bins, W, 8)
+    lmerge = words[off_lm:off_lm + 32 * n_bins].reshape(n_bins, 32)
+    pt = words[hdr[8]:hdr[9]]
+    assert int(hdr[1]) == n_bins * W
+    cover = {}                                                     # (segment, page) -> (bin, wavefront)
+    seg_bin = {}
+    loads = []
+    for b in range(n_bins):
+        cut = {}                                                   # segment -> [(wavefront, slot)] of its pieces in LDS
+        units_b = 0
+        for k in range(W):
+            seg, p, rem = (int(x) for x in waves[b, k, :3])
+            if rem == 0:
+                continue
+            assert waves[b, k, 4:7].tolist() == [int(pt[int(segs[seg, 0]) + min(p + i, int(segs[seg, 3]) - 1)]) for i in range(3)]
+            piece = 0
+            while rem > 0:
+                pb, pe = int(segs[seg, 2]), int(segs[seg, 3])
+                assert pb <= p < pe
+                cnt = min(rem, pe - p)
+                for x in range(p, p + cnt):
+                    assert (seg, x) not in cover
+                    cover[(seg, x)] = (b, k)
+                assert seg_bin.setdefault(seg, b) == b             # a segment lives in one bin
+                if not (p == pb and cnt == pe - pb):
+                    cut.setdefault(seg, []).append((k, 2 * k if piece == 0 else 2 * k + 1))
+                piece += 1
+                units_b += cnt
+                rem -= cnt
+                seg, p = seg + 1, (int(segs[seg + 1, 2]) if seg + 1 < n_segs else 0)
+        # the in-bin merge list names exactly the cut segments, each with the slot of its first piece, that piece's
+        # wavefront and the count; later pieces are first pieces of the following wavefronts (slot 2 * wavefront)
+        cnt = int(lmerge[b, 0])
+        assert cnt <= W - 1 and cnt == len(cut)
+        listed = {}
+        for e in lmerge[b, 4:4 + 4 * cnt].reshape(cnt, 4).tolist():
+            listed[e[0]] = e[1:]
+        for seg, ps in cut.items():
+            s0, w0, n = listed[seg]
+            assert n == len(ps) >= 2 and ps[0] == (w0, s0)
+            assert [q for q in ps[1:]] == [(w0 + i, 2 * (w0 + i)) for i in range(1, n)]
+        assert len({s for ps in cut.values() for _, s in ps}) == sum(len(ps) for ps in cut.values())   # no slot used twice
+        loads.append(units_b)
+    return segs, cover, seg_bin, loads, n_bins, W
+
+
+@pytest.mark.parametrize("lengths,n_tok,waves,range_cost", [
+    ([38, 81, 130, 201], [1, 1, 1, 1], 64, 3), ([700, 16, 17, 1, 4096], [1, 1, 1, 1, 1], 2048, 3), ([5], [1], 8, 0),
+    ([1030, 64, 333, 2000], [1, 1, 1, 1], 96, 3), ([70000, 33], [1, 1], 2048, 3), ([300] * 40, [1] * 40, 256, 0),
+    (list(range(20, 2000, 37)), [1] * 54, 2048, 3)])
+def test_descriptor_bins_cover_every_unit_once_and_are_balanced(lengths, n_tok, waves, range_cost, monkeypatch):
+    """The bins of the vector-unit decode kernel: segments are whole (row, kv head) ranges, or the parts of a range that a
+    bin boundary divides; every (row, head, page) is covered by exactly one wavefront; a range in one segment writes the
+    output, the segments of a divided range number their partials consecutively and share a merge entry; the bins
+    carry equal cost."""
+    Hkv, G = 8, 4
+    monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
+    c = host_ctx(1 << 15, decode_waves=waves)
+    rng = np.random.default_rng(2)
+    np_l = [-(-L // 16) for L in lengths]
+    flat = rng.permutation(1 << 15)[:sum(np_l)].astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
+    words = c.build_desc(n_tok, flat, off, lengths)
+    n_rows, n_waves, n_partials, rows, _, merge, pt, ptoff = _walk_desc(words, Hkv)
+    assert n_rows == len(lengths) and np.array_equal(pt, flat)
+    segs, cover, seg_bin, loads, n_bins, W = _walk_bins(words)
+    assert W == 8 and n_bins * W <= max(waves, W)
+    # segments against the rows: per (row, head) consecutive pieces that tile [0, pages)
+    by_range = {}
+    for i, (tbl, g, pb, pe, vis, qh, dest, app) in enumerate(segs.tolist()):
+        assert app == -1                                            # build_desc alone appends nothing
+        qrow = qh // 32
+        assert qh == qrow * 32 + g * G                              # q row * Hq + first query head of the kv head
+        by_range.setdefault((qrow, g), []).append((pb, pe, dest, i))
+        assert tbl == int(off[qrow]) and vis == lengths[qrow]
+    assert sorted(by_range) == [(r, g) for r in range(n_rows) for g in range(Hkv)]
+    parts = []
+    items = {int(m[2]): m for m in merge.tolist()}
+    for (row, g), ps in by_range.items():
+        ps.sort()
+        assert ps[0][0] == 0 and ps[-1][1] == np_l[row] and all(a[1] == b[0] for a, b in zip(ps, ps[1:]))
+        for pb, pe, dest, i in ps:
+            assert all((i, x) in cover for x in range(pb, pe))
+        key = row * 32 + g * G
+        if len(ps) == 1:
+            assert ps[0][2] == -1 and key not in items              # whole range in one segment: the final output
+        else:
+            first, cnt, _, xf, xs, xc, stride, _ = items.pop(key)
+            assert cnt == len(ps) and stride == 1 and xc == 0 and [p[2] for p in ps] == list(range(first, first + cnt))
+            parts += [p[2] for p in ps]
+    assert not items and sorted(parts) == list(range(n_partials))
+    assert len(cover) == sum(np_l) * Hkv == sum(loads)
+    # balance.  Whole ranges handed out longest first (several ranges per bin): nothing is split and the fullest bin is within
+    # 3 % of the mean; otherwise contiguous shares of equal cost: at most n_bins - 1 ranges are cut, and the bins differ by no
+    # more than a boundary snapped across one range start
+    cost = [0] * n_bins
+    for i, (tbl, g, pb, pe, *_rest) in enumerate(segs.tolist()):
+        cost[seg_bin[i]] += pe - pb + range_cost
+    mean = sum(cost) / n_bins
+    if n_partials == 0 and n_bins > 1:
+        assert len(segs) >= 3 * n_bins and max(cost) <= 1.03 * mean + 1
+    else:
+        assert len(parts) - len({k for k, ps in by_range.items() if len(ps) > 1}) <= n_bins - 1       # one extra segment per boundary
+        assert max(cost) - min(cost) <= 1 + 2 * range_cost
+        assert [seg_bin[i] for i in range(len(segs))] == sorted(seg_bin[i] for i in range(len(segs)))   # contiguous shares
 
 
 def test_descriptor_rejects_bad_tables():
