@@ -113,6 +113,12 @@ def _i32(a):
     return a, a.ctypes.data_as(_I32P)
 
 
+def as_i32p(a):
+    """Pointer to the data of a contiguous int32 numpy array (the caller keeps the array alive)."""
+    assert a.dtype == np.int32 and a.flags.c_contiguous
+    return C.cast(a.ctypes.data, _I32P)
+
+
 def _i64(a):
     a = np.ascontiguousarray(a, np.int64)
     return a, a.ctypes.data_as(_I64P)
