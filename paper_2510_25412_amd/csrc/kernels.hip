@@ -45,6 +45,26 @@ __device__ __forceinline__ float row_xor8(float x) {
   return as_f32(__builtin_amdgcn_update_dpp(0, as_u32(x), 0x128, 0xf, 0xf, false));   // row_ror:8
 }
 
+// max / sum of x over the lane pairs (l, l ^ 32) and (l, l ^ 16), in every lane, with the lane-swap instructions: swapping
+// the upper 32 lanes of x with the lower 32 of a copy leaves one register holding the lower half twice and the other the
+// upper half twice (likewise the odd and even rows of 16 lanes), so combining the two needs no select.
+__device__ __forceinline__ float pair32_max(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(as_u32(x), as_u32(x), false, false);
+  return fmaxf(as_f32(sw[0]), as_f32(sw[1]));
+}
+__device__ __forceinline__ float pair16_max(float x) {
+  const auto sw = __builtin_amdgcn_permlane16_swap(as_u32(x), as_u32(x), false, false);
+  return fmaxf(as_f32(sw[0]), as_f32(sw[1]));
+}
+__device__ __forceinline__ float pair32_sum(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(as_u32(x), as_u32(x), false, false);
+  return as_f32(sw[0]) + as_f32(sw[1]);
+}
+__device__ __forceinline__ float pair16_sum(float x) {
+  const auto sw = __builtin_amdgcn_permlane16_swap(as_u32(x), as_u32(x), false, false);
+  return as_f32(sw[0]) + as_f32(sw[1]);
+}
+
 // Element-type traits.  A lane holds, per row half, one 16-byte chunk of a K/V row.
 struct ElemBF16 {
   static constexpr int kDimsPerChunk = 8;
@@ -377,30 +397,33 @@ __device__ __forceinline__ void decode_bins(const DecodeArgs& a, const int bin, 
     for (int h = 0; h < G; ++h) {
       float M = m[h];
       M = fmaxf(M, row_xor8(M));
-      M = fmaxf(M, __shfl_xor(M, 16));
-      M = fmaxf(M, __shfl_xor(M, 32));
+      M = pair16_max(M);
+      M = pair32_max(M);
       const float f = __builtin_amdgcn_exp2f(m[h] - M);
       float ls = l[h] * f;
       ls += row_xor8(ls);
-      ls += __shfl_xor(ls, 16);
-      ls += __shfl_xor(ls, 32);
+      ls = pair16_sum(ls);
+      ls = pair32_sum(ls);
       lsum[h] = ls;
       Mh[h] = M;
 #pragma unroll
       for (int d = 0; d < DPL; ++d) vals[h * DPL + d] = acc[h][d] * f;
     }
     {
-      const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+      // lane bits 5 and 4: the lane-swap instructions do "keep one, send the other" in one go: after swapping the upper
+      // 32 lanes of x with the lower 32 of y, x + y is x summed over the lane pairs (l, l + 32) in the lower half and y
+      // summed in the upper half; likewise with the odd and even rows of 16 lanes
 #pragma unroll
       for (int i = 0; i < V / 2; ++i) {
-        const float keep = b5 ? vals[i + V / 2] : vals[i], send = b5 ? vals[i] : vals[i + V / 2];
-        vals[i] = keep + __shfl_xor(send, 32);
+        const auto sw = __builtin_amdgcn_permlane32_swap(as_u32(vals[i]), as_u32(vals[i + V / 2]), false, false);
+        vals[i] = as_f32(sw[0]) + as_f32(sw[1]);
       }
 #pragma unroll
       for (int i = 0; i < V / 4; ++i) {
-        const float keep = b4 ? vals[i + V / 4] : vals[i], send = b4 ? vals[i] : vals[i + V / 4];
-        vals[i] = keep + __shfl_xor(send, 16);
+        const auto sw = __builtin_amdgcn_permlane16_swap(as_u32(vals[i]), as_u32(vals[i + V / 4]), false, false);
+        vals[i] = as_f32(sw[0]) + as_f32(sw[1]);
       }
+      const bool b3 = (lane & 8) != 0;
 #pragma unroll
       for (int i = 0; i < V / 8; ++i) {
         const float keep = b3 ? vals[i + V / 8] : vals[i], send = b3 ? vals[i] : vals[i + V / 8];
