@@ -367,7 +367,7 @@ def run_attention_workload(args, name, np, torch, binding, synth, HipSession, de
     # ---- build the files, every layer (inputs resident in HBM before the timed region)
     entries = sum(wl.pages_after_batch().values()) + 64 * n_lips + grow_pages
     sess = HipSession(shape, n_pages, wl.free_order, dev, max_lips=n_lips, max_tokens=max(T, max(wl.lengths.values())) + 64,
-                      max_entries=entries, n_layers=layers)
+                      max_entries=entries, n_layers=layers, tuning=args.tuning_dict, decode_waves=args.decode_waves)
     sess.setup(wl.setup_ops())
     print(f"[bench] {name}: {layers} layer(s) of {n_pages} pages built", file=sys.stderr, flush=True)
     batch = wl.batch()
@@ -530,7 +530,8 @@ def run_attention_workload(args, name, np, torch, binding, synth, HipSession, de
                                "(host: plan + descriptor once per step; device: one attention launch per layer, every layer with K/V pages of its own)",
                    "layers_per_step": layers, "kv_tokens_per_layer": int(unique_tokens), "algorithmic_bytes_per_layer": int(layer_bytes),
                    "algorithmic_bytes_per_step": int(layer_bytes) * layers,
-                   "logical_kv_tokens_per_layer": int(logical_tokens), "logical_bytes_per_layer": int(logical_bytes)},
+                   "logical_kv_tokens_per_layer": int(logical_tokens), "logical_bytes_per_layer": int(logical_bytes),
+                   "tuning": args.tuning_dict or "library defaults"},
         "us_per_layer": round(ms_per_layer * 1e3, 3),
         "pct_hbm_peak": round(100 * tbps / HBM_PEAK_TBPS, 2),
         "effective_TBps_logical": round(logical_bytes / (ms_per_layer * 1e-3) / 1e12, 4),
@@ -563,9 +564,13 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=None, help="wall-time budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--pool-pages", type=int, default=3_000_000, help="pages of the long-context pool")
     ap.add_argument("--no-calib", action="store_true")
+    ap.add_argument("--tuning", default="", help="planner settings to change from the library's defaults, as name=value,name=value "
+                                                 "(the fields of sym_tuning); the attention workloads only")
+    ap.add_argument("--decode-waves", type=int, default=0, help="sym_config.decode_waves (0 = the library's choice)")
     ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     ap.add_argument("--rag-rate", type=float, default=6000.0, help="request arrivals per second of the rag workload")
     args = ap.parse_args()
+    args.tuning_dict = {k.strip(): int(v) for k, v in (kv.split("=") for kv in args.tuning.split(",") if kv.strip())} or None
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path is single-GPU: it would shard by LIP or by kv head, with no exchange inside attention); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)

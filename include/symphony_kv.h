@@ -57,8 +57,39 @@ extern "C" {
 typedef struct sym_ctx sym_ctx;   /* opaque; owns host metadata and pinned staging only */
 typedef int32_t sym_kv;           /* file handle >= 0; the lowest free slot is reused   */
 
+/* Planner settings.  They decide how a batch is laid over the GPU, never what it computes:
+ * every setting gives the same outputs up to the order of floating-point sums (the tests
+ * sweep them).  sym_tuning_defaults() fills the values that sym_init uses when
+ * sym_config.tuning is NULL; a caller changes the fields it wants and passes the struct.
+ * Out-of-range values are clamped to the nearest allowed one.                             */
+typedef struct sym_tuning {
+  int32_t decode_mfma;     /* ranges of single tokens and short drafts on the matrix cores (1)
+                              or on the vector ALUs (0); bf16 only.  Default: 1 when
+                              Hq/Hkv = 8, else 0                                          */
+  int32_t min_units;       /* smallest piece, in pairs of pages, that a long range is cut
+                              into; >= 1, default 4                                       */
+  int32_t prefill_min;     /* a pred of at least this many new tokens is computed by tiles
+                              (bf16); >= 2, default 16                                    */
+  int32_t share_min_lips;  /* files of a batch that must share a page-list prefix before
+                              the prefix is read once for all of them; 0 = never group,
+                              default 4                                                   */
+  int32_t share_min_pages; /* shortest shared prefix that is grouped; >= 2, default 8     */
+  int32_t tile_rows;       /* query rows of a tile: 256 (default) or 128                  */
+  int32_t row_tokens;      /* new tokens of a short draft that share one pass over the file:
+                              1 .. 16 / (Hq/Hkv), default the maximum; bf16 only          */
+  int32_t range_cost;      /* what the start of a range costs, in pairs of pages, when work
+                              is divided; >= 0, default 3                                 */
+  int32_t bin_tolerance;   /* whole ranges are packed into workgroups only if the fullest
+                              then holds at most this many percent more than the mean;
+                              otherwise ranges are cut at equal cost; >= 0, default 3     */
+  int32_t bin_waves;       /* wavefronts of a decode workgroup: 8 (default) or 4          */
+  int32_t fuse_append;     /* 1 (default): the K/V row of a single new token is written by
+                              the wavefront that reads the row's last page; 0: by a launch
+                              of its own before attention                                 */
+} sym_tuning;
+
 typedef struct sym_config {
-  int32_t n_q_heads;       /* Hq                                                         */
+  int32_t n_q_heads;       /* Hq; Hq / Hkv must be 1, 2, 4 or 8                           */
   int32_t n_kv_heads;      /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv)   */
   int32_t head_dim;        /* D; D * sizeof(element) must be 256 (bf16: 128, f32: 64)    */
   int32_t page_tokens;     /* P = 16                                                     */
@@ -76,6 +107,8 @@ typedef struct sym_config {
   int32_t n_layers;        /* attention layers that share the files' page tables; 0 or 1 =
                               one.  The pool then holds n_layers * n_pages pages, layer after
                               layer: page p of layer l is page l * n_pages + p of the pool.   */
+  const sym_tuning* tuning;  /* host, optional: planner settings, NULL = the defaults.
+                                Copied by sym_init.                                        */
 } sym_config;
 
 typedef struct sym_stats {
@@ -98,6 +131,9 @@ typedef struct sym_stats {
  * files, max_tokens new tokens in total and max_table_entries page-table entries summed
  * over the batch's files (after the append). */
 int64_t sym_page_bytes(const sym_config* cfg);
+/* The planner settings sym_init uses for this shape when cfg->tuning is NULL (cfg->tuning
+ * itself is not read).  SYM_EINVAL for an unsupported shape.                             */
+int     sym_tuning_defaults(const sym_config* cfg, sym_tuning* out);
 int64_t sym_workspace_bytes(const sym_config* cfg, int64_t max_lips, int64_t max_tokens,
                             int64_t max_table_entries);
 
@@ -273,18 +309,36 @@ int sym_plan_copies_first(sym_ctx* ctx);
 
 /* The packed descriptor of the attention launch for a batch given by page tables (same
  * arguments as sym_pred_batch_raw), written to host memory for inspection: int32 words.
- * Layout: words[0..31] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then word
+ * Layout: words[0..47] = header {n_rows, n_waves, n_partials, n_lips, n_tiles, then word
  * offsets of the sections: rows, wave_work, merge, page_table, pt_off, tiles; total words;
  * total units (lo, hi); n_merge; offset of the member list; n_members; n_shared_tiles;
  * [18] workgroups of the tile part of the launch; [20..28] the 9 offsets that cut the tile list
- * into 8 shares of equal cost, one per XCD (workgroup b runs tile b / 8 of share b % 8)}, then
+ * into 8 shares of equal cost, one per XCD (workgroup b runs tile b / 8 of share b % 8);
+ * [32] n_segs, [33] offset of the segments, [34] n_bins, [35] wavefronts of a bin,
+ * [36] offset of the in-bin merge lists (all five 0 when ranges are cut globally, as the
+ * matrix-core decode kernel wants: wave_work is then one record per wavefront slot)}, then
  * the sections:
  *   rows      [n_rows][4]   page-table offset, tokens the row's first new token sees, its q/out
  *                           row, and in one word: first page of the row's own range (low 28 bits;
  *                           pages before it belong to a shared prefix) | (new tokens in the
  *                           row - 1) << 28 (a row holds up to 4 consecutive draft tokens of a LIP)
- *   wave_work [n_waves][8]  row, kv head, page, units, first partial, ids of the first three
- *                           pages of the first range (its first loads need no table lookup)
+ *   wave_work [n_waves][8]  global cut: row, kv head, page, units, first partial, ids of the
+ *                           first three pages of the first range (its first loads need no
+ *                           table lookup).  Bins (decode workgroups of [35] wavefronts; wavefront
+ *                           w of bin b is record b * [35] + w): first segment, page inside it,
+ *                           units, 0, ids of its first three pages, 0: the wavefronts of a bin
+ *                           take equal consecutive parts of the bin's segments
+ *   segs      [n_segs + 2][8]  (bins) a (row, kv head) range or the part of one that falls
+ *                           into a bin: page-table offset, kv head, first page, end page,
+ *                           tokens the row sees, q row * Hq + first query head, destination
+ *                           (-1: the output rows; else the partial slot of its first piece),
+ *                           pool slot (page * 16 + token) that receives the row's new K/V
+ *                           row from the wavefront reading the last page (-1: none); two
+ *                           spare records end the list
+ *   lmerge    [n_bins][32]  (bins) segments of the bin that its wavefronts cut into pieces,
+ *                           combined through LDS when the workgroup ends: count, first and
+ *                           end segment of the bin, 0, then per cut segment: segment, LDS
+ *                           slot of its first piece, wavefront of that piece, pieces
  *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
  *                           partials of the row's shared prefix: first, stride, count; then the
  *                           distance between the own pieces (tokens in the row); 0

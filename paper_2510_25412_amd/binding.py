@@ -16,12 +16,21 @@ SYM_F32, SYM_BF16 = 0, 1
 K_PROLOGUE, K_ATTN, K_MERGE, K_MOVE, K_SWAP = 0, 1, 2, 3, 4
 
 
+TUNING_FIELDS = ("decode_mfma", "min_units", "prefill_min", "share_min_lips", "share_min_pages", "tile_rows",
+                 "row_tokens", "range_cost", "bin_tolerance", "bin_waves", "fuse_append")
+
+
+class SymTuning(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in TUNING_FIELDS]
+
+
 class SymConfig(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_tokens", C.c_int32), ("dtype", C.c_int32), ("device", C.c_int32),
                 ("n_pages", C.c_int64), ("pool", C.c_void_p), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_int64), ("free_order", C.POINTER(C.c_int32)),
-                ("softmax_scale", C.c_float), ("decode_waves", C.c_int32), ("n_layers", C.c_int32)]
+                ("softmax_scale", C.c_float), ("decode_waves", C.c_int32), ("n_layers", C.c_int32),
+                ("tuning", C.POINTER(SymTuning))]
 
 
 class SymStats(C.Structure):
@@ -42,6 +51,7 @@ _I32P, _I64P = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
 
 _SIGNATURES = {
     "sym_page_bytes": (C.c_int64, [C.POINTER(SymConfig)]),
+    "sym_tuning_defaults": (C.c_int, [C.POINTER(SymConfig), C.POINTER(SymTuning)]),
     "sym_workspace_bytes": (C.c_int64, [C.POINTER(SymConfig), C.c_int64, C.c_int64, C.c_int64]),
     "sym_init": (C.c_int, [C.POINTER(SymConfig), C.POINTER(C.c_void_p)]),
     "sym_destroy": (None, [C.c_void_p]),
@@ -135,7 +145,8 @@ def _ptr(t):
 
 
 def make_config(n_q_heads, n_kv_heads, head_dim, page_tokens, dtype, n_pages, device=-1, pool=None, workspace=None,
-                workspace_bytes=0, free_order=None, softmax_scale=0.0, decode_waves=0, n_layers=1):
+                workspace_bytes=0, free_order=None, softmax_scale=0.0, decode_waves=0, n_layers=1, tuning=None):
+    """`tuning`: dict of sym_tuning fields to change from the library's defaults for this shape."""
     cfg = SymConfig()
     cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_tokens = n_q_heads, n_kv_heads, head_dim, page_tokens
     cfg.dtype = {"f32": SYM_F32, "bf16": SYM_BF16}.get(dtype, dtype)
@@ -147,6 +158,16 @@ def make_config(n_q_heads, n_kv_heads, head_dim, page_tokens, dtype, n_pages, de
         cfg.free_order = p
     cfg.softmax_scale, cfg.decode_waves, cfg.n_layers = softmax_scale, decode_waves, n_layers
     cfg._keep = keep
+    if tuning:
+        t = SymTuning()
+        if load().sym_tuning_defaults(C.byref(cfg), C.byref(t)) != SYM_OK:
+            raise SymError(SYM_EINVAL, "sym_tuning_defaults: unsupported shape")
+        for name, value in tuning.items():
+            if name not in TUNING_FIELDS:
+                raise KeyError(f"no planner setting called {name!r}")
+            setattr(t, name, int(value))
+        cfg._tuning = t
+        cfg.tuning = C.pointer(t)
     return cfg
 
 

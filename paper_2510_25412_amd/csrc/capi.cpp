@@ -30,9 +30,23 @@ inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline void copy_bytes(void* dst, const void* src, size_t bytes) {
   if (bytes) std::memcpy(dst, src, bytes);
 }
-inline int env_int(const char* name, int dflt) {
-  const char* s = std::getenv(name);
-  return (s && *s) ? std::atoi(s) : dflt;
+// The planner settings of a shape when the caller gives none.
+sym_tuning default_tuning(const sym_config* cfg) {
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  const bool bf16 = cfg->dtype == SYM_BF16;
+  sym_tuning t;
+  t.decode_mfma = (bf16 && G == 8) ? 1 : 0;   // 8 query heads per kv head are bound by vector issue on the VALU path
+  t.min_units = 4;
+  t.prefill_min = 16;
+  t.share_min_lips = 4;
+  t.share_min_pages = 8;
+  t.tile_rows = 256;
+  t.row_tokens = bf16 ? std::min<int>(ROW_TOKENS_MAX, 16 / G) : 1;
+  t.range_cost = 3;                            // measured: a range start costs about 3 units
+  t.bin_tolerance = 3;
+  t.bin_waves = 8;
+  t.fuse_append = 1;
+  return t;
 }
 }  // namespace
 
@@ -534,6 +548,12 @@ int64_t sym_page_bytes(const sym_config* cfg) {
   return (int64_t)cfg->n_kv_heads * 2 * cfg->page_tokens * 256;
 }
 
+int sym_tuning_defaults(const sym_config* cfg, sym_tuning* out) {
+  if (!shape_ok(cfg) || !out) return SYM_EINVAL;
+  *out = default_tuning(cfg);
+  return SYM_OK;
+}
+
 int64_t sym_workspace_bytes(const sym_config* cfg, int64_t max_lips, int64_t max_tokens, int64_t max_table_entries) {
   if (!shape_ok(cfg)) return 0;
   sym_ctx tmp;
@@ -557,9 +577,11 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
       seen[p] = 1;
     }
   }
+  const sym_tuning tun = cfg->tuning ? *cfg->tuning : default_tuning(cfg);
   sym_ctx* c = new sym_ctx();
   c->cfg = *cfg;
   c->cfg.free_order = nullptr;
+  c->cfg.tuning = nullptr;
   c->G = cfg->n_q_heads / cfg->n_kv_heads;
   c->page_bytes = sym_page_bytes(cfg);
   c->n_layers = std::max(1, cfg->n_layers);
@@ -590,25 +612,23 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
       delete c;
       return SYM_EHIP;
     }
-    // two wavefronts per SIMD; with 8 query heads per kv head a range takes two wavefronts
-    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * ((c->G == 8 && !env_int("SYM_DECODE_MFMA", 1)) ? 4 : 8);
+    // two wavefronts per SIMD; with 8 query heads per kv head a range of the VALU kernel takes two wavefronts
+    if (cfg->decode_waves <= 0) c->max_waves = std::max(cus, 1) * ((c->G == 8 && !tun.decode_mfma) ? 4 : 8);
   }
-  c->max_waves = std::min(env_int("SYM_DECODE_WAVES", c->max_waves), 1 << 16);
-  c->min_units = std::max(1, env_int("SYM_MIN_UNITS", 4));
-  // 8 query heads per kv head are bound by vector issue in the VALU decode kernel: matrix cores by default
-  c->decode_mode = env_int("SYM_DECODE_MFMA", (cfg->dtype == SYM_BF16 && c->G == 8) ? 1 : 0) ? 1 : 0;
-  if (cfg->dtype != SYM_BF16) c->decode_mode = 0;
-  c->prefill_min = std::max(2, env_int("SYM_PREFILL_MIN", 16));
-  c->share_min_lips = std::max(0, env_int("SYM_SHARE_MIN_LIPS", 4));   // 0 = never group
-  c->share_min_pages = std::max(2, env_int("SYM_SHARE_MIN_PAGES", 8));
-  c->tile_rows = env_int("SYM_TILE_ROWS", 256) == 128 ? 128 : 256;
+  c->max_waves = std::min(c->max_waves, 1 << 16);
+  c->min_units = std::max(1, tun.min_units);
+  c->decode_mode = (tun.decode_mfma && cfg->dtype == SYM_BF16) ? 1 : 0;
+  c->prefill_min = std::max(2, tun.prefill_min);
+  c->share_min_lips = std::max(0, tun.share_min_lips);   // 0 = never group
+  c->share_min_pages = std::max(2, tun.share_min_pages);
+  c->tile_rows = tun.tile_rows == 128 ? 128 : 256;
   c->tile_tokens = cfg->dtype == SYM_BF16 ? c->tile_rows / c->G : 0;   // new tokens (or sharing members) per tile
   // a short draft (2 .. prefill_min - 1 new tokens) shares one pass over its file: 16 MFMA columns = tokens x heads
-  c->row_tokens = cfg->dtype == SYM_BF16 ? std::max(1, std::min(env_int("SYM_ROW_TOKENS", ROW_TOKENS_MAX), std::min<int>(ROW_TOKENS_MAX, 16 / c->G))) : 1;
-  c->range_cost = std::max(0, env_int("SYM_RANGE_COST", 3));   // measured: a range start costs about 3 units
-  c->bin_tolerance = std::max(0, env_int("SYM_BIN_TOL", 3));
-  c->bin_waves = env_int("SYM_BIN_WAVES", 8) == 4 ? 4 : 8;
-  c->fuse_append = env_int("SYM_FUSE_APPEND", 1) ? 1 : 0;
+  c->row_tokens = cfg->dtype == SYM_BF16 ? std::max(1, std::min(tun.row_tokens, std::min<int>(ROW_TOKENS_MAX, 16 / c->G))) : 1;
+  c->range_cost = std::max(0, tun.range_cost);
+  c->bin_tolerance = std::max(0, tun.bin_tolerance);
+  c->bin_waves = tun.bin_waves == 4 ? 4 : 8;
+  c->fuse_append = tun.fuse_append ? 1 : 0;
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
     return SYM_ENOSPC;

@@ -18,12 +18,13 @@ class HipSession:
     layers of every page; setup() appends the same rows to every layer unless an op carries rows per layer."""
 
     def __init__(self, shape, n_pages, free_order=None, device="cuda:0", max_lips=4096, max_tokens=1 << 16,
-                 max_entries=1 << 21, decode_waves=0, poison=False, n_layers=1):
+                 max_entries=1 << 21, decode_waves=0, poison=False, n_layers=1, tuning=None):
         self.shape = shape
         self.n_layers = n_layers
         self.device = torch.device(device)
         cfg = binding.make_config(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.page_tokens, shape.dtype, n_pages,
-                                  device=self.device.index or 0, free_order=free_order, decode_waves=decode_waves, n_layers=n_layers)
+                                  device=self.device.index or 0, free_order=free_order, decode_waves=decode_waves, n_layers=n_layers,
+                                  tuning=tuning)
         pb = binding.page_bytes(cfg)
         assert pb > 0, "unsupported shape"
         self.page_bytes = pb

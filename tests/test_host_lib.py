@@ -11,8 +11,9 @@ from paper_2510_25412_amd import binding
 from trace_util import load_trace, parse_expect
 
 
-def host_ctx(n_pages, free_order=None, Hq=32, Hkv=8, D=128, dtype="bf16", decode_waves=0):
-    cfg = binding.make_config(Hq, Hkv, D, 16, dtype, n_pages, device=-1, free_order=free_order, decode_waves=decode_waves)
+def host_ctx(n_pages, free_order=None, Hq=32, Hkv=8, D=128, dtype="bf16", decode_waves=0, tuning=None):
+    cfg = binding.make_config(Hq, Hkv, D, 16, dtype, n_pages, device=-1, free_order=free_order, decode_waves=decode_waves,
+                              tuning=tuning)
     return binding.Context(cfg)
 
 
@@ -36,6 +37,38 @@ def test_shapes_supported_and_rejected():
     assert binding.page_bytes(binding.make_config(24, 8, 128, 16, "bf16", 8)) == 0     # group of 3
     with pytest.raises(binding.SymError):
         binding.Context(binding.make_config(32, 8, 128, 16, "bf16", 8, device=-1, free_order=[0, 1, 2, 3, 4, 5, 6, 6]))
+
+
+def test_planner_settings_defaults_overrides_and_clamping():
+    """sym_tuning: the defaults depend on the shape only (matrix-core decode and one token per row of heads at 8 query
+    heads per kv head; no draft rows in fp32); a caller's struct replaces them; values out of range are clamped, which
+    the tile count of a descriptor shows (tile_rows 7 acts as 256, prefill_min -5 as 2)."""
+    import ctypes as C
+    lib = binding.load()
+
+    def defaults(*shape):
+        t = binding.SymTuning()
+        assert lib.sym_tuning_defaults(C.byref(binding.make_config(*shape, 8)), C.byref(t)) == 0
+        return {n: getattr(t, n) for n in binding.TUNING_FIELDS}
+
+    d4 = defaults(32, 8, 128, 16, "bf16")
+    assert d4 == dict(decode_mfma=0, min_units=4, prefill_min=16, share_min_lips=4, share_min_pages=8, tile_rows=256,
+                      row_tokens=4, range_cost=3, bin_tolerance=3, bin_waves=8, fuse_append=1)
+    d8 = defaults(64, 8, 128, 16, "bf16")
+    assert d8["decode_mfma"] == 1 and d8["row_tokens"] == 2
+    assert defaults(8, 8, 64, 16, "f32")["row_tokens"] == 1 and defaults(8, 8, 64, 16, "f32")["decode_mfma"] == 0
+    t = binding.SymTuning()
+    assert lib.sym_tuning_defaults(C.byref(binding.make_config(24, 8, 128, 16, "bf16", 8)), C.byref(t)) == binding.SYM_EINVAL
+    assert lib.sym_tuning_defaults(C.byref(binding.make_config(32, 8, 128, 16, "bf16", 8)), None) == binding.SYM_EINVAL
+    with pytest.raises(KeyError):
+        binding.make_config(32, 8, 128, 16, "bf16", 8, tuning={"no_such_setting": 1})
+
+    def n_tiles(tuning):
+        c = host_ctx(64, tuning=tuning)
+        words = c.build_desc([64], np.arange(4, dtype=np.int32), [0, 4], [64])
+        return int(words[4])
+    assert n_tiles(None) == 8 and n_tiles({"tile_rows": 128}) == 16 and n_tiles({"tile_rows": 7}) == 8
+    assert n_tiles({"prefill_min": 65}) == 0 and n_tiles({"prefill_min": -5}) == 8
 
 
 def test_fig1_hand_trace_library():
@@ -367,15 +400,13 @@ def _walk_desc(words, Hkv, P=16):
                                                  ([40, 300], [8, 1], 32), ([5], [5], 8), ([1030, 64, 333, 2000], [3, 2, 1, 7], 96)])
 @pytest.mark.parametrize("range_cost", [0, 3])
 @pytest.mark.parametrize("row_tokens", [1, 4])
-def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves, range_cost, row_tokens, monkeypatch):
+def test_descriptor_covers_every_unit_once_and_is_balanced(lengths, n_tok, waves, range_cost, row_tokens):
     """Rows (up to row_tokens new tokens of one LIP each, a short draft sharing one pass over the
     file), wave ranges, partial numbering and merge entries of the descriptor, walked the way the
     decode kernel walks them."""
     Hkv = 8
-    monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
-    monkeypatch.setenv("SYM_ROW_TOKENS", str(row_tokens))
-    monkeypatch.setenv("SYM_DECODE_MFMA", "1")          # the global cut of the matrix-core decode kernel (else: bins, below)
-    c = host_ctx(4096, decode_waves=waves)
+    # decode_mfma: the global cut of the matrix-core decode kernel (else: bins, below)
+    c = host_ctx(4096, decode_waves=waves, tuning={"range_cost": range_cost, "row_tokens": row_tokens, "decode_mfma": 1})
     rng = np.random.default_rng(1)
     np_l = [-(-L // 16) for L in lengths]
     flat = rng.permutation(4096)[:sum(np_l)].astype(np.int32)
@@ -505,14 +536,13 @@ def _walk_bins(words, P=16):
     ([38, 81, 130, 201], [1, 1, 1, 1], 64, 3), ([700, 16, 17, 1, 4096], [1, 1, 1, 1, 1], 2048, 3), ([5], [1], 8, 0),
     ([1030, 64, 333, 2000], [1, 1, 1, 1], 96, 3), ([70000, 33], [1, 1], 2048, 3), ([300] * 40, [1] * 40, 256, 0),
     (list(range(20, 2000, 37)), [1] * 54, 2048, 3)])
-def test_descriptor_bins_cover_every_unit_once_and_are_balanced(lengths, n_tok, waves, range_cost, monkeypatch):
+def test_descriptor_bins_cover_every_unit_once_and_are_balanced(lengths, n_tok, waves, range_cost):
     """The bins of the vector-unit decode kernel: segments are whole (row, kv head) ranges, or the parts of a range that a
     bin boundary divides; every (row, head, page) is covered by exactly one wavefront; a range in one segment writes the
     output, the segments of a divided range number their partials consecutively and share a merge entry; the bins
     carry equal cost."""
     Hkv, G = 8, 4
-    monkeypatch.setenv("SYM_RANGE_COST", str(range_cost))
-    c = host_ctx(1 << 15, decode_waves=waves)
+    c = host_ctx(1 << 15, decode_waves=waves, tuning={"range_cost": range_cost})
     rng = np.random.default_rng(2)
     np_l = [-(-L // 16) for L in lengths]
     flat = rng.permutation(1 << 15)[:sum(np_l)].astype(np.int32)
@@ -573,12 +603,11 @@ def test_descriptor_rejects_bad_tables():
 
 
 @pytest.mark.parametrize("tile_rows", [128, 256])
-def test_descriptor_tiles_for_prefill_chunks(tile_rows, monkeypatch):
+def test_descriptor_tiles_for_prefill_chunks(tile_rows):
     """LIPs with 16+ new tokens become tiles (one per kv head and tile_rows / 4 new tokens at 4 heads
     per group); the others stay decode rows; q rows keep the batch's token order."""
-    monkeypatch.setenv("SYM_TILE_ROWS", str(tile_rows))
     TQ = tile_rows // 4
-    c = host_ctx(4096)
+    c = host_ctx(4096, tuning={"tile_rows": tile_rows})
     lengths, n_tok = [100, 77, 40, 16], [70, 1, 3, 16]
     np_l = [-(-L // 16) for L in lengths]
     flat = np.arange(sum(np_l), dtype=np.int32)
