@@ -86,6 +86,14 @@ typedef struct sym_tuning {
   int32_t fuse_append;     /* 1 (default): the K/V row of a single new token is written by
                               the wavefront that reads the row's last page; 0: by a launch
                               of its own before attention                                 */
+  int32_t mix_lead;        /* a launch that holds tiles and decode workgroups starts with this
+                              many percent of its tile workgroups (0..100, default 0) ...  */
+  int32_t mix_spread;      /* ... and spreads the decode workgroups evenly among the next this
+                              many percent of them (0..100 - mix_lead, default 50); the other
+                              tile workgroups follow                                      */
+  int32_t share_tiles;     /* shared prefixes are cut by key chunk (at most 8 chunks each) until
+                              the batch has about this many tiles; >= 1, default 512 (two
+                              workgroups per CU)                                          */
 } sym_tuning;
 
 typedef struct sym_config {

@@ -17,7 +17,7 @@ K_PROLOGUE, K_ATTN, K_MERGE, K_MOVE, K_SWAP = 0, 1, 2, 3, 4
 
 
 TUNING_FIELDS = ("decode_mfma", "min_units", "prefill_min", "share_min_lips", "share_min_pages", "tile_rows",
-                 "row_tokens", "range_cost", "bin_tolerance", "bin_waves", "fuse_append")
+                 "row_tokens", "range_cost", "bin_tolerance", "bin_waves", "fuse_append", "mix_lead", "mix_spread", "share_tiles")
 
 
 class SymTuning(C.Structure):

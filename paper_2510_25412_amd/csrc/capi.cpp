@@ -46,6 +46,9 @@ sym_tuning default_tuning(const sym_config* cfg) {
   t.bin_tolerance = 3;
   t.bin_waves = 8;
   t.fuse_append = 1;
+  t.mix_lead = 0;
+  t.mix_spread = 50;
+  t.share_tiles = 512;
   return t;
 }
 }  // namespace
@@ -75,6 +78,8 @@ struct sym_ctx {
   int32_t prefill_min = 16, tile_tokens = 0;   // LIPs with >= prefill_min new tokens use the MFMA tile kernel (bf16 only)
   int32_t row_tokens = 1;                      // new tokens of one LIP per decode row (bf16: up to 16 / G, at most 4)
   int32_t fuse_append = 1;                     // 1: the attention kernel appends the tokens of single-token LIPs itself
+  int32_t mix_lead = 0, mix_spread = 50;       // where decode workgroups sit among the tile workgroups of a launch (percent)
+  int32_t share_tiles = 512;                   // shared-prefix tiles a batch is cut into (by key chunk), about
   int32_t bin_waves = 8;                       // wavefronts per decode bin (workgroup) of a batch without tiles: 4 or 8
   int32_t bin_tolerance = 3;                   // percent of imbalance between the decode bins that is accepted before ranges are split
   std::mutex mu;
@@ -142,7 +147,10 @@ int64_t blob_words_bound(const sym_ctx* c, int64_t n_lips, int64_t T, int64_t en
   // partial slots for them: 2 * tokens per row * wavefront slots), an in-bin merge list per workgroup of at least 4 wavefronts
   const int64_t bins = (T * c->cfg.n_kv_heads + 2 * (int64_t)c->row_tokens * c->max_waves + 2) * (SEG_WORDS + MERGE_WORDS) +
                        ((int64_t)c->max_waves / 4 + 1) * LMERGE_WORDS;
-  return bins + DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + ROW_TOKENS_MAX * MERGE_WORDS) + entries +
+  // the order table of a launch with tiles and bins: a word per tile (chunks of at least 16 tokens of a LIP per kv
+  // head; up to 8 key chunks of a shared prefix per LIP and kv head) and per 8 bins
+  const int64_t order = (T / 16 + 9 * n_lips) * c->cfg.n_kv_heads + (int64_t)c->max_waves / 32 + 8;
+  return bins + order + DESC_HEADER_WORDS + T * ROW_WORDS + (int64_t)c->max_waves * (WAVE_WORDS + ROW_TOKENS_MAX * MERGE_WORDS) + entries +
          (T + 8 * n_lips) * c->cfg.n_kv_heads * 2 + n_lips * (1 + c->cfg.n_kv_heads * (MERGE_WORDS + 8 * TILE_WORDS)) +
          n_lips + 1 + 3 * n_lips + T + 64;
 }
@@ -174,6 +182,9 @@ DescParams desc_params(const sym_ctx* c, int64_t partials, bool fuse_append = fa
   p.bin_waves = (c->G < 8 && !c->decode_mode) ? c->bin_waves : 0;
   p.fuse_append = (fuse_append && p.bin_waves && c->fuse_append) ? 1 : 0;
   p.bin_tolerance = c->bin_tolerance;
+  p.mix_lead = c->mix_lead;
+  p.mix_spread = c->mix_spread;
+  p.share_tiles = c->share_tiles;
   return p;
 }
 
@@ -306,6 +317,8 @@ int launch_attention(sym_ctx* c, const Scratch& ws, int64_t blob_words, const vo
   pa.Hkv = c->cfg.n_kv_heads;
   pa.scale_log2e = c->scale_log2e;
   pa.small_shared_only = d.small_shared_only;
+  pa.group_map = hdr[H_N_GROUPS] > 0 ? dw + hdr[H_OFF_GROUPS] : nullptr;
+  pa.n_groups = hdr[H_N_GROUPS];
   {
     Timed t(c, SYM_K_ATTN, st, true, timed);
     // rows that hold several new tokens exist for the matrix-core decode kernel only
@@ -629,6 +642,9 @@ int sym_init(const sym_config* cfg, sym_ctx** out) {
   c->bin_tolerance = std::max(0, tun.bin_tolerance);
   c->bin_waves = tun.bin_waves == 4 ? 4 : 8;
   c->fuse_append = tun.fuse_append ? 1 : 0;
+  c->mix_lead = std::min(std::max(tun.mix_lead, 0), 100);
+  c->mix_spread = std::min(std::max(tun.mix_spread, 0), 100 - c->mix_lead);
+  c->share_tiles = std::min(std::max(tun.share_tiles, 1), 1 << 16);
   if (cfg->device >= 0 && cfg->workspace_bytes < partial_bytes(c) + 4096) {
     sym_destroy(c);
     return SYM_ENOSPC;

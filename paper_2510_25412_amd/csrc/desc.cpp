@@ -127,7 +127,7 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       lo = hi;
     }
     if (!groups.empty()) {
-      const int64_t target = 512;                             // about two workgroups per CU
+      const int64_t target = std::max(1, prm.share_tiles);    // default 512: about two workgroups per CU
       int32_t nc_want = (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, (target + base_tiles - 1) / base_tiles));
       // every member leaves one partial per kv head and key chunk: the same number of chunks for all groups
       // that the partial slots can hold (not the wanted number for the first groups and none for the last)
@@ -377,7 +377,10 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
   const int64_t off_members = off_tiles + n_tiles * TILE_WORDS;
   const int64_t off_segs = off_members + n_members;
   const int64_t off_lmerge = off_segs + (bins ? (n_segs + 2) * SEG_WORDS : 0);       // two spare records: the kernel looks ahead
-  const int64_t total = off_lmerge + (bins ? n_bins * LMERGE_WORDS : 0);
+  // the order table of a launch with tiles and bins: a word per group of 8 workgroups (no more tile groups than tiles)
+  const int64_t off_groups = off_lmerge + (bins ? n_bins * LMERGE_WORDS : 0);
+  const int64_t groups_cap = (bins && n_tiles > 0) ? n_tiles + (n_bins + 7) / 8 : 0;
+  const int64_t total = off_groups + groups_cap;
   if (total > 0x7fffffff) return SYM_EINVAL;
   int32_t* const w = out->alloc ? out->alloc(total) : nullptr;   // the caller's buffer (pinned staging memory on the GPU path)
   if (!w) return SYM_ENOSPC;
@@ -682,6 +685,24 @@ int build_desc(const DescParams& prm, int32_t n_lips, const int32_t* n_tokens, c
       for (int x = 0; x < 8; ++x) tile_blocks = std::max(tile_blocks, 8 * count[x]);
     }
     w[H_TILE_BLOCKS] = tile_blocks;
+  }
+  if (groups_cap > 0) {
+    // Tiles come longest first and decode groups all cost the same.  Default: the decode groups go among the first
+    // half of the tile groups, so that some CUs stream K/V from HBM for decode ranges while the others keep the
+    // matrix cores busy, and no decode group starts late and becomes the tail of the grid.
+    const int64_t T = tile_blocks / 8, D = (n_bins + 7) / 8;
+    const int64_t lead = T * std::min(std::max(prm.mix_lead, 0), 100) / 100;
+    const int64_t spread = std::min(T - lead, (T * std::min(std::max(prm.mix_spread, 0), 100) + 99) / 100);
+    const int64_t gs = spread + D;                       // groups of the mixed stretch
+    int32_t* gm = w + off_groups;
+    int64_t t = 0, d = 0;
+    for (int64_t j = 0; j < T + D; ++j) {
+      const int64_t jj = j - lead;
+      const bool dec = jj >= 0 && jj < gs && (jj + 1) * D / gs > jj * D / gs;
+      gm[j] = dec ? ~(int32_t)d++ : (int32_t)t++;
+    }
+    w[H_N_GROUPS] = (int32_t)(T + D);
+    w[H_OFF_GROUPS] = (int32_t)off_groups;
   }
 
   // every (member row, head): extra partials first + i * stride, i < count

@@ -51,7 +51,10 @@ enum {
   H_TILE_BLOCKS = 18,     // workgroups of the tile part of the launch = 8 * (tiles of the fullest share)
   H_XCD_OFF = 20,         // 9 words: share x of the tile list is [H_XCD_OFF + x, H_XCD_OFF + x + 1)
   // bins (0 everywhere when the batch uses the global cut)
-  H_N_SEGS = 32, H_OFF_SEGS, H_N_BINS, H_BIN_WAVES, H_OFF_LMERGE
+  H_N_SEGS = 32, H_OFF_SEGS, H_N_BINS, H_BIN_WAVES, H_OFF_LMERGE,
+  // order of the workgroups of a launch that holds tiles and decode bins: one word per group of eight workgroups
+  // (one per XCD): g >= 0 = tile group g, g < 0 = decode group ~g
+  H_N_GROUPS = 37, H_OFF_GROUPS
 };
 // segment words: page-table offset, kv head, first page, end page | tokens the row sees, q/out row * Hq + first
 // query head of the kv head, destination (-1 = the final output rows; otherwise a partial slot in device memory), slot of the row's last
@@ -106,6 +109,10 @@ struct DescParams {
                               //   without tiles: 4 if this is 4, else 8)
   int32_t bin_tolerance = 3;  // percent by which the fullest bin may exceed the mean before ranges are split finer
   int32_t fuse_append = 0;    // 1: single-token LIPs are appended by the attention kernel (bins only)
+  // order of a launch with tiles and decode bins, in percent of the tile groups: `mix_lead` tile groups first, then
+  // all decode groups spread evenly among the next `mix_spread`, then the other tile groups
+  int32_t mix_lead = 0, mix_spread = 50;
+  int32_t share_tiles = 512;  // shared prefixes are cut by key chunk (up to 8 chunks) until the batch has about this many tiles
 };
 
 // n_tokens[b] new tokens of LIP b; len_after[b] = file length including them; LIP b's page

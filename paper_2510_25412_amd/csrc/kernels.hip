@@ -1491,19 +1491,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs da) {
 // work fill the GPU together and there is no launch boundary between them.
 // ---------------------------------------------------------------------------------------
 template <typename E, int G, int TW, bool SPLIT = false>
-__global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, PrefillArgs pa, int tile_groups, int decode_groups) {
-  // Workgroups come in groups of eight (one per XCD, which the tile order relies on).  Decode groups
-  // are spread among the tile groups, so that some CUs stream K/V from HBM for decode ranges while
-  // the others keep the matrix cores busy: the two kinds of work are bound by different units.
-  // Tiles come longest first and decode groups all cost the same, so the decode groups go among the
-  // first half of the tile groups: none of them starts late and becomes the tail of the grid.
-  // (Measured on the mixed batch: 1.85 ms against 1.91 ms with all tiles first; spread over the
-  // whole grid: 2.02 ms.  A CU that runs decode ranges alone has only its eight wavefronts' loads
-  // in flight, so the gain is small.)
+__global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, PrefillArgs pa) {
+  // Workgroups come in groups of eight (one per XCD, which the tile order relies on).  The host's table says what a
+  // group runs: tile group g (g >= 0) or decode group ~g.  By default the decode groups are spread among the
+  // first half of the tile groups, so that some CUs stream K/V from HBM for decode ranges while the others keep
+  // the matrix cores busy: the two kinds of work are bound by different units.  (Measured on the mixed batch:
+  // 1.85 ms against 1.91 ms with all tiles first; spread over the whole grid: 2.02 ms.  A CU that runs decode
+  // ranges alone has only its eight wavefronts' loads in flight, so the gain is small.)
   const uint32_t j = blockIdx.x >> 3, x = blockIdx.x & 7;
-  const uint64_t gs = (uint64_t)((tile_groups + 1) / 2) + (uint64_t)decode_groups;     // groups of the mixed stretch
-  const uint32_t d0 = j < gs ? (uint32_t)((uint64_t)j * (uint64_t)decode_groups / gs) : (uint32_t)decode_groups;   // decode groups before group j
-  const bool is_decode = j < gs && (uint32_t)((uint64_t)(j + 1) * (uint64_t)decode_groups / gs) > d0;
+  const int32_t g = pa.group_map ? __builtin_amdgcn_readfirstlane(pa.group_map[j]) : (int32_t)j;   // no table: tiles only
+  const bool is_decode = g < 0;
   // LDS: the K/V buffers of a tile workgroup, or the piece slots of a decode bin (a workgroup is one or the other)
   constexpr int kTileLds = E::kDimsPerChunk == 8 ? (SPLIT ? 4 : 3) * (kKLds + kVLds) : 0;      // tiles exist for bf16 storage only
   constexpr int kBinLds = G < 8 ? 2 * TW * BinLds<E, G < 8 ? G : 1>::kSlot * 4 : 0;
@@ -1511,12 +1508,12 @@ __global__ __launch_bounds__(64 * TW, 8 / TW) void attn_kernel(DecodeArgs da, Pr
   __shared__ __align__(16) uint8_t lds[kLds];
   if constexpr (E::kDimsPerChunk == 8) {
     if (!is_decode) {
-      tile_block<G, TW, SPLIT>(pa, (int)((j - d0) * 8 + x), (uint8_t(*)[kKLds + kVLds])lds);
+      tile_block<G, TW, SPLIT>(pa, (int)(g * 8 + x), (uint8_t(*)[kKLds + kVLds])lds);
       return;
     }
   }
   if constexpr (G < 8) {
-    if (is_decode) decode_bins<E, G>(da, (int)(d0 * 8 + x), TW, (float*)lds);
+    if (is_decode) decode_bins<E, G>(da, (int)(~g * 8 + x), TW, (float*)lds);
   }
 }
 
@@ -1813,15 +1810,18 @@ hipError_t launch_attn_g(const DecodeArgs& da, const PrefillArgs& pa, int decode
   const int decode_blocks = mode == 0 ? da.n_bins : 0;
   const int tile_groups = (tile_blocks + 7) / 8, decode_groups = (decode_blocks + 7) / 8;
   const dim3 grid((tile_groups + decode_groups) * 8), block(256), block8(512);
+  // tiles and bins in one grid: the host's order table must cover it; tiles alone run in list order
+  if (tile_groups > 0 && decode_groups > 0 && (!ps.group_map || ps.n_groups != tile_groups + decode_groups)) return hipErrorInvalidValue;
+  if (decode_groups == 0) ps.group_map = nullptr;
   if (ps.n_tiles > 0 && ps.tile_rows != 128 && ps.tile_rows != 256) return hipErrorInvalidValue;
   const bool second = da.n_waves > 0 && mode != 0;          // decode ranges in a launch of their own
   const hipEvent_t e_first = second ? nullptr : ev1;
   const hipEvent_t s_second = grid.x > 0 ? nullptr : ev0;
 #define SYM_ATTN_CASE(GG) \
   case GG: \
-    if (tw == 8) launch(attn_kernel<E, GG, 8>, grid, block8, ev0, e_first, da, ps, tile_groups, decode_groups); \
-    else if (split_tiles) launch(attn_kernel<E, GG, 4, true>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
-    else launch(attn_kernel<E, GG, 4>, grid, block, ev0, e_first, da, ps, tile_groups, decode_groups); \
+    if (tw == 8) launch(attn_kernel<E, GG, 8>, grid, block8, ev0, e_first, da, ps); \
+    else if (split_tiles) launch(attn_kernel<E, GG, 4, true>, grid, block, ev0, e_first, da, ps); \
+    else launch(attn_kernel<E, GG, 4>, grid, block, ev0, e_first, da, ps); \
     break;
   if (tile_blocks == 0 && mode == 0 && da.n_bins > 0) {      // plain decode: the lean kernel
     const dim3 dgrid(da.n_bins), dblock(64 * da.bin_waves);

@@ -50,6 +50,8 @@ struct PrefillArgs {
   int32_t Hq, Hkv;
   float scale_log2e;
   int32_t small_shared_only;     // every tile is a shared-prefix tile of at most 64 query rows (members x heads per kv head)
+  const int32_t* group_map;      // a launch with tiles and decode bins: per group of 8 workgroups, tile group g or ~(decode group)
+  int32_t n_groups;
 };
 
 struct MergeArgs {

@@ -53,7 +53,7 @@ def test_planner_settings_defaults_overrides_and_clamping():
 
     d4 = defaults(32, 8, 128, 16, "bf16")
     assert d4 == dict(decode_mfma=0, min_units=4, prefill_min=16, share_min_lips=4, share_min_pages=8, tile_rows=256,
-                      row_tokens=4, range_cost=3, bin_tolerance=3, bin_waves=8, fuse_append=1)
+                      row_tokens=4, range_cost=3, bin_tolerance=3, bin_waves=8, fuse_append=1, mix_lead=0, mix_spread=50, share_tiles=512)
     d8 = defaults(64, 8, 128, 16, "bf16")
     assert d8["decode_mfma"] == 1 and d8["row_tokens"] == 2
     assert defaults(8, 8, 64, 16, "f32")["row_tokens"] == 1 and defaults(8, 8, 64, 16, "f32")["decode_mfma"] == 0
