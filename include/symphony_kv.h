@@ -324,8 +324,9 @@ int sym_plan_copies_first(sym_ctx* ctx);
  * into 8 shares of equal cost, one per XCD (workgroup b runs tile b / 8 of share b % 8);
  * [32] n_segs, [33] offset of the segments, [34] n_bins, [35] wavefronts of a bin,
  * [36] offset of the in-bin merge lists (all five 0 when ranges are cut globally, as the
- * matrix-core decode kernel wants: wave_work is then one record per wavefront slot)}, then
- * the sections:
+ * matrix-core decode kernel wants: wave_work is then one record per wavefront slot);
+ * [37] n_groups, [38] offset of the order table (0 unless the launch holds tiles and bins)},
+ * then the sections:
  *   rows      [n_rows][4]   page-table offset, tokens the row's first new token sees, its q/out
  *                           row, and in one word: first page of the row's own range (low 28 bits;
  *                           pages before it belong to a shared prefix) | (new tokens in the
@@ -347,6 +348,9 @@ int sym_plan_copies_first(sym_ctx* ctx);
  *                           combined through LDS when the workgroup ends: count, first and
  *                           end segment of the bin, 0, then per cut segment: segment, LDS
  *                           slot of its first piece, wavefront of that piece, pieces
+ *   order     [n_groups]    (tiles and bins in one launch) what each group of 8 workgroups
+ *                           (one per XCD) runs, in launch order: g >= 0 = tile workgroups
+ *                           8g .. 8g + 7, g < 0 = bins 8 * ~g .. 8 * ~g + 7
  *   merge     [n_merge][8]  first partial, pieces, q row * Hq + first query head, then the
  *                           partials of the row's shared prefix: first, stride, count; then the
  *                           distance between the own pieces (tokens in the row); 0

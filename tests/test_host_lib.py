@@ -602,6 +602,38 @@ def test_descriptor_rejects_bad_tables():
         c.build_desc([0], np.array([1], np.int32), [0, 1], [4])
 
 
+@pytest.mark.parametrize("lead,spread", [(0, 50), (100, 0), (0, 0), (0, 100), (30, 40), (99, 1)])
+def test_descriptor_order_table_names_every_group_once(lead, spread):
+    """A launch with tiles and bins: the order table lists every tile group and every decode group exactly once, tile
+    groups in increasing order (tiles come longest first), decode groups too; `mix_lead` percent of the tile groups
+    precede the first decode group and all decode groups lie before the end of the next `mix_spread` percent."""
+    c = host_ctx(1 << 14, tuning={"mix_lead": lead, "mix_spread": spread})
+    lengths = [600, 40, 1000, 333, 64, 2000, 90, 2100] * 5
+    n_tok = [64, 1, 128, 1, 16, 1, 1, 1] * 5
+    np_l = [-(-L // 16) for L in lengths]
+    flat = np.arange(sum(np_l), dtype=np.int32)
+    off = np.concatenate([[0], np.cumsum(np_l)]).astype(np.int64)
+    words = c.build_desc(n_tok, flat, off, lengths)
+    hdr = words[:48]
+    n_groups, off_groups, tile_blocks, n_bins = int(hdr[37]), int(hdr[38]), int(hdr[18]), int(hdr[34])
+    T, D = tile_blocks // 8, -(-n_bins // 8)
+    assert T > 8 and D > 1 and n_groups == T + D
+    order = words[off_groups:off_groups + n_groups].tolist()
+    assert [g for g in order if g >= 0] == list(range(T))
+    assert [~g for g in order if g < 0] == list(range(D))
+    first_dec = next(i for i, g in enumerate(order) if g < 0)
+    last_dec = max(i for i, g in enumerate(order) if g < 0)
+    n_lead = T * lead // 100
+    n_spread = min(T - n_lead, -(-T * spread // 100))
+    assert first_dec >= n_lead and sum(g >= 0 for g in order[:first_dec]) <= n_lead + max(1, -(-n_spread // D))
+    assert sum(g >= 0 for g in order[:last_dec]) <= n_lead + n_spread
+    # a batch without tiles, and one without bins, carry no table
+    w2 = c.build_desc([1, 1], flat[:100], [0, 40, 100], [630, 950])
+    assert int(w2[37]) == 0
+    w3 = c.build_desc([64], flat[:40], [0, 40], [600])
+    assert int(w3[37]) == 0 and int(w3[4]) > 0
+
+
 @pytest.mark.parametrize("tile_rows", [128, 256])
 def test_descriptor_tiles_for_prefill_chunks(tile_rows):
     """LIPs with 16+ new tokens become tiles (one per kv head and tile_rows / 4 new tokens at 4 heads
