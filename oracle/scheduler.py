@@ -2,8 +2,8 @@
 
 The paper (section 4.4) says that the inference scheduler aggregates pred calls into one GPU
 batch, that firing too early wastes the GPU and firing too late makes threads wait, and that
-the batch size follows the average frequency of the calls, "leveraging models like Poisson
-process".  It gives no formula.  The policy below is this build's reading, written out step by
+the batch size follows the average frequency of the calls, for which it names arrival models
+such as the Poisson process.  It gives no formula.  The policy below is this build's reading, written out step by
 step in plain floating point (IEEE doubles, one operation at a time, so that the library's
 controller can be compared with it decision by decision):
 
