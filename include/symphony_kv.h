@@ -132,6 +132,8 @@ typedef struct sym_stats {
   int64_t pages_referenced;  /* pages those calls shared with the source instead of copying */
   int64_t pages_offloaded, pages_restored;   /* page copies of sym_kv_offload / sym_kv_restore */
   int64_t host_slots;        /* pinned host slots (pages) the context has created so far      */
+  int64_t last_batch_tiles;        /* of the last pred batch planned: matrix-core tiles ...            */
+  int64_t last_batch_shared_rows;  /* ... and rows whose shared prefix is read through such tiles      */
 } sym_stats;
 
 /* Sizes.  sym_page_bytes: bytes of one page for this shape (0 if unsupported).

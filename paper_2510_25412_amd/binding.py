@@ -37,7 +37,8 @@ class SymStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("pages_total", "pages_free", "pages_shared", "cow_copies", "pages_allocated",
                                          "tokens_appended", "pred_batches", "kernel_launches", "files", "handles",
                                          "host_ns_plan", "host_ns_pred", "tokens_moved", "pages_referenced",
-                                         "pages_offloaded", "pages_restored", "host_slots")]
+                                         "pages_offloaded", "pages_restored", "host_slots", "last_batch_tiles",
+                                         "last_batch_shared_rows")]
 
 
 class SymError(RuntimeError):

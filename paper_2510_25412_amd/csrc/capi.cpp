@@ -59,6 +59,7 @@ struct OpenPred {
   int64_t words = 0, cow_off = 0, slots_off = 0;   // blob size; offsets of the copy list and of the slot map in it
   int32_t n_cow = 0, n_append = 0;                 // page copies; rows for the append kernel (0 when the attention kernel appends them all)
   bool copies_first = false;
+  int64_t partials = 0;                            // partial slots behind the blob in the workspace
   std::vector<uint8_t> done;                       // per layer: sym_pred_layer has run
   int32_t n_done = 0;
 };
@@ -464,7 +465,16 @@ struct PlannedBatch {
   int64_t dwords = 0, words = 0, cow_off = 0, slots_off = 0;
   int32_t n_cow = 0, n_append = 0;
   int64_t wait_ns = 0;
+  int64_t partials = 0;      // partial slots of this batch's scratch (see below)
 };
+// Partial slots of a batch in the caller's workspace: everything behind the descriptor's bound, not just the minimum the
+// context was sized for (the slots left over after the cut pieces decide how many files may share a prefix, and into how
+// many key chunks it is cut).  Capped so that slot * G * D stays far inside 32 bits.
+int64_t partials_behind(const sym_ctx* c, const Scratch& ws, int64_t bound_words) {
+  const int64_t slot_bytes = (int64_t)c->G * (2 + c->cfg.head_dim) * 4;
+  const int64_t fit = (ws.bytes - align_up(bound_words * 4, 256) - 512) / slot_bytes;
+  return std::max(ws.partials, std::min<int64_t>(fit, 1 << 20));
+}
 int pred_plan_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* n_tokens, const Scratch& ws, bool no_alloc,
                      PlannedBatch* pb) {
   const int P = c->cfg.page_tokens;
@@ -479,7 +489,9 @@ int pred_plan_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t
   }
   const int64_t bound = blob_words_bound(c, n_lips, T, entries);
   if (no_alloc && bound > kStaticBlobWords) return fail(c, SYM_ENOSPC, "pred_batch_static: batch too large (descriptor beyond the static limit)");
-  if (align_up(bound * 4, 256) + partial_bytes_for(c, ws.partials) > ws.bytes) return fail(c, SYM_ENOSPC, "workspace too small for this batch");
+  const int64_t partials = no_alloc ? ws.partials : partials_behind(c, ws, bound);
+  pb->partials = partials;
+  if (align_up(bound * 4, 256) + partial_bytes_for(c, partials) > ws.bytes) return fail(c, SYM_ENOSPC, "workspace too small for this batch");
   int rc;
   if ((rc = stage_reserve(c, bound, !no_alloc))) return rc;      // the last thing that can fail for want of memory
   c->plan.clear();
@@ -491,7 +503,7 @@ int pred_plan_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t
     c->tables[b] = f->pages.data();
     c->len_after[b] = f->len;
   }
-  const DescParams prm = desc_params(c, ws.partials, true);
+  const DescParams prm = desc_params(c, partials, true);
   // The descriptor is built straight into the pinned staging buffer; copy list and slot map follow it.
   const int64_t tail_words = (int64_t)c->plan.cow.size() + (int64_t)c->plan.slots.size() + 4;
   int si = -1;
@@ -531,6 +543,7 @@ int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_
   PlannedBatch pb;
   int rc;
   if ((rc = pred_plan_locked(c, n_lips, kv, n_tokens, ws, no_alloc, &pb))) return rc;
+  const Scratch used{ws.base, ws.bytes, pb.partials};
   const auto t_planned = std::chrono::steady_clock::now();
   const int32_t* cow = c->stage[pb.si] + pb.cow_off;
   const int32_t* slots = c->stage[pb.si] + pb.slots_off;
@@ -544,7 +557,7 @@ int pred_batch_locked(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_
       (rc = stage_release(c, pb.si, st)))
     return rc;
   ++c->pred_batches;
-  rc = launch_attention(c, ws, pb.words, q, out, st, !no_alloc, k_new, v_new);
+  rc = launch_attention(c, used, pb.words, q, out, st, !no_alloc, k_new, v_new);
   const auto t_end = std::chrono::steady_clock::now();
   const auto ns = [](auto d) { return (int64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(d).count(); };
   c->host_ns_plan += ns(t_planned - t_begin) - pb.wait_ns;
@@ -771,6 +784,8 @@ int sym_get_stats(sym_ctx* c, sym_stats* s) {
   s->pages_offloaded = c->pages_offloaded;
   s->pages_restored = c->pages_restored;
   s->host_slots = c->fs->host_slots();
+  s->last_batch_tiles = c->desc_hdr[H_N_TILES];
+  s->last_batch_shared_rows = c->desc_hdr[H_N_MEMBERS];
   return SYM_OK;
 }
 
@@ -1001,6 +1016,7 @@ int sym_pred_begin(sym_ctx* c, int32_t n_lips, const sym_kv* kv, const int32_t* 
   o.n_cow = pb.n_cow;
   o.n_append = pb.n_append;
   o.copies_first = c->plan.copies_first;
+  o.partials = pb.partials;
   o.done.assign((size_t)c->n_layers, 0);
   o.n_done = 0;
   ++c->pred_batches;
@@ -1019,7 +1035,7 @@ int sym_pred_layer(sym_ctx* c, int32_t layer, const void* q, const void* k_new, 
   if (o.done[layer]) return fail(c, SYM_EBUSY, "pred_layer: this layer of the batch has already run");
   const auto t_begin = std::chrono::steady_clock::now();
   hipStream_t st = (hipStream_t)stream;
-  const Scratch ws = workspace_of(c);
+  const Scratch ws{(uint8_t*)c->cfg.workspace, c->cfg.workspace_bytes, o.partials};
   const int32_t* cow = (const int32_t*)ws.base + o.cow_off;          // the device copy of the blob
   const int32_t* slots = (const int32_t*)ws.base + o.slots_off;
   int rc, n_cow = o.n_cow;

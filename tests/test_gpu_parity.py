@@ -336,6 +336,28 @@ def test_shared_prefix_groups(Hq, Hkv):
     check_outputs(got, plain, tol=1e-3)     # the tile kernel rounds softmax weights to fp16, the decode kernel does not
 
 
+def test_many_sharing_members_use_the_slots_the_workspace_holds():
+    """1600 LIPs in 100 forked groups (9 shared pages each): more sharing members than the partial slots a context
+    needs at the least (1280 at 8 kv heads) would hold.  The slots are counted from what the caller's workspace holds
+    behind the batch's descriptor, so every group is still read through tiles; all outputs against the oracle, and
+    against the run that shares nothing."""
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    n_groups, fan = 100, 16
+    files = [("new", 16 * 9 + 3) for _ in range(n_groups)]
+    files += [("fork", g, 1 + (7 * g + 3 * i) % 30) for g in range(n_groups) for i in range(fan)]
+    batch = [(f, 1) for f in range(n_groups, len(files))]
+    wl = synth.custom("many_members", shape, files, batch, 8192, seed=4242)
+    got, sess, ref, osess = run_both(wl)
+    st = sess.ctx.get_stats()
+    assert st["last_batch_shared_rows"] == n_groups * fan and st["last_batch_tiles"] >= n_groups * 8
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+    plain, sess2 = _hip().run_workload(wl, poison=True, tuning={"share_min_lips": 0})
+    sess2.close()
+    check_outputs(got, plain, tol=1e-3)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 8)])
 @pytest.mark.parametrize("prefix_pages", [1, 2, 3, 4, 5, 7, 9, 16, 41])
 def test_small_shared_prefix_tiles_split_by_key_block(Hq, Hkv, prefix_pages):
