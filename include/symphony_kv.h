@@ -101,7 +101,10 @@ typedef struct sym_config {
   int32_t n_kv_heads;      /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv)   */
   int32_t head_dim;        /* D; D * sizeof(element) must be 256 (bf16: 128, f32: 64)    */
   int32_t page_tokens;     /* P = 16                                                     */
-  int32_t dtype;           /* SYM_F32 or SYM_BF16: storage type of Q, K, V               */
+  int32_t dtype;           /* SYM_F32 or SYM_BF16: storage type of Q, K, V.  The matrix-core
+                              paths (tiles for preds of many tokens and for shared prefixes,
+                              rows of several draft tokens) exist for SYM_BF16 only: with
+                              SYM_F32 every new token is a row of its own that reads the file */
   int32_t device;          /* HIP device ordinal, or -1 for a host-only context          */
   int64_t n_pages;         /* pages in the pool; page ids are int32, n_pages < 2^27      */
   void*   pool;            /* device, n_pages * sym_page_bytes() bytes, 256-aligned      */
