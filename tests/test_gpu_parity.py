@@ -743,6 +743,38 @@ def test_every_kind_of_work_in_one_batch(Hq, Hkv):
         print(f"all kinds {Hq}/{Hkv} waves={waves}: worst scaled error {worst:.2e}")
 
 
+_SETTINGS = [{"bin_waves": 4}, {"fuse_append": 0}, {"bin_tolerance": 0}, {"bin_tolerance": 1000}, {"min_units": 1, "range_cost": 0},
+             {"mix_lead": 100, "mix_spread": 0}, {"mix_lead": 0, "mix_spread": 0}, {"mix_lead": 0, "mix_spread": 100}, {"mix_lead": 40, "mix_spread": 30},
+             {"share_tiles": 16}, {"share_tiles": 4096}, {"share_min_lips": 2, "share_min_pages": 2}, {"tile_rows": 128}, {"prefill_min": 2},
+             {"prefill_min": 200}, {"row_tokens": 1}, {"decode_mfma": 1}, {"decode_mfma": 1, "row_tokens": 2}]
+
+
+@pytest.mark.parametrize("with_chunk", [False, True])
+def test_every_planner_setting_gives_the_oracles_outputs(with_chunk):
+    """sym_tuning decides where work runs, never what is computed: one batch (two fork groups, plain LIPs of very
+    different lengths, a short draft; with or without a prefill chunk, i.e. as `attn_kernel` with its order table or as
+    `decode_only_kernel`) under every setting in turn, few wavefront slots so that ranges are cut; each run against the
+    oracle (computed once) and the final page tables against the model."""
+    shape = synth.Shape(32, 8, 128, 16, synth.BF16)
+    files = [("new", 700), ("new", 330), ("new", 1500), ("new", 64), ("new", 909), ("new", 15), ("new", 2300)]
+    files += [("fork", 0, int(x)) for x in (5, 40, 0, 17, 90, 33)]          # forks of file 0
+    files += [("fork", 1, int(x)) for x in (1, 2, 3, 60, 7)]                # forks of file 1
+    batch = [(f, 1) for f in range(7, 18)] + [(2, 1), (4, 1), (5, 1), (6, 1), (0, 3)]
+    if with_chunk:
+        batch += [(3, 100)]
+    else:
+        batch.remove((0, 3))             # a plain decode batch: one new token everywhere
+    wl = synth.custom(f"settings_{int(with_chunk)}", shape, files, batch, 1024, seed=777 + int(with_chunk))
+    ref, osess = run_oracle(wl, dtype=np.float64)
+    for tuning in [None] + _SETTINGS:
+        print(f"[case] {wl.name} tuning={tuning}", flush=True)
+        got, sess = _hip().run_workload(wl, poison=True, tuning=tuning, decode_waves=48)
+        worst = check_outputs(got, ref)
+        check_state(wl, sess, osess)
+        sess.close()
+        print(f"  worst scaled error {worst:.2e}")
+
+
 @pytest.mark.parametrize("Hq,Hkv,D,dtype,multi", [(32, 8, 128, synth.BF16, 1), (32, 8, 128, synth.BF16, 3), (8, 8, 64, synth.F32, 3),
                                                   (64, 8, 128, synth.BF16, 1), (16, 8, 128, synth.BF16, 1)])
 def test_layered_pred_layer_by_layer_against_the_oracle(Hq, Hkv, D, dtype, multi):
