@@ -319,7 +319,7 @@ def bench_rag(args, np, torch, binding, synth, HipSession, dev):
     print(json.dumps(line))
 
 
-WORKLOADS = ("decode", "fork", "mixed", "prefill", "long", "draft", "short")
+WORKLOADS = ("decode", "fork", "mixed", "prefill", "long", "draft", "short", "decode64q")
 
 
 def workload_table(args, synth):
@@ -340,6 +340,8 @@ def workload_table(args, synth):
                   "bf16, contexts U{512..4096}) with 4 new tokens per LIP and call"),
         "long": (lambda: synth.config5(n_pages=args.pool_pages), 1, 40, 5, False, 0.0, "long context: 16 LIPs U{32768..131072}, "
                  "64Q/8KV, bf16, pages scattered over a %d-page pool, 1 new token each" % args.pool_pages),
+        "decode64q": (lambda: synth.config2(n_q_heads=64), 16, 20, 5, False, 0.0, "decode batch with 8 query heads per kv head: 64 LIPs, 64Q/8KV heads, "
+                      "head_dim 128, bf16, contexts U{512..4096}, 1 new token each"),
         "short": (lambda: synth.config2(n_lips=256, lo=100, hi=260, slack_pages=256), 16, 40, 5, False, 0.0, "short contexts: 256 LIPs, 32Q/8KV, bf16, "
                   "contexts U{100..260}, 1 new token each (the answer phase of the RAG scenario, freshly forked threads)"),
     }

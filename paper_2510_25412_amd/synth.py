@@ -131,14 +131,15 @@ def config1():
     return _finish(wl, st)
 
 
-def config2(n_lips=64, lo=512, hi=4096, slack_pages=2048, n_new=1):
+def config2(n_lips=64, lo=512, hi=4096, slack_pages=2048, n_new=1, n_q_heads=32):
     """Decode batch: 64 LIPs, 32 Q / 8 KV heads, D 128, bf16, lengths U{512..4096}; n_new tokens
-    per LIP and call (1 = plain decode; 2..8 = a draft being verified, paper section 4.1)."""
+    per LIP and call (1 = plain decode; 2..8 = a draft being verified, paper section 4.1).
+    n_q_heads = 64: the same batch with 8 query heads per kv head."""
     st = _Streams(1002)
     lengths = st.root.integers(lo, hi + 1, size=n_lips)
     P = 16
     n_pages = int(sum(-(-(int(L) + n_new) // P) for L in lengths)) + slack_pages
-    wl = Workload("decode_batch" if n_new == 1 else f"draft{n_new}_batch", Shape(32, 8, 128, P, BF16), n_pages, None)
+    wl = Workload("decode_batch" if n_new == 1 else f"draft{n_new}_batch", Shape(n_q_heads, 8, 128, P, BF16), n_pages, None)
     _plain_files(wl, st, lengths)
     wl.batch_files = list(range(n_lips))
     wl.batch_n = [int(n_new)] * n_lips
