@@ -336,6 +336,24 @@ def test_shared_prefix_groups(Hq, Hkv):
     check_outputs(got, plain, tol=1e-3)     # the tile kernel rounds softmax weights to fp16, the decode kernel does not
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,dtype", [(32, 8, 128, synth.BF16), (64, 8, 128, synth.BF16), (8, 8, 64, synth.F32)])
+def test_very_wide_batch_of_tiny_files(Hq, Hkv, D, dtype):
+    """4096 LIPs in one batch, files of 0..40 tokens (empty ones among them), one new token each: 32 768 ranges of one to
+    three pages, over a hundred per workgroup, most wavefronts switching range after every page; every output and every
+    page table against the oracle."""
+    shape = synth.Shape(Hq, Hkv, D, 16, dtype)
+    rng = np.random.default_rng(11)
+    lengths = rng.integers(0, 41, size=4096)
+    lengths[:7] = [0, 1, 15, 16, 17, 31, 32]
+    files = [("new", int(L)) for L in lengths]
+    batch = [(f, 1) for f in range(len(files))]
+    wl = synth.custom(f"wide_{Hq}_{Hkv}", shape, files, batch, 3 * 4096 + 64, seed=606 + Hq)
+    got, sess, ref, osess = run_both(wl)
+    check_outputs(got, ref)
+    check_state(wl, sess, osess)
+    sess.close()
+
+
 def test_many_sharing_members_use_the_slots_the_workspace_holds():
     """1600 LIPs in 100 forked groups (9 shared pages each): more sharing members than the partial slots a context
     needs at the least (1280 at 8 kv heads) would hold.  The slots are counted from what the caller's workspace holds
