@@ -66,8 +66,8 @@ typedef struct sym_tuning {
   int32_t decode_mfma;     /* ranges of single tokens and short drafts on the matrix cores (1)
                               or on the vector ALUs (0); bf16 only.  Default: 1 when
                               Hq/Hkv = 8, else 0                                          */
-  int32_t min_units;       /* smallest piece, in pairs of pages, that a long range is cut
-                              into; >= 1, default 4                                       */
+  int32_t min_units;       /* smallest piece, in pages, that a long range is cut into;
+                              >= 1, default 4                                             */
   int32_t prefill_min;     /* a pred of at least this many new tokens is computed by tiles
                               (bf16); >= 2, default 16                                    */
   int32_t share_min_lips;  /* files of a batch that must share a page-list prefix before
@@ -77,8 +77,8 @@ typedef struct sym_tuning {
   int32_t tile_rows;       /* query rows of a tile: 256 (default) or 128                  */
   int32_t row_tokens;      /* new tokens of a short draft that share one pass over the file:
                               1 .. 16 / (Hq/Hkv), default the maximum; bf16 only          */
-  int32_t range_cost;      /* what the start of a range costs, in pairs of pages, when work
-                              is divided; >= 0, default 3                                 */
+  int32_t range_cost;      /* what the start of a range costs, in pages' worth of work, when
+                              work is divided; >= 0, default 3                            */
   int32_t bin_tolerance;   /* whole ranges are packed into workgroups only if the fullest
                               then holds at most this many percent more than the mean;
                               otherwise ranges are cut at equal cost; >= 0, default 3     */
